@@ -1,0 +1,208 @@
+/*
+ * keep.h -- C ABI of the selective-KV-recompute prefill library for MI355X (gfx950).
+ *
+ * The library implements the hot path of KEEP (arxiv 2602.23592): memory groups
+ * whose KV caches were computed independently (Section 4.1) are joined into one
+ * prompt, instruction last (Section 1); at every layer only the memories in the
+ * current relevant set are recomputed over the joined cache (Section 4.2,
+ * "Selective Recomputation"; Section 5, `prefill_layer`), the set for the next
+ * layer is found by multi-hop importance propagation over group-to-group
+ * attention (Section 4.2, the four steps; Section 5, `importance_evaluation`),
+ * and group caches held in host memory are loaded layer by layer, overlapped
+ * with compute (Section 4.3; Section 5, `load_memory`).
+ *
+ * Conventions
+ *   - Plain C types only.  Every pointer argument says whether it is a HOST or a
+ *     DEVICE pointer.  The caller owns every buffer it passes in or gets results
+ *     in; the library never frees caller memory.  A context owns its workspace
+ *     (sized at keep_init from max_tokens / max_groups) and its RoPE table.
+ *   - Weights and the embedding table are borrowed for the context's lifetime.
+ *   - Tensors are dense row-major.  `dtype` (KEEP_F32 or KEEP_BF16) is the storage
+ *     type of weights, caches, hidden rows; arithmetic accumulates in fp32.
+ *   - Every function returns a keep_status and never throws or aborts;
+ *     keep_last_error() gives the text of the last failure on that context (or of
+ *     the last failed keep_init when passed NULL).
+ *   - Device outputs are ordered on the compute stream given to keep_init; host
+ *     outputs are valid on return.  One context must not be used from two threads
+ *     at once.
+ *   - Token positions are indices into the joined prompt: group g starts at
+ *     off_g = len_0 + ... + len_{g-1}; instruction rows follow the last group.
+ *     N_mem = sum of group_len, N = N_mem + instr_len.
+ *   - A "relevant set" is a strictly ascending list of group indices.  The rows
+ *     recomputed at a layer are the tokens of those groups in prompt order followed
+ *     by every instruction row; n_rows = sum of their lengths + instr_len.
+ */
+#ifndef KEEP_H
+#define KEEP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct keep_ctx keep_ctx; /* opaque, library-owned */
+
+typedef enum {
+  KEEP_OK = 0,
+  KEEP_ERR_INVALID_ARG = 1, /* NULL pointer, out-of-range scalar, unsorted set, bad ratio schedule */
+  KEEP_ERR_SHAPE = 2,       /* model or prompt shape the kernels cannot take */
+  KEEP_ERR_STATE = 3,       /* call out of order (scores asked before the layer was computed) */
+  KEEP_ERR_WORKSPACE = 4,   /* prompt larger than max_tokens / max_groups given at init */
+  KEEP_ERR_HIP = 5,         /* a HIP runtime call failed; text in keep_last_error */
+  KEEP_ERR_UNSUPPORTED = 6
+} keep_status;
+
+typedef enum { KEEP_F32 = 0, KEEP_BF16 = 1 } keep_dtype;
+typedef enum { KEEP_KV_DEVICE = 0, KEEP_KV_PINNED_HOST = 1 } keep_kv_location;
+
+/* How a ratio becomes a budget (Section 4.2, "a ratio of top r_i memories"):
+ * a number of memories, ceil(ratio * n_groups - 1e-3), or a number of tokens,
+ * floor(ratio * N_mem + 1e-3), filled by walking the importance order. */
+typedef enum { KEEP_BUDGET_GROUP_COUNT = 0, KEEP_BUDGET_TOKENS = 1 } keep_budget_mode;
+
+/* Host->device loading of group caches (Section 4.3, Fig. 8 a/b/c):
+ * SERIAL: load layer l, then compute it.  NEXT_LAYER: while layer l computes, load
+ * layer l+1 for the groups outside the current set.  LAYER_BALANCED: as NEXT_LAYER,
+ * and while compute is still running keep pre-loading later layers for groups that
+ * can no longer be recomputed.  All three give bit-identical results. */
+typedef enum { KEEP_LOAD_SERIAL = 0, KEEP_LOAD_NEXT_LAYER = 1, KEEP_LOAD_LAYER_BALANCED = 2 } keep_load_mode;
+
+/* Kernel family.  AUTO: MFMA kernels when dtype is bf16 and head_dim is 128 and
+ * hidden, ffn_dim are multiples of 64; otherwise the generic kernels.  GENERIC:
+ * always the scalar-FMA kernels (any head_dim that is even, fp32 or bf16). */
+typedef enum { KEEP_KERNELS_AUTO = 0, KEEP_KERNELS_GENERIC = 1 } keep_kernel_path;
+
+typedef struct {
+  int32_t n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn_dim, vocab;
+  float rope_theta; /* RoPE base; rotate-half pairing (j, j + head_dim/2) */
+  float rms_eps;
+  int32_t dtype;       /* keep_dtype */
+  int32_t max_tokens;  /* largest N of any prompt given to this context */
+  int32_t max_groups;  /* largest n_groups */
+  int32_t kernel_path; /* keep_kernel_path */
+} keep_model_desc;
+
+/* One decoder layer (pre-norm, GQA, SwiGLU).  DEVICE pointers, torch.nn.Linear
+ * layout [out_features, in_features] row-major.  bq/bk/bv may be NULL (no bias).
+ * ln1/ln2: RMSNorm weights [hidden]. */
+typedef struct {
+  const void *ln1, *wq, *wk, *wv, *bq, *bk, *bv, *wo, *ln2, *wgate, *wup, *wdown;
+} keep_layer_weights;
+
+/* The joined prompt (Section 1: retrieved memory then instruction). */
+typedef struct {
+  int32_t n_groups;          /* G >= 0 */
+  const int32_t* group_len;  /* HOST [G], each >= 1: a static group or one dynamic segment (Section 4.1) */
+  const uint8_t* group_kind; /* HOST [G] or NULL: 0 static, 1 dynamic (bookkeeping only) */
+  int32_t instr_len;         /* >= 1 */
+  const int32_t* token_ids;  /* HOST [N]: groups in order, then the instruction */
+  /* [n_layers * G], index layer*G + g: that group's cached K and V of that layer,
+   * each [len_g, n_kv_heads, head_dim], K rotated at group-local positions 0..len_g-1.
+   * The arrays of pointers are HOST arrays; the blocks are DEVICE memory
+   * (KEEP_KV_DEVICE) or pinned HOST memory (KEEP_KV_PINNED_HOST). */
+  const void* const* k_blocks;
+  const void* const* v_blocks;
+  int32_t kv_location; /* keep_kv_location */
+} keep_prompt;
+
+#define KEEP_REPORT_MAX_LAYERS 128
+/* Filled by keep_prefill when a report is asked for (caller-allocated, HOST). */
+typedef struct {
+  int32_t n_layers;
+  int32_t used_mfma;                          /* 1 if the MFMA kernel family ran */
+  float ms_total;                             /* whole call, host clock */
+  int32_t rows[KEEP_REPORT_MAX_LAYERS];       /* n_rows recomputed at each layer */
+  int32_t set_size[KEEP_REPORT_MAX_LAYERS];   /* groups recomputed at each layer */
+  int32_t hops_run[KEEP_REPORT_MAX_LAYERS];   /* selections run after each layer */
+  float ms_realign[KEEP_REPORT_MAX_LAYERS];   /* device time per phase, compute stream */
+  float ms_qkv[KEEP_REPORT_MAX_LAYERS];
+  float ms_attn[KEEP_REPORT_MAX_LAYERS];
+  float ms_ffn[KEEP_REPORT_MAX_LAYERS];       /* output projection + FFN */
+  float ms_score[KEEP_REPORT_MAX_LAYERS];     /* score reduction + selection, eval stream */
+  float ms_load_wait[KEEP_REPORT_MAX_LAYERS]; /* compute stream stalled on the copy stream */
+  uint64_t bytes_loaded[KEEP_REPORT_MAX_LAYERS]; /* host->device bytes enqueued while this layer ran */
+} keep_report;
+
+/* Create a context.  desc, layers[n_layers]: HOST structs holding DEVICE pointers;
+ * embed_table: DEVICE [vocab, hidden].  The three streams are hipStream_t handles
+ * (NULL = the default stream) for layer compute, importance evaluation (runs beside
+ * the FFN, Section 4.2 "System advantage") and host->device loading (Section 5,
+ * the three pipelined threads).  All must be at the default priority.
+ * Errors: INVALID_ARG (NULL, non-positive sizes, n_q_heads not a multiple of
+ * n_kv_heads, odd head_dim), SHAPE (head_dim > 256, n_layers > 128), HIP. */
+keep_status keep_init(const keep_model_desc* desc, const keep_layer_weights* layers, const void* embed_table,
+                      void* stream_compute, void* stream_eval, void* stream_copy, keep_ctx** out);
+
+/* Waits for the context's streams, frees workspace and RoPE table.  NULL is OK. */
+keep_status keep_destroy(keep_ctx* ctx);
+
+/* HOST string owned by the library, valid until the next call on that context. */
+const char* keep_last_error(const keep_ctx* ctx);
+
+/* Device bytes a context for this description allocates (0 if desc is invalid). */
+uint64_t keep_workspace_bytes(const keep_model_desc* desc);
+
+/* `prefill_layer` (Section 5): one layer of selective recomputation.
+ *   groups[n_sel]: HOST, ascending: the relevant set R of this layer.
+ *   x_in:  DEVICE [n_rows, hidden] hidden rows of the recomputed tokens in prompt
+ *          order; NULL at layer 0 = embedding rows of those tokens.
+ *   x_out: DEVICE [n_rows, hidden] hidden rows after the layer (may equal x_in).
+ *   k_cache_l, v_cache_l: DEVICE [N, n_kv_heads, head_dim], written in full: rows of
+ *          groups outside R get the cached K rotated on by the group's offset and the
+ *          cached V (position re-alignment); rows of R and of the instruction get the
+ *          refreshed K (RoPE at the global position) and V.
+ * Steps: re-align + concatenate, RMSNorm, QKV projection of the n_rows rows, RoPE,
+ * scatter, causal attention of those rows over all N cache rows, output projection,
+ * residual, RMSNorm, SwiGLU FFN, residual.  Leaves q, k and the softmax
+ * log-sum-exp of this layer in the workspace for keep_score_groups.
+ * With KEEP_KV_PINNED_HOST blocks the call copies the needed blocks itself.
+ * Errors: INVALID_ARG, WORKSPACE (N > max_tokens, G > max_groups), HIP. */
+keep_status keep_recompute_layer(keep_ctx* ctx, const keep_prompt* prompt, int32_t layer, const int32_t* groups,
+                                 int32_t n_sel, const void* x_in, void* x_out, void* k_cache_l, void* v_cache_l);
+
+/* `importance_evaluation` (Section 5; Section 4.2 steps 1-3) for the layer last given
+ * to keep_recompute_layer, with the same `groups`.
+ *   S[a, b] = attention probability from the rows of a to the keys of b averaged over
+ *   heads, rows and keys; a over groups[] then the instruction (last row), b over
+ *   groups[]; S[a, a] = 0.  Then: row-normalise, importance = query row, relevant set =
+ *   top of the importance order within the budget, importance = mean of the normalised
+ *   rows of the query and of the relevant set, repeat until the set repeats or `hops`
+ *   selections were made (hops = 1: initialisation only).  Ties: lower group index.
+ *   ratio_next: share of the prompt's memories (or memory tokens) kept for the next layer.
+ *   S_out: HOST [(n_sel+1) * n_sel] or NULL.  next_groups: HOST, capacity n_sel,
+ *   ascending subset of groups[].  n_next, hops_run: HOST scalars.
+ * Errors: STATE if `layer`/`groups` differ from the last keep_recompute_layer,
+ * INVALID_ARG, HIP. */
+keep_status keep_score_groups(keep_ctx* ctx, const keep_prompt* prompt, int32_t layer, const int32_t* groups,
+                              int32_t n_sel, float ratio_next, int32_t hops, int32_t budget_mode, float* S_out,
+                              int32_t* next_groups, int32_t* n_next, int32_t* hops_run);
+
+/* The selection steps alone (Section 4.2 steps 1-3) on a caller-supplied score
+ * matrix S: HOST [(n_sel+1) * n_sel], last row the query; group_len: HOST
+ * [n_groups_total] lengths of all the prompt's groups.  Same outputs as above. */
+keep_status keep_select_groups(keep_ctx* ctx, const float* S, const int32_t* groups, int32_t n_sel,
+                               const int32_t* group_len, int32_t n_groups_total, float ratio_next, int32_t hops,
+                               int32_t budget_mode, int32_t* next_groups, int32_t* n_next, int32_t* hops_run);
+
+/* Whole selective prefill (Section 4.2 + 4.3 + 5): for l = 0..n_layers-1 recompute
+ * the relevant set of layer l, evaluate importance beside the FFN, load what layer
+ * l+1 needs.
+ *   ratios: HOST [n_layers]; ratios[0] is 1 (recompute every memory at the first
+ *           layer, Section 4.2) or 0 (pure reuse); ratios[1..] non-increasing (a memory
+ *           dropped once is never recomputed, Section 4.3).
+ *   k_cache, v_cache: DEVICE [n_layers][N, n_kv_heads, head_dim], written in full.
+ *   x_final: DEVICE [instr_len, hidden]: hidden rows of the instruction after the
+ *           last layer (before any final norm).
+ *   sel_groups: HOST [n_layers * n_groups] or NULL; row l holds the set of layer l.
+ *   sel_counts: HOST [n_layers] or NULL.  report: HOST or NULL.
+ * Errors: INVALID_ARG (schedule), WORKSPACE, SHAPE, HIP. */
+keep_status keep_prefill(keep_ctx* ctx, const keep_prompt* prompt, const float* ratios, int32_t hops,
+                         int32_t budget_mode, int32_t load_mode, void* k_cache, void* v_cache, void* x_final,
+                         int32_t* sel_groups, int32_t* sel_counts, keep_report* report);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KEEP_H */

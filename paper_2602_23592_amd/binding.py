@@ -1,0 +1,246 @@
+"""ctypes binding of libkeep_hip.so: argument marshalling only.
+
+Every step of the path runs inside the library's HIP kernels; this module turns
+torch tensors (device memory, streams) and Python lists into the plain pointers
+and sizes of include/keep.h and raises KeepError on a non-zero status.  There is
+no CPU fallback: loading fails loudly when the library has not been built.
+"""
+import ctypes as C
+import os
+from typing import List, Optional, Sequence
+
+import numpy as np
+import torch
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libkeep_hip.so")
+
+KEEP_OK = 0
+KEEP_ERR_INVALID_ARG, KEEP_ERR_SHAPE, KEEP_ERR_STATE, KEEP_ERR_WORKSPACE, KEEP_ERR_HIP, KEEP_ERR_UNSUPPORTED = range(1, 7)
+KEEP_F32, KEEP_BF16 = 0, 1
+KEEP_KV_DEVICE, KEEP_KV_PINNED_HOST = 0, 1
+KEEP_BUDGET_GROUP_COUNT, KEEP_BUDGET_TOKENS = 0, 1
+KEEP_LOAD_SERIAL, KEEP_LOAD_NEXT_LAYER, KEEP_LOAD_LAYER_BALANCED = 0, 1, 2
+KEEP_KERNELS_AUTO, KEEP_KERNELS_GENERIC = 0, 1
+KEEP_REPORT_MAX_LAYERS = 128
+
+EXPORTED = ("keep_init", "keep_destroy", "keep_last_error", "keep_workspace_bytes", "keep_recompute_layer",
+            "keep_score_groups", "keep_select_groups", "keep_prefill")
+
+
+class KeepError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__("keep status %d: %s" % (status, text))
+        self.status = status
+
+
+class ModelDesc(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("n_layers", "hidden", "n_q_heads", "n_kv_heads", "head_dim", "ffn_dim", "vocab")] + \
+               [("rope_theta", C.c_float), ("rms_eps", C.c_float)] + \
+               [(n, C.c_int32) for n in ("dtype", "max_tokens", "max_groups", "kernel_path")]
+
+
+_W_NAMES = ("ln1", "wq", "wk", "wv", "bq", "bk", "bv", "wo", "ln2", "wgate", "wup", "wdown")
+
+
+class LayerWeights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in _W_NAMES]
+
+
+class Prompt(C.Structure):
+    _fields_ = [("n_groups", C.c_int32), ("group_len", C.POINTER(C.c_int32)), ("group_kind", C.POINTER(C.c_uint8)),
+                ("instr_len", C.c_int32), ("token_ids", C.POINTER(C.c_int32)),
+                ("k_blocks", C.POINTER(C.c_void_p)), ("v_blocks", C.POINTER(C.c_void_p)), ("kv_location", C.c_int32)]
+
+
+class Report(C.Structure):
+    _L = KEEP_REPORT_MAX_LAYERS
+    _fields_ = [("n_layers", C.c_int32), ("used_mfma", C.c_int32), ("ms_total", C.c_float),
+                ("rows", C.c_int32 * _L), ("set_size", C.c_int32 * _L), ("hops_run", C.c_int32 * _L),
+                ("ms_realign", C.c_float * _L), ("ms_qkv", C.c_float * _L), ("ms_attn", C.c_float * _L),
+                ("ms_ffn", C.c_float * _L), ("ms_score", C.c_float * _L), ("ms_load_wait", C.c_float * _L),
+                ("bytes_loaded", C.c_uint64 * _L)]
+
+
+_lib = None
+
+
+def load_library() -> C.CDLL:
+    """dlopen the HIP library; raises if it has not been built (no fallback)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError("libkeep_hip.so is missing: build it with `python -m paper_2602_23592_amd.build` "
+                          "(there is no CPU fallback)")
+    lib = C.CDLL(_LIB_PATH)
+    vp, i32, f32 = C.c_void_p, C.c_int32, C.c_float
+    pi32 = C.POINTER(C.c_int32)
+    lib.keep_init.restype = i32
+    lib.keep_init.argtypes = [C.POINTER(ModelDesc), C.POINTER(LayerWeights), vp, vp, vp, vp, C.POINTER(vp)]
+    lib.keep_destroy.restype = i32
+    lib.keep_destroy.argtypes = [vp]
+    lib.keep_last_error.restype = C.c_char_p
+    lib.keep_last_error.argtypes = [vp]
+    lib.keep_workspace_bytes.restype = C.c_uint64
+    lib.keep_workspace_bytes.argtypes = [C.POINTER(ModelDesc)]
+    lib.keep_recompute_layer.restype = i32
+    lib.keep_recompute_layer.argtypes = [vp, C.POINTER(Prompt), i32, pi32, i32, vp, vp, vp, vp]
+    lib.keep_score_groups.restype = i32
+    lib.keep_score_groups.argtypes = [vp, C.POINTER(Prompt), i32, pi32, i32, f32, i32, i32, C.POINTER(f32), pi32, pi32, pi32]
+    lib.keep_select_groups.restype = i32
+    lib.keep_select_groups.argtypes = [vp, C.POINTER(f32), pi32, i32, pi32, i32, f32, i32, i32, pi32, pi32, pi32]
+    lib.keep_prefill.restype = i32
+    lib.keep_prefill.argtypes = [vp, C.POINTER(Prompt), C.POINTER(f32), i32, i32, i32, vp, vp, vp, pi32, pi32,
+                                 C.POINTER(Report)]
+    _lib = lib
+    return lib
+
+
+def _i32_array(values: Sequence[int]):
+    a = np.ascontiguousarray(np.asarray(values, dtype=np.int32))
+    return a, a.ctypes.data_as(C.POINTER(C.c_int32))
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream_handle(s) -> Optional[int]:
+    if s is None:
+        return None
+    return s.cuda_stream if hasattr(s, "cuda_stream") else int(s)
+
+
+class KeepPrompt:
+    """Keeps the host arrays of a keep_prompt alive and exposes the C struct."""
+
+    def __init__(self, group_len: Sequence[int], instr_len: int, token_ids: Sequence[int], k_blocks, v_blocks,
+                 n_layers: int, kv_location: int = KEEP_KV_DEVICE, group_kind: Optional[Sequence[int]] = None):
+        self.group_len = [int(v) for v in group_len]
+        self.instr_len = int(instr_len)
+        self.n_groups = len(self.group_len)
+        self._gl, gl_p = _i32_array(self.group_len if self.n_groups else [0])
+        self._tok, tok_p = _i32_array(token_ids)
+        self._kind = None
+        kind_p = None
+        if group_kind is not None:
+            self._kind = np.ascontiguousarray(np.asarray(group_kind, dtype=np.uint8))
+            kind_p = self._kind.ctypes.data_as(C.POINTER(C.c_uint8))
+        # k_blocks[l][g]: tensors (device or pinned host); flattened to layer*G + g
+        self._blocks = (k_blocks, v_blocks)     # keep the tensors alive
+        n = max(1, n_layers * self.n_groups)
+        self._kp = (C.c_void_p * n)()
+        self._vp = (C.c_void_p * n)()
+        if k_blocks is not None:
+            for l in range(n_layers):
+                for g in range(self.n_groups):
+                    self._kp[l * self.n_groups + g] = k_blocks[l][g].data_ptr()
+                    self._vp[l * self.n_groups + g] = v_blocks[l][g].data_ptr()
+        self.c = Prompt(self.n_groups, gl_p, kind_p, self.instr_len, tok_p,
+                        C.cast(self._kp, C.POINTER(C.c_void_p)), C.cast(self._vp, C.POINTER(C.c_void_p)), kv_location)
+
+    @property
+    def n_mem(self) -> int:
+        return sum(self.group_len)
+
+    @property
+    def n_tokens(self) -> int:
+        return self.n_mem + self.instr_len
+
+    def n_rows(self, groups: Sequence[int]) -> int:
+        return sum(self.group_len[g] for g in groups) + self.instr_len
+
+
+class KeepContext:
+    """keep_ctx handle.  Weights: list of dicts name -> device tensor (or None for absent biases)."""
+
+    def __init__(self, shape, layers: List[dict], embed: torch.Tensor, max_tokens: int, max_groups: int,
+                 kernel_path: int = KEEP_KERNELS_AUTO, stream_compute=None, stream_eval=None, stream_copy=None):
+        self.lib = load_library()
+        self.shape = shape
+        self.dtype = KEEP_BF16 if shape.storage == "bf16" else KEEP_F32
+        self.torch_dtype = torch.bfloat16 if shape.storage == "bf16" else torch.float32
+        self.desc = ModelDesc(shape.n_layers, shape.hidden, shape.n_q_heads, shape.n_kv_heads, shape.head_dim,
+                              shape.ffn_dim, shape.vocab, shape.rope_theta, shape.rms_eps, self.dtype,
+                              int(max_tokens), int(max_groups), kernel_path)
+        self._keep = (layers, embed, stream_compute, stream_eval, stream_copy)
+        arr = (LayerWeights * shape.n_layers)()
+        for l, w in enumerate(layers):
+            for n in _W_NAMES:
+                t = w.get(n)
+                if t is not None:
+                    assert t.is_cuda and t.is_contiguous() and t.dtype == self.torch_dtype, n
+                setattr(arr[l], n, _ptr(t))
+        assert embed.is_cuda and embed.is_contiguous() and embed.dtype == self.torch_dtype
+        self.device = embed.device
+        handle = C.c_void_p()
+        st = self.lib.keep_init(C.byref(self.desc), arr, embed.data_ptr(), _stream_handle(stream_compute),
+                                _stream_handle(stream_eval), _stream_handle(stream_copy), C.byref(handle))
+        if st != KEEP_OK:
+            raise KeepError(st, self.lib.keep_last_error(None).decode())
+        self.handle = handle
+
+    def close(self):
+        if getattr(self, "handle", None):
+            self.lib.keep_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, st: int):
+        if st != KEEP_OK:
+            raise KeepError(st, self.lib.keep_last_error(self.handle).decode())
+
+    # -- the C entry points ---------------------------------------------------
+    def recompute_layer(self, prompt: KeepPrompt, layer: int, groups: Sequence[int], x_in: Optional[torch.Tensor],
+                        x_out: torch.Tensor, k_cache_l: torch.Tensor, v_cache_l: torch.Tensor):
+        g, gp = _i32_array(groups if len(groups) else [0])
+        self._check(self.lib.keep_recompute_layer(self.handle, C.byref(prompt.c), layer, gp, len(groups), _ptr(x_in),
+                                                  x_out.data_ptr(), k_cache_l.data_ptr(), v_cache_l.data_ptr()))
+
+    def score_groups(self, prompt: KeepPrompt, layer: int, groups: Sequence[int], ratio_next: float, hops: int,
+                     budget_mode: int = KEEP_BUDGET_GROUP_COUNT, want_scores: bool = True):
+        m = len(groups)
+        g, gp = _i32_array(groups if m else [0])
+        S = np.zeros((m + 1, max(m, 1)), dtype=np.float32) if want_scores else None
+        nxt = np.zeros(max(m, 1), dtype=np.int32)
+        n_next, runs = C.c_int32(0), C.c_int32(0)
+        self._check(self.lib.keep_score_groups(
+            self.handle, C.byref(prompt.c), layer, gp, m, float(ratio_next), hops, budget_mode,
+            S.ctypes.data_as(C.POINTER(C.c_float)) if want_scores else None,
+            nxt.ctypes.data_as(C.POINTER(C.c_int32)), C.byref(n_next), C.byref(runs)))
+        scores = S[:, :m].reshape(m + 1, m) if want_scores else None
+        return [int(v) for v in nxt[:n_next.value]], runs.value, scores
+
+    def select_groups(self, S: np.ndarray, groups: Sequence[int], group_len: Sequence[int], ratio_next: float,
+                      hops: int, budget_mode: int = KEEP_BUDGET_GROUP_COUNT):
+        m = len(groups)
+        S = np.ascontiguousarray(S, dtype=np.float32)
+        assert S.shape == (m + 1, m)
+        g, gp = _i32_array(groups if m else [0])
+        gl, glp = _i32_array(group_len if len(group_len) else [0])
+        nxt = np.zeros(max(m, 1), dtype=np.int32)
+        n_next, runs = C.c_int32(0), C.c_int32(0)
+        self._check(self.lib.keep_select_groups(
+            self.handle, S.ctypes.data_as(C.POINTER(C.c_float)), gp, m, glp, len(group_len), float(ratio_next), hops,
+            budget_mode, nxt.ctypes.data_as(C.POINTER(C.c_int32)), C.byref(n_next), C.byref(runs)))
+        return [int(v) for v in nxt[:n_next.value]], runs.value
+
+    def prefill(self, prompt: KeepPrompt, ratios: Sequence[float], hops: int, k_cache: torch.Tensor,
+                v_cache: torch.Tensor, x_final: torch.Tensor, budget_mode: int = KEEP_BUDGET_GROUP_COUNT,
+                load_mode: int = KEEP_LOAD_LAYER_BALANCED, want_report: bool = False):
+        L, G = self.shape.n_layers, prompt.n_groups
+        r = np.ascontiguousarray(np.asarray(ratios, dtype=np.float32))
+        sel = np.zeros(max(1, L * G), dtype=np.int32)
+        cnt = np.zeros(L, dtype=np.int32)
+        rep = Report() if want_report else None
+        self._check(self.lib.keep_prefill(
+            self.handle, C.byref(prompt.c), r.ctypes.data_as(C.POINTER(C.c_float)), hops, budget_mode, load_mode,
+            k_cache.data_ptr(), v_cache.data_ptr(), x_final.data_ptr(), sel.ctypes.data_as(C.POINTER(C.c_int32)),
+            cnt.ctypes.data_as(C.POINTER(C.c_int32)), C.byref(rep) if want_report else None))
+        sets = [[int(v) for v in sel[l * G:l * G + cnt[l]]] for l in range(L)]
+        return sets, rep

@@ -1,0 +1,1101 @@
+// C ABI of libkeep_hip.so: argument checks, workspace, per-layer orchestration of the
+// kernels over three HIP streams (layer compute / importance evaluation / host->device
+// loading), following the pipeline of Section 5 of the paper.
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <algorithm>
+#include <chrono>
+#include <string>
+#include <type_traits>
+#include <vector>
+
+#include "keep_internal.h"
+
+using namespace keep;
+
+namespace {
+
+thread_local std::string g_init_error;
+
+constexpr double BUDGET_EPS = 1.0e-3;
+constexpr int EV_PER_LAYER = 7;  // begin, realign, qkv, attn, ffn, score_begin, score_end
+// Host->device pre-loads are enqueued only while fewer bytes than this are in flight,
+// so that the copies a layer is waiting for never queue behind a long run of pre-loads.
+constexpr size_t PRELOAD_INFLIGHT_CAP = 48u << 20;
+
+struct Staging {  // pinned host mirror of the small per-layer device arrays
+  int32_t* set_off;
+  int32_t* row_start;
+  int32_t* gather_src;
+  int32_t* gather_dst;
+  int32_t* cand_len;
+  RealignSeg* segs;
+  hipEvent_t done;
+  bool used;
+};
+
+}  // namespace
+
+struct keep_ctx {
+  keep_model_desc d;
+  std::vector<keep_layer_weights> w;
+  const void* embed = nullptr;
+  hipStream_t s_comp = nullptr, s_eval = nullptr, s_copy = nullptr;
+  bool mfma = false;
+  size_t esz = 4;
+  std::string err;
+
+  // device workspace
+  std::vector<void*> allocs;
+  size_t bytes = 0;
+  float *rope_cos = nullptr, *rope_sin = nullptr;
+  int32_t *d_token_ids = nullptr, *d_row_pos = nullptr, *d_row_slot = nullptr;
+  int32_t *d_set_off = nullptr, *d_row_start = nullptr, *d_gather_src = nullptr, *d_cand_len = nullptr;
+  RealignSeg* d_segs = nullptr;
+  void *xa = nullptr, *xb = nullptr, *hbuf = nullptr, *q = nullptr, *kc = nullptr, *o = nullptr, *x1 = nullptr,
+       *act = nullptr;
+  float *qkv_raw = nullptr, *lse = nullptr, *score_scratch = nullptr, *S = nullptr, *sel_work = nullptr;
+  int32_t *sel_iwork = nullptr, *sel_out = nullptr;
+
+  // pinned host
+  std::vector<Staging> stage;       // one slot per layer
+  int32_t* h_sel_out = nullptr;     // [max_groups + 2]
+  float* h_S = nullptr;             // [(max_groups+1) * max_groups]
+  int32_t* h_token_ids = nullptr;   // [max_tokens]
+
+  std::vector<hipEvent_t> ev;       // EV_PER_LAYER per layer
+  hipEvent_t ev_attn = nullptr, ev_eval = nullptr, ev_load = nullptr, ev_comp = nullptr, ev_tok = nullptr;
+  bool tok_pending = false;          // an upload from h_token_ids may still be in flight
+  std::vector<hipEvent_t> ev_chunk; // ring for pre-load flow control
+
+  // state left by keep_recompute_layer for keep_score_groups
+  int last_layer = -1;
+  std::vector<int32_t> last_groups;
+  std::vector<int32_t> last_row_start;  // host copy, m+2 entries
+  int last_n_rows = 0;
+  const void* tokens_uploaded_for = nullptr;  // prompt token array currently in d_token_ids
+  int tokens_uploaded_n = 0;
+};
+
+namespace {
+
+keep_status fail(keep_ctx* c, keep_status st, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  if (c)
+    c->err = buf;
+  else
+    g_init_error = buf;
+  return st;
+}
+
+#define HIP_TRY(c, expr)                                                                             \
+  do {                                                                                               \
+    hipError_t e__ = (expr);                                                                         \
+    if (e__ != hipSuccess)                                                                           \
+      return fail((c), KEEP_ERR_HIP, "%s failed: %s (%s:%d)", #expr, hipGetErrorString(e__), __FILE__, __LINE__); \
+  } while (0)
+
+keep_status check_desc(const keep_model_desc* d, const char** why) {
+  *why = "";
+  if (!d) {
+    *why = "desc is NULL";
+    return KEEP_ERR_INVALID_ARG;
+  }
+  if (d->n_layers <= 0 || d->hidden <= 0 || d->n_q_heads <= 0 || d->n_kv_heads <= 0 || d->head_dim <= 0 ||
+      d->ffn_dim <= 0 || d->vocab <= 0 || d->max_tokens <= 0 || d->max_groups < 0) {
+    *why = "non-positive size in keep_model_desc";
+    return KEEP_ERR_INVALID_ARG;
+  }
+  if (d->n_q_heads % d->n_kv_heads) {
+    *why = "n_q_heads must be a multiple of n_kv_heads";
+    return KEEP_ERR_INVALID_ARG;
+  }
+  if (d->dtype != KEEP_F32 && d->dtype != KEEP_BF16) {
+    *why = "dtype must be KEEP_F32 or KEEP_BF16";
+    return KEEP_ERR_INVALID_ARG;
+  }
+  if (d->kernel_path != KEEP_KERNELS_AUTO && d->kernel_path != KEEP_KERNELS_GENERIC) {
+    *why = "unknown kernel_path";
+    return KEEP_ERR_INVALID_ARG;
+  }
+  if (!(d->rope_theta > 0.f) || !(d->rms_eps >= 0.f)) {
+    *why = "rope_theta must be > 0 and rms_eps >= 0";
+    return KEEP_ERR_INVALID_ARG;
+  }
+  if (d->head_dim % 16 || d->head_dim > 256) {
+    *why = "head_dim must be a multiple of 16 and at most 256";
+    return KEEP_ERR_SHAPE;
+  }
+  if (d->hidden % 8 || d->ffn_dim % 8) {
+    *why = "hidden and ffn_dim must be multiples of 8";
+    return KEEP_ERR_SHAPE;
+  }
+  if (d->n_layers > KEEP_REPORT_MAX_LAYERS) {
+    *why = "n_layers above 128";
+    return KEEP_ERR_SHAPE;
+  }
+  return KEEP_OK;
+}
+
+bool wants_mfma(const keep_model_desc* d) {
+  return false && d->kernel_path == KEEP_KERNELS_AUTO && d->dtype == KEEP_BF16 && d->head_dim == 128 && d->hidden % 64 == 0 &&
+         d->ffn_dim % 64 == 0;
+}
+
+struct Sizes {
+  size_t M, G, d, qd, kvd, F, esz;
+};
+Sizes sizes_of(const keep_model_desc* d) {
+  Sizes z;
+  z.M = (size_t)d->max_tokens;
+  z.G = (size_t)std::max(1, d->max_groups);
+  z.d = (size_t)d->hidden;
+  z.qd = (size_t)d->n_q_heads * d->head_dim;
+  z.kvd = (size_t)d->n_kv_heads * d->head_dim;
+  z.F = (size_t)d->ffn_dim;
+  z.esz = d->dtype == KEEP_BF16 ? 2 : 4;
+  return z;
+}
+
+size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
+
+// list of (bytes) in a fixed order; used both to size and to carve the workspace
+size_t score_scratch_bytes(const keep_model_desc* d) {
+  Sizes z = sizes_of(d);
+  size_t generic = z.M * z.G * sizeof(float);
+  size_t mf = wants_mfma(d) ? score_mfma_scratch_bytes((int32_t)z.M, (int32_t)z.G) : 0;
+  return std::max(generic, mf);
+}
+
+uint64_t workspace_bytes(const keep_model_desc* d) {
+  Sizes z = sizes_of(d);
+  size_t half = (size_t)d->head_dim / 2;
+  size_t t = 0;
+  t += 2 * align256(z.M * half * sizeof(float));                       // rope cos, sin
+  t += 3 * align256(z.M * sizeof(int32_t));                            // token ids, row_pos, row_slot
+  t += 4 * align256((z.G + 2) * sizeof(int32_t));                      // set_off, row_start, gather_src, cand_len
+  t += align256(z.G * sizeof(RealignSeg));
+  t += 4 * align256(z.M * z.d * z.esz);                                // xa, xb, h, x1
+  t += 2 * align256(z.M * z.qd * z.esz);                               // q, o
+  t += align256(z.M * z.kvd * z.esz);                                  // k compact
+  t += align256(z.M * z.F * z.esz);                                    // act
+  t += align256(z.M * (z.qd + 2 * z.kvd) * sizeof(float));             // qkv_raw
+  t += align256(z.M * (size_t)d->n_q_heads * sizeof(float));           // lse
+  t += align256(score_scratch_bytes(d));
+  t += align256((z.G + 1) * z.G * sizeof(float));                      // S
+  t += align256(((z.G + 1) * z.G + 2 * z.G) * sizeof(float));          // sel_work
+  t += align256(4 * z.G * sizeof(int32_t)) + align256((z.G + 2) * sizeof(int32_t));
+  return t;
+}
+
+template <typename P>
+keep_status dev_alloc(keep_ctx* c, P** p, size_t bytes) {
+  void* v = nullptr;
+  HIP_TRY(c, hipMalloc(&v, align256(std::max<size_t>(bytes, 256))));
+  c->allocs.push_back(v);
+  c->bytes += align256(bytes);
+  *p = reinterpret_cast<P*>(v);
+  return KEEP_OK;
+}
+
+template <typename P>
+keep_status pin_alloc(keep_ctx* c, P** p, size_t bytes) {
+  void* v = nullptr;
+  HIP_TRY(c, hipHostMalloc(&v, std::max<size_t>(bytes, 64), hipHostMallocDefault));
+  *p = reinterpret_cast<P*>(v);
+  return KEEP_OK;
+}
+
+struct PromptInfo {
+  int G = 0, Lq = 0, n_mem = 0, N = 0;
+  std::vector<int32_t> off;  // G+1
+};
+
+keep_status check_prompt(keep_ctx* c, const keep_prompt* p, PromptInfo* pi, bool need_blocks) {
+  if (!p) return fail(c, KEEP_ERR_INVALID_ARG, "prompt is NULL");
+  if (p->n_groups < 0) return fail(c, KEEP_ERR_INVALID_ARG, "n_groups is negative");
+  if (p->instr_len < 1) return fail(c, KEEP_ERR_INVALID_ARG, "instr_len must be at least 1 (the query drives the selection)");
+  if (p->n_groups > 0 && !p->group_len) return fail(c, KEEP_ERR_INVALID_ARG, "group_len is NULL");
+  if (!p->token_ids) return fail(c, KEEP_ERR_INVALID_ARG, "token_ids is NULL");
+  if (p->kv_location != KEEP_KV_DEVICE && p->kv_location != KEEP_KV_PINNED_HOST)
+    return fail(c, KEEP_ERR_INVALID_ARG, "unknown kv_location");
+  if (need_blocks && p->n_groups > 0 && (!p->k_blocks || !p->v_blocks))
+    return fail(c, KEEP_ERR_INVALID_ARG, "k_blocks / v_blocks is NULL");
+  if (p->n_groups > c->d.max_groups)
+    return fail(c, KEEP_ERR_WORKSPACE, "n_groups %d above max_groups %d", p->n_groups, c->d.max_groups);
+  pi->G = p->n_groups;
+  pi->Lq = p->instr_len;
+  pi->off.assign(pi->G + 1, 0);
+  int64_t tot = 0;
+  for (int g = 0; g < pi->G; ++g) {
+    if (p->group_len[g] < 1) return fail(c, KEEP_ERR_INVALID_ARG, "group_len[%d] = %d, must be >= 1", g, p->group_len[g]);
+    tot += p->group_len[g];
+    if (tot + p->instr_len > c->d.max_tokens)
+      return fail(c, KEEP_ERR_WORKSPACE, "prompt longer than max_tokens %d", c->d.max_tokens);
+    pi->off[g + 1] = (int32_t)tot;
+  }
+  if (tot + p->instr_len > c->d.max_tokens)
+    return fail(c, KEEP_ERR_WORKSPACE, "prompt longer than max_tokens %d", c->d.max_tokens);
+  pi->n_mem = (int)tot;
+  pi->N = pi->n_mem + pi->Lq;
+  for (int i = 0; i < pi->N; ++i)
+    if (p->token_ids[i] < 0 || p->token_ids[i] >= c->d.vocab)
+      return fail(c, KEEP_ERR_INVALID_ARG, "token_ids[%d] = %d outside the vocabulary", i, p->token_ids[i]);
+  return KEEP_OK;
+}
+
+keep_status check_set(keep_ctx* c, const PromptInfo& pi, const int32_t* groups, int n_sel) {
+  if (n_sel < 0 || n_sel > pi.G) return fail(c, KEEP_ERR_INVALID_ARG, "n_sel %d outside [0, n_groups]", n_sel);
+  if (n_sel > 0 && !groups) return fail(c, KEEP_ERR_INVALID_ARG, "groups is NULL");
+  for (int i = 0; i < n_sel; ++i) {
+    if (groups[i] < 0 || groups[i] >= pi.G) return fail(c, KEEP_ERR_INVALID_ARG, "groups[%d] = %d out of range", i, groups[i]);
+    if (i && groups[i] <= groups[i - 1]) return fail(c, KEEP_ERR_INVALID_ARG, "groups must be strictly ascending");
+  }
+  return KEEP_OK;
+}
+
+int budget_count(float ratio, int n_groups_total, int n_cand) {
+  int k = (int)ceil((double)ratio * (double)n_groups_total - BUDGET_EPS);
+  return std::max(0, std::min(n_cand, k));
+}
+int budget_tokens(float ratio, int mem_tokens) { return (int)floor((double)ratio * (double)mem_tokens + BUDGET_EPS); }
+
+// --- typed dispatch helpers -------------------------------------------------
+template <typename T>
+struct Typed {
+  static T* p(void* v) { return reinterpret_cast<T*>(v); }
+  static const T* p(const void* v) { return reinterpret_cast<const T*>(v); }
+};
+
+keep_status upload_tokens(keep_ctx* c, const keep_prompt* p, const PromptInfo& pi) {
+  // token ids go through pinned memory so the async copy does not read caller memory later
+  if (c->tok_pending) HIP_TRY(c, hipEventSynchronize(c->ev_tok));
+  memcpy(c->h_token_ids, p->token_ids, (size_t)pi.N * sizeof(int32_t));
+  HIP_TRY(c, hipMemcpyAsync(c->d_token_ids, c->h_token_ids, (size_t)pi.N * sizeof(int32_t), hipMemcpyHostToDevice,
+                            c->s_comp));
+  HIP_TRY(c, hipEventRecord(c->ev_tok, c->s_comp));
+  c->tok_pending = true;
+  return KEEP_OK;
+}
+
+struct LayerPlan {
+  int m = 0, n_rows = 0, n_realign_rows = 0, n_segs = 0;
+  std::vector<int32_t> row_start;  // m+2
+};
+
+// Fill the layer's staging slot (set offsets, compact row starts, re-align segments) and
+// enqueue its upload on the compute stream.
+keep_status stage_layer(keep_ctx* c, const keep_prompt* p, const PromptInfo& pi, int layer, const int32_t* groups,
+                        int m, const void* k_cache_l, const void* v_cache_l, bool blocks_at_dst, LayerPlan* plan) {
+  Staging& st = c->stage[layer];
+  if (st.used) HIP_TRY(c, hipEventSynchronize(st.done));
+  plan->m = m;
+  plan->row_start.assign(m + 2, 0);
+  int acc = 0;
+  for (int i = 0; i < m; ++i) {
+    st.set_off[i] = pi.off[groups[i]];
+    st.cand_len[i] = p->group_len[groups[i]];
+    st.row_start[i] = acc;
+    plan->row_start[i] = acc;
+    acc += p->group_len[groups[i]];
+  }
+  st.row_start[m] = plan->row_start[m] = acc;
+  acc += pi.Lq;
+  st.row_start[m + 1] = plan->row_start[m + 1] = acc;
+  plan->n_rows = acc;
+  // groups outside the set: re-align segments
+  const size_t row_bytes = (size_t)c->d.n_kv_heads * c->d.head_dim * c->esz;
+  int ns = 0, rows = 0, gi = 0;
+  for (int g = 0; g < pi.G; ++g) {
+    if (gi < m && groups[gi] == g) {
+      ++gi;
+      continue;
+    }
+    RealignSeg& sg = st.segs[ns++];
+    if (blocks_at_dst) {
+      sg.k_src = (const char*)k_cache_l + (size_t)pi.off[g] * row_bytes;
+      sg.v_src = (const char*)v_cache_l + (size_t)pi.off[g] * row_bytes;
+    } else {
+      sg.k_src = p->k_blocks[(size_t)layer * pi.G + g];
+      sg.v_src = p->v_blocks[(size_t)layer * pi.G + g];
+      if (!sg.k_src || !sg.v_src)
+        return fail(c, KEEP_ERR_INVALID_ARG, "k_blocks/v_blocks entry of layer %d group %d is NULL", layer, g);
+    }
+    sg.dst_off = pi.off[g];
+    sg.len = p->group_len[g];
+    sg.row_start = rows;
+    sg.pad = 0;
+    rows += sg.len;
+  }
+  plan->n_segs = ns;
+  plan->n_realign_rows = rows;
+  hipStream_t s = c->s_comp;
+  if (m > 0) {
+    HIP_TRY(c, hipMemcpyAsync(c->d_set_off, st.set_off, (size_t)m * 4, hipMemcpyHostToDevice, s));
+    HIP_TRY(c, hipMemcpyAsync(c->d_cand_len, st.cand_len, (size_t)m * 4, hipMemcpyHostToDevice, s));
+  }
+  HIP_TRY(c, hipMemcpyAsync(c->d_row_start, st.row_start, (size_t)(m + 2) * 4, hipMemcpyHostToDevice, s));
+  if (ns > 0) HIP_TRY(c, hipMemcpyAsync(c->d_segs, st.segs, (size_t)ns * sizeof(RealignSeg), hipMemcpyHostToDevice, s));
+  return KEEP_OK;
+}
+
+// Steps of one layer on the compute stream, up to and including attention.
+template <typename T>
+keep_status layer_front(keep_ctx* c, const PromptInfo& pi, int layer, const LayerPlan& plan, const void* x_in,
+                        void* k_cache_l, void* v_cache_l, hipEvent_t* evs) {
+  const keep_model_desc& d = c->d;
+  const keep_layer_weights& w = c->w[layer];
+  hipStream_t s = c->s_comp;
+  const int n = plan.n_rows;
+  if (evs) HIP_TRY(c, hipEventRecord(evs[0], s));
+  launch_realign<T>(c->d_segs, plan.n_segs, plan.n_realign_rows, d.n_kv_heads, d.head_dim, c->rope_cos, c->rope_sin,
+                    Typed<T>::p(k_cache_l), Typed<T>::p(v_cache_l), s);
+  if (evs) HIP_TRY(c, hipEventRecord(evs[1], s));
+  launch_build_rows(c->d_set_off, c->d_row_start, plan.m, pi.n_mem, n, c->d_row_pos, c->d_row_slot, s);
+  const T* x = Typed<T>::p(x_in);
+  if (!x) {
+    launch_embed_gather<T>(Typed<T>::p(c->embed), c->d_token_ids, c->d_row_pos, n, d.hidden, Typed<T>::p(c->xa), s);
+    x = Typed<T>::p(c->xa);
+  }
+  launch_rmsnorm<T>(x, Typed<T>::p(w.ln1), n, d.hidden, d.rms_eps, Typed<T>::p(c->hbuf), s);
+  GemmB b;
+  b.n_parts = 3;
+  b.ptr[0] = w.wq; b.ptr[1] = w.wk; b.ptr[2] = w.wv;
+  b.bias[0] = w.bq; b.bias[1] = w.bk; b.bias[2] = w.bv;
+  b.n_rows[0] = d.n_q_heads * d.head_dim;
+  b.n_rows[1] = b.n_rows[2] = d.n_kv_heads * d.head_dim;
+  const int n_qkv = b.n_rows[0] + 2 * b.n_rows[1];
+  if (c->mfma)
+    launch_gemm_mfma(reinterpret_cast<const bf16_t*>(c->hbuf), n, d.hidden, b, nullptr, n_qkv, EPI_STORE_F32, nullptr,
+                     c->qkv_raw, s);
+  else
+    launch_gemm_generic<T>(Typed<T>::p(c->hbuf), n, d.hidden, b, nullptr, n_qkv, EPI_STORE_F32, nullptr, c->qkv_raw, s);
+  launch_rope_scatter<T>(c->qkv_raw, Typed<T>::p(w.bq), Typed<T>::p(w.bk), Typed<T>::p(w.bv), c->d_row_pos, n,
+                         d.n_q_heads, d.n_kv_heads, d.head_dim, c->rope_cos, c->rope_sin, Typed<T>::p(c->q),
+                         Typed<T>::p(c->kc), Typed<T>::p(k_cache_l), Typed<T>::p(v_cache_l), s);
+  if (evs) HIP_TRY(c, hipEventRecord(evs[2], s));
+  if (c->mfma)
+    launch_attn_mfma(reinterpret_cast<const bf16_t*>(c->q), reinterpret_cast<const bf16_t*>(k_cache_l),
+                     reinterpret_cast<const bf16_t*>(v_cache_l), c->d_row_pos, n, pi.N, d.n_q_heads, d.n_kv_heads,
+                     reinterpret_cast<bf16_t*>(c->o), c->lse, s);
+  else
+    launch_attn_generic<T>(Typed<T>::p(c->q), Typed<T>::p(k_cache_l), Typed<T>::p(v_cache_l), c->d_row_pos, n,
+                           d.n_q_heads, d.n_kv_heads, d.head_dim, Typed<T>::p(c->o), c->lse, s);
+  if (evs) HIP_TRY(c, hipEventRecord(evs[3], s));
+  HIP_TRY(c, hipGetLastError());
+  return KEEP_OK;
+}
+
+// Output projection + residual, RMSNorm, SwiGLU FFN + residual on the compute stream.
+template <typename T>
+keep_status layer_back(keep_ctx* c, int layer, int n, const void* x_in, void* x_out, hipEvent_t* evs) {
+  const keep_model_desc& d = c->d;
+  const keep_layer_weights& w = c->w[layer];
+  hipStream_t s = c->s_comp;
+  const int qd = d.n_q_heads * d.head_dim;
+  GemmB bo{}; bo.n_parts = 1; bo.ptr[0] = w.wo; bo.n_rows[0] = d.hidden;
+  GemmB bg{}; bg.n_parts = 1; bg.ptr[0] = w.wgate; bg.n_rows[0] = d.ffn_dim;
+  GemmB bd{}; bd.n_parts = 1; bd.ptr[0] = w.wdown; bd.n_rows[0] = d.hidden;
+  if (c->mfma) {
+    auto B = [](const void* p) { return reinterpret_cast<const bf16_t*>(p); };
+    launch_gemm_mfma(B(c->o), n, qd, bo, nullptr, d.hidden, EPI_RESIDUAL_STORE, B(x_in), c->x1, s);
+    launch_rmsnorm<bf16_t>(B(c->x1), B(w.ln2), n, d.hidden, d.rms_eps, reinterpret_cast<bf16_t*>(c->hbuf), s);
+    launch_gemm_mfma(B(c->hbuf), n, d.hidden, bg, w.wup, d.ffn_dim, EPI_SWIGLU_STORE, nullptr, c->act, s);
+    launch_gemm_mfma(B(c->act), n, d.ffn_dim, bd, nullptr, d.hidden, EPI_RESIDUAL_STORE, B(c->x1), x_out, s);
+  } else {
+    launch_gemm_generic<T>(Typed<T>::p(c->o), n, qd, bo, nullptr, d.hidden, EPI_RESIDUAL_STORE, Typed<T>::p(x_in),
+                           c->x1, s);
+    launch_rmsnorm<T>(Typed<T>::p(c->x1), Typed<T>::p(w.ln2), n, d.hidden, d.rms_eps, Typed<T>::p(c->hbuf), s);
+    launch_gemm_generic<T>(Typed<T>::p(c->hbuf), n, d.hidden, bg, w.wup, d.ffn_dim, EPI_SWIGLU_STORE, nullptr, c->act,
+                           s);
+    launch_gemm_generic<T>(Typed<T>::p(c->act), n, d.ffn_dim, bd, nullptr, d.hidden, EPI_RESIDUAL_STORE,
+                           Typed<T>::p(c->x1), x_out, s);
+  }
+  if (evs) HIP_TRY(c, hipEventRecord(evs[4], s));
+  HIP_TRY(c, hipGetLastError());
+  return KEEP_OK;
+}
+
+// Score matrix of the layer whose q / k / lse are in the workspace, on stream s.
+template <typename T>
+keep_status score_matrix(keep_ctx* c, const LayerPlan& plan, hipStream_t s) {
+  const keep_model_desc& d = c->d;
+  if (plan.m == 0) return KEEP_OK;
+  if (c->mfma) {
+    launch_score_mfma(reinterpret_cast<const bf16_t*>(c->q), reinterpret_cast<const bf16_t*>(c->kc), c->lse,
+                      plan.row_start.data(), c->d_row_start, plan.m, plan.n_rows, d.n_q_heads, d.n_kv_heads,
+                      c->score_scratch, c->S, s);
+  } else {
+    launch_score_rows_generic<T>(Typed<T>::p(c->q), Typed<T>::p(c->kc), c->lse, c->d_row_start, plan.m, plan.n_rows,
+                                 d.n_q_heads, d.n_kv_heads, d.head_dim, c->score_scratch, s);
+    launch_score_finish(c->score_scratch, c->d_row_start, plan.m, d.n_q_heads, c->S, s);
+  }
+  HIP_TRY(c, hipGetLastError());
+  return KEEP_OK;
+}
+
+// Decide the next set.  Returns immediately (no device work) when the budget takes all
+// or none of the candidates.  Otherwise enqueues the selection on stream s and the
+// read-back of its result into c->h_sel_out; the caller waits and calls finish_select.
+enum SelectKind { SEL_ALL, SEL_NONE, SEL_DEVICE };
+SelectKind classify_budget(const PromptInfo& pi, const keep_prompt* p, const int32_t* groups, int m, float ratio,
+                           int mode, int* k_count, int* tok_budget) {
+  *k_count = budget_count(ratio, pi.G, m);
+  *tok_budget = budget_tokens(ratio, pi.n_mem);
+  if (m == 0) return SEL_NONE;
+  if (mode == KEEP_BUDGET_GROUP_COUNT) {
+    if (*k_count >= m) return SEL_ALL;
+    if (*k_count == 0) return SEL_NONE;
+  } else {
+    int64_t tot = 0;
+    for (int i = 0; i < m; ++i) tot += p->group_len[groups[i]];
+    if (*tok_budget >= tot) return SEL_ALL;
+    if (*tok_budget <= 0) return SEL_NONE;
+  }
+  return SEL_DEVICE;
+}
+
+keep_status enqueue_select(keep_ctx* c, int m, int k_count, int tok_budget, int mode, int hops, hipStream_t s) {
+  launch_select(c->S, m, c->d_cand_len, k_count, tok_budget, mode, hops, c->sel_work, c->sel_iwork, c->sel_out, s);
+  HIP_TRY(c, hipGetLastError());
+  HIP_TRY(c, hipMemcpyAsync(c->h_sel_out, c->sel_out, (size_t)(m + 2) * 4, hipMemcpyDeviceToHost, s));
+  return KEEP_OK;
+}
+
+template <typename F>
+keep_status by_dtype(keep_ctx* c, F&& f) {
+  return c->d.dtype == KEEP_BF16 ? f((bf16_t*)nullptr) : f((float*)nullptr);
+}
+
+}  // namespace
+
+// ===========================================================================
+// public functions
+// ===========================================================================
+extern "C" {
+
+const char* keep_last_error(const keep_ctx* ctx) { return ctx ? ctx->err.c_str() : g_init_error.c_str(); }
+
+uint64_t keep_workspace_bytes(const keep_model_desc* desc) {
+  const char* why;
+  if (check_desc(desc, &why) != KEEP_OK) return 0;
+  return workspace_bytes(desc);
+}
+
+keep_status keep_destroy(keep_ctx* c) {
+  if (!c) return KEEP_OK;
+  (void)hipStreamSynchronize(c->s_comp);
+  (void)hipStreamSynchronize(c->s_eval);
+  (void)hipStreamSynchronize(c->s_copy);
+  for (void* p : c->allocs) (void)hipFree(p);
+  for (Staging& st : c->stage) {
+    if (st.set_off) (void)hipHostFree(st.set_off);
+    if (st.row_start) (void)hipHostFree(st.row_start);
+    if (st.gather_src) (void)hipHostFree(st.gather_src);
+    if (st.gather_dst) (void)hipHostFree(st.gather_dst);
+    if (st.cand_len) (void)hipHostFree(st.cand_len);
+    if (st.segs) (void)hipHostFree(st.segs);
+    if (st.done) (void)hipEventDestroy(st.done);
+  }
+  if (c->h_sel_out) (void)hipHostFree(c->h_sel_out);
+  if (c->h_S) (void)hipHostFree(c->h_S);
+  if (c->h_token_ids) (void)hipHostFree(c->h_token_ids);
+  for (hipEvent_t e : c->ev) (void)hipEventDestroy(e);
+  for (hipEvent_t e : c->ev_chunk) (void)hipEventDestroy(e);
+  for (hipEvent_t e : {c->ev_attn, c->ev_eval, c->ev_load, c->ev_comp, c->ev_tok})
+    if (e) (void)hipEventDestroy(e);
+  delete c;
+  return KEEP_OK;
+}
+
+keep_status keep_init(const keep_model_desc* desc, const keep_layer_weights* layers, const void* embed_table,
+                      void* stream_compute, void* stream_eval, void* stream_copy, keep_ctx** out) {
+  if (!out) return fail(nullptr, KEEP_ERR_INVALID_ARG, "out is NULL");
+  *out = nullptr;
+  const char* why;
+  keep_status st = check_desc(desc, &why);
+  if (st != KEEP_OK) return fail(nullptr, st, "%s", why);
+  if (!layers || !embed_table) return fail(nullptr, KEEP_ERR_INVALID_ARG, "layers or embed_table is NULL");
+  for (int l = 0; l < desc->n_layers; ++l) {
+    const keep_layer_weights& w = layers[l];
+    if (!w.ln1 || !w.wq || !w.wk || !w.wv || !w.wo || !w.ln2 || !w.wgate || !w.wup || !w.wdown)
+      return fail(nullptr, KEEP_ERR_INVALID_ARG, "a weight pointer of layer %d is NULL", l);
+  }
+  int n_dev = 0;
+  hipError_t he = hipGetDeviceCount(&n_dev);
+  if (he != hipSuccess || n_dev < 1)
+    return fail(nullptr, KEEP_ERR_HIP, "no HIP device available (%s)", hipGetErrorString(he));
+
+  keep_ctx* c = new keep_ctx();
+  c->d = *desc;
+  c->w.assign(layers, layers + desc->n_layers);
+  c->embed = embed_table;
+  c->s_comp = (hipStream_t)stream_compute;
+  c->s_eval = (hipStream_t)stream_eval;
+  c->s_copy = (hipStream_t)stream_copy;
+  c->mfma = wants_mfma(desc);
+  c->esz = desc->dtype == KEEP_BF16 ? 2 : 4;
+  const Sizes z = sizes_of(desc);
+  const size_t half = (size_t)desc->head_dim / 2;
+
+#define TRY_INIT(expr)                       \
+  do {                                       \
+    keep_status s__ = (expr);                \
+    if (s__ != KEEP_OK) {                    \
+      g_init_error = c->err;                 \
+      keep_destroy(c);                       \
+      return s__;                            \
+    }                                        \
+  } while (0)
+
+  TRY_INIT(dev_alloc(c, &c->rope_cos, z.M * half * sizeof(float)));
+  TRY_INIT(dev_alloc(c, &c->rope_sin, z.M * half * sizeof(float)));
+  TRY_INIT(dev_alloc(c, &c->d_token_ids, z.M * 4));
+  TRY_INIT(dev_alloc(c, &c->d_row_pos, z.M * 4));
+  TRY_INIT(dev_alloc(c, &c->d_row_slot, z.M * 4));
+  TRY_INIT(dev_alloc(c, &c->d_set_off, (z.G + 2) * 4));
+  TRY_INIT(dev_alloc(c, &c->d_row_start, (z.G + 2) * 4));
+  TRY_INIT(dev_alloc(c, &c->d_gather_src, (z.G + 2) * 4));
+  TRY_INIT(dev_alloc(c, &c->d_cand_len, (z.G + 2) * 4));
+  TRY_INIT(dev_alloc(c, &c->d_segs, z.G * sizeof(RealignSeg)));
+  TRY_INIT(dev_alloc(c, &c->xa, z.M * z.d * z.esz));
+  TRY_INIT(dev_alloc(c, &c->xb, z.M * z.d * z.esz));
+  TRY_INIT(dev_alloc(c, &c->hbuf, z.M * z.d * z.esz));
+  TRY_INIT(dev_alloc(c, &c->x1, z.M * z.d * z.esz));
+  TRY_INIT(dev_alloc(c, &c->q, z.M * z.qd * z.esz));
+  TRY_INIT(dev_alloc(c, &c->o, z.M * z.qd * z.esz));
+  TRY_INIT(dev_alloc(c, &c->kc, z.M * z.kvd * z.esz));
+  TRY_INIT(dev_alloc(c, &c->act, z.M * z.F * z.esz));
+  TRY_INIT(dev_alloc(c, &c->qkv_raw, z.M * (z.qd + 2 * z.kvd) * sizeof(float)));
+  TRY_INIT(dev_alloc(c, &c->lse, z.M * (size_t)desc->n_q_heads * sizeof(float)));
+  TRY_INIT(dev_alloc(c, &c->score_scratch, score_scratch_bytes(desc)));
+  TRY_INIT(dev_alloc(c, &c->S, (z.G + 1) * z.G * sizeof(float)));
+  TRY_INIT(dev_alloc(c, &c->sel_work, ((z.G + 1) * z.G + 2 * z.G) * sizeof(float)));
+  TRY_INIT(dev_alloc(c, &c->sel_iwork, 4 * z.G * 4));
+  TRY_INIT(dev_alloc(c, &c->sel_out, (z.G + 2) * 4));
+
+  // RoPE table: angle = position * theta^(-2j/head_dim), evaluated in double, stored fp32
+  {
+    std::vector<float> hc(z.M * half), hs(z.M * half);
+    std::vector<double> freq(half);
+    for (size_t j = 0; j < half; ++j) freq[j] = pow((double)desc->rope_theta, -2.0 * (double)j / (double)desc->head_dim);
+    for (size_t p = 0; p < z.M; ++p)
+      for (size_t j = 0; j < half; ++j) {
+        const double a = (double)p * freq[j];
+        hc[p * half + j] = (float)cos(a);
+        hs[p * half + j] = (float)sin(a);
+      }
+    auto up = [&](float* dst, const std::vector<float>& src) -> keep_status {
+      HIP_TRY(c, hipMemcpy(dst, src.data(), src.size() * sizeof(float), hipMemcpyHostToDevice));
+      return KEEP_OK;
+    };
+    TRY_INIT(up(c->rope_cos, hc));
+    TRY_INIT(up(c->rope_sin, hs));
+  }
+
+  c->stage.resize(desc->n_layers);
+  for (Staging& sg : c->stage) {
+    sg = Staging{};
+    TRY_INIT(pin_alloc(c, &sg.set_off, (z.G + 2) * 4));
+    TRY_INIT(pin_alloc(c, &sg.row_start, (z.G + 2) * 4));
+    TRY_INIT(pin_alloc(c, &sg.gather_src, (z.G + 2) * 4));
+    TRY_INIT(pin_alloc(c, &sg.gather_dst, (z.G + 2) * 4));
+    TRY_INIT(pin_alloc(c, &sg.cand_len, (z.G + 2) * 4));
+    TRY_INIT(pin_alloc(c, &sg.segs, z.G * sizeof(RealignSeg)));
+    auto mk = [&]() -> keep_status {
+      HIP_TRY(c, hipEventCreateWithFlags(&sg.done, hipEventDisableTiming));
+      return KEEP_OK;
+    };
+    TRY_INIT(mk());
+  }
+  TRY_INIT(pin_alloc(c, &c->h_sel_out, (z.G + 2) * 4));
+  TRY_INIT(pin_alloc(c, &c->h_S, (z.G + 1) * z.G * sizeof(float)));
+  TRY_INIT(pin_alloc(c, &c->h_token_ids, z.M * 4));
+  auto mk_events = [&]() -> keep_status {
+    c->ev.resize((size_t)desc->n_layers * EV_PER_LAYER);
+    for (hipEvent_t& e : c->ev) HIP_TRY(c, hipEventCreate(&e));
+    HIP_TRY(c, hipEventCreateWithFlags(&c->ev_attn, hipEventDisableTiming));
+    HIP_TRY(c, hipEventCreateWithFlags(&c->ev_eval, hipEventDisableTiming));
+    HIP_TRY(c, hipEventCreateWithFlags(&c->ev_load, hipEventDisableTiming));
+    HIP_TRY(c, hipEventCreateWithFlags(&c->ev_comp, hipEventDisableTiming));
+    HIP_TRY(c, hipEventCreateWithFlags(&c->ev_tok, hipEventDisableTiming));
+    c->ev_chunk.resize(64);
+    for (hipEvent_t& e : c->ev_chunk) HIP_TRY(c, hipEventCreateWithFlags(&e, hipEventDisableTiming));
+    return KEEP_OK;
+  };
+  TRY_INIT(mk_events());
+#undef TRY_INIT
+  *out = c;
+  return KEEP_OK;
+}
+
+// ---------------------------------------------------------------------------
+// host->device copies of group blocks (Section 5, load_memory)
+// ---------------------------------------------------------------------------
+namespace {
+struct Loader {
+  keep_ctx* c;
+  const keep_prompt* p;
+  const PromptInfo* pi;
+  char* k_cache;
+  char* v_cache;
+  size_t row_bytes, layer_bytes;
+  std::vector<uint8_t> loaded;  // [L * G]
+  size_t inflight_head = 0, inflight_tail = 0;  // ring of chunk events
+  std::vector<size_t> chunk_bytes;
+  size_t inflight = 0;
+  uint64_t bytes_total = 0;
+
+  keep_status copy_group(int layer, int g) {
+    const size_t idx = (size_t)layer * pi->G + g;
+    if (loaded[idx]) return KEEP_OK;
+    const size_t nb = (size_t)p->group_len[g] * row_bytes;
+    const size_t dst = (size_t)layer * layer_bytes + (size_t)pi->off[g] * row_bytes;
+    if (!p->k_blocks[idx] || !p->v_blocks[idx])
+      return fail(c, KEEP_ERR_INVALID_ARG, "k_blocks/v_blocks entry of layer %d group %d is NULL", layer, g);
+    HIP_TRY(c, hipMemcpyAsync(k_cache + dst, p->k_blocks[idx], nb, hipMemcpyHostToDevice, c->s_copy));
+    HIP_TRY(c, hipMemcpyAsync(v_cache + dst, p->v_blocks[idx], nb, hipMemcpyHostToDevice, c->s_copy));
+    loaded[idx] = 1;
+    bytes_total += 2 * nb;
+    // flow control bookkeeping
+    const size_t slot = inflight_head % c->ev_chunk.size();
+    if (inflight_head - inflight_tail == c->ev_chunk.size()) {  // ring full: retire the oldest
+      HIP_TRY(c, hipEventSynchronize(c->ev_chunk[inflight_tail % c->ev_chunk.size()]));
+      inflight -= chunk_bytes[inflight_tail % c->ev_chunk.size()];
+      ++inflight_tail;
+    }
+    HIP_TRY(c, hipEventRecord(c->ev_chunk[slot], c->s_copy));
+    chunk_bytes[slot] = 2 * nb;
+    inflight += 2 * nb;
+    ++inflight_head;
+    return KEEP_OK;
+  }
+  void retire() {
+    while (inflight_tail < inflight_head) {
+      const size_t slot = inflight_tail % c->ev_chunk.size();
+      if (hipEventQuery(c->ev_chunk[slot]) != hipSuccess) break;
+      inflight -= chunk_bytes[slot];
+      ++inflight_tail;
+    }
+  }
+  // every group of `layer` outside `set` (ascending) that is not loaded yet
+  keep_status copy_outside(int layer, const std::vector<int32_t>& set) {
+    size_t gi = 0;
+    for (int g = 0; g < pi->G; ++g) {
+      if (gi < set.size() && set[gi] == g) {
+        ++gi;
+        continue;
+      }
+      keep_status st = copy_group(layer, g);
+      if (st != KEEP_OK) return st;
+    }
+    return KEEP_OK;
+  }
+};
+}  // namespace
+
+keep_status keep_recompute_layer(keep_ctx* c, const keep_prompt* p, int32_t layer, const int32_t* groups, int32_t n_sel,
+                                 const void* x_in, void* x_out, void* k_cache_l, void* v_cache_l) {
+  if (!c) return KEEP_ERR_INVALID_ARG;
+  if (layer < 0 || layer >= c->d.n_layers) return fail(c, KEEP_ERR_INVALID_ARG, "layer %d out of range", layer);
+  if (!x_out || !k_cache_l || !v_cache_l) return fail(c, KEEP_ERR_INVALID_ARG, "x_out / k_cache_l / v_cache_l is NULL");
+  PromptInfo pi;
+  keep_status st = check_prompt(c, p, &pi, true);
+  if (st != KEEP_OK) return st;
+  st = check_set(c, pi, groups, n_sel);
+  if (st != KEEP_OK) return st;
+  c->last_layer = -1;
+
+  const bool host_kv = p->kv_location == KEEP_KV_PINNED_HOST;
+  if (host_kv) {
+    // bring the blocks of the groups outside the set to their place in the cache
+    // (the caller gave this layer's slice of the cache: layer stride 0)
+    Loader ld{c, p, &pi, (char*)k_cache_l, (char*)v_cache_l, (size_t)c->d.n_kv_heads * c->d.head_dim * c->esz, 0};
+    ld.loaded.assign((size_t)c->d.n_layers * pi.G, 0);
+    ld.chunk_bytes.assign(c->ev_chunk.size(), 0);
+    std::vector<int32_t> set(groups, groups + n_sel);
+    st = ld.copy_outside(layer, set);
+    if (st != KEEP_OK) return st;
+    HIP_TRY(c, hipEventRecord(c->ev_load, c->s_copy));
+    HIP_TRY(c, hipStreamWaitEvent(c->s_comp, c->ev_load, 0));
+  }
+  st = upload_tokens(c, p, pi);
+  if (st != KEEP_OK) return st;
+  LayerPlan plan;
+  st = stage_layer(c, p, pi, layer, groups, n_sel, k_cache_l, v_cache_l, host_kv, &plan);
+  if (st != KEEP_OK) return st;
+  st = by_dtype(c, [&](auto* tag) {
+    using T = std::remove_pointer_t<decltype(tag)>;
+    keep_status s2 = layer_front<T>(c, pi, layer, plan, x_in, k_cache_l, v_cache_l, nullptr);
+    if (s2 != KEEP_OK) return s2;
+    return layer_back<T>(c, layer, plan.n_rows, x_in ? x_in : c->xa, x_out, nullptr);
+  });
+  if (st != KEEP_OK) return st;
+  Staging& sg = c->stage[layer];
+  HIP_TRY(c, hipEventRecord(sg.done, c->s_comp));
+  sg.used = true;
+  c->last_layer = layer;
+  c->last_groups.assign(groups, groups + n_sel);
+  c->last_row_start = plan.row_start;
+  c->last_n_rows = plan.n_rows;
+  return KEEP_OK;
+}
+
+keep_status keep_score_groups(keep_ctx* c, const keep_prompt* p, int32_t layer, const int32_t* groups, int32_t n_sel,
+                              float ratio_next, int32_t hops, int32_t budget_mode, float* S_out, int32_t* next_groups,
+                              int32_t* n_next, int32_t* hops_run) {
+  if (!c) return KEEP_ERR_INVALID_ARG;
+  if (!n_next || !hops_run || (n_sel > 0 && !next_groups))
+    return fail(c, KEEP_ERR_INVALID_ARG, "next_groups / n_next / hops_run is NULL");
+  if (budget_mode != KEEP_BUDGET_GROUP_COUNT && budget_mode != KEEP_BUDGET_TOKENS)
+    return fail(c, KEEP_ERR_INVALID_ARG, "unknown budget_mode");
+  if (!(ratio_next >= 0.f && ratio_next <= 1.f)) return fail(c, KEEP_ERR_INVALID_ARG, "ratio_next outside [0, 1]");
+  if (hops < 1) return fail(c, KEEP_ERR_INVALID_ARG, "hops must be at least 1");
+  PromptInfo pi;
+  keep_status st = check_prompt(c, p, &pi, false);
+  if (st != KEEP_OK) return st;
+  st = check_set(c, pi, groups, n_sel);
+  if (st != KEEP_OK) return st;
+  if (c->last_layer != layer || (int)c->last_groups.size() != n_sel ||
+      !std::equal(c->last_groups.begin(), c->last_groups.end(), groups))
+    return fail(c, KEEP_ERR_STATE, "keep_score_groups(layer %d) needs keep_recompute_layer of that layer and set first",
+                layer);
+  LayerPlan plan;
+  plan.m = n_sel;
+  plan.n_rows = c->last_n_rows;
+  plan.row_start = c->last_row_start;
+  // attention of the layer must be complete before its scores are read (second
+  // dependency of the paper's pipeline): order the eval stream after the compute stream
+  HIP_TRY(c, hipEventRecord(c->ev_attn, c->s_comp));
+  HIP_TRY(c, hipStreamWaitEvent(c->s_eval, c->ev_attn, 0));
+  st = by_dtype(c, [&](auto* tag) {
+    using T = std::remove_pointer_t<decltype(tag)>;
+    return score_matrix<T>(c, plan, c->s_eval);
+  });
+  if (st != KEEP_OK) return st;
+  if (S_out && n_sel > 0)
+    HIP_TRY(c, hipMemcpyAsync(c->h_S, c->S, (size_t)(n_sel + 1) * n_sel * sizeof(float), hipMemcpyDeviceToHost,
+                              c->s_eval));
+  int k_count, tok;
+  const SelectKind kind = classify_budget(pi, p, groups, n_sel, ratio_next, budget_mode, &k_count, &tok);
+  if (kind == SEL_DEVICE) {
+    st = enqueue_select(c, n_sel, k_count, tok, budget_mode, hops, c->s_eval);
+    if (st != KEEP_OK) return st;
+  }
+  HIP_TRY(c, hipStreamSynchronize(c->s_eval));
+  if (S_out && n_sel > 0) memcpy(S_out, c->h_S, (size_t)(n_sel + 1) * n_sel * sizeof(float));
+  if (kind == SEL_ALL) {
+    for (int i = 0; i < n_sel; ++i) next_groups[i] = groups[i];
+    *n_next = n_sel;
+    *hops_run = 0;
+  } else if (kind == SEL_NONE) {
+    *n_next = 0;
+    *hops_run = 0;
+  } else {
+    *n_next = c->h_sel_out[0];
+    *hops_run = c->h_sel_out[1];
+    for (int i = 0; i < *n_next; ++i) next_groups[i] = groups[c->h_sel_out[2 + i]];
+  }
+  return KEEP_OK;
+}
+
+keep_status keep_select_groups(keep_ctx* c, const float* S, const int32_t* groups, int32_t n_sel,
+                               const int32_t* group_len, int32_t n_groups_total, float ratio_next, int32_t hops,
+                               int32_t budget_mode, int32_t* next_groups, int32_t* n_next, int32_t* hops_run) {
+  if (!c) return KEEP_ERR_INVALID_ARG;
+  if (!n_next || !hops_run || !group_len || (n_sel > 0 && (!next_groups || !S || !groups)))
+    return fail(c, KEEP_ERR_INVALID_ARG, "a pointer argument is NULL");
+  if (budget_mode != KEEP_BUDGET_GROUP_COUNT && budget_mode != KEEP_BUDGET_TOKENS)
+    return fail(c, KEEP_ERR_INVALID_ARG, "unknown budget_mode");
+  if (!(ratio_next >= 0.f && ratio_next <= 1.f)) return fail(c, KEEP_ERR_INVALID_ARG, "ratio_next outside [0, 1]");
+  if (hops < 1) return fail(c, KEEP_ERR_INVALID_ARG, "hops must be at least 1");
+  if (n_groups_total < 0 || n_groups_total > c->d.max_groups)
+    return fail(c, KEEP_ERR_WORKSPACE, "n_groups_total %d above max_groups %d", n_groups_total, c->d.max_groups);
+  if (n_sel < 0 || n_sel > n_groups_total) return fail(c, KEEP_ERR_INVALID_ARG, "n_sel outside [0, n_groups_total]");
+  PromptInfo pi;
+  pi.G = n_groups_total;
+  int64_t tot = 0;
+  for (int g = 0; g < n_groups_total; ++g) {
+    if (group_len[g] < 1) return fail(c, KEEP_ERR_INVALID_ARG, "group_len[%d] must be >= 1", g);
+    tot += group_len[g];
+  }
+  pi.n_mem = (int)tot;
+  for (int i = 0; i < n_sel; ++i) {
+    if (groups[i] < 0 || groups[i] >= n_groups_total) return fail(c, KEEP_ERR_INVALID_ARG, "groups[%d] out of range", i);
+    if (i && groups[i] <= groups[i - 1]) return fail(c, KEEP_ERR_INVALID_ARG, "groups must be strictly ascending");
+  }
+  keep_prompt fake{};
+  fake.group_len = group_len;
+  int k_count, tok;
+  const SelectKind kind = classify_budget(pi, &fake, groups, n_sel, ratio_next, budget_mode, &k_count, &tok);
+  if (kind == SEL_ALL) {
+    for (int i = 0; i < n_sel; ++i) next_groups[i] = groups[i];
+    *n_next = n_sel;
+    *hops_run = 0;
+    return KEEP_OK;
+  }
+  if (kind == SEL_NONE) {
+    *n_next = 0;
+    *hops_run = 0;
+    return KEEP_OK;
+  }
+  c->last_layer = -1;  // the score workspace is overwritten
+  hipStream_t s = c->s_eval;
+  memcpy(c->h_S, S, (size_t)(n_sel + 1) * n_sel * sizeof(float));
+  HIP_TRY(c, hipMemcpyAsync(c->S, c->h_S, (size_t)(n_sel + 1) * n_sel * sizeof(float), hipMemcpyHostToDevice, s));
+  std::vector<int32_t> cl(n_sel);
+  for (int i = 0; i < n_sel; ++i) cl[i] = group_len[groups[i]];
+  HIP_TRY(c, hipMemcpyAsync(c->d_cand_len, cl.data(), (size_t)n_sel * 4, hipMemcpyHostToDevice, s));
+  HIP_TRY(c, hipStreamSynchronize(s));  // cl is pageable host memory
+  keep_status st = enqueue_select(c, n_sel, k_count, tok, budget_mode, hops, s);
+  if (st != KEEP_OK) return st;
+  HIP_TRY(c, hipStreamSynchronize(s));
+  *n_next = c->h_sel_out[0];
+  *hops_run = c->h_sel_out[1];
+  for (int i = 0; i < *n_next; ++i) next_groups[i] = groups[c->h_sel_out[2 + i]];
+  return KEEP_OK;
+}
+
+keep_status keep_prefill(keep_ctx* c, const keep_prompt* p, const float* ratios, int32_t hops, int32_t budget_mode,
+                         int32_t load_mode, void* k_cache, void* v_cache, void* x_final, int32_t* sel_groups,
+                         int32_t* sel_counts, keep_report* report) {
+  if (!c) return KEEP_ERR_INVALID_ARG;
+  const auto t_begin = std::chrono::steady_clock::now();
+  const keep_model_desc& d = c->d;
+  const int L = d.n_layers;
+  if (!ratios || !k_cache || !v_cache || !x_final)
+    return fail(c, KEEP_ERR_INVALID_ARG, "ratios / k_cache / v_cache / x_final is NULL");
+  if (budget_mode != KEEP_BUDGET_GROUP_COUNT && budget_mode != KEEP_BUDGET_TOKENS)
+    return fail(c, KEEP_ERR_INVALID_ARG, "unknown budget_mode");
+  if (load_mode < KEEP_LOAD_SERIAL || load_mode > KEEP_LOAD_LAYER_BALANCED)
+    return fail(c, KEEP_ERR_INVALID_ARG, "unknown load_mode");
+  if (hops < 1) return fail(c, KEEP_ERR_INVALID_ARG, "hops must be at least 1");
+  if (ratios[0] != 0.f && ratios[0] != 1.f)
+    return fail(c, KEEP_ERR_INVALID_ARG, "ratios[0] must be 1 (recompute all memories at the first layer) or 0");
+  for (int l = 1; l < L; ++l) {
+    if (!(ratios[l] >= 0.f && ratios[l] <= 1.f)) return fail(c, KEEP_ERR_INVALID_ARG, "ratios[%d] outside [0, 1]", l);
+    if (ratios[l] > ratios[l - 1])
+      return fail(c, KEEP_ERR_INVALID_ARG, "ratios must not increase (ratios[%d] > ratios[%d])", l, l - 1);
+  }
+  PromptInfo pi;
+  keep_status st = check_prompt(c, p, &pi, true);
+  if (st != KEEP_OK) return st;
+  c->last_layer = -1;
+  const bool host_kv = p->kv_location == KEEP_KV_PINNED_HOST;
+  const size_t row_bytes = (size_t)d.n_kv_heads * d.head_dim * c->esz;
+  const size_t layer_bytes = (size_t)pi.N * row_bytes;
+  if (report) {
+    memset(report, 0, sizeof *report);
+    report->n_layers = L;
+    report->used_mfma = c->mfma ? 1 : 0;
+  }
+
+  Loader ld{c, p, &pi, (char*)k_cache, (char*)v_cache, row_bytes, layer_bytes};
+  if (host_kv) {
+    ld.loaded.assign((size_t)L * pi.G, 0);
+    ld.chunk_bytes.assign(c->ev_chunk.size(), 0);
+  }
+
+  st = upload_tokens(c, p, pi);
+  if (st != KEEP_OK) return st;
+
+  std::vector<int32_t> cur;
+  if (ratios[0] == 1.f)
+    for (int g = 0; g < pi.G; ++g) cur.push_back(g);
+  std::vector<int32_t> nxt;
+  void* x_cur = c->xa;   // hidden rows of the current layer (compact)
+  void* x_nxt = c->xb;
+  bool x_from_embed = true;
+  LayerPlan plan;
+  int preload_layer = 2, preload_group = 0;  // cursor of the layer-balanced pre-loader
+
+  if (host_kv) {  // what layer 0 needs must be there before it starts
+    st = ld.copy_outside(0, cur);
+    if (st != KEEP_OK) return st;
+    HIP_TRY(c, hipEventRecord(c->ev_load, c->s_copy));
+    HIP_TRY(c, hipStreamWaitEvent(c->s_comp, c->ev_load, 0));
+    if (report) report->bytes_loaded[0] = ld.bytes_total;
+  }
+
+  for (int l = 0; l < L; ++l) {
+    hipEvent_t* evs = report ? &c->ev[(size_t)l * EV_PER_LAYER] : nullptr;
+    char* kl = (char*)k_cache + (size_t)l * layer_bytes;
+    char* vl = (char*)v_cache + (size_t)l * layer_bytes;
+    const int m = (int)cur.size();
+    if (sel_counts) sel_counts[l] = m;
+    if (sel_groups)
+      for (int i = 0; i < m; ++i) sel_groups[(size_t)l * pi.G + i] = cur[i];
+    st = stage_layer(c, p, pi, l, cur.data(), m, kl, vl, host_kv, &plan);
+    if (st != KEEP_OK) return st;
+    if (report) {
+      report->rows[l] = plan.n_rows;
+      report->set_size[l] = m;
+    }
+    const bool last = l + 1 == L;
+    const void* x_in = x_from_embed ? nullptr : x_cur;
+    // ---- compute stream: everything up to attention
+    st = by_dtype(c, [&](auto* tag) {
+      using T = std::remove_pointer_t<decltype(tag)>;
+      return layer_front<T>(c, pi, l, plan, x_in, kl, vl, evs);
+    });
+    if (st != KEEP_OK) return st;
+    // ---- eval stream: scores + selection beside the FFN
+    int k_count = 0, tok = 0;
+    SelectKind kind = SEL_NONE;
+    if (!last) {
+      kind = classify_budget(pi, p, cur.data(), m, ratios[l + 1], budget_mode, &k_count, &tok);
+      if (kind == SEL_DEVICE) {
+        HIP_TRY(c, hipEventRecord(c->ev_attn, c->s_comp));
+        HIP_TRY(c, hipStreamWaitEvent(c->s_eval, c->ev_attn, 0));
+        if (evs) HIP_TRY(c, hipEventRecord(evs[5], c->s_eval));
+        st = by_dtype(c, [&](auto* tag) {
+          using T = std::remove_pointer_t<decltype(tag)>;
+          return score_matrix<T>(c, plan, c->s_eval);
+        });
+        if (st != KEEP_OK) return st;
+        st = enqueue_select(c, m, k_count, tok, budget_mode, hops, c->s_eval);
+        if (st != KEEP_OK) return st;
+        if (evs) HIP_TRY(c, hipEventRecord(evs[6], c->s_eval));
+        HIP_TRY(c, hipEventRecord(c->ev_eval, c->s_eval));
+      }
+    }
+    // ---- compute stream: output projection + FFN
+    st = by_dtype(c, [&](auto* tag) {
+      using T = std::remove_pointer_t<decltype(tag)>;
+      return layer_back<T>(c, l, plan.n_rows, x_cur, x_nxt, evs);
+    });
+    if (st != KEEP_OK) return st;
+    {
+      Staging& sg = c->stage[l];
+      HIP_TRY(c, hipEventRecord(sg.done, c->s_comp));
+      sg.used = true;
+    }
+    if (last) break;
+
+    // ---- loading for the layers ahead, while this layer computes
+    const uint64_t bytes_before = ld.bytes_total;
+    if (host_kv && load_mode != KEEP_LOAD_SERIAL) {
+      // groups outside the current set can never come back: their blocks of layer l+1 are needed for sure
+      st = ld.copy_outside(l + 1, cur);
+      if (st != KEEP_OK) return st;
+    }
+    // ---- wait for the selection (host needs the set to size the next layer's launches)
+    if (kind == SEL_DEVICE) {
+      if (host_kv && load_mode == KEEP_LOAD_LAYER_BALANCED) {
+        // idle loader: pre-load later layers for the groups that are out for good
+        preload_layer = l + 2;
+        preload_group = 0;
+        while (hipEventQuery(c->ev_eval) == hipErrorNotReady) {
+          ld.retire();
+          if (preload_layer >= L || ld.inflight >= PRELOAD_INFLIGHT_CAP) continue;
+          // next group outside `cur` at the cursor
+          bool issued = false;
+          while (preload_layer < L && !issued) {
+            while (preload_group < pi.G && std::binary_search(cur.begin(), cur.end(), preload_group)) ++preload_group;
+            if (preload_group >= pi.G) {
+              ++preload_layer;
+              preload_group = 0;
+              continue;
+            }
+            if (!ld.loaded[(size_t)preload_layer * pi.G + preload_group]) {
+              st = ld.copy_group(preload_layer, preload_group);
+              if (st != KEEP_OK) return st;
+              issued = true;
+            }
+            ++preload_group;
+          }
+        }
+      }
+      HIP_TRY(c, hipEventSynchronize(c->ev_eval));
+      nxt.clear();
+      const int nn = c->h_sel_out[0];
+      for (int i = 0; i < nn; ++i) nxt.push_back(cur[c->h_sel_out[2 + i]]);
+      if (report) report->hops_run[l] = c->h_sel_out[1];
+    } else if (kind == SEL_ALL) {
+      nxt = cur;
+    } else {
+      nxt.clear();
+    }
+    // ---- finish loading layer l+1: the groups that just left the set
+    if (host_kv) {
+      if (load_mode == KEEP_LOAD_SERIAL) {
+        // load strictly after this layer's compute
+        HIP_TRY(c, hipEventRecord(c->ev_comp, c->s_comp));
+        HIP_TRY(c, hipStreamWaitEvent(c->s_copy, c->ev_comp, 0));
+      }
+      st = ld.copy_outside(l + 1, nxt);
+      if (st != KEEP_OK) return st;
+      HIP_TRY(c, hipEventRecord(c->ev_load, c->s_copy));
+      HIP_TRY(c, hipStreamWaitEvent(c->s_comp, c->ev_load, 0));
+      if (report) report->bytes_loaded[l + 1] = ld.bytes_total - bytes_before;
+    }
+    // ---- hidden rows of the next set: gather from this layer's output
+    if (nxt.size() == cur.size()) {
+      std::swap(x_cur, x_nxt);  // same rows: this layer's output is the next layer's input
+      x_from_embed = false;
+    } else {
+      // source compact start of each kept block inside the current layout
+      Staging& sg = c->stage[l];  // gather_src of slot l is free: uploaded now, consumed by this gather
+      std::vector<int32_t> dst_start(nxt.size() + 2);
+      int acc = 0;
+      size_t ci = 0;
+      for (size_t i = 0; i < nxt.size(); ++i) {
+        while (cur[ci] != nxt[i]) ++ci;
+        sg.gather_src[i] = plan.row_start[ci];
+        dst_start[i] = acc;
+        acc += p->group_len[nxt[i]];
+      }
+      sg.gather_src[nxt.size()] = plan.row_start[m];
+      dst_start[nxt.size()] = acc;
+      acc += pi.Lq;
+      dst_start[nxt.size() + 1] = acc;
+      // the destination starts are exactly the next layer's row_start: upload them into
+      // d_row_start after the FFN that still reads nothing from it (stream order)
+      memcpy(sg.gather_dst, dst_start.data(), dst_start.size() * 4);
+      HIP_TRY(c, hipMemcpyAsync(c->d_gather_src, sg.gather_src, (nxt.size() + 1) * 4, hipMemcpyHostToDevice, c->s_comp));
+      HIP_TRY(c, hipMemcpyAsync(c->d_row_start, sg.gather_dst, dst_start.size() * 4, hipMemcpyHostToDevice, c->s_comp));
+      void* x_out_buf = x_nxt;  // this layer's output
+      void* x_dst = x_cur;      // this layer's input buffer is free once the layer is done
+      st = by_dtype(c, [&](auto* tag) {
+        using T = std::remove_pointer_t<decltype(tag)>;
+        launch_rows_gather<T>(Typed<T>::p(x_out_buf), c->d_gather_src, c->d_row_start, (int)nxt.size() + 1, acc,
+                              d.hidden, Typed<T>::p(x_dst), c->s_comp);
+        return KEEP_OK;
+      });
+      HIP_TRY(c, hipGetLastError());
+      HIP_TRY(c, hipEventRecord(sg.done, c->s_comp));
+      x_cur = x_dst;
+      x_from_embed = false;
+    }
+    cur.swap(nxt);
+  }
+  // final hidden rows of the instruction
+  {
+    const char* src = (const char*)x_nxt + (size_t)(plan.n_rows - pi.Lq) * d.hidden * c->esz;
+    HIP_TRY(c, hipMemcpyAsync(x_final, src, (size_t)pi.Lq * d.hidden * c->esz, hipMemcpyDeviceToDevice, c->s_comp));
+  }
+  HIP_TRY(c, hipStreamSynchronize(c->s_copy));
+  HIP_TRY(c, hipStreamSynchronize(c->s_eval));
+  HIP_TRY(c, hipStreamSynchronize(c->s_comp));
+  if (report) {
+    report->ms_total = std::chrono::duration<float, std::milli>(std::chrono::steady_clock::now() - t_begin).count();
+    for (int l = 0; l < L; ++l) {
+      hipEvent_t* e = &c->ev[(size_t)l * EV_PER_LAYER];
+      (void)hipEventElapsedTime(&report->ms_realign[l], e[0], e[1]);
+      (void)hipEventElapsedTime(&report->ms_qkv[l], e[1], e[2]);
+      (void)hipEventElapsedTime(&report->ms_attn[l], e[2], e[3]);
+      (void)hipEventElapsedTime(&report->ms_ffn[l], e[3], e[4]);
+      if (report->hops_run[l] > 0) (void)hipEventElapsedTime(&report->ms_score[l], e[5], e[6]);
+    }
+  }
+  return KEEP_OK;
+}
+
+}  // extern "C"

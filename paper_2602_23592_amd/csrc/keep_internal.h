@@ -1,0 +1,132 @@
+// Internal declarations shared by the HIP translation units of libkeep_hip.so.
+// Not part of the public ABI (that is include/keep.h).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "keep.h"
+
+namespace keep {
+
+// ---------------------------------------------------------------------------
+// storage types
+// ---------------------------------------------------------------------------
+struct bf16_t {
+  uint16_t bits;
+};
+
+__host__ __device__ inline float bf16_bits_to_f32(uint16_t b) {
+  union {
+    uint32_t u;
+    float f;
+  } c;
+  c.u = (uint32_t)b << 16;
+  return c.f;
+}
+// round-to-nearest-even; NaN stays NaN (quiet)
+__host__ __device__ inline uint16_t f32_to_bf16_bits(float f) {
+  union {
+    uint32_t u;
+    float f;
+  } c;
+  c.f = f;
+  if ((c.u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((c.u >> 16) | 0x0040u);
+  c.u += 0x7fffu + ((c.u >> 16) & 1u);
+  return (uint16_t)(c.u >> 16);
+}
+
+__device__ inline float ldf(const float* p) { return *p; }
+__device__ inline float ldf(const bf16_t* p) { return bf16_bits_to_f32(p->bits); }
+__device__ inline void stf(float* p, float v) { *p = v; }
+__device__ inline void stf(bf16_t* p, float v) { p->bits = f32_to_bf16_bits(v); }
+
+// ---------------------------------------------------------------------------
+// per-layer row bookkeeping that lives on the device
+// ---------------------------------------------------------------------------
+// Segment of rows to re-align: one memory group outside the relevant set.
+struct RealignSeg {
+  const void* k_src;  // [len, Hkv, dh], rotated at local positions
+  const void* v_src;
+  int32_t dst_off;    // first global position
+  int32_t len;
+  int32_t row_start;  // prefix sum of len over the segments of this launch
+  int32_t pad;
+};
+
+enum GemmEpilogue {
+  EPI_STORE_F32 = 0,      // C (fp32) = acc
+  EPI_RESIDUAL_STORE = 1, // C (T) = residual (T) + acc
+  EPI_SWIGLU_STORE = 2,   // C (T) = silu(acc_gate) * acc_up   (B = gate rows, B2 = up rows)
+};
+
+// One B operand made of up to three row blocks stacked along N (Wq | Wk | Wv).
+struct GemmB {
+  const void* ptr[3];
+  const void* bias[3];  // unused by the GEMM itself
+  int32_t n_rows[3];
+  int32_t n_parts;
+};
+
+// ---------------------------------------------------------------------------
+// launchers (every one validates nothing: api.hip checks shapes first)
+// ---------------------------------------------------------------------------
+// rows bookkeeping: row_pos[n_rows], row_slot[n_rows] from the set
+void launch_build_rows(const int32_t* d_set_off /*[m] global offset of each selected group*/,
+                       const int32_t* d_row_start /*[m+2] compact prefix, last two: instr start, n_rows*/,
+                       int32_t m, int32_t instr_off, int32_t n_rows, int32_t* d_row_pos, int32_t* d_row_slot,
+                       hipStream_t s);
+
+template <typename T>
+void launch_embed_gather(const T* embed, const int32_t* d_token_ids /*[N]*/, const int32_t* d_row_pos,
+                         int32_t n_rows, int32_t hidden, T* x, hipStream_t s);
+template <typename T>
+void launch_rows_gather(const T* x_src, const int32_t* d_src_start /*[m'+1]*/, const int32_t* d_dst_start /*[m'+2]*/,
+                        int32_t n_blocks_sel, int32_t n_rows_dst, int32_t hidden, T* x_dst, hipStream_t s);
+template <typename T>
+void launch_realign(const RealignSeg* d_segs, int32_t n_segs, int32_t total_rows, int32_t n_kv_heads,
+                    int32_t head_dim, const float* rope_cos, const float* rope_sin, T* k_cache, T* v_cache,
+                    hipStream_t s);
+template <typename T>
+void launch_rmsnorm(const T* x, const T* w, int32_t n_rows, int32_t hidden, float eps, T* y, hipStream_t s);
+// bias + RoPE + write q/k/v compact + scatter K,V into the cache rows row_pos[]
+template <typename T>
+void launch_rope_scatter(const float* qkv_raw /*[n_rows, q_dim + 2 kv_dim]*/, const T* bq, const T* bk, const T* bv,
+                         const int32_t* d_row_pos, int32_t n_rows, int32_t n_q_heads, int32_t n_kv_heads,
+                         int32_t head_dim, const float* rope_cos, const float* rope_sin, T* q, T* k_compact,
+                         T* k_cache, T* v_cache, hipStream_t s);
+
+// generic (scalar FMA) kernels
+template <typename T>
+void launch_gemm_generic(const T* A, int32_t M, int32_t K, const GemmB& B, const void* B2, int32_t N, int epilogue,
+                         const T* residual, void* C, hipStream_t s);
+template <typename T>
+void launch_attn_generic(const T* q, const T* k_cache, const T* v_cache, const int32_t* d_row_pos, int32_t n_rows,
+                         int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, T* o, float* lse, hipStream_t s);
+// rowmass[t, j] = sum over heads and over the keys s of candidate j (compact rows
+// key_start[j]..key_start[j+1]) with s <= t of exp(q_t.k_s/sqrt(dh) - lse[t,h])
+template <typename T>
+void launch_score_rows_generic(const T* q, const T* k_compact, const float* lse, const int32_t* d_row_start,
+                               int32_t m, int32_t n_rows, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                               float* rowmass /*[n_rows, m]*/, hipStream_t s);
+// S[(m+1), m] from rowmass: sum rows of each block in order, divide by heads*len_a*len_b, zero diagonal
+void launch_score_finish(const float* rowmass, const int32_t* d_row_start, int32_t m, int32_t n_q_heads, float* S,
+                         hipStream_t s);
+
+// MFMA (bf16, head_dim 128) kernels
+void launch_gemm_mfma(const bf16_t* A, int32_t M, int32_t K, const GemmB& B, const void* B2, int32_t N, int epilogue,
+                      const bf16_t* residual, void* C, hipStream_t s);
+void launch_attn_mfma(const bf16_t* q, const bf16_t* k_cache, const bf16_t* v_cache, const int32_t* d_row_pos,
+                      int32_t n_rows, int32_t n_total, int32_t n_q_heads, int32_t n_kv_heads, bf16_t* o, float* lse,
+                      hipStream_t s);
+// colmass[tile, s] for row tiles of 32 compact rows that never straddle a block boundary
+size_t score_mfma_scratch_bytes(int32_t max_rows, int32_t max_groups);
+void launch_score_mfma(const bf16_t* q, const bf16_t* k_compact, const float* lse, const int32_t* h_row_start,
+                       const int32_t* d_row_start, int32_t m, int32_t n_rows, int32_t n_q_heads, int32_t n_kv_heads,
+                       void* scratch, float* S, hipStream_t s);
+
+// multi-hop selection on the device; d_out: [0] = n_next, [1] = hops_run, [2..] = slots kept (ascending)
+void launch_select(const float* S, int32_t m, const int32_t* d_cand_len, int32_t k_count, int32_t token_budget,
+                   int32_t mode, int32_t hops, float* d_work /*[(m+1)*m + 2m]*/, int32_t* d_iwork /*[4m]*/,
+                   int32_t* d_out /*[m+2]*/, hipStream_t s);
+
+}  // namespace keep

@@ -1,0 +1,111 @@
+// Multi-hop importance propagation and selection (Section 4.2 of the paper:
+// initialisation, importance propagation, convergence check) on the device.
+//
+// One workgroup.  Every floating-point value that decides the selection is
+// computed in binary32 in a fixed order (sums over candidates in ascending
+// order, one division each), so the result is a pure function of S.
+#include "keep_internal.h"
+
+namespace keep {
+
+constexpr int SEL_THREADS = 1024;
+
+// rank every candidate by (importance descending, index ascending) and mark the
+// ones taken: the first k of the order (count mode) or a walk of the order that
+// takes a memory iff it still fits the token budget (token mode).
+__device__ void take(const float* imp, int m, const int32_t* cand_len, int k_count, int token_budget, int mode,
+                     int32_t* order, int32_t* taken) {
+  for (int b = threadIdx.x; b < m; b += SEL_THREADS) {
+    const float v = imp[b];
+    int rank = 0;
+    for (int c = 0; c < m; ++c) {
+      const float u = imp[c];
+      rank += (u > v) || (u == v && c < b);
+    }
+    order[rank] = b;
+    if (mode == KEEP_BUDGET_GROUP_COUNT) taken[b] = rank < k_count;
+  }
+  __syncthreads();
+  if (mode != KEEP_BUDGET_GROUP_COUNT) {
+    if (threadIdx.x == 0) {
+      int used = 0;
+      for (int i = 0; i < m; ++i) {
+        const int b = order[i];
+        const int fits = used + cand_len[b] <= token_budget;
+        taken[b] = fits;
+        if (fits) used += cand_len[b];
+      }
+    }
+    __syncthreads();
+  }
+}
+
+__global__ void __launch_bounds__(SEL_THREADS)
+    k_select(const float* __restrict__ S, int m, const int32_t* __restrict__ cand_len, int k_count, int token_budget,
+             int mode, int hops, float* __restrict__ work, int32_t* __restrict__ iwork, int32_t* __restrict__ out) {
+  float* norm = work;                     // [(m+1) * m]
+  float* imp = work + (size_t)(m + 1) * m;  // [m]
+  float* imp2 = imp + m;                  // [m]
+  int32_t* order = iwork;                 // [m]
+  int32_t* rel = iwork + m;               // [m]
+  int32_t* rel2 = iwork + 2 * m;          // [m]
+  __shared__ int s_same, s_cnt;
+
+  // row-normalise over the candidate targets
+  for (int a = threadIdx.x; a <= m; a += SEL_THREADS) {
+    const float* row = S + (size_t)a * m;
+    float total = 0.f;
+    for (int b = 0; b < m; ++b) total = total + row[b];
+    for (int b = 0; b < m; ++b) norm[(size_t)a * m + b] = total > 0.f ? row[b] / total : 0.f;
+  }
+  __syncthreads();
+  for (int b = threadIdx.x; b < m; b += SEL_THREADS) imp[b] = norm[(size_t)m * m + b];
+  __syncthreads();
+  take(imp, m, cand_len, k_count, token_budget, mode, order, rel);
+  int runs = 1;
+  const int max_runs = hops > 1 ? hops : 1;
+  while (runs < max_runs) {
+    if (threadIdx.x == 0) {
+      int c = 0;
+      for (int a = 0; a < m; ++a) c += rel[a];
+      s_cnt = c;
+    }
+    __syncthreads();
+    const float denom = (float)(1 + s_cnt);
+    for (int b = threadIdx.x; b < m; b += SEL_THREADS) {
+      float acc = norm[(size_t)m * m + b];
+      for (int a = 0; a < m; ++a)
+        if (rel[a]) acc = acc + norm[(size_t)a * m + b];
+      imp2[b] = acc / denom;
+    }
+    __syncthreads();
+    take(imp2, m, cand_len, k_count, token_budget, mode, order, rel2);
+    ++runs;
+    if (threadIdx.x == 0) {
+      int same = 1;
+      for (int a = 0; a < m; ++a) same &= (rel[a] == rel2[a]);
+      s_same = same;
+    }
+    __syncthreads();
+    const int same = s_same;
+    __syncthreads();
+    if (same) break;
+    for (int b = threadIdx.x; b < m; b += SEL_THREADS) rel[b] = rel2[b];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    int n = 0;
+    for (int a = 0; a < m; ++a)
+      if (rel[a]) out[2 + n++] = a;
+    out[0] = n;
+    out[1] = runs;
+  }
+}
+
+void launch_select(const float* S, int32_t m, const int32_t* d_cand_len, int32_t k_count, int32_t token_budget,
+                   int32_t mode, int32_t hops, float* d_work, int32_t* d_iwork, int32_t* d_out, hipStream_t s) {
+  hipLaunchKernelGGL(k_select, dim3(1), dim3(SEL_THREADS), 0, s, S, m, d_cand_len, k_count, token_budget, mode, hops,
+                     d_work, d_iwork, d_out);
+}
+
+}  // namespace keep
