@@ -141,6 +141,9 @@ keep_status keep_destroy(keep_ctx* ctx);
 /* HOST string owned by the library, valid until the next call on that context. */
 const char* keep_last_error(const keep_ctx* ctx);
 
+/* 1 if this context runs the MFMA kernel family, 0 if the generic one, -1 if ctx is NULL. */
+int32_t keep_uses_mfma(const keep_ctx* ctx);
+
 /* Device bytes a context for this description allocates (0 if desc is invalid). */
 uint64_t keep_workspace_bytes(const keep_model_desc* desc);
 

@@ -23,7 +23,7 @@ KEEP_LOAD_SERIAL, KEEP_LOAD_NEXT_LAYER, KEEP_LOAD_LAYER_BALANCED = 0, 1, 2
 KEEP_KERNELS_AUTO, KEEP_KERNELS_GENERIC = 0, 1
 KEEP_REPORT_MAX_LAYERS = 128
 
-EXPORTED = ("keep_init", "keep_destroy", "keep_last_error", "keep_workspace_bytes", "keep_recompute_layer",
+EXPORTED = ("keep_init", "keep_destroy", "keep_last_error", "keep_uses_mfma", "keep_workspace_bytes", "keep_recompute_layer",
             "keep_score_groups", "keep_select_groups", "keep_prefill")
 
 
@@ -81,6 +81,8 @@ def load_library() -> C.CDLL:
     lib.keep_destroy.argtypes = [vp]
     lib.keep_last_error.restype = C.c_char_p
     lib.keep_last_error.argtypes = [vp]
+    lib.keep_uses_mfma.restype = i32
+    lib.keep_uses_mfma.argtypes = [vp]
     lib.keep_workspace_bytes.restype = C.c_uint64
     lib.keep_workspace_bytes.argtypes = [C.POINTER(ModelDesc)]
     lib.keep_recompute_layer.restype = i32
@@ -190,6 +192,10 @@ class KeepContext:
             self.close()
         except Exception:
             pass
+
+    @property
+    def uses_mfma(self) -> bool:
+        return self.lib.keep_uses_mfma(self.handle) == 1
 
     def _check(self, st: int):
         if st != KEEP_OK:

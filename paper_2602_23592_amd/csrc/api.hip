@@ -32,6 +32,7 @@ struct Staging {  // pinned host mirror of the small per-layer device arrays
   int32_t* gather_src;
   int32_t* gather_dst;
   int32_t* cand_len;
+  int32_t* score_tiles;  // row-tile table of the MFMA score pass
   RealignSeg* segs;
   hipEvent_t done;
   bool used;
@@ -145,7 +146,7 @@ keep_status check_desc(const keep_model_desc* d, const char** why) {
 }
 
 bool wants_mfma(const keep_model_desc* d) {
-  return false && d->kernel_path == KEEP_KERNELS_AUTO && d->dtype == KEEP_BF16 && d->head_dim == 128 && d->hidden % 64 == 0 &&
+  return d->kernel_path == KEEP_KERNELS_AUTO && d->dtype == KEEP_BF16 && d->head_dim == 128 && d->hidden % 64 == 0 &&
          d->ffn_dim % 64 == 0;
 }
 
@@ -425,13 +426,13 @@ keep_status layer_back(keep_ctx* c, int layer, int n, const void* x_in, void* x_
 
 // Score matrix of the layer whose q / k / lse are in the workspace, on stream s.
 template <typename T>
-keep_status score_matrix(keep_ctx* c, const LayerPlan& plan, hipStream_t s) {
+keep_status score_matrix(keep_ctx* c, int layer, const LayerPlan& plan, hipStream_t s) {
   const keep_model_desc& d = c->d;
   if (plan.m == 0) return KEEP_OK;
   if (c->mfma) {
     launch_score_mfma(reinterpret_cast<const bf16_t*>(c->q), reinterpret_cast<const bf16_t*>(c->kc), c->lse,
                       plan.row_start.data(), c->d_row_start, plan.m, plan.n_rows, d.n_q_heads, d.n_kv_heads,
-                      c->score_scratch, c->S, s);
+                      c->stage[layer].score_tiles, c->score_scratch, d.max_tokens, std::max(1, d.max_groups), c->S, s);
   } else {
     launch_score_rows_generic<T>(Typed<T>::p(c->q), Typed<T>::p(c->kc), c->lse, c->d_row_start, plan.m, plan.n_rows,
                                  d.n_q_heads, d.n_kv_heads, d.head_dim, c->score_scratch, s);
@@ -483,6 +484,8 @@ extern "C" {
 
 const char* keep_last_error(const keep_ctx* ctx) { return ctx ? ctx->err.c_str() : g_init_error.c_str(); }
 
+int32_t keep_uses_mfma(const keep_ctx* ctx) { return ctx ? (ctx->mfma ? 1 : 0) : -1; }
+
 uint64_t keep_workspace_bytes(const keep_model_desc* desc) {
   const char* why;
   if (check_desc(desc, &why) != KEEP_OK) return 0;
@@ -501,6 +504,7 @@ keep_status keep_destroy(keep_ctx* c) {
     if (st.gather_src) (void)hipHostFree(st.gather_src);
     if (st.gather_dst) (void)hipHostFree(st.gather_dst);
     if (st.cand_len) (void)hipHostFree(st.cand_len);
+    if (st.score_tiles) (void)hipHostFree(st.score_tiles);
     if (st.segs) (void)hipHostFree(st.segs);
     if (st.done) (void)hipEventDestroy(st.done);
   }
@@ -608,6 +612,7 @@ keep_status keep_init(const keep_model_desc* desc, const keep_layer_weights* lay
     TRY_INIT(pin_alloc(c, &sg.gather_src, (z.G + 2) * 4));
     TRY_INIT(pin_alloc(c, &sg.gather_dst, (z.G + 2) * 4));
     TRY_INIT(pin_alloc(c, &sg.cand_len, (z.G + 2) * 4));
+    if (c->mfma) TRY_INIT(pin_alloc(c, &sg.score_tiles, score_mfma_stage_ints((int32_t)z.M, (int32_t)z.G) * 4));
     TRY_INIT(pin_alloc(c, &sg.segs, z.G * sizeof(RealignSeg)));
     auto mk = [&]() -> keep_status {
       HIP_TRY(c, hipEventCreateWithFlags(&sg.done, hipEventDisableTiming));
@@ -777,7 +782,7 @@ keep_status keep_score_groups(keep_ctx* c, const keep_prompt* p, int32_t layer, 
   HIP_TRY(c, hipStreamWaitEvent(c->s_eval, c->ev_attn, 0));
   st = by_dtype(c, [&](auto* tag) {
     using T = std::remove_pointer_t<decltype(tag)>;
-    return score_matrix<T>(c, plan, c->s_eval);
+    return score_matrix<T>(c, layer, plan, c->s_eval);
   });
   if (st != KEEP_OK) return st;
   if (S_out && n_sel > 0)
@@ -957,7 +962,7 @@ keep_status keep_prefill(keep_ctx* c, const keep_prompt* p, const float* ratios,
         if (evs) HIP_TRY(c, hipEventRecord(evs[5], c->s_eval));
         st = by_dtype(c, [&](auto* tag) {
           using T = std::remove_pointer_t<decltype(tag)>;
-          return score_matrix<T>(c, plan, c->s_eval);
+          return score_matrix<T>(c, l, plan, c->s_eval);
         });
         if (st != KEEP_OK) return st;
         st = enqueue_select(c, m, k_count, tok, budget_mode, hops, c->s_eval);

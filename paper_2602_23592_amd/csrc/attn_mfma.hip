@@ -1,0 +1,230 @@
+// Sparse-row causal attention over the joined cache on the gfx950 matrix cores
+// (bf16 operands, fp32 accumulate, head_dim 128, grouped-query heads).
+//
+// Each of the n_rows recomputed rows attends to cache rows 0..p (its global position),
+// whatever lies between the recomputed rows.  A workgroup owns one KV head and 128
+// "query rows" (a recomputed row paired with one of the query heads of that KV head);
+// each of its 4 waves owns 32 of them.  K/V tiles of 64 keys are staged through LDS
+// (two buffers, next tile prefetched into registers).
+//
+// The scores are computed transposed, S^T = K . Q^T, so that a lane owns one query row
+// (column l % 32 of the 32x32 MFMA result) and the keys sit in its registers: row max and
+// row sum are register reductions plus one exchange between the two lane halves.  Those
+// registers are, as they stand, the B operand of O^T = V^T . P^T; V^T's A operand comes
+// straight from the row-major V tile through the LDS transpose read (ds_read_b64_tr_b16).
+// The softmax statistics therefore stay per lane from the first tile to the final divide.
+#include "keep_internal.h"
+
+namespace keep {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+constexpr int DH = 128;
+constexpr int KT_KEYS = 64;
+constexpr int KSTRIDE = 136;  // bf16 elements per K row in LDS (272 B: 16-byte reads of 16 rows hit 64 banks)
+constexpr int VSTRIDE = 144;  // bf16 elements per V row in LDS (288 B: 4 rows x 32 B of a transpose read are disjoint)
+constexpr int ATT_BUF = KT_KEYS * KSTRIDE + KT_KEYS * VSTRIDE;  // elements per buffer
+
+typedef __attribute__((ext_vector_type(8))) short s16x8;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
+__device__ __forceinline__ bf16x8 cat4(s16x4 a, s16x4 b) {
+  return __builtin_bit_cast(bf16x8, __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7));
+}
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
+  return (uint32_t)f32_to_bf16_bits(a) | ((uint32_t)f32_to_bf16_bits(b) << 16);
+}
+
+__global__ void __launch_bounds__(256, 2)
+    k_attn_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k_cache, const bf16_t* __restrict__ v_cache,
+                const int32_t* __restrict__ row_pos, int n_rows, int n_total, int n_q_heads, int n_kv_heads, int n_tiles,
+                float scale_log2e, bf16_t* __restrict__ o, float* __restrict__ lse) {
+  extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int g = lane >> 5, lq = lane & 31;
+  const int rep = n_q_heads / n_kv_heads;
+  const int hk = blockIdx.x % n_kv_heads;
+  const int tile = n_tiles - 1 - blockIdx.x / n_kv_heads;  // longest key ranges first
+  const int QR = n_rows * rep;
+  const int kv_dim = n_kv_heads * DH;
+
+  // this lane's query row
+  const int x = tile * 128 + wave * 32 + lq;
+  const bool valid = x < QR;
+  const int r = valid ? x / rep : 0;
+  const int head = hk * rep + (valid ? x % rep : 0);
+  const int pos = valid ? row_pos[r] : 0;
+  int wmax = pos, wmin = pos;
+#pragma unroll
+  for (int off = 16; off > 0; off >>= 1) {
+    wmax = max(wmax, __shfl_xor(wmax, off, 64));
+    wmin = min(wmin, __shfl_xor(wmin, off, 64));
+  }
+  const int x_last = min(QR, (tile + 1) * 128) - 1;
+  const int bmax = row_pos[x_last / rep];
+  const int n_kt = bmax / KT_KEYS + 1;
+
+  // Q^T operand: 8 k-steps of 16 head-dim elements
+  bf16x8 qf[8];
+  {
+    const bf16_t* qp = q + ((size_t)r * n_q_heads + head) * DH + g * 8;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 16);
+  }
+
+  f32x16 oacc[4];
+#pragma unroll
+  for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) oacc[nt][e] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;
+
+  // global -> LDS staging: 4 chunks of K and 4 of V per thread per tile
+  const int ld_row = tid >> 4, ld_c = tid & 15;  // rows ld_row + 16 i
+  uint4 kreg0, kreg1, kreg2, kreg3, vreg0, vreg1, vreg2, vreg3;
+#define ATT_GLOAD1(KR, VR, I, KT)                                                        \
+  {                                                                                      \
+    const int key_ = min((KT) * KT_KEYS + ld_row + 16 * (I), n_total - 1);               \
+    const size_t off_ = ((size_t)key_ * n_kv_heads + hk) * DH + ld_c * 8;                \
+    KR = *reinterpret_cast<const uint4*>(k_cache + off_);                                \
+    VR = *reinterpret_cast<const uint4*>(v_cache + off_);                                \
+  }
+#define ATT_GLOAD(KT) \
+  ATT_GLOAD1(kreg0, vreg0, 0, KT) ATT_GLOAD1(kreg1, vreg1, 1, KT) ATT_GLOAD1(kreg2, vreg2, 2, KT) ATT_GLOAD1(kreg3, vreg3, 3, KT)
+#define ATT_SSTORE1(KR, VR, I, BUFI)                                                                      \
+  {                                                                                                       \
+    uint16_t* sk_ = smem + (BUFI) * ATT_BUF;                                                              \
+    *reinterpret_cast<uint4*>(sk_ + (ld_row + 16 * (I)) * KSTRIDE + ld_c * 8) = KR;                       \
+    *reinterpret_cast<uint4*>(sk_ + KT_KEYS * KSTRIDE + (ld_row + 16 * (I)) * VSTRIDE + ld_c * 8) = VR;   \
+  }
+#define ATT_SSTORE(BUFI) \
+  ATT_SSTORE1(kreg0, vreg0, 0, BUFI) ATT_SSTORE1(kreg1, vreg1, 1, BUFI) ATT_SSTORE1(kreg2, vreg2, 2, BUFI) ATT_SSTORE1(kreg3, vreg3, 3, BUFI)
+  ATT_GLOAD(0)
+  ATT_SSTORE(0)
+  __syncthreads();
+
+  for (int kt = 0; kt < n_kt; ++kt) {
+    const int cur = kt & 1;
+    const int k0 = kt * KT_KEYS;
+    if (kt + 1 < n_kt) { ATT_GLOAD(kt + 1) }
+    if (k0 <= wmax) {
+      const uint16_t* sk = smem + cur * ATT_BUF;
+      const uint16_t* sv = sk + KT_KEYS * KSTRIDE;
+      // ---- S^T = K . Q^T for the two 32-key halves of the tile
+      f32x16 sacc[2];
+#pragma unroll
+      for (int st = 0; st < 2; ++st) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) sacc[st][e] = 0.f;
+        const uint16_t* krow = sk + (st * 32 + lq) * KSTRIDE + g * 8;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+          const bf16x8 kf = *reinterpret_cast<const bf16x8*>(krow + ks * 16);
+          sacc[st] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], sacc[st], 0, 0, 0);
+        }
+      }
+      // ---- scale, causal mask, running max
+      const bool need_mask = k0 + KT_KEYS - 1 > wmin;
+      float tmax = -INFINITY;
+#pragma unroll
+      for (int st = 0; st < 2; ++st)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          float s = sacc[st][e] * scale_log2e;
+          if (need_mask) {
+            const int key = k0 + st * 32 + 8 * (e >> 2) + 4 * g + (e & 3);
+            s = key <= pos ? s : -INFINITY;
+          }
+          sacc[st][e] = s;
+          tmax = fmaxf(tmax, s);
+        }
+      tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+      const float m_new = fmaxf(m_run, tmax);
+      const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+      m_run = m_new;
+      float psum = 0.f;
+      uint32_t pk[2][8];
+#pragma unroll
+      for (int st = 0; st < 2; ++st)
+#pragma unroll
+        for (int e = 0; e < 16; e += 2) {
+          const float p0 = __builtin_amdgcn_exp2f(sacc[st][e] - m_new), p1 = __builtin_amdgcn_exp2f(sacc[st][e + 1] - m_new);
+          psum += p0 + p1;
+          pk[st][e >> 1] = pack_bf16x2(p0, p1);
+        }
+      l_run = l_run * alpha + psum;
+#pragma unroll
+      for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) oacc[nt][e] *= alpha;
+      // ---- O^T += V^T . P^T : 4 k-steps of 16 keys, 4 head-dim tiles of 32
+#pragma unroll
+      for (int st = 0; st < 2; ++st)
+#pragma unroll
+        for (int hh = 0; hh < 2; ++hh) {
+          u32x4 pu;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) pu[i] = pk[st][hh * 4 + i];
+          const bf16x8 pf = __builtin_bit_cast(bf16x8, pu);
+          // A operand slot (g, i) holds key base + 8*(i/4) + 4*g + i%4: the keys of P^T's registers
+          const int key_l = st * 32 + hh * 16 + 4 * g + ((lane & 15) >> 2);
+          const uint16_t* vbase = sv + key_l * VSTRIDE + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+#pragma unroll
+          for (int nt = 0; nt < 4; ++nt) {
+            typedef s16x4 __attribute__((address_space(3))) * lds_s16x4_ptr;
+            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(vbase + nt * 32));
+            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(vbase + nt * 32 + 8 * VSTRIDE));
+            oacc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cat4(lo, hi), pf, oacc[nt], 0, 0, 0);
+          }
+        }
+    }
+    if (kt + 1 < n_kt) { ATT_SSTORE(cur ^ 1) }
+    __syncthreads();
+  }
+
+  // ---- finish: combine the two lane halves' sums, normalise, write O and LSE
+  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  if (valid) {
+    const float inv = 1.0f / l_tot;
+    bf16_t* op = o + ((size_t)r * n_q_heads + head) * DH;
+#pragma unroll
+    for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+      for (int e = 0; e < 16; e += 4) {
+        const int d = nt * 32 + 8 * (e >> 2) + 4 * g;
+        uint2 u;
+        u.x = pack_bf16x2(oacc[nt][e] * inv, oacc[nt][e + 1] * inv);
+        u.y = pack_bf16x2(oacc[nt][e + 2] * inv, oacc[nt][e + 3] * inv);
+        *reinterpret_cast<uint2*>(op + d) = u;
+      }
+    if (g == 0) lse[(size_t)r * n_q_heads + head] = 0.6931471805599453f * (m_run + log2f(l_tot));
+  }
+}
+#undef ATT_GLOAD
+#undef ATT_GLOAD1
+#undef ATT_SSTORE
+#undef ATT_SSTORE1
+
+void launch_attn_mfma(const bf16_t* q, const bf16_t* k_cache, const bf16_t* v_cache, const int32_t* d_row_pos,
+                      int32_t n_rows, int32_t n_total, int32_t n_q_heads, int32_t n_kv_heads, bf16_t* o, float* lse,
+                      hipStream_t s) {
+  if (n_rows <= 0) return;
+  const int rep = n_q_heads / n_kv_heads;
+  const int n_tiles = (n_rows * rep + 127) / 128;
+  const size_t sh = (size_t)2 * ATT_BUF * sizeof(uint16_t);
+  static bool attr_set = false;
+  if (!attr_set) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_attn_mfma), hipFuncAttributeMaxDynamicSharedMemorySize,
+                              (int)sh);
+    attr_set = true;
+  }
+  const float scale_log2e = 1.4426950408889634f / sqrtf((float)DH);
+  hipLaunchKernelGGL(k_attn_mfma, dim3(n_tiles * n_kv_heads), dim3(256), sh, s, q, k_cache, v_cache, d_row_pos, n_rows,
+                     n_total, n_q_heads, n_kv_heads, n_tiles, scale_log2e, o, lse);
+}
+
+}  // namespace keep

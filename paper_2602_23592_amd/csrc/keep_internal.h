@@ -118,11 +118,15 @@ void launch_gemm_mfma(const bf16_t* A, int32_t M, int32_t K, const GemmB& B, con
 void launch_attn_mfma(const bf16_t* q, const bf16_t* k_cache, const bf16_t* v_cache, const int32_t* d_row_pos,
                       int32_t n_rows, int32_t n_total, int32_t n_q_heads, int32_t n_kv_heads, bf16_t* o, float* lse,
                       hipStream_t s);
-// colmass[tile, s] for row tiles of 32 compact rows that never straddle a block boundary
+// group-score matrix S[(m+1), m] of the layer whose q / compact k / lse are given.
+// h_stage: pinned host ints (score_mfma_stage_ints of them), d_scratch: device bytes
+// (score_mfma_scratch_bytes), both sized with the same max_rows / max_groups.
 size_t score_mfma_scratch_bytes(int32_t max_rows, int32_t max_groups);
+size_t score_mfma_stage_ints(int32_t max_rows, int32_t max_groups);
 void launch_score_mfma(const bf16_t* q, const bf16_t* k_compact, const float* lse, const int32_t* h_row_start,
                        const int32_t* d_row_start, int32_t m, int32_t n_rows, int32_t n_q_heads, int32_t n_kv_heads,
-                       void* scratch, float* S, hipStream_t s);
+                       int32_t* h_stage, void* d_scratch, int32_t max_rows, int32_t max_groups, float* S,
+                       hipStream_t s);
 
 // multi-hop selection on the device; d_out: [0] = n_next, [1] = hops_run, [2..] = slots kept (ascending)
 void launch_select(const float* S, int32_t m, const int32_t* d_cand_len, int32_t k_count, int32_t token_budget,

@@ -32,10 +32,17 @@ __global__ void __launch_bounds__(256)
   const int bn = n0 + lrow;
   const T* brow = nullptr;
   if (bn < N) {
-    int p = 0;
-    if (B.n_parts > 1 && bn >= B.begin[1]) p = 1;
-    if (B.n_parts > 2 && bn >= B.begin[2]) p = 2;
-    brow = reinterpret_cast<const T*>(B.ptr[p]) + (size_t)(bn - B.begin[p]) * K;
+    const void* base = B.ptr[0];
+    int first = 0;
+    if (B.n_parts > 1 && bn >= B.begin[1]) {
+      base = B.ptr[1];
+      first = B.begin[1];
+    }
+    if (B.n_parts > 2 && bn >= B.begin[2]) {
+      base = B.ptr[2];
+      first = B.begin[2];
+    }
+    brow = reinterpret_cast<const T*>(base) + (size_t)(bn - first) * K;
   }
   const T* brow2 = (EPI == EPI_SWIGLU_STORE && bn < N) ? B2 + (size_t)bn * K : nullptr;
   const int am = m0 + lrow;

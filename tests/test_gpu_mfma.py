@@ -1,0 +1,96 @@
+"""GPU parity of the MFMA kernel family (bf16, head_dim 128) against the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+import keep_synth as ks
+from oracle import keep_oracle as ko
+from gpu_util import Problem, max_rel, to_np
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-2      # bf16 mode: max |a-b| / max |b| per tensor
+
+
+def _shape(n_layers, hidden, hq, hkv, ffn):
+    return ks.ModelShape(n_layers, hidden, hq, hkv, 128, ffn, 509, 1.0e6, 1e-6, "bf16")
+
+
+CASES = {
+    # name: (shape, group lengths, instruction length)
+    "rep4_ragged": (_shape(2, 512, 8, 2, 1024), [1, 31, 33, 64, 65, 200, 129], 37),
+    "rep5_multi_tile": (_shape(2, 640, 10, 2, 1280), [300, 257, 411, 128, 96, 350, 290, 333], 130),
+    "rep7_one_kv_head": (_shape(1, 896, 7, 1, 640), [70, 5, 190], 3),
+    "rep1_tiny_prompt": (_shape(1, 256, 2, 2, 256), [2], 1),
+}
+
+
+@pytest.mark.parametrize("case", list(CASES))
+def test_mfma_layer_teacher_forced(case):
+    shape, glen, lq = CASES[case]
+    pb = Problem(shape, glen, lq, seed=3, std=0.05, bias=True)
+    ctx, pr = pb.context(), pb.prompt()
+    assert ctx.uses_mfma
+    G = len(glen)
+    rng = np.random.default_rng(5)
+    sets = [list(range(G)), sorted(rng.choice(G, size=max(1, G // 2), replace=False).tolist()), []]
+    for layer, groups in zip([0, shape.n_layers - 1, shape.n_layers - 1], sets):
+        n_rows = pr.n_rows(groups)
+        x_t = ks.make_random_rows(n_rows, shape.hidden, shape.storage, seed=11 + layer)
+        x_np = ks.to_numpy_f64(x_t)
+        kh, vh = pb.oracle_joined_cache(layer)
+        xo_ref, lse_ref, S_ref = ko.selective_layer(pb.sh, pb.layers[layer], x_np, groups, glen, lq, kh, vh)
+        kc, vc = pb.empty_cache(1)
+        x_out = torch.empty_like(x_t, device="cuda")
+        ctx.recompute_layer(pr, layer, groups, x_t.cuda(), x_out, kc[0], vc[0])
+        nxt, runs, S = ctx.score_groups(pr, layer, groups, 0.5, 2)
+        torch.cuda.synchronize()
+        ek, ev, ex = max_rel(to_np(kc[0]), kh), max_rel(to_np(vc[0]), vh), max_rel(to_np(x_out), xo_ref)
+        print(case, layer, len(groups), "K %.2e V %.2e X %.2e" % (ek, ev, ex))
+        assert ek < TOL and ev < TOL and ex < TOL, (case, layer, groups)
+        if len(groups):
+            es = np.abs(S - S_ref).max() / S_ref.max()
+            print("   S %.2e" % es)
+            assert es < TOL
+            want, want_runs = ko.select_multihop(S, groups, glen, 0.5, 2)
+            assert nxt == want and runs == want_runs
+
+
+def test_mfma_matches_generic_family_on_device():
+    """Same bf16 problem through both kernel families: agreement well inside the bf16 budget."""
+    shape, glen, lq = CASES["rep5_multi_tile"]
+    pb = Problem(shape, glen, lq, seed=3, std=0.05, bias=True)
+    pr = pb.prompt()
+    outs = []
+    for path in (0, 1):
+        ctx = pb.context(kernel_path=path)
+        assert ctx.uses_mfma == (path == 0)
+        kc, vc = pb.empty_cache()
+        xf = torch.empty((lq, shape.hidden), dtype=torch.bfloat16, device="cuda")
+        forced = ks.ratio_schedule(0.4, shape.n_layers, "const")
+        sets, _ = ctx.prefill(pr, forced, 2, kc, vc, xf)
+        outs.append((sets, to_np(kc), to_np(vc), to_np(xf)))
+        ctx.close()
+    assert outs[0][0] == outs[1][0]
+    for i in (1, 2, 3):
+        assert max_rel(outs[0][i], outs[1][i]) < 1e-2
+
+
+def test_mfma_prefill_end_to_end_teacher_forced_sets():
+    """Whole prefill in bf16: the device's own selection, then the oracle teacher-forced to the same sets."""
+    shape, glen, lq = CASES["rep5_multi_tile"]
+    pb = Problem(shape, glen, lq, seed=4, std=0.05, bias=False)
+    ctx, pr = pb.context(), pb.prompt()
+    ratios = [1.0, 0.5]
+    kc, vc = pb.empty_cache()
+    xf = torch.empty((lq, shape.hidden), dtype=torch.bfloat16, device="cuda")
+    sets, rep = ctx.prefill(pr, ratios, 3, kc, vc, xf, want_report=True)
+    assert rep.used_mfma == 1
+    ref_free = ko.keep_prefill(pb.sh, pb.layers, pb.embed, pb.ids, glen, lq, pb.kb, pb.vb, ratios, 3)
+    overlap = len(set(sets[1]) & set(ref_free["sets"][1])) / max(1, len(ref_free["sets"][1]))
+    print("device sets", sets, "oracle sets", ref_free["sets"], "overlap", overlap)
+    ref = ko.keep_prefill(pb.sh, pb.layers, pb.embed, pb.ids, glen, lq, pb.kb, pb.vb, ratios, 3, forced_sets=sets)
+    for l in range(shape.n_layers):
+        assert max_rel(to_np(kc[l]), ref["k_hat"][l]) < TOL
+        assert max_rel(to_np(vc[l]), ref["v_hat"][l]) < TOL
+    assert max_rel(to_np(xf), ref["x_final"]) < TOL
+    assert overlap >= 0.75          # 4 of 8 groups kept: at most one near-tie may flip
