@@ -1,0 +1,277 @@
+"""Benchmark of the selective-KV-recompute prefill on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
+
+A step is one whole keep_prefill (every layer: re-alignment of cached groups, QKV of the
+recomputed rows, sparse-row attention over the joined cache, group scores + multi-hop
+selection, output projection and FFN) of one seeded synthetic prompt, with weights and
+group KV caches already resident in HBM.  Prints ONE JSON line: TTFT per step, prefill
+tokens/s, the roofline figures of the dominant kernel measured with HIP events on the
+stream the kernel runs on, and the CPU oracle timed on the host cores on a bounded sample.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="qwen14b_32k")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--schedule", default=None, help="ratio schedule: linear (default of the workload) or const")
+    ap.add_argument("--budget", default=None, help="groups or tokens (default: the workload's)")
+    ap.add_argument("--load-mode", type=int, default=2, help="0 serial, 1 next-layer, 2 layer-balanced")
+    ap.add_argument("--random-cache", action="store_true",
+                    help="random group caches instead of caches prefilled by the library (faster set-up)")
+    return ap.parse_args()
+
+
+def precompute_group_caches(ctx, w, glen, ids, torch):
+    """Group caches made by the library's own dense path on each group alone, at group-local
+    positions (a lone group recomputed at every layer is a dense prefill of that group)."""
+    from paper_2602_23592_amd import KeepPrompt
+    s = w.shape
+    L, n_mem = s.n_layers, int(np.sum(glen))
+    dt = torch.bfloat16 if s.storage == "bf16" else torch.float32
+    kb_all = torch.empty((L, n_mem, s.n_kv_heads, s.head_dim), dtype=dt, device="cuda")
+    vb_all = torch.empty_like(kb_all)
+    off = np.concatenate([[0], np.cumsum(glen)])
+    ones = [1.0] * L
+    scratch = {}
+    for g, n in enumerate(glen):
+        n = int(n)
+        if n not in scratch:
+            scratch[n] = (torch.empty((L, n + 1, s.n_kv_heads, s.head_dim), dtype=dt, device="cuda"),
+                          torch.empty((L, n + 1, s.n_kv_heads, s.head_dim), dtype=dt, device="cuda"),
+                          torch.empty((1, s.hidden), dtype=dt, device="cuda"))
+        kc, vc, xf = scratch[n]
+        tok = np.concatenate([ids[off[g]:off[g + 1]], ids[-1:]])
+        dummy = [[kc[l] for _ in range(1)] for l in range(L)]          # never read: the group is always in the set
+        pr = KeepPrompt([n], 1, tok, dummy, dummy, L)
+        ctx.prefill(pr, ones, 1, kc, vc, xf)
+        kb_all[:, off[g]:off[g + 1]] = kc[:, :n]
+        vb_all[:, off[g]:off[g + 1]] = vc[:, :n]
+    torch.cuda.synchronize()
+    return kb_all, vb_all
+
+
+def visible_keys(sets, glen, lq):
+    """sum over recomputed rows of (position + 1), per layer: the attention's key count."""
+    off = np.concatenate([[0], np.cumsum(glen)]).astype(np.int64)
+    n_mem = int(off[-1])
+    out = []
+    for st in sets:
+        tot = 0
+        for g in st:
+            a, b = int(off[g]), int(off[g + 1])
+            tot += (a + 1 + b) * (b - a) // 2
+        a, b = n_mem, n_mem + lq
+        tot += (a + 1 + b) * (b - a) // 2
+        out.append(tot)
+    return out
+
+
+def cpu_baseline(w, glen, rows_per_layer, n_tokens):
+    """The CPU oracle as it stands, timed on a bounded sample: one selective layer of this
+    workload (layer 1, seeded random set of the layer's budget, random-draw caches and
+    hidden rows), K/V refresh of all its rows, attention + projections + FFN of 128 and of
+    256 sampled rows.  Whole-prefill tokens/s is extrapolated by row count."""
+    import keep_synth as ks
+    from oracle import keep_oracle as ko
+    s = w.shape
+    sh = ko.Shape(s.n_layers, s.hidden, s.n_q_heads, s.n_kv_heads, s.head_dim, s.ffn_dim, s.vocab, s.rope_theta,
+                  s.rms_eps, s.storage)
+    G = len(glen)
+    ratios = ks.ratio_schedule(w.ratio, s.n_layers, w.schedule)
+    rng = np.random.Generator(np.random.PCG64(5))
+    if w.budget == "tokens":        # a seeded random set that fills the layer's token budget
+        left, groups = ko.budget_tokens(float(ratios[1]), int(np.sum(glen))), []
+        for g in rng.permutation(G):
+            if glen[g] <= left:
+                groups.append(int(g))
+                left -= int(glen[g])
+        groups.sort()
+    else:
+        groups = sorted(rng.choice(G, size=ko.budget_count(float(ratios[1]), G, G), replace=False).tolist())
+    lw = {kk: (None if v is None else ks.to_numpy_f64(v)) for kk, v in ks.make_layer_weights(s, 1, "cpu").items()}
+    kb, vb = ks.make_random_group_cache(s, glen, 1, seed=7)
+    kb = [ks.to_numpy_f64(t) for t in kb]
+    vb = [ks.to_numpy_f64(t) for t in vb]
+    glist = [int(v) for v in glen]
+    kh, vh = ko.realign_concat(sh, kb, vb, glist, w.instr_len)
+    n_l = sum(glist[g] for g in groups) + w.instr_len
+    x = ks.to_numpy_f64(ks.make_random_rows(n_l, s.hidden, s.storage, seed=11))
+    times = []
+    for n_s in (128, 256):
+        pick = np.sort(rng.choice(n_l, size=min(n_s, n_l), replace=False))
+        t0 = time.perf_counter()
+        ko.selective_layer(sh, lw, x, groups, glist, w.instr_len, kh.copy(), vh.copy(), want_scores=False,
+                           only_rows=pick)
+        times.append(time.perf_counter() - t0)
+    per_row = max((times[1] - times[0]) / 128.0, 1e-9)
+    fixed = max(times[0] - 128 * per_row, 0.0)
+    row_cost = per_row + fixed / n_l
+    total_rows = int(np.sum(rows_per_layer))
+    est = total_rows * row_cost
+    cores = len(os.sched_getaffinity(0))
+    threads = int(os.environ.get("OMP_NUM_THREADS", cores))
+    return {"value": n_tokens / est, "unit": "tokens/s", "cores": min(cores, threads), "kind": "oracle",
+            "sample": "oracle selective_layer, layer 1 of %d, %d rows over the %d-token cache: K/V refresh of all rows "
+                      "+ attention/FFN of 128 and 256 sampled rows (%.1f s + %.1f s); whole prefill extrapolated by "
+                      "row count (%d rows over all layers)" % (s.n_layers, n_l, n_tokens, times[0], times[1], total_rows),
+            "seconds": times[0] + times[1], "extrapolated": True}
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py measures one GPU: the selective-recompute prefill is built and measured on a single "
+              "MI355X in this repository; run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import keep_synth as ks
+    from paper_2602_23592_amd import KeepContext, KeepPrompt
+    from paper_2602_23592_amd import binding as kb
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU (no CPU fallback exists)", file=sys.stderr)
+        sys.exit(3)
+    w = ks.workload(a.workload)
+    s = w.shape
+    sched = a.schedule or w.schedule
+    budget = a.budget or w.budget
+    budget_mode = kb.KEEP_BUDGET_TOKENS if budget == "tokens" else kb.KEEP_BUDGET_GROUP_COUNT
+    glen, kinds = ks.group_lengths(w)
+    G, lq = len(glen), w.instr_len
+    n_tokens = w.mem_tokens + lq
+    dt = torch.bfloat16 if s.storage == "bf16" else torch.float32
+    t_setup = time.perf_counter()
+    layers = [ks.make_layer_weights(s, l, "cuda") for l in range(s.n_layers)]
+    embed = ks.make_embedding(s, "cuda")
+    ids = ks.make_token_ids(n_tokens, s.vocab, 0)
+    streams = [torch.cuda.Stream() for _ in range(3)]
+    torch.cuda.synchronize()
+    ctx = KeepContext(s, layers, embed, n_tokens, G, kb.KEEP_KERNELS_AUTO, *streams)
+    if a.random_cache:
+        kb_all = torch.empty((s.n_layers, w.mem_tokens, s.n_kv_heads, s.head_dim), dtype=dt, device="cuda")
+        vb_all = torch.empty_like(kb_all)
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(7)
+        for l in range(s.n_layers):
+            kb_all[l] = torch.randn(kb_all[l].shape, generator=gen, device="cuda").to(dt)
+            vb_all[l] = torch.randn(vb_all[l].shape, generator=gen, device="cuda").to(dt)
+    else:
+        kb_all, vb_all = precompute_group_caches(ctx, w, glen, ids, torch)
+    off = np.concatenate([[0], np.cumsum(glen)]).astype(np.int64)
+    host = w.kv_location == "pinned_host"
+    if host:
+        kb_src = kb_all.cpu().pin_memory()
+        vb_src = vb_all.cpu().pin_memory()
+        del kb_all, vb_all
+    else:
+        kb_src, vb_src = kb_all, vb_all
+    k_blocks = [[kb_src[l, off[g]:off[g + 1]] for g in range(G)] for l in range(s.n_layers)]
+    v_blocks = [[vb_src[l, off[g]:off[g + 1]] for g in range(G)] for l in range(s.n_layers)]
+    prompt = KeepPrompt(glen, lq, ids, k_blocks, v_blocks, s.n_layers,
+                        kb.KEEP_KV_PINNED_HOST if host else kb.KEEP_KV_DEVICE, kinds)
+    ratios = ks.ratio_schedule(w.ratio, s.n_layers, sched)
+    k_cache = torch.empty((s.n_layers, n_tokens, s.n_kv_heads, s.head_dim), dtype=dt, device="cuda")
+    v_cache = torch.empty_like(k_cache)
+    x_final = torch.empty((lq, s.hidden), dtype=dt, device="cuda")
+    torch.cuda.synchronize()
+    t_setup = time.perf_counter() - t_setup
+
+    def step(report):
+        return ctx.prefill(prompt, ratios, w.hops, k_cache, v_cache, x_final, budget_mode,
+                           a.load_mode, want_report=report)
+
+    for _ in range(a.warmup):
+        step(False)
+    torch.cuda.synchronize()
+    reports = []
+    t0 = time.perf_counter()
+    for _ in range(a.steps):
+        sets, rep = step(True)
+        reports.append(rep)
+    torch.cuda.synchronize()
+    dt_s = time.perf_counter() - t0
+    ms_per_step = dt_s * 1e3 / max(1, a.steps)
+
+    # ---- per-kernel figures from the HIP-event report (averaged over the timed steps)
+    L = s.n_layers
+    rows = np.array([reports[-1].rows[l] for l in range(L)], dtype=np.float64)
+    re_rows = np.array([reports[-1].realign_rows[l] for l in range(L)], dtype=np.float64)
+    vis = np.array(visible_keys(sets, glen, lq), dtype=np.float64)
+
+    def mean_ms(name):
+        return np.mean([[getattr(r, name)[l] for l in range(L)] for r in reports], axis=0)
+
+    qd, kvd = s.n_q_heads * s.head_dim, s.n_kv_heads * s.head_dim
+    esz = 2 if s.storage == "bf16" else 4
+    kern = {}
+
+    def add(name, ms, work, unit, peak):
+        tot_ms = float(np.sum(ms))
+        ach = float(np.sum(work)) / (tot_ms * 1e-3) if tot_ms > 0 else 0.0
+        scale = 1e12 if unit == "TFLOP/s" else 1e9
+        kern[name] = {"ms_per_step": round(tot_ms, 3), "achieved": round(ach / scale, 2), "unit": unit,
+                      "frac": round(ach / scale / peak, 4)}
+
+    add("gemm_gate_up_swiglu", mean_ms("ms_gateup"), 2.0 * rows * s.hidden * 2 * s.ffn_dim, "TFLOP/s", PEAK_BF16_TFLOPS)
+    add("gemm_down", mean_ms("ms_down"), 2.0 * rows * s.hidden * s.ffn_dim, "TFLOP/s", PEAK_BF16_TFLOPS)
+    add("gemm_qkv", mean_ms("ms_qkv_gemm"), 2.0 * rows * s.hidden * (qd + 2 * kvd), "TFLOP/s", PEAK_BF16_TFLOPS)
+    add("gemm_out_proj", mean_ms("ms_oproj"), 2.0 * rows * qd * s.hidden, "TFLOP/s", PEAK_BF16_TFLOPS)
+    add("sparse_row_attention", mean_ms("ms_attn"), 4.0 * s.head_dim * s.n_q_heads * vis, "TFLOP/s", PEAK_BF16_TFLOPS)
+    add("realign_concat", mean_ms("ms_realign"), 4.0 * re_rows * kvd * esz, "GB/s", PEAK_HBM_GBS)
+    add("rope_scatter", mean_ms("ms_rope"), rows * ((qd + 2 * kvd) * 4.0 + (qd + 3 * kvd) * esz), "GB/s", PEAK_HBM_GBS)
+    add("score_select", mean_ms("ms_score"), np.zeros(L), "GB/s", PEAK_HBM_GBS)
+    # attention in bytes too: one pass over the visible K and V per (row tile, KV head) is the algorithmic
+    # minimum only when rows share tiles; report the cache-size figure (K_hat + V_hat of the layer, once)
+    att_ms = float(np.sum(mean_ms("ms_attn")))
+    kern["sparse_row_attention"]["cache_gbs"] = round(L * 2.0 * n_tokens * kvd * esz / (att_ms * 1e-3) / 1e9, 1) if att_ms else 0
+
+    gu = kern["gemm_gate_up_swiglu"]
+    n_launch = L
+    roofline = {"kernel": "k_gemm_mfma<256,256,2,2,SWIGLU> (gate/up projection with fused SiLU*mul)",
+                "bound": "mfma", "achieved": gu["achieved"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                "frac": gu["frac"], "traffic": None,
+                "avg_launch_ms": round(gu["ms_per_step"] / n_launch, 4), "launches_per_step": n_launch}
+
+    out = {
+        "metric": "prefill tokens/s with KV reuse (TTFT in ms_per_step)",
+        "value": round(n_tokens / (ms_per_step * 1e-3), 1), "unit": "tokens/s",
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": round(ms_per_step, 3),
+        "ttft_ms": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": s.storage, "data": "synthetic",
+        "config": {"workload": "%s: %d layers, hidden %d, %d Q / %d KV heads, head_dim %d, FFN %d; %d tokens = %d "
+                               "memory groups (%d tokens) + %d-token instruction; ratio %.2f of the %s (%s), %d hops; KV %s"
+                               % (w.name, L, s.hidden, s.n_q_heads, s.n_kv_heads, s.head_dim, s.ffn_dim, n_tokens, G,
+                                  w.mem_tokens, lq, w.ratio, budget, sched, w.hops, w.kv_location),
+                   "rows_per_layer_mean": round(float(np.mean(rows[1:])) if L > 1 else float(rows[0]), 1),
+                   "rows_layer0": int(rows[0]), "set_sizes": [len(x) for x in sets],
+                   "group_caches": "random draws" if a.random_cache else "library dense prefill of each group alone",
+                   "load_mode": a.load_mode, "setup_s": round(t_setup, 1)},
+        "roofline": roofline,
+        "kernels": kern,
+    }
+    if not a.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, glen, rows, n_tokens)
+    ctx.close()
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -108,21 +108,28 @@ typedef struct {
 } keep_prompt;
 
 #define KEEP_REPORT_MAX_LAYERS 128
-/* Filled by keep_prefill when a report is asked for (caller-allocated, HOST). */
+/* Filled by keep_prefill when a report is asked for (caller-allocated, HOST).
+ * Times are device times between HIP events recorded on the stream the kernels run
+ * on (compute stream; eval stream for ms_score), in milliseconds, per layer. */
 typedef struct {
   int32_t n_layers;
-  int32_t used_mfma;                          /* 1 if the MFMA kernel family ran */
-  float ms_total;                             /* whole call, host clock */
-  int32_t rows[KEEP_REPORT_MAX_LAYERS];       /* n_rows recomputed at each layer */
-  int32_t set_size[KEEP_REPORT_MAX_LAYERS];   /* groups recomputed at each layer */
-  int32_t hops_run[KEEP_REPORT_MAX_LAYERS];   /* selections run after each layer */
-  float ms_realign[KEEP_REPORT_MAX_LAYERS];   /* device time per phase, compute stream */
-  float ms_qkv[KEEP_REPORT_MAX_LAYERS];
-  float ms_attn[KEEP_REPORT_MAX_LAYERS];
-  float ms_ffn[KEEP_REPORT_MAX_LAYERS];       /* output projection + FFN */
-  float ms_score[KEEP_REPORT_MAX_LAYERS];     /* score reduction + selection, eval stream */
-  float ms_load_wait[KEEP_REPORT_MAX_LAYERS]; /* compute stream stalled on the copy stream */
-  uint64_t bytes_loaded[KEEP_REPORT_MAX_LAYERS]; /* host->device bytes enqueued while this layer ran */
+  int32_t used_mfma;                           /* 1 if the MFMA kernel family ran */
+  float ms_total;                              /* whole call, host clock */
+  int32_t rows[KEEP_REPORT_MAX_LAYERS];        /* n_rows recomputed at each layer */
+  int32_t set_size[KEEP_REPORT_MAX_LAYERS];    /* groups recomputed at each layer */
+  int32_t hops_run[KEEP_REPORT_MAX_LAYERS];    /* selections run after each layer */
+  int32_t realign_rows[KEEP_REPORT_MAX_LAYERS];/* cache rows re-aligned (groups outside the set) */
+  float ms_realign[KEEP_REPORT_MAX_LAYERS];    /* re-align + concatenate kernel */
+  float ms_prep[KEEP_REPORT_MAX_LAYERS];       /* row table, gather, first RMSNorm */
+  float ms_qkv_gemm[KEEP_REPORT_MAX_LAYERS];   /* QKV projection GEMM alone */
+  float ms_rope[KEEP_REPORT_MAX_LAYERS];       /* bias + RoPE + scatter kernel */
+  float ms_attn[KEEP_REPORT_MAX_LAYERS];       /* sparse-row attention kernel */
+  float ms_oproj[KEEP_REPORT_MAX_LAYERS];      /* output projection GEMM (+ residual) */
+  float ms_norm2[KEEP_REPORT_MAX_LAYERS];      /* second RMSNorm */
+  float ms_gateup[KEEP_REPORT_MAX_LAYERS];     /* gate/up GEMM with fused SwiGLU */
+  float ms_down[KEEP_REPORT_MAX_LAYERS];       /* down GEMM (+ residual) */
+  float ms_score[KEEP_REPORT_MAX_LAYERS];      /* score reduction + selection, eval stream */
+  uint64_t bytes_loaded[KEEP_REPORT_MAX_LAYERS]; /* host->device bytes enqueued for this layer's turn */
 } keep_report;
 
 /* Create a context.  desc, layers[n_layers]: HOST structs holding DEVICE pointers;

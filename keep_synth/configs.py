@@ -46,6 +46,10 @@ class Workload:
     hops: int
     kv_location: str = "device"     # "device" or "pinned_host"
     schedule: str = "linear"
+    # what the ratio counts: "groups" (share of the memories) or "tokens" (share of the memory
+    # tokens; used where group sizes differ by an order of magnitude, so that the ratio still
+    # bounds the recomputed rows)
+    budget: str = "groups"
 
 
 _TINY = ModelShape(2, 256, 4, 2, 64, 688, 4096, storage="f32")
@@ -57,7 +61,7 @@ WORKLOADS = {
     "tiny": Workload("tiny", _TINY, ((8, 128, 128, 1),), 1024, 64, 0.15, 1),
     "qwen7b_16k": Workload("qwen7b_16k", _Q7B, ((64, 256, 256, 1),), 16384, 256, 0.15, 2),
     "qwen14b_32k": Workload("qwen14b_32k", _Q14B, ((16, 1024, 1024, 0), (256, 64, 64, 1)),
-                            32512, 256, 0.10, 3),
+                            32768, 256, 0.10, 3, budget="tokens"),
     "qwen32b_32k_host": Workload("qwen32b_32k_host", _Q32B, ((128, 128, 384, 1),), 32768, 256,
                                  0.10, 2, kv_location="pinned_host"),
     "qwen14b_64k_stress": Workload("qwen14b_64k_stress", _Q14B, ((1024, 32, 96, 1),), 65536, 256,

@@ -52,13 +52,17 @@ class Prompt(C.Structure):
                 ("k_blocks", C.POINTER(C.c_void_p)), ("v_blocks", C.POINTER(C.c_void_p)), ("kv_location", C.c_int32)]
 
 
+_L = KEEP_REPORT_MAX_LAYERS
+_REPORT_MS = ("ms_realign", "ms_prep", "ms_qkv_gemm", "ms_rope", "ms_attn", "ms_oproj", "ms_norm2", "ms_gateup",
+              "ms_down", "ms_score")
+
+
 class Report(C.Structure):
-    _L = KEEP_REPORT_MAX_LAYERS
-    _fields_ = [("n_layers", C.c_int32), ("used_mfma", C.c_int32), ("ms_total", C.c_float),
-                ("rows", C.c_int32 * _L), ("set_size", C.c_int32 * _L), ("hops_run", C.c_int32 * _L),
-                ("ms_realign", C.c_float * _L), ("ms_qkv", C.c_float * _L), ("ms_attn", C.c_float * _L),
-                ("ms_ffn", C.c_float * _L), ("ms_score", C.c_float * _L), ("ms_load_wait", C.c_float * _L),
-                ("bytes_loaded", C.c_uint64 * _L)]
+    _fields_ = ([("n_layers", C.c_int32), ("used_mfma", C.c_int32), ("ms_total", C.c_float),
+                 ("rows", C.c_int32 * _L), ("set_size", C.c_int32 * _L), ("hops_run", C.c_int32 * _L),
+                 ("realign_rows", C.c_int32 * _L)]
+                + [(_n, C.c_float * _L) for _n in _REPORT_MS]
+                + [("bytes_loaded", C.c_uint64 * _L)])
 
 
 _lib = None

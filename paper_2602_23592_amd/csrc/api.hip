@@ -21,7 +21,9 @@ namespace {
 thread_local std::string g_init_error;
 
 constexpr double BUDGET_EPS = 1.0e-3;
-constexpr int EV_PER_LAYER = 7;  // begin, realign, qkv, attn, ffn, score_begin, score_end
+// events per layer: 0 begin, 1 re-align done, 2 rows/gather/norm done, 3 QKV GEMM done, 4 RoPE+scatter done,
+// 5 attention done, 6 output projection done, 7 second norm done, 8 gate/up done, 9 down done, 10/11 score begin/end
+constexpr int EV_PER_LAYER = 12;
 // Host->device pre-loads are enqueued only while fewer bytes than this are in flight,
 // so that the copies a layer is waiting for never queue behind a long run of pre-loads.
 constexpr size_t PRELOAD_INFLIGHT_CAP = 48u << 20;
@@ -366,6 +368,7 @@ keep_status layer_front(keep_ctx* c, const PromptInfo& pi, int layer, const Laye
     x = Typed<T>::p(c->xa);
   }
   launch_rmsnorm<T>(x, Typed<T>::p(w.ln1), n, d.hidden, d.rms_eps, Typed<T>::p(c->hbuf), s);
+  if (evs) HIP_TRY(c, hipEventRecord(evs[2], s));
   GemmB b;
   b.n_parts = 3;
   b.ptr[0] = w.wq; b.ptr[1] = w.wk; b.ptr[2] = w.wv;
@@ -378,10 +381,11 @@ keep_status layer_front(keep_ctx* c, const PromptInfo& pi, int layer, const Laye
                      c->qkv_raw, s);
   else
     launch_gemm_generic<T>(Typed<T>::p(c->hbuf), n, d.hidden, b, nullptr, n_qkv, EPI_STORE_F32, nullptr, c->qkv_raw, s);
+  if (evs) HIP_TRY(c, hipEventRecord(evs[3], s));
   launch_rope_scatter<T>(c->qkv_raw, Typed<T>::p(w.bq), Typed<T>::p(w.bk), Typed<T>::p(w.bv), c->d_row_pos, n,
                          d.n_q_heads, d.n_kv_heads, d.head_dim, c->rope_cos, c->rope_sin, Typed<T>::p(c->q),
                          Typed<T>::p(c->kc), Typed<T>::p(k_cache_l), Typed<T>::p(v_cache_l), s);
-  if (evs) HIP_TRY(c, hipEventRecord(evs[2], s));
+  if (evs) HIP_TRY(c, hipEventRecord(evs[4], s));
   if (c->mfma)
     launch_attn_mfma(reinterpret_cast<const bf16_t*>(c->q), reinterpret_cast<const bf16_t*>(k_cache_l),
                      reinterpret_cast<const bf16_t*>(v_cache_l), c->d_row_pos, n, pi.N, d.n_q_heads, d.n_kv_heads,
@@ -389,7 +393,7 @@ keep_status layer_front(keep_ctx* c, const PromptInfo& pi, int layer, const Laye
   else
     launch_attn_generic<T>(Typed<T>::p(c->q), Typed<T>::p(k_cache_l), Typed<T>::p(v_cache_l), c->d_row_pos, n,
                            d.n_q_heads, d.n_kv_heads, d.head_dim, Typed<T>::p(c->o), c->lse, s);
-  if (evs) HIP_TRY(c, hipEventRecord(evs[3], s));
+  if (evs) HIP_TRY(c, hipEventRecord(evs[5], s));
   HIP_TRY(c, hipGetLastError());
   return KEEP_OK;
 }
@@ -404,22 +408,31 @@ keep_status layer_back(keep_ctx* c, int layer, int n, const void* x_in, void* x_
   GemmB bo{}; bo.n_parts = 1; bo.ptr[0] = w.wo; bo.n_rows[0] = d.hidden;
   GemmB bg{}; bg.n_parts = 1; bg.ptr[0] = w.wgate; bg.n_rows[0] = d.ffn_dim;
   GemmB bd{}; bd.n_parts = 1; bd.ptr[0] = w.wdown; bd.n_rows[0] = d.hidden;
+#define EV(i) \
+  if (evs) HIP_TRY(c, hipEventRecord(evs[i], s))
   if (c->mfma) {
     auto B = [](const void* p) { return reinterpret_cast<const bf16_t*>(p); };
     launch_gemm_mfma(B(c->o), n, qd, bo, nullptr, d.hidden, EPI_RESIDUAL_STORE, B(x_in), c->x1, s);
+    EV(6);
     launch_rmsnorm<bf16_t>(B(c->x1), B(w.ln2), n, d.hidden, d.rms_eps, reinterpret_cast<bf16_t*>(c->hbuf), s);
+    EV(7);
     launch_gemm_mfma(B(c->hbuf), n, d.hidden, bg, w.wup, d.ffn_dim, EPI_SWIGLU_STORE, nullptr, c->act, s);
+    EV(8);
     launch_gemm_mfma(B(c->act), n, d.ffn_dim, bd, nullptr, d.hidden, EPI_RESIDUAL_STORE, B(c->x1), x_out, s);
   } else {
     launch_gemm_generic<T>(Typed<T>::p(c->o), n, qd, bo, nullptr, d.hidden, EPI_RESIDUAL_STORE, Typed<T>::p(x_in),
                            c->x1, s);
+    EV(6);
     launch_rmsnorm<T>(Typed<T>::p(c->x1), Typed<T>::p(w.ln2), n, d.hidden, d.rms_eps, Typed<T>::p(c->hbuf), s);
+    EV(7);
     launch_gemm_generic<T>(Typed<T>::p(c->hbuf), n, d.hidden, bg, w.wup, d.ffn_dim, EPI_SWIGLU_STORE, nullptr, c->act,
                            s);
+    EV(8);
     launch_gemm_generic<T>(Typed<T>::p(c->act), n, d.ffn_dim, bd, nullptr, d.hidden, EPI_RESIDUAL_STORE,
                            Typed<T>::p(c->x1), x_out, s);
   }
-  if (evs) HIP_TRY(c, hipEventRecord(evs[4], s));
+  EV(9);
+#undef EV
   HIP_TRY(c, hipGetLastError());
   return KEEP_OK;
 }
@@ -942,6 +955,7 @@ keep_status keep_prefill(keep_ctx* c, const keep_prompt* p, const float* ratios,
     if (report) {
       report->rows[l] = plan.n_rows;
       report->set_size[l] = m;
+      report->realign_rows[l] = plan.n_realign_rows;
     }
     const bool last = l + 1 == L;
     const void* x_in = x_from_embed ? nullptr : x_cur;
@@ -959,7 +973,7 @@ keep_status keep_prefill(keep_ctx* c, const keep_prompt* p, const float* ratios,
       if (kind == SEL_DEVICE) {
         HIP_TRY(c, hipEventRecord(c->ev_attn, c->s_comp));
         HIP_TRY(c, hipStreamWaitEvent(c->s_eval, c->ev_attn, 0));
-        if (evs) HIP_TRY(c, hipEventRecord(evs[5], c->s_eval));
+        if (evs) HIP_TRY(c, hipEventRecord(evs[10], c->s_eval));
         st = by_dtype(c, [&](auto* tag) {
           using T = std::remove_pointer_t<decltype(tag)>;
           return score_matrix<T>(c, l, plan, c->s_eval);
@@ -967,7 +981,7 @@ keep_status keep_prefill(keep_ctx* c, const keep_prompt* p, const float* ratios,
         if (st != KEEP_OK) return st;
         st = enqueue_select(c, m, k_count, tok, budget_mode, hops, c->s_eval);
         if (st != KEEP_OK) return st;
-        if (evs) HIP_TRY(c, hipEventRecord(evs[6], c->s_eval));
+        if (evs) HIP_TRY(c, hipEventRecord(evs[11], c->s_eval));
         HIP_TRY(c, hipEventRecord(c->ev_eval, c->s_eval));
       }
     }
@@ -1094,10 +1108,15 @@ keep_status keep_prefill(keep_ctx* c, const keep_prompt* p, const float* ratios,
     for (int l = 0; l < L; ++l) {
       hipEvent_t* e = &c->ev[(size_t)l * EV_PER_LAYER];
       (void)hipEventElapsedTime(&report->ms_realign[l], e[0], e[1]);
-      (void)hipEventElapsedTime(&report->ms_qkv[l], e[1], e[2]);
-      (void)hipEventElapsedTime(&report->ms_attn[l], e[2], e[3]);
-      (void)hipEventElapsedTime(&report->ms_ffn[l], e[3], e[4]);
-      if (report->hops_run[l] > 0) (void)hipEventElapsedTime(&report->ms_score[l], e[5], e[6]);
+      (void)hipEventElapsedTime(&report->ms_prep[l], e[1], e[2]);
+      (void)hipEventElapsedTime(&report->ms_qkv_gemm[l], e[2], e[3]);
+      (void)hipEventElapsedTime(&report->ms_rope[l], e[3], e[4]);
+      (void)hipEventElapsedTime(&report->ms_attn[l], e[4], e[5]);
+      (void)hipEventElapsedTime(&report->ms_oproj[l], e[5], e[6]);
+      (void)hipEventElapsedTime(&report->ms_norm2[l], e[6], e[7]);
+      (void)hipEventElapsedTime(&report->ms_gateup[l], e[7], e[8]);
+      (void)hipEventElapsedTime(&report->ms_down[l], e[8], e[9]);
+      if (report->hops_run[l] > 0) (void)hipEventElapsedTime(&report->ms_score[l], e[10], e[11]);
     }
   }
   return KEEP_OK;

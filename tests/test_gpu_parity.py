@@ -198,3 +198,46 @@ def test_three_streams_give_the_same_result():
     assert outs[0][0] == outs[1][0]
     for i in (1, 2, 3):
         assert torch.equal(outs[0][i], outs[1][i])
+
+
+def test_error_paths_with_a_live_context():
+    from paper_2602_23592_amd import KeepError, KeepPrompt
+    from paper_2602_23592_amd import binding as kbind
+    shape = SHAPES["f32_small"]
+    glen, lq = [5, 9, 4], 3
+    pb = Problem(shape, glen, lq, seed=2, std=0.1)
+    ctx, pr = pb.context(), pb.prompt()
+    kc, vc = pb.empty_cache()
+    xf = torch.empty((lq, shape.hidden), dtype=torch.float32, device="cuda")
+    x = torch.zeros((pr.n_rows([0, 2]), shape.hidden), dtype=torch.float32, device="cuda")
+
+    def status(fn):
+        with pytest.raises(KeepError) as e:
+            fn()
+        return e.value.status
+
+    # scores before the layer was computed, or for another set: STATE
+    assert status(lambda: ctx.score_groups(pr, 0, [0, 2], 0.5, 1)) == kbind.KEEP_ERR_STATE
+    ctx.recompute_layer(pr, 0, [0, 2], x, x.clone(), kc[0], vc[0])
+    assert status(lambda: ctx.score_groups(pr, 0, [0, 1], 0.5, 1)) == kbind.KEEP_ERR_STATE
+    assert status(lambda: ctx.score_groups(pr, 1, [0, 2], 0.5, 1)) == kbind.KEEP_ERR_STATE
+    ctx.score_groups(pr, 0, [0, 2], 0.5, 1)                   # the matching call works
+    # bad sets and layers: INVALID_ARG
+    assert status(lambda: ctx.recompute_layer(pr, 0, [2, 0], x, x, kc[0], vc[0])) == kbind.KEEP_ERR_INVALID_ARG
+    assert status(lambda: ctx.recompute_layer(pr, 0, [0, 3], x, x, kc[0], vc[0])) == kbind.KEEP_ERR_INVALID_ARG
+    assert status(lambda: ctx.recompute_layer(pr, 2, [0], x, x, kc[0], vc[0])) == kbind.KEEP_ERR_INVALID_ARG
+    # ratio schedules: first layer is all or nothing, later layers never grow
+    assert status(lambda: ctx.prefill(pr, [0.5, 0.5], 1, kc, vc, xf)) == kbind.KEEP_ERR_INVALID_ARG
+    assert status(lambda: ctx.prefill(pr, [0.0, 0.5], 1, kc, vc, xf)) == kbind.KEEP_ERR_INVALID_ARG
+    assert status(lambda: ctx.prefill(pr, [1.0, 0.5], 0, kc, vc, xf)) == kbind.KEEP_ERR_INVALID_ARG
+    # prompt larger than the workspace: WORKSPACE
+    big = KeepPrompt([5, 9, 4, 300], lq, np.zeros(321, dtype=np.int32), None, None, shape.n_layers)
+    assert status(lambda: ctx.prefill(big, [1.0, 0.5], 1, kc, vc, xf)) == kbind.KEEP_ERR_WORKSPACE
+    # token ids outside the vocabulary, empty instruction
+    bad_tok = KeepPrompt(glen, lq, np.full(21, 97, dtype=np.int32), pb.kb_d, pb.vb_d, shape.n_layers)
+    assert status(lambda: ctx.prefill(bad_tok, [1.0, 0.5], 1, kc, vc, xf)) == kbind.KEEP_ERR_INVALID_ARG
+    no_q = KeepPrompt(glen, 0, pb.ids[:18], pb.kb_d, pb.vb_d, shape.n_layers)
+    assert status(lambda: ctx.prefill(no_q, [1.0, 0.5], 1, kc, vc, xf)) == kbind.KEEP_ERR_INVALID_ARG
+    # the context still works after the errors
+    sets, _ = ctx.prefill(pr, [1.0, 0.5], 2, kc, vc, xf)
+    assert len(sets[1]) == 2
