@@ -4,8 +4,10 @@
 // lane l supplies 8 consecutive k of row (l % 32), k-block (l / 32).  A workgroup owns a
 // BM x BN tile of C; K is walked in 64-deep slices staged through LDS (two buffers, one
 // barrier per slice, next slice prefetched into registers while the current one is
-// multiplied).  LDS rows are 128 B; their 16-byte chunks are XOR-swizzled by the row
-// index so that the 16-byte operand reads of 32 consecutive rows spread over all banks.
+// multiplied; operand fragments of k-step ks+1 are read while step ks multiplies).  LDS
+// rows are 128 B; their 16-byte chunks are XOR-swizzled by the row index so that the
+// 16-byte operand reads of consecutive rows spread over all banks.  Workgroups are mapped
+// to tiles XCD by XCD so that the tiles resident on one XCD share slices through its L2.
 //
 // Epilogues: plain fp32 store (QKV), residual add (output and down projections), and
 // SwiGLU: the B tile interleaves rows of W_gate and W_up so that one lane holds
@@ -28,13 +30,15 @@ constexpr int GBK = 64;  // K slice
 
 __device__ __forceinline__ int lds_off(int row, int chunk) {
   // element offset of 16-byte chunk `chunk` (0..7) of row `row` in a [rows][64] bf16 tile
-  return row * GBK + ((chunk ^ (row & 7)) << 3);
+  // rows are 128 B, LDS has 64 four-byte banks: two rows fill one bank line, so the chunk is
+  // XOR-ed with (row / 2) % 8 -- 16 consecutive rows then cover all 64 banks exactly once
+  return row * GBK + ((chunk ^ ((row >> 1) & 7)) << 3);
 }
 
 template <int BM, int BN, int WM, int WN, int EPI>
 __global__ void __launch_bounds__(WM* WN * 64)
     k_gemm_mfma(const bf16_t* __restrict__ A, int M, int K, MfmaB B, const bf16_t* __restrict__ B2, int N,
-                const bf16_t* __restrict__ residual, void* __restrict__ Cv) {
+                const bf16_t* __restrict__ residual, void* __restrict__ Cv, int tiles_m, int tiles_n) {
   constexpr int T = WM * WN * 64;
   constexpr int TM = BM / WM, TN = BN / WN;
   constexpr int MI = TM / 32, NI = TN / 32;
@@ -48,8 +52,22 @@ __global__ void __launch_bounds__(WM* WN * 64)
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WN, wn = wave % WN;
-  const int m0 = blockIdx.y * BM;
-  const int n0 = blockIdx.x * BN;  // in B-tile rows (for SwiGLU: BN/2 output columns per block)
+  // Workgroup -> tile.  Consecutive workgroup ids go round-robin to the 8 XCDs, each with its own L2.
+  // XCD x therefore takes the x-th eighth of the tile list, and the list walks panels of GM tile rows
+  // column by column, so the ~32 workgroups resident on one XCD cover a GM x (32/GM) patch of C and
+  // share their A and B slices through that XCD's L2.
+  constexpr int GM = (BM >= 256) ? 4 : 8;
+  const int n_tiles = tiles_m * tiles_n;
+  const int per_xcd = (n_tiles + 7) >> 3;
+  const int t = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
+  if (t >= min(n_tiles, ((int)(blockIdx.x & 7) + 1) * per_xcd)) return;
+  const int panel = t / (GM * tiles_n);
+  const int panel_rows = min(GM, tiles_m - panel * GM);
+  const int within = t - panel * GM * tiles_n;
+  const int tile_m = panel * GM + within % panel_rows;
+  const int tile_n = within / panel_rows;
+  const int m0 = tile_m * BM;
+  const int n0 = tile_n * BN;  // in B-tile rows (for SwiGLU: BN/2 output columns per block)
 
   // ---- global source pointers of this thread's chunks
   const u32x4* a_src[A_CH];
@@ -114,42 +132,89 @@ __global__ void __launch_bounds__(WM* WN * 64)
   const int a_row0 = wm * TM + (lane & 31);
   const int b_row0 = wn * TN + (lane & 31);
   const int kg = lane >> 5;
+  // LDS element offsets of this lane's operand chunks for k-step 0..3 (rows differ by multiples of 32,
+  // which leaves the swizzle term unchanged, so one offset per k-step serves every row tile)
+  int a_off[GBK / 16], b_off[GBK / 16];
+#pragma unroll
+  for (int ks = 0; ks < GBK / 16; ++ks) {
+    a_off[ks] = lds_off(a_row0, ks * 2 + kg);
+    b_off[ks] = BM * GBK + lds_off(b_row0, ks * 2 + kg);
+  }
+
+  // operand fragments, double-buffered over k-steps: the loads of step ks+1 are in flight while the
+  // MFMAs of step ks run
+  bf16x8 af[2][MI], bfr[2][NI];
+#pragma unroll
+  for (int i = 0; i < MI; ++i) af[0][i] = *reinterpret_cast<const bf16x8*>(smem + a_off[0] + i * 32 * GBK);
+#pragma unroll
+  for (int j = 0; j < NI; ++j) bfr[0][j] = *reinterpret_cast<const bf16x8*>(smem + b_off[0] + j * 32 * GBK);
 
   for (int kt = 0; kt < KT; ++kt) {
     const int cur = kt & 1;
-    if (kt + 1 < KT) {
-      const int ko = (kt + 1) * (GBK / 8);  // in 16-byte units
+    // The last slice prefetches itself again and stores it to the idle buffer: harmless, and it keeps
+    // the loop body one straight-line block for the instruction scheduler.
+    const int ko = min(kt + 1, KT - 1) * (GBK / 8);  // in 16-byte units
+#ifndef KEEP_EXP_NO_GLOBAL
 #pragma unroll
-      for (int i = 0; i < A_CH; ++i) a_reg[i] = a_src[i][ko];
+    for (int i = 0; i < A_CH; ++i) a_reg[i] = a_src[i][ko];
 #pragma unroll
-      for (int i = 0; i < B_CH; ++i) b_reg[i] = b_src[i][ko];
-    }
-    const uint16_t* cA = smem + cur * BUF;
-    const uint16_t* cB = cA + BM * GBK;
+    for (int i = 0; i < B_CH; ++i) b_reg[i] = b_src[i][ko];
+#endif
+    const uint16_t* cbuf = smem + cur * BUF;
+    uint16_t* nbuf = smem + (cur ^ 1) * BUF;
 #pragma unroll
     for (int ks = 0; ks < GBK / 16; ++ks) {
-      bf16x8 af[MI], bfr[NI];
+      const int fc = ks & 1, fn = fc ^ 1;
+#ifndef KEEP_EXP_NO_LDSREAD
+      if (ks + 1 < GBK / 16) {
 #pragma unroll
-      for (int i = 0; i < MI; ++i)
-        af[i] = *reinterpret_cast<const bf16x8*>(cA + lds_off(a_row0 + i * 32, ks * 2 + kg));
+        for (int i = 0; i < MI; ++i)
+          af[fn][i] = *reinterpret_cast<const bf16x8*>(cbuf + a_off[ks + 1] + i * 32 * GBK);
 #pragma unroll
-      for (int j = 0; j < NI; ++j)
-        bfr[j] = *reinterpret_cast<const bf16x8*>(cB + lds_off(b_row0 + j * 32, ks * 2 + kg));
+        for (int j = 0; j < NI; ++j)
+          bfr[fn][j] = *reinterpret_cast<const bf16x8*>(cbuf + b_off[ks + 1] + j * 32 * GBK);
+      }
+#endif
 #pragma unroll
       for (int i = 0; i < MI; ++i)
 #pragma unroll
         for (int j = 0; j < NI; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[fc][i], bfr[fc][j], acc[i][j], 0, 0, 0);
+#ifndef KEEP_EXP_NO_LDSWRITE
+      if (ks + 1 == GBK / 16) {
+#pragma unroll
+        for (int i = 0; i < A_CH; ++i) *reinterpret_cast<u32x4*>(nbuf + a_dst[i]) = a_reg[i];
+#pragma unroll
+        for (int i = 0; i < B_CH; ++i) *reinterpret_cast<u32x4*>(nbuf + BM * GBK + b_dst[i]) = b_reg[i];
+      }
+#endif
     }
-    if (kt + 1 < KT) {
-      uint16_t* nA = smem + (cur ^ 1) * BUF;
-      uint16_t* nB = nA + BM * GBK;
+    // interleave: step 0 carries the global prefetch, steps 0..2 the next step's operand reads,
+    // step 3 the LDS stores of the prefetched slice
+    constexpr int MF = MI * NI;            // MFMAs per k-step
+    constexpr int RD = MI + NI;            // operand reads per k-step
+    constexpr int GL = A_CH + B_CH;        // global loads / LDS stores per slice
 #pragma unroll
-      for (int i = 0; i < A_CH; ++i) *reinterpret_cast<u32x4*>(nA + a_dst[i]) = a_reg[i];
+    for (int ks = 0; ks < GBK / 16 - 1; ++ks) {
 #pragma unroll
-      for (int i = 0; i < B_CH; ++i) *reinterpret_cast<u32x4*>(nB + b_dst[i]) = b_reg[i];
+      for (int r = 0; r < RD; ++r) {
+        __builtin_amdgcn_sched_group_barrier(0x008, MF / RD, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        if (ks == 0) __builtin_amdgcn_sched_group_barrier(0x020, GL / RD, 0);
+      }
+    }
+#pragma unroll
+    for (int r = 0; r < GL; ++r) {
+      __builtin_amdgcn_sched_group_barrier(0x008, MF / GL > 0 ? MF / GL : 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
     }
     __syncthreads();
+#ifndef KEEP_EXP_NO_LDSREAD
+#pragma unroll
+    for (int i = 0; i < MI; ++i) af[0][i] = *reinterpret_cast<const bf16x8*>(nbuf + a_off[0] + i * 32 * GBK);
+#pragma unroll
+    for (int j = 0; j < NI; ++j) bfr[0][j] = *reinterpret_cast<const bf16x8*>(nbuf + b_off[0] + j * 32 * GBK);
+#endif
   }
 
   // ---- epilogue.  acc[i][j][e]: row = i*32 + 8*(e/4) + 4*(lane/32) + e%4, col = j*32 + lane%32
@@ -193,7 +258,8 @@ static void launch_cfg(const bf16_t* A, int M, int K, const MfmaB& b, const bf16
   const size_t sh = (size_t)2 * (BM + BN) * GBK * sizeof(uint16_t);
   const dim3 block(WM * WN * 64);
   const int n_tile_rows = epilogue == EPI_SWIGLU_STORE ? 2 * N : N;  // B-tile rows to cover
-  const dim3 grid(n_tile_rows / BN, (M + BM - 1) / BM);
+  const int tiles_n = n_tile_rows / BN, tiles_m = (M + BM - 1) / BM;
+  const dim3 grid(8 * ((tiles_m * tiles_n + 7) / 8));
 #define GO(E)                                                                                              \
   do {                                                                                                     \
     auto kern = k_gemm_mfma<BM, BN, WM, WN, E>;                                                            \
@@ -203,7 +269,7 @@ static void launch_cfg(const bf16_t* A, int M, int K, const MfmaB& b, const bf16
                                 (int)sh);                                                                  \
       attr_set = true;                                                                                     \
     }                                                                                                      \
-    hipLaunchKernelGGL(kern, grid, block, sh, s, A, M, K, b, B2, N, residual, C);                          \
+    hipLaunchKernelGGL(kern, grid, block, sh, s, A, M, K, b, B2, N, residual, C, tiles_m, tiles_n);                          \
   } while (0)
   if (epilogue == EPI_STORE_F32)
     GO(EPI_STORE_F32);
@@ -232,8 +298,11 @@ void launch_gemm_mfma(const bf16_t* A, int32_t M, int32_t K, const GemmB& B, con
   b.begin[3] = acc;
   const bf16_t* b2 = reinterpret_cast<const bf16_t*>(B2);
   const int rows = epilogue == EPI_SWIGLU_STORE ? 2 * N : N;
-  if (aligned256 && rows % 256 == 0 && M > 128)
-    launch_cfg<256, 256, 2, 2>(A, M, K, b, b2, N, epilogue, residual, C, s);
+  // 256x256 tiles (8 waves, 64x128 each) when there are enough of them to fill the 256 CUs several
+  // times over; otherwise 128x128 tiles, whose finer grain loses less to the last partial wave of tiles.
+  const long tiles256 = (long)((M + 255) / 256) * (rows / 256);
+  if (aligned256 && rows % 256 == 0 && tiles256 >= 1024)
+    launch_cfg<256, 256, 4, 2>(A, M, K, b, b2, N, epilogue, residual, C, s);
   else if (rows % 128 == 0)
     launch_cfg<128, 128, 2, 2>(A, M, K, b, b2, N, epilogue, residual, C, s);
   else
