@@ -35,6 +35,7 @@ struct Staging {  // pinned host mirror of the small per-layer device arrays
   int32_t* gather_dst;
   int32_t* cand_len;
   int32_t* score_tiles;  // row-tile table of the MFMA score pass
+  int32_t* attn_items;   // work list of the MFMA attention
   RealignSeg* segs;
   hipEvent_t done;
   bool used;
@@ -59,7 +60,7 @@ struct keep_ctx {
   int32_t *d_set_off = nullptr, *d_row_start = nullptr, *d_gather_src = nullptr, *d_cand_len = nullptr;
   RealignSeg* d_segs = nullptr;
   void *xa = nullptr, *xb = nullptr, *hbuf = nullptr, *q = nullptr, *kc = nullptr, *o = nullptr, *x1 = nullptr,
-       *act = nullptr;
+       *act = nullptr, *attn_scratch = nullptr;
   float *qkv_raw = nullptr, *lse = nullptr, *score_scratch = nullptr, *S = nullptr, *sel_work = nullptr;
   int32_t *sel_iwork = nullptr, *sel_out = nullptr;
 
@@ -192,6 +193,7 @@ uint64_t workspace_bytes(const keep_model_desc* d) {
   t += align256(z.M * (z.qd + 2 * z.kvd) * sizeof(float));             // qkv_raw
   t += align256(z.M * (size_t)d->n_q_heads * sizeof(float));           // lse
   t += align256(score_scratch_bytes(d));
+  if (wants_mfma(d)) t += align256(attn_mfma_scratch_bytes((int32_t)z.M, d->n_q_heads, d->n_kv_heads));
   t += align256((z.G + 1) * z.G * sizeof(float));                      // S
   t += align256(((z.G + 1) * z.G + 2 * z.G) * sizeof(float));          // sel_work
   t += align256(4 * z.G * sizeof(int32_t)) + align256((z.G + 2) * sizeof(int32_t));
@@ -388,8 +390,9 @@ keep_status layer_front(keep_ctx* c, const PromptInfo& pi, int layer, const Laye
   if (evs) HIP_TRY(c, hipEventRecord(evs[4], s));
   if (c->mfma)
     launch_attn_mfma(reinterpret_cast<const bf16_t*>(c->q), reinterpret_cast<const bf16_t*>(k_cache_l),
-                     reinterpret_cast<const bf16_t*>(v_cache_l), c->d_row_pos, n, pi.N, d.n_q_heads, d.n_kv_heads,
-                     reinterpret_cast<bf16_t*>(c->o), c->lse, s);
+                     reinterpret_cast<const bf16_t*>(v_cache_l), c->d_row_pos, plan.row_start.data(),
+                     c->stage[layer].set_off, plan.m, pi.n_mem, n, pi.N, d.n_q_heads, d.n_kv_heads, d.max_tokens,
+                     c->stage[layer].attn_items, c->attn_scratch, reinterpret_cast<bf16_t*>(c->o), c->lse, s);
   else
     launch_attn_generic<T>(Typed<T>::p(c->q), Typed<T>::p(k_cache_l), Typed<T>::p(v_cache_l), c->d_row_pos, n,
                            d.n_q_heads, d.n_kv_heads, d.head_dim, Typed<T>::p(c->o), c->lse, s);
@@ -518,6 +521,7 @@ keep_status keep_destroy(keep_ctx* c) {
     if (st.gather_dst) (void)hipHostFree(st.gather_dst);
     if (st.cand_len) (void)hipHostFree(st.cand_len);
     if (st.score_tiles) (void)hipHostFree(st.score_tiles);
+    if (st.attn_items) (void)hipHostFree(st.attn_items);
     if (st.segs) (void)hipHostFree(st.segs);
     if (st.done) (void)hipEventDestroy(st.done);
   }
@@ -593,6 +597,9 @@ keep_status keep_init(const keep_model_desc* desc, const keep_layer_weights* lay
   TRY_INIT(dev_alloc(c, &c->qkv_raw, z.M * (z.qd + 2 * z.kvd) * sizeof(float)));
   TRY_INIT(dev_alloc(c, &c->lse, z.M * (size_t)desc->n_q_heads * sizeof(float)));
   TRY_INIT(dev_alloc(c, &c->score_scratch, score_scratch_bytes(desc)));
+  if (c->mfma)
+    TRY_INIT(dev_alloc(c, reinterpret_cast<char**>(&c->attn_scratch),
+                       attn_mfma_scratch_bytes((int32_t)z.M, desc->n_q_heads, desc->n_kv_heads)));
   TRY_INIT(dev_alloc(c, &c->S, (z.G + 1) * z.G * sizeof(float)));
   TRY_INIT(dev_alloc(c, &c->sel_work, ((z.G + 1) * z.G + 2 * z.G) * sizeof(float)));
   TRY_INIT(dev_alloc(c, &c->sel_iwork, 4 * z.G * 4));
@@ -625,7 +632,10 @@ keep_status keep_init(const keep_model_desc* desc, const keep_layer_weights* lay
     TRY_INIT(pin_alloc(c, &sg.gather_src, (z.G + 2) * 4));
     TRY_INIT(pin_alloc(c, &sg.gather_dst, (z.G + 2) * 4));
     TRY_INIT(pin_alloc(c, &sg.cand_len, (z.G + 2) * 4));
-    if (c->mfma) TRY_INIT(pin_alloc(c, &sg.score_tiles, score_mfma_stage_ints((int32_t)z.M, (int32_t)z.G) * 4));
+    if (c->mfma) {
+      TRY_INIT(pin_alloc(c, &sg.score_tiles, score_mfma_stage_ints((int32_t)z.M, (int32_t)z.G) * 4));
+      TRY_INIT(pin_alloc(c, &sg.attn_items, attn_mfma_stage_ints((int32_t)z.M, desc->n_q_heads, desc->n_kv_heads) * 4));
+    }
     TRY_INIT(pin_alloc(c, &sg.segs, z.G * sizeof(RealignSeg)));
     auto mk = [&]() -> keep_status {
       HIP_TRY(c, hipEventCreateWithFlags(&sg.done, hipEventDisableTiming));

@@ -13,6 +13,15 @@
 // registers are, as they stand, the B operand of O^T = V^T . P^T; V^T's A operand comes
 // straight from the row-major V tile through the LDS transpose read (ds_read_b64_tr_b16).
 // The softmax statistics therefore stay per lane from the first tile to the final divide.
+//
+// Work list.  With few recomputed rows there are few (tile, KV head) pairs and the longest
+// ones (instruction rows see the whole cache) would run alone on a few CUs.  The host
+// therefore cuts long key ranges into chunks: a work item is (tile, key-tile range); items of
+// a cut tile write un-normalised partial sums (fp32) with their running max and sum, and
+// k_attn_combine merges them per row in chunk order (no atomics, reproducible).
+#include <algorithm>
+#include <vector>
+
 #include "keep_internal.h"
 
 namespace keep {
@@ -39,16 +48,21 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
   return (uint32_t)f32_to_bf16_bits(a) | ((uint32_t)f32_to_bf16_bits(b) << 16);
 }
 
+constexpr float M_FLOOR = -1.0e30f;  // running max starts here (finite, so a fully masked tile gives alpha = 1, p = 0)
+constexpr int PART_FLOATS = 128 * DH;  // partial O of one (item, KV head): [dh/4][q 128][4]
+
 __global__ void __launch_bounds__(256, 2)
     k_attn_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k_cache, const bf16_t* __restrict__ v_cache,
-                const int32_t* __restrict__ row_pos, int n_rows, int n_total, int n_q_heads, int n_kv_heads, int n_tiles,
-                float scale_log2e, bf16_t* __restrict__ o, float* __restrict__ lse) {
+                const int32_t* __restrict__ row_pos, int n_rows, int n_total, int n_q_heads, int n_kv_heads,
+                const int4* __restrict__ items, float scale_log2e, bf16_t* __restrict__ o, float* __restrict__ lse,
+                float* __restrict__ part_o, float* __restrict__ part_ml) {
   extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int g = lane >> 5, lq = lane & 31;
   const int rep = n_q_heads / n_kv_heads;
   const int hk = blockIdx.x % n_kv_heads;
-  const int tile = n_tiles - 1 - blockIdx.x / n_kv_heads;  // longest key ranges first
+  const int4 item = items[blockIdx.x / n_kv_heads];  // {tile, first key tile, end key tile, partial slot or -1}
+  const int tile = item.x;
   const int QR = n_rows * rep;
   const int kv_dim = n_kv_heads * DH;
 
@@ -64,9 +78,7 @@ __global__ void __launch_bounds__(256, 2)
     wmax = max(wmax, __shfl_xor(wmax, off, 64));
     wmin = min(wmin, __shfl_xor(wmin, off, 64));
   }
-  const int x_last = min(QR, (tile + 1) * 128) - 1;
-  const int bmax = row_pos[x_last / rep];
-  const int n_kt = bmax / KT_KEYS + 1;
+  const int kt0 = item.y, n_kt = item.z;
 
   // Q^T operand: 8 k-steps of 16 head-dim elements
   bf16x8 qf[8];
@@ -81,7 +93,7 @@ __global__ void __launch_bounds__(256, 2)
   for (int nt = 0; nt < 4; ++nt)
 #pragma unroll
     for (int e = 0; e < 16; ++e) oacc[nt][e] = 0.f;
-  float m_run = -INFINITY, l_run = 0.f;
+  float m_run = M_FLOOR, l_run = 0.f;
 
   // global -> LDS staging: 4 chunks of K and 4 of V per thread per tile
   const int ld_row = tid >> 4, ld_c = tid & 15;  // rows ld_row + 16 i
@@ -103,12 +115,12 @@ __global__ void __launch_bounds__(256, 2)
   }
 #define ATT_SSTORE(BUFI) \
   ATT_SSTORE1(kreg0, vreg0, 0, BUFI) ATT_SSTORE1(kreg1, vreg1, 1, BUFI) ATT_SSTORE1(kreg2, vreg2, 2, BUFI) ATT_SSTORE1(kreg3, vreg3, 3, BUFI)
-  ATT_GLOAD(0)
+  ATT_GLOAD(kt0)
   ATT_SSTORE(0)
   __syncthreads();
 
-  for (int kt = 0; kt < n_kt; ++kt) {
-    const int cur = kt & 1;
+  for (int kt = kt0; kt < n_kt; ++kt) {
+    const int cur = (kt - kt0) & 1;
     const int k0 = kt * KT_KEYS;
     if (kt + 1 < n_kt) { ATT_GLOAD(kt + 1) }
     if (k0 <= wmax) {
@@ -186,22 +198,41 @@ __global__ void __launch_bounds__(256, 2)
     __syncthreads();
   }
 
-  // ---- finish: combine the two lane halves' sums, normalise, write O and LSE
+  // ---- finish: combine the two lane halves' sums, then either normalise and write O and LSE, or
+  // (cut tile) store the un-normalised partial with its max and sum for k_attn_combine
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
-  if (valid) {
-    const float inv = 1.0f / l_tot;
-    bf16_t* op = o + ((size_t)r * n_q_heads + head) * DH;
+  if (item.w < 0) {
+    if (valid) {
+      const float inv = 1.0f / l_tot;
+      bf16_t* op = o + ((size_t)r * n_q_heads + head) * DH;
+#pragma unroll
+      for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+        for (int e = 0; e < 16; e += 4) {
+          const int d = nt * 32 + 8 * (e >> 2) + 4 * g;
+          uint2 u;
+          u.x = pack_bf16x2(oacc[nt][e] * inv, oacc[nt][e + 1] * inv);
+          u.y = pack_bf16x2(oacc[nt][e + 2] * inv, oacc[nt][e + 3] * inv);
+          *reinterpret_cast<uint2*>(op + d) = u;
+        }
+      if (g == 0) lse[(size_t)r * n_q_heads + head] = 0.6931471805599453f * (m_run + log2f(l_tot));
+    }
+  } else {
+    const size_t slot = (size_t)item.w * n_kv_heads + hk;
+    float* po = part_o + slot * PART_FLOATS;
+    const int ql = wave * 32 + lq;
 #pragma unroll
     for (int nt = 0; nt < 4; ++nt)
 #pragma unroll
       for (int e = 0; e < 16; e += 4) {
-        const int d = nt * 32 + 8 * (e >> 2) + 4 * g;
-        uint2 u;
-        u.x = pack_bf16x2(oacc[nt][e] * inv, oacc[nt][e + 1] * inv);
-        u.y = pack_bf16x2(oacc[nt][e + 2] * inv, oacc[nt][e + 3] * inv);
-        *reinterpret_cast<uint2*>(op + d) = u;
+        const int d4 = (nt * 32 + 8 * (e >> 2) + 4 * g) >> 2;
+        *reinterpret_cast<float4*>(po + ((size_t)d4 * 128 + ql) * 4) =
+            make_float4(oacc[nt][e], oacc[nt][e + 1], oacc[nt][e + 2], oacc[nt][e + 3]);
       }
-    if (g == 0) lse[(size_t)r * n_q_heads + head] = 0.6931471805599453f * (m_run + log2f(l_tot));
+    if (g == 0) {
+      part_ml[slot * 256 + ql] = m_run;
+      part_ml[slot * 256 + 128 + ql] = l_tot;
+    }
   }
 }
 #undef ATT_GLOAD
@@ -209,12 +240,129 @@ __global__ void __launch_bounds__(256, 2)
 #undef ATT_SSTORE
 #undef ATT_SSTORE1
 
+// Merge the partials of one cut tile and one KV head: rows q = 0..127, chunks in order.
+__global__ void __launch_bounds__(256)
+    k_attn_combine(const int4* __restrict__ splits, const float* __restrict__ part_o, const float* __restrict__ part_ml,
+                   int n_rows, int n_q_heads, int n_kv_heads, bf16_t* __restrict__ o, float* __restrict__ lse) {
+  const int hk = blockIdx.x % n_kv_heads;
+  const int4 sp = splits[blockIdx.x / n_kv_heads];  // {tile, first slot, chunks, -}
+  const int rep = n_q_heads / n_kv_heads;
+  const int ql = threadIdx.x & 127, half = threadIdx.x >> 7;
+  const int x = sp.x * 128 + ql;
+  if (x >= n_rows * rep) return;
+  const int r = x / rep, head = hk * rep + x % rep;
+  float m_all = M_FLOOR;
+  for (int c = 0; c < sp.z; ++c) m_all = fmaxf(m_all, part_ml[((size_t)(sp.y + c) * n_kv_heads + hk) * 256 + ql]);
+  float l_all = 0.f;
+  for (int c = 0; c < sp.z; ++c) {
+    const size_t slot = (size_t)(sp.y + c) * n_kv_heads + hk;
+    l_all += part_ml[slot * 256 + 128 + ql] * __builtin_amdgcn_exp2f(part_ml[slot * 256 + ql] - m_all);
+  }
+  const float inv = 1.0f / l_all;
+  bf16_t* op = o + ((size_t)r * n_q_heads + head) * DH;
+  for (int d4 = half * 16; d4 < half * 16 + 16; ++d4) {
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int c = 0; c < sp.z; ++c) {
+      const size_t slot = (size_t)(sp.y + c) * n_kv_heads + hk;
+      const float w = __builtin_amdgcn_exp2f(part_ml[slot * 256 + ql] - m_all);
+      const float4 v = *reinterpret_cast<const float4*>(part_o + slot * PART_FLOATS + ((size_t)d4 * 128 + ql) * 4);
+      acc.x += w * v.x;
+      acc.y += w * v.y;
+      acc.z += w * v.z;
+      acc.w += w * v.w;
+    }
+    uint2 u;
+    u.x = pack_bf16x2(acc.x * inv, acc.y * inv);
+    u.y = pack_bf16x2(acc.z * inv, acc.w * inv);
+    *reinterpret_cast<uint2*>(op + d4 * 4) = u;
+  }
+  if (half == 0) lse[(size_t)r * n_q_heads + head] = 0.6931471805599453f * (m_all + log2f(l_all));
+}
+
+// ---- host-side work list ---------------------------------------------------
+constexpr int ATT_MAX_SLOTS = 4096;      // partial buffers (cut items x KV heads) the scratch can hold
+constexpr int ATT_TARGET_BLOCKS = 2048;  // cut long tiles until about this many workgroups exist
+constexpr int ATT_MIN_CHUNK = 16;        // never cut below 16 key tiles (1024 keys)
+
+static inline int att_max_tiles(int max_rows, int rep) { return (int)(((long)max_rows * rep + 127) / 128); }
+
+size_t attn_mfma_stage_ints(int32_t max_rows, int32_t n_q_heads, int32_t n_kv_heads) {
+  const int mt = att_max_tiles(max_rows, n_q_heads / n_kv_heads);
+  return (size_t)4 * (mt + ATT_MAX_SLOTS) + (size_t)4 * mt;  // items then splits
+}
+size_t attn_mfma_scratch_bytes(int32_t max_rows, int32_t n_q_heads, int32_t n_kv_heads) {
+  return attn_mfma_stage_ints(max_rows, n_q_heads, n_kv_heads) * sizeof(int32_t) + 256 +
+         (size_t)ATT_MAX_SLOTS * (PART_FLOATS + 256) * sizeof(float);
+}
+
 void launch_attn_mfma(const bf16_t* q, const bf16_t* k_cache, const bf16_t* v_cache, const int32_t* d_row_pos,
-                      int32_t n_rows, int32_t n_total, int32_t n_q_heads, int32_t n_kv_heads, bf16_t* o, float* lse,
-                      hipStream_t s) {
+                      const int32_t* h_row_start, const int32_t* h_set_off, int32_t m, int32_t instr_off,
+                      int32_t n_rows, int32_t n_total, int32_t n_q_heads, int32_t n_kv_heads, int32_t max_rows,
+                      int32_t* h_stage, void* d_scratch, bf16_t* o, float* lse, hipStream_t s) {
   if (n_rows <= 0) return;
   const int rep = n_q_heads / n_kv_heads;
   const int n_tiles = (n_rows * rep + 127) / 128;
+  const int mt = att_max_tiles(max_rows, rep);
+  // key tiles each query tile needs: up to the position of its last row
+  auto pos_of_row = [&](int r) {
+    int lo = 0, hi = m;  // blocks 0..m
+    while (lo < hi) {
+      const int mid = (lo + hi + 1) >> 1;
+      if (h_row_start[mid] <= r)
+        lo = mid;
+      else
+        hi = mid - 1;
+    }
+    return (lo < m ? h_set_off[lo] : instr_off) + (r - h_row_start[lo]);
+  };
+  int4* h_items = reinterpret_cast<int4*>(h_stage);
+  int4* h_splits = reinterpret_cast<int4*>(h_stage + (size_t)4 * (mt + ATT_MAX_SLOTS));
+  long total_steps = 0;
+  // steps of tile t are kept in h_splits[t].w for the second pass (overwritten afterwards is fine: separate array)
+  static thread_local std::vector<int> steps;
+  steps.resize(n_tiles);
+  for (int t = 0; t < n_tiles; ++t) {
+    const int x_last = std::min(n_rows * rep, (t + 1) * 128) - 1;
+    steps[t] = pos_of_row(x_last / rep) / KT_KEYS + 1;
+    total_steps += steps[t];
+  }
+  int chunk = 1 << 30;
+  if ((long)n_tiles * n_kv_heads < ATT_TARGET_BLOCKS) {
+    const long want_items = ATT_TARGET_BLOCKS / n_kv_heads;
+    chunk = (int)std::max<long>(ATT_MIN_CHUNK, (total_steps + want_items - 1) / want_items);
+    for (;;) {
+      long slots = 0;
+      for (int t = 0; t < n_tiles; ++t) {
+        const int nc = (steps[t] + chunk - 1) / chunk;
+        if (nc > 1) slots += nc;
+      }
+      if (slots * n_kv_heads <= ATT_MAX_SLOTS) break;
+      chunk *= 2;
+    }
+  }
+  int n_items = 0, n_splits = 0, slot = 0;
+  for (int t = n_tiles - 1; t >= 0; --t) {  // longest key ranges first
+    const int nc = (steps[t] + chunk - 1) / chunk;
+    if (nc <= 1) {
+      h_items[n_items++] = make_int4(t, 0, steps[t], -1);
+    } else {
+      const int len = (steps[t] + nc - 1) / nc;
+      h_splits[n_splits++] = make_int4(t, slot, nc, 0);
+      for (int c = 0; c < nc; ++c) h_items[n_items++] = make_int4(t, c * len, std::min(steps[t], (c + 1) * len), slot + c);
+      slot += nc;
+    }
+  }
+  char* base = reinterpret_cast<char*>(d_scratch);
+  int4* d_items = reinterpret_cast<int4*>(base);
+  int4* d_splits = d_items + (mt + ATT_MAX_SLOTS);
+  size_t off = attn_mfma_stage_ints(max_rows, n_q_heads, n_kv_heads) * sizeof(int32_t);
+  off = (off + 255) & ~(size_t)255;
+  float* part_o = reinterpret_cast<float*>(base + off);
+  float* part_ml = part_o + (size_t)ATT_MAX_SLOTS * PART_FLOATS;
+  (void)hipMemcpyAsync(d_items, h_items, (size_t)n_items * sizeof(int4), hipMemcpyHostToDevice, s);
+  if (n_splits)
+    (void)hipMemcpyAsync(d_splits, h_splits, (size_t)n_splits * sizeof(int4), hipMemcpyHostToDevice, s);
+
   const size_t sh = (size_t)2 * ATT_BUF * sizeof(uint16_t);
   static bool attr_set = false;
   if (!attr_set) {
@@ -223,8 +371,11 @@ void launch_attn_mfma(const bf16_t* q, const bf16_t* k_cache, const bf16_t* v_ca
     attr_set = true;
   }
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)DH);
-  hipLaunchKernelGGL(k_attn_mfma, dim3(n_tiles * n_kv_heads), dim3(256), sh, s, q, k_cache, v_cache, d_row_pos, n_rows,
-                     n_total, n_q_heads, n_kv_heads, n_tiles, scale_log2e, o, lse);
+  hipLaunchKernelGGL(k_attn_mfma, dim3(n_items * n_kv_heads), dim3(256), sh, s, q, k_cache, v_cache, d_row_pos, n_rows,
+                     n_total, n_q_heads, n_kv_heads, d_items, scale_log2e, o, lse, part_o, part_ml);
+  if (n_splits)
+    hipLaunchKernelGGL(k_attn_combine, dim3(n_splits * n_kv_heads), dim3(256), 0, s, d_splits, part_o, part_ml, n_rows,
+                       n_q_heads, n_kv_heads, o, lse);
 }
 
 }  // namespace keep

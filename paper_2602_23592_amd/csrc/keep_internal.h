@@ -115,9 +115,15 @@ void launch_score_finish(const float* rowmass, const int32_t* d_row_start, int32
 // MFMA (bf16, head_dim 128) kernels
 void launch_gemm_mfma(const bf16_t* A, int32_t M, int32_t K, const GemmB& B, const void* B2, int32_t N, int epilogue,
                       const bf16_t* residual, void* C, hipStream_t s);
+// h_row_start / h_set_off / m / instr_off: the host copy of the layer's row layout (as for
+// launch_build_rows), from which the work list is planned; h_stage: pinned host ints
+// (attn_mfma_stage_ints), d_scratch: device bytes (attn_mfma_scratch_bytes).
+size_t attn_mfma_stage_ints(int32_t max_rows, int32_t n_q_heads, int32_t n_kv_heads);
+size_t attn_mfma_scratch_bytes(int32_t max_rows, int32_t n_q_heads, int32_t n_kv_heads);
 void launch_attn_mfma(const bf16_t* q, const bf16_t* k_cache, const bf16_t* v_cache, const int32_t* d_row_pos,
-                      int32_t n_rows, int32_t n_total, int32_t n_q_heads, int32_t n_kv_heads, bf16_t* o, float* lse,
-                      hipStream_t s);
+                      const int32_t* h_row_start, const int32_t* h_set_off, int32_t m, int32_t instr_off,
+                      int32_t n_rows, int32_t n_total, int32_t n_q_heads, int32_t n_kv_heads, int32_t max_rows,
+                      int32_t* h_stage, void* d_scratch, bf16_t* o, float* lse, hipStream_t s);
 // group-score matrix S[(m+1), m] of the layer whose q / compact k / lse are given.
 // h_stage: pinned host ints (score_mfma_stage_ints of them), d_scratch: device bytes
 // (score_mfma_scratch_bytes), both sized with the same max_rows / max_groups.
