@@ -34,6 +34,7 @@ def parse():
     ap.add_argument("--schedule", default=None, help="ratio schedule: linear (default of the workload) or const")
     ap.add_argument("--budget", default=None, help="groups or tokens (default: the workload's)")
     ap.add_argument("--load-mode", type=int, default=2, help="0 serial, 1 next-layer, 2 layer-balanced")
+    ap.add_argument("--layers-json", default=None, help="also write the per-layer timing report to this file")
     ap.add_argument("--random-cache", action="store_true",
                     help="random group caches instead of caches prefilled by the library (faster set-up)")
     return ap.parse_args()
@@ -295,6 +296,13 @@ def main():
         "roofline": roofline,
         "kernels": kern,
     }
+    if a.layers_json:
+        from paper_2602_23592_amd.binding import _REPORT_MS
+        per_layer = {"rows": [int(v) for v in rows], "set_sizes": [len(x) for x in sets]}
+        for name in _REPORT_MS:
+            per_layer[name] = [round(float(v), 4) for v in mean_ms(name)]
+        with open(a.layers_json, "w") as f:
+            json.dump(per_layer, f)
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, glen, rows, n_tokens)
     ctx.close()

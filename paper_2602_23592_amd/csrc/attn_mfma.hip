@@ -44,10 +44,6 @@ __device__ __forceinline__ bf16x8 cat4(s16x4 a, s16x4 b) {
   return __builtin_bit_cast(bf16x8, __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7));
 }
 
-__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
-  return (uint32_t)f32_to_bf16_bits(a) | ((uint32_t)f32_to_bf16_bits(b) << 16);
-}
-
 constexpr float M_FLOOR = -1.0e30f;  // running max starts here (finite, so a fully masked tile gives alpha = 1, p = 0)
 constexpr int PART_FLOATS = 128 * DH;  // partial O of one (item, KV head): [dh/4][q 128][4]
 
@@ -139,40 +135,46 @@ __global__ void __launch_bounds__(256, 2)
           sacc[st] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], sacc[st], 0, 0, 0);
         }
       }
-      // ---- scale, causal mask, running max
+      // ---- causal mask, running max (raw scores; the scale is folded into the exponent's fma)
       const bool need_mask = k0 + KT_KEYS - 1 > wmin;
+      if (need_mask) {
+#pragma unroll
+        for (int st = 0; st < 2; ++st)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) {
+            const int key = k0 + st * 32 + 8 * (e >> 2) + 4 * g + (e & 3);
+            sacc[st][e] = key <= pos ? sacc[st][e] : -INFINITY;
+          }
+      }
       float tmax = -INFINITY;
 #pragma unroll
       for (int st = 0; st < 2; ++st)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          float s = sacc[st][e] * scale_log2e;
-          if (need_mask) {
-            const int key = k0 + st * 32 + 8 * (e >> 2) + 4 * g + (e & 3);
-            s = key <= pos ? s : -INFINITY;
-          }
-          sacc[st][e] = s;
-          tmax = fmaxf(tmax, s);
-        }
+        for (int e = 0; e < 16; ++e) tmax = fmaxf(tmax, sacc[st][e]);
       tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-      const float m_new = fmaxf(m_run, tmax);
-      const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-      m_run = m_new;
+      const float m_new = fmaxf(m_run, tmax * scale_log2e);  // log2 domain
+      // rescale the running sums only when some row's max moved (after the first tiles it rarely does)
+      if (__builtin_amdgcn_ballot_w64(m_new != m_run) != 0) {
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+        l_run *= alpha;
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) oacc[nt][e] *= alpha;
+        m_run = m_new;
+      }
       float psum = 0.f;
       uint32_t pk[2][8];
 #pragma unroll
       for (int st = 0; st < 2; ++st)
 #pragma unroll
         for (int e = 0; e < 16; e += 2) {
-          const float p0 = __builtin_amdgcn_exp2f(sacc[st][e] - m_new), p1 = __builtin_amdgcn_exp2f(sacc[st][e + 1] - m_new);
+          const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[st][e], scale_log2e, -m_new));
+          const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[st][e + 1], scale_log2e, -m_new));
           psum += p0 + p1;
           pk[st][e >> 1] = pack_bf16x2(p0, p1);
         }
-      l_run = l_run * alpha + psum;
-#pragma unroll
-      for (int nt = 0; nt < 4; ++nt)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) oacc[nt][e] *= alpha;
+      l_run += psum;
       // ---- O^T += V^T . P^T : 4 k-steps of 16 keys, 4 head-dim tiles of 32
 #pragma unroll
       for (int st = 0; st < 2; ++st)

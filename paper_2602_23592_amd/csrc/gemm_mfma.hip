@@ -154,67 +154,59 @@ __global__ void __launch_bounds__(WM* WN * 64)
     // The last slice prefetches itself again and stores it to the idle buffer: harmless, and it keeps
     // the loop body one straight-line block for the instruction scheduler.
     const int ko = min(kt + 1, KT - 1) * (GBK / 8);  // in 16-byte units
-#ifndef KEEP_EXP_NO_GLOBAL
 #pragma unroll
     for (int i = 0; i < A_CH; ++i) a_reg[i] = a_src[i][ko];
 #pragma unroll
     for (int i = 0; i < B_CH; ++i) b_reg[i] = b_src[i][ko];
-#endif
     const uint16_t* cbuf = smem + cur * BUF;
     uint16_t* nbuf = smem + (cur ^ 1) * BUF;
 #pragma unroll
     for (int ks = 0; ks < GBK / 16; ++ks) {
       const int fc = ks & 1, fn = fc ^ 1;
-#ifndef KEEP_EXP_NO_LDSREAD
       if (ks + 1 < GBK / 16) {
+#ifndef KEEP_EXP_NO_LDSREAD
 #pragma unroll
         for (int i = 0; i < MI; ++i)
           af[fn][i] = *reinterpret_cast<const bf16x8*>(cbuf + a_off[ks + 1] + i * 32 * GBK);
 #pragma unroll
         for (int j = 0; j < NI; ++j)
           bfr[fn][j] = *reinterpret_cast<const bf16x8*>(cbuf + b_off[ks + 1] + j * 32 * GBK);
-      }
 #endif
+      } else {
+        // Last k-step of the slice: its operands are already in registers, so the prefetched slice
+        // goes to the other LDS buffer and the workgroup synchronises BEFORE these MFMAs; the first
+        // operand reads of the next slice are then in flight while they run.
+#ifndef KEEP_EXP_NO_LDSWRITE
+#pragma unroll
+        for (int i = 0; i < A_CH; ++i) *reinterpret_cast<u32x4*>(nbuf + a_dst[i]) = a_reg[i];
+#pragma unroll
+        for (int i = 0; i < B_CH; ++i) *reinterpret_cast<u32x4*>(nbuf + BM * GBK + b_dst[i]) = b_reg[i];
+#endif
+        __syncthreads();
+#ifndef KEEP_EXP_NO_LDSREAD
+#pragma unroll
+        for (int i = 0; i < MI; ++i) af[fn][i] = *reinterpret_cast<const bf16x8*>(nbuf + a_off[0] + i * 32 * GBK);
+#pragma unroll
+        for (int j = 0; j < NI; ++j) bfr[fn][j] = *reinterpret_cast<const bf16x8*>(nbuf + b_off[0] + j * 32 * GBK);
+#endif
+      }
 #pragma unroll
       for (int i = 0; i < MI; ++i)
 #pragma unroll
         for (int j = 0; j < NI; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[fc][i], bfr[fc][j], acc[i][j], 0, 0, 0);
-#ifndef KEEP_EXP_NO_LDSWRITE
-      if (ks + 1 == GBK / 16) {
-#pragma unroll
-        for (int i = 0; i < A_CH; ++i) *reinterpret_cast<u32x4*>(nbuf + a_dst[i]) = a_reg[i];
-#pragma unroll
-        for (int i = 0; i < B_CH; ++i) *reinterpret_cast<u32x4*>(nbuf + BM * GBK + b_dst[i]) = b_reg[i];
-      }
-#endif
-    }
-    // interleave: step 0 carries the global prefetch, steps 0..2 the next step's operand reads,
-    // step 3 the LDS stores of the prefetched slice
-    constexpr int MF = MI * NI;            // MFMAs per k-step
-    constexpr int RD = MI + NI;            // operand reads per k-step
-    constexpr int GL = A_CH + B_CH;        // global loads / LDS stores per slice
-#pragma unroll
-    for (int ks = 0; ks < GBK / 16 - 1; ++ks) {
+      // interleave the MFMAs of this k-step with the operand reads issued above (and, in step 0,
+      // with the global prefetch of the next slice)
+      constexpr int MF = MI * NI;      // MFMAs per k-step
+      constexpr int RD = MI + NI;      // operand reads per k-step
+      constexpr int GL = A_CH + B_CH;  // global loads per slice
 #pragma unroll
       for (int r = 0; r < RD; ++r) {
-        __builtin_amdgcn_sched_group_barrier(0x008, MF / RD, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, MF / RD > 0 ? MF / RD : 1, 0);
         __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-        if (ks == 0) __builtin_amdgcn_sched_group_barrier(0x020, GL / RD, 0);
+        if (ks == 0) __builtin_amdgcn_sched_group_barrier(0x020, (GL + RD - 1) / RD, 0);
       }
     }
-#pragma unroll
-    for (int r = 0; r < GL; ++r) {
-      __builtin_amdgcn_sched_group_barrier(0x008, MF / GL > 0 ? MF / GL : 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
-    }
-    __syncthreads();
-#ifndef KEEP_EXP_NO_LDSREAD
-#pragma unroll
-    for (int i = 0; i < MI; ++i) af[0][i] = *reinterpret_cast<const bf16x8*>(nbuf + a_off[0] + i * 32 * GBK);
-#pragma unroll
-    for (int j = 0; j < NI; ++j) bfr[0][j] = *reinterpret_cast<const bf16x8*>(nbuf + b_off[0] + j * 32 * GBK);
-#endif
   }
 
   // ---- epilogue.  acc[i][j][e]: row = i*32 + 8*(e/4) + 4*(lane/32) + e%4, col = j*32 + lane%32

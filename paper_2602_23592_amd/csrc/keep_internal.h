@@ -23,8 +23,12 @@ __host__ __device__ inline float bf16_bits_to_f32(uint16_t b) {
   c.u = (uint32_t)b << 16;
   return c.f;
 }
-// round-to-nearest-even; NaN stays NaN (quiet)
+// round-to-nearest-even; NaN stays NaN (quiet).  On the device this is the hardware conversion
+// (v_cvt_pk_bf16_f32 on gfx950): no branches in the kernels' inner loops.
 __host__ __device__ inline uint16_t f32_to_bf16_bits(float f) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  return __builtin_bit_cast(uint16_t, (__bf16)f);
+#else
   union {
     uint32_t u;
     float f;
@@ -33,6 +37,14 @@ __host__ __device__ inline uint16_t f32_to_bf16_bits(float f) {
   if ((c.u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((c.u >> 16) | 0x0040u);
   c.u += 0x7fffu + ((c.u >> 16) & 1u);
   return (uint16_t)(c.u >> 16);
+#endif
+}
+// two floats -> packed bf16 pair (low half = a)
+__device__ inline uint32_t pack_bf16x2(float a, float b) {
+  typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+  typedef float f32x2_t __attribute__((ext_vector_type(2)));
+  const f32x2_t v = {a, b};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
 
 __device__ inline float ldf(const float* p) { return *p; }
