@@ -3,8 +3,8 @@
 // Both operands are K-contiguous, which is the layout v_mfma_f32_32x32x16_bf16 wants:
 // lane l supplies 8 consecutive k of row (l % 32), k-block (l / 32).  A workgroup owns a
 // BM x BN tile of C; K is walked in 64-deep slices staged through LDS (two buffers, one
-// barrier per slice, next slice prefetched into registers while the current one is
-// multiplied; operand fragments of k-step ks+1 are read while step ks multiplies).  LDS
+// barrier per slice, next slice streamed global -> LDS by global_load_lds_dwordx4 while the
+// current one is multiplied; operand fragments of k-step ks+1 are read while step ks multiplies).  LDS
 // rows are 128 B; their 16-byte chunks are XOR-swizzled by the row index so that the
 // 16-byte operand reads of consecutive rows spread over all banks.  Workgroups are mapped
 // to tiles XCD by XCD so that the tiles resident on one XCD share slices through its L2.
@@ -26,24 +26,26 @@ struct MfmaB {
   int32_t n_parts;
 };
 
-constexpr int GBK = 64;  // K slice
-
+// Element offset of 16-byte chunk `chunk` of row `row` in a [rows][GBK] bf16 tile.  LDS has 64 four-byte
+// banks (256 B per bank line); a row is GBK*2 bytes, so 256/(GBK*2) rows share a line.  The chunk index
+// is XOR-ed with (row / rows-per-line) % chunks-per-row: 16 consecutive rows then cover all 64 banks
+// exactly once for the 16-byte operand reads.
+template <int GBK>
 __device__ __forceinline__ int lds_off(int row, int chunk) {
-  // element offset of 16-byte chunk `chunk` (0..7) of row `row` in a [rows][64] bf16 tile
-  // rows are 128 B, LDS has 64 four-byte banks: two rows fill one bank line, so the chunk is
-  // XOR-ed with (row / 2) % 8 -- 16 consecutive rows then cover all 64 banks exactly once
-  return row * GBK + ((chunk ^ ((row >> 1) & 7)) << 3);
+  constexpr int CPR = GBK / 8, RPL = 128 / GBK;
+  return row * GBK + ((chunk ^ ((row / RPL) & (CPR - 1))) << 3);
 }
 
-template <int BM, int BN, int WM, int WN, int EPI>
+// s_waitcnt vmcnt(n) with the other counters left alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14)
+__device__ __forceinline__ constexpr int vmcnt_imm(int n) { return 0x0F70 | (n & 15) | ((n >> 4) << 14); }
+
+template <int BM, int BN, int WM, int WN, int EPI, int GBK, int NST>
 __global__ void __launch_bounds__(WM* WN * 64)
     k_gemm_mfma(const bf16_t* __restrict__ A, int M, int K, MfmaB B, const bf16_t* __restrict__ B2, int N,
                 const bf16_t* __restrict__ residual, void* __restrict__ Cv, int tiles_m, int tiles_n) {
   constexpr int T = WM * WN * 64;
   constexpr int TM = BM / WM, TN = BN / WN;
   constexpr int MI = TM / 32, NI = TN / 32;
-  constexpr int A_CH = BM * 8 / T, B_CH = BN * 8 / T;  // 16-byte chunks per thread per slice
-  static_assert(BM * 8 % T == 0 && BN * 8 % T == 0, "tile / thread mismatch");
   static_assert(EPI != EPI_SWIGLU_STORE || (NI % 2 == 0), "SwiGLU needs an even number of N tiles per wave");
 
   extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
@@ -56,7 +58,11 @@ __global__ void __launch_bounds__(WM* WN * 64)
   // XCD x therefore takes the x-th eighth of the tile list, and the list walks panels of GM tile rows
   // column by column, so the ~32 workgroups resident on one XCD cover a GM x (32/GM) patch of C and
   // share their A and B slices through that XCD's L2.
+#ifdef KEEP_EXP_GM
+  constexpr int GM = KEEP_EXP_GM;
+#else
   constexpr int GM = (BM >= 256) ? 4 : 8;
+#endif
   const int n_tiles = tiles_m * tiles_n;
   const int per_xcd = (n_tiles + 7) >> 3;
   const int t = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
@@ -69,20 +75,35 @@ __global__ void __launch_bounds__(WM* WN * 64)
   const int m0 = tile_m * BM;
   const int n0 = tile_n * BN;  // in B-tile rows (for SwiGLU: BN/2 output columns per block)
 
-  // ---- global source pointers of this thread's chunks
-  const u32x4* a_src[A_CH];
-  const u32x4* b_src[B_CH];
-  int a_dst[A_CH], b_dst[B_CH];
+  // ---- global -> LDS staging without registers: global_load_lds_dwordx4 writes lane l's 16 bytes at
+  // (wave-uniform LDS base) + 16 l, so one instruction fills 8 consecutive 128-byte tile rows.  The
+  // XOR swizzle is applied on the global side: the lane whose bytes land in physical chunk pc of row r
+  // fetches logical chunk pc ^ ((r / 2) % 8) of that row.
+  constexpr int NW = WM * WN;
+  constexpr int CPR = GBK / 8;      // 16-byte chunks per tile row
+  constexpr int RPL = 128 / GBK;    // tile rows per 256-byte LDS bank line
+  constexpr int RPI = 64 / CPR;     // tile rows filled by one wave-wide load instruction (1 KiB)
+  constexpr int KS = GBK / 16;      // MFMA k-steps per slice
+  constexpr int A_LD = BM / RPI / NW, B_LD = BN / RPI / NW;  // load instructions per wave per slice
+  constexpr int LD = A_LD + B_LD;
+  static_assert(BM % (RPI * NW) == 0 && BN % (RPI * NW) == 0, "tile rows must split evenly over the waves");
+  typedef const void __attribute__((address_space(1))) * gptr_t;
+  typedef void __attribute__((address_space(3))) * lptr_t;
+  const bf16_t* a_src[A_LD];
+  const bf16_t* b_src[B_LD];
 #pragma unroll
-  for (int i = 0; i < A_CH; ++i) {
-    const int q = tid + i * T, r = q >> 3, c = q & 7;
+  for (int i = 0; i < A_LD; ++i) {
+    const int r = (wave * A_LD + i) * RPI + lane / CPR, c = (lane % CPR) ^ ((r / RPL) & (CPR - 1));
+#ifdef KEEP_EXP_A_WRAP
+    const int gm = min(m0 + r, M - 1) % KEEP_EXP_A_WRAP;
+#else
     const int gm = min(m0 + r, M - 1);
-    a_src[i] = reinterpret_cast<const u32x4*>(A + (size_t)gm * K + c * 8);
-    a_dst[i] = lds_off(r, c);
+#endif
+    a_src[i] = A + (size_t)gm * K + c * 8;
   }
 #pragma unroll
-  for (int i = 0; i < B_CH; ++i) {
-    const int q = tid + i * T, r = q >> 3, c = q & 7;
+  for (int i = 0; i < B_LD; ++i) {
+    const int r = (wave * B_LD + i) * RPI + lane / CPR, c = (lane % CPR) ^ ((r / RPL) & (CPR - 1));
     const bf16_t* row;
     if (EPI == EPI_SWIGLU_STORE) {
       // tile row r -> wave column block, gate/up half, column inside the half
@@ -104,8 +125,17 @@ __global__ void __launch_bounds__(WM* WN * 64)
       }
       row = base + (size_t)(gn - first) * K;
     }
-    b_src[i] = reinterpret_cast<const u32x4*>(row + c * 8);
-    b_dst[i] = lds_off(r, c);
+    b_src[i] = row + c * 8;
+  }
+  // issue the loads of K-slice `slice` into LDS stage `stage`
+#define GEMM_STAGE(slice, stage)                                                                               \
+  {                                                                                                            \
+    uint16_t* sa_ = smem + (stage) * BUF + (wave * A_LD) * RPI * GBK;                                          \
+    uint16_t* sb_ = smem + (stage) * BUF + BM * GBK + (wave * B_LD) * RPI * GBK;                               \
+    _Pragma("unroll") for (int i = 0; i < A_LD; ++i)                                                           \
+        __builtin_amdgcn_global_load_lds((gptr_t)(a_src[i] + (size_t)(slice) * GBK), (lptr_t)(sa_ + i * RPI * GBK), 16, 0, 0); \
+    _Pragma("unroll") for (int i = 0; i < B_LD; ++i)                                                           \
+        __builtin_amdgcn_global_load_lds((gptr_t)(b_src[i] + (size_t)(slice) * GBK), (lptr_t)(sb_ + i * RPI * GBK), 16, 0, 0); \
   }
 
   f32x16 acc[MI][NI];
@@ -116,29 +146,23 @@ __global__ void __launch_bounds__(WM* WN * 64)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  u32x4 a_reg[A_CH], b_reg[B_CH];
+  // NST LDS stages: slices kt+1 .. kt+NST-1 are in flight (or landed) while slice kt is multiplied
   const int KT = K / GBK;
-  // prologue: slice 0 -> LDS buffer 0
 #pragma unroll
-  for (int i = 0; i < A_CH; ++i) a_reg[i] = a_src[i][0];
-#pragma unroll
-  for (int i = 0; i < B_CH; ++i) b_reg[i] = b_src[i][0];
-#pragma unroll
-  for (int i = 0; i < A_CH; ++i) *reinterpret_cast<u32x4*>(smem + a_dst[i]) = a_reg[i];
-#pragma unroll
-  for (int i = 0; i < B_CH; ++i) *reinterpret_cast<u32x4*>(smem + BM * GBK + b_dst[i]) = b_reg[i];
+  for (int p = 0; p < NST - 1; ++p) GEMM_STAGE(min(p, KT - 1), p)
+  __builtin_amdgcn_s_waitcnt(vmcnt_imm((NST - 2) * LD));  // slice 0 has landed in LDS
   __syncthreads();
 
   const int a_row0 = wm * TM + (lane & 31);
   const int b_row0 = wn * TN + (lane & 31);
   const int kg = lane >> 5;
-  // LDS element offsets of this lane's operand chunks for k-step 0..3 (rows differ by multiples of 32,
+  // LDS element offsets of this lane's operand chunks per k-step (rows differ by multiples of 32,
   // which leaves the swizzle term unchanged, so one offset per k-step serves every row tile)
-  int a_off[GBK / 16], b_off[GBK / 16];
+  int a_off[KS], b_off[KS];
 #pragma unroll
-  for (int ks = 0; ks < GBK / 16; ++ks) {
-    a_off[ks] = lds_off(a_row0, ks * 2 + kg);
-    b_off[ks] = BM * GBK + lds_off(b_row0, ks * 2 + kg);
+  for (int ks = 0; ks < KS; ++ks) {
+    a_off[ks] = lds_off<GBK>(a_row0, ks * 2 + kg);
+    b_off[ks] = BM * GBK + lds_off<GBK>(b_row0, ks * 2 + kg);
   }
 
   // operand fragments, double-buffered over k-steps: the loads of step ks+1 are in flight while the
@@ -149,65 +173,54 @@ __global__ void __launch_bounds__(WM* WN * 64)
 #pragma unroll
   for (int j = 0; j < NI; ++j) bfr[0][j] = *reinterpret_cast<const bf16x8*>(smem + b_off[0] + j * 32 * GBK);
 
+  int stage = 0;
   for (int kt = 0; kt < KT; ++kt) {
-    const int cur = kt & 1;
-    // The last slice prefetches itself again and stores it to the idle buffer: harmless, and it keeps
-    // the loop body one straight-line block for the instruction scheduler.
-    const int ko = min(kt + 1, KT - 1) * (GBK / 8);  // in 16-byte units
+    // The stage that held slice kt-1 was last read before the previous barrier, so slice kt+NST-1
+    // can stream into it now.  (Past the end the last slice is fetched again: harmless, and it keeps
+    // the loop body one straight-line block for the instruction scheduler.)
+    const int free_stage = stage == 0 ? NST - 1 : stage - 1;
+    GEMM_STAGE(min(kt + NST - 1, KT - 1), free_stage)
+    const int next_stage = stage + 1 == NST ? 0 : stage + 1;
+    const uint16_t* cbuf = smem + stage * BUF;
+    const uint16_t* nbuf = smem + next_stage * BUF;
 #pragma unroll
-    for (int i = 0; i < A_CH; ++i) a_reg[i] = a_src[i][ko];
-#pragma unroll
-    for (int i = 0; i < B_CH; ++i) b_reg[i] = b_src[i][ko];
-    const uint16_t* cbuf = smem + cur * BUF;
-    uint16_t* nbuf = smem + (cur ^ 1) * BUF;
-#pragma unroll
-    for (int ks = 0; ks < GBK / 16; ++ks) {
+    for (int ks = 0; ks < KS; ++ks) {
       const int fc = ks & 1, fn = fc ^ 1;
-      if (ks + 1 < GBK / 16) {
-#ifndef KEEP_EXP_NO_LDSREAD
+      if (ks + 1 < KS) {
 #pragma unroll
         for (int i = 0; i < MI; ++i)
           af[fn][i] = *reinterpret_cast<const bf16x8*>(cbuf + a_off[ks + 1] + i * 32 * GBK);
 #pragma unroll
         for (int j = 0; j < NI; ++j)
           bfr[fn][j] = *reinterpret_cast<const bf16x8*>(cbuf + b_off[ks + 1] + j * 32 * GBK);
-#endif
       } else {
-        // Last k-step of the slice: its operands are already in registers, so the prefetched slice
-        // goes to the other LDS buffer and the workgroup synchronises BEFORE these MFMAs; the first
-        // operand reads of the next slice are then in flight while they run.
-#ifndef KEEP_EXP_NO_LDSWRITE
-#pragma unroll
-        for (int i = 0; i < A_CH; ++i) *reinterpret_cast<u32x4*>(nbuf + a_dst[i]) = a_reg[i];
-#pragma unroll
-        for (int i = 0; i < B_CH; ++i) *reinterpret_cast<u32x4*>(nbuf + BM * GBK + b_dst[i]) = b_reg[i];
-#endif
+        // Last k-step of the slice: its operands are already in registers, so the workgroup waits for
+        // slice kt+1 and synchronises BEFORE these MFMAs; the first operand reads of the next slice
+        // are then in flight while they run.
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm((NST - 2) * LD));
         __syncthreads();
-#ifndef KEEP_EXP_NO_LDSREAD
 #pragma unroll
         for (int i = 0; i < MI; ++i) af[fn][i] = *reinterpret_cast<const bf16x8*>(nbuf + a_off[0] + i * 32 * GBK);
 #pragma unroll
         for (int j = 0; j < NI; ++j) bfr[fn][j] = *reinterpret_cast<const bf16x8*>(nbuf + b_off[0] + j * 32 * GBK);
-#endif
       }
 #pragma unroll
       for (int i = 0; i < MI; ++i)
 #pragma unroll
         for (int j = 0; j < NI; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[fc][i], bfr[fc][j], acc[i][j], 0, 0, 0);
-      // interleave the MFMAs of this k-step with the operand reads issued above (and, in step 0,
-      // with the global prefetch of the next slice)
-      constexpr int MF = MI * NI;      // MFMAs per k-step
-      constexpr int RD = MI + NI;      // operand reads per k-step
-      constexpr int GL = A_CH + B_CH;  // global loads per slice
+      // interleave the MFMAs of this k-step with the operand reads issued above
+      constexpr int MF = MI * NI;  // MFMAs per k-step
+      constexpr int RD = MI + NI;  // operand reads per k-step
 #pragma unroll
       for (int r = 0; r < RD; ++r) {
         __builtin_amdgcn_sched_group_barrier(0x008, MF / RD > 0 ? MF / RD : 1, 0);
         __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-        if (ks == 0) __builtin_amdgcn_sched_group_barrier(0x020, (GL + RD - 1) / RD, 0);
       }
     }
+    stage = next_stage;
   }
+#undef GEMM_STAGE
 
   // ---- epilogue.  acc[i][j][e]: row = i*32 + 8*(e/4) + 4*(lane/32) + e%4, col = j*32 + lane%32
   const int col_l = lane & 31;
@@ -244,17 +257,17 @@ __global__ void __launch_bounds__(WM* WN * 64)
   }
 }
 
-template <int BM, int BN, int WM, int WN>
+template <int BM, int BN, int WM, int WN, int GBK, int NST>
 static void launch_cfg(const bf16_t* A, int M, int K, const MfmaB& b, const bf16_t* B2, int N, int epilogue,
                        const bf16_t* residual, void* C, hipStream_t s) {
-  const size_t sh = (size_t)2 * (BM + BN) * GBK * sizeof(uint16_t);
+  const size_t sh = (size_t)NST * (BM + BN) * GBK * sizeof(uint16_t);
   const dim3 block(WM * WN * 64);
   const int n_tile_rows = epilogue == EPI_SWIGLU_STORE ? 2 * N : N;  // B-tile rows to cover
   const int tiles_n = n_tile_rows / BN, tiles_m = (M + BM - 1) / BM;
   const dim3 grid(8 * ((tiles_m * tiles_n + 7) / 8));
 #define GO(E)                                                                                              \
   do {                                                                                                     \
-    auto kern = k_gemm_mfma<BM, BN, WM, WN, E>;                                                            \
+    auto kern = k_gemm_mfma<BM, BN, WM, WN, E, GBK, NST>;                                                            \
     static bool attr_set = false;                                                                          \
     if (!attr_set) {                                                                                       \
       (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, \
@@ -294,11 +307,14 @@ void launch_gemm_mfma(const bf16_t* A, int32_t M, int32_t K, const GemmB& B, con
   // times over; otherwise 128x128 tiles, whose finer grain loses less to the last partial wave of tiles.
   const long tiles256 = (long)((M + 255) / 256) * (rows / 256);
   if (aligned256 && rows % 256 == 0 && tiles256 >= 1024)
-    launch_cfg<256, 256, 4, 2>(A, M, K, b, b2, N, epilogue, residual, C, s);
+#ifndef KEEP_EXP_CFG
+#define KEEP_EXP_CFG 256, 256, 4, 2, 64, 2
+#endif
+    launch_cfg<KEEP_EXP_CFG>(A, M, K, b, b2, N, epilogue, residual, C, s);
   else if (rows % 128 == 0)
-    launch_cfg<128, 128, 2, 2>(A, M, K, b, b2, N, epilogue, residual, C, s);
+    launch_cfg<128, 128, 2, 2, 64, 2>(A, M, K, b, b2, N, epilogue, residual, C, s);
   else
-    launch_cfg<64, 64, 1, 1>(A, M, K, b, b2, N, epilogue, residual, C, s);
+    launch_cfg<64, 64, 1, 1, 64, 2>(A, M, K, b, b2, N, epilogue, residual, C, s);
 }
 
 }  // namespace keep

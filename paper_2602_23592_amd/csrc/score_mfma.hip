@@ -47,10 +47,10 @@ size_t score_mfma_stage_ints(int32_t max_rows, int32_t max_groups) {
 }
 
 template <int CH>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(256, 2)
     k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ kc, const float* __restrict__ lse,
                  const RowTile* __restrict__ tiles, int n_rt, int n_keys, int n_q_heads, int n_kv_heads,
-                 float scale_log2e, float* __restrict__ colmass, int col_ld) {
+                 int hk_per_slice, float scale_log2e, float* __restrict__ colmass, int col_ld) {
   __shared__ __attribute__((aligned(16))) uint16_t s_k[2 * S_KEYS * S_KSTRIDE];
   __shared__ float s_col[4][S_CHUNK];
   __shared__ __attribute__((aligned(16))) float s_l2[4][CH][32];  // rows' log-sum-exp, log2 domain
@@ -87,13 +87,18 @@ __global__ void __launch_bounds__(256)
   *reinterpret_cast<uint4*>(&s_k[(BUFI) * S_KEYS * S_KSTRIDE + (ld_row + 16 * (I)) * S_KSTRIDE + ld_c * 8]) = KR;
 #define SC_SSTORE(BUFI) SC_SSTORE1(kreg0, 0, BUFI) SC_SSTORE1(kreg1, 1, BUFI) SC_SSTORE1(kreg2, 2, BUFI) SC_SSTORE1(kreg3, 3, BUFI)
 
-  for (int hk = 0; hk < n_kv_heads; ++hk) {
+  // blockIdx.z selects a slice of the KV heads (small problems are spread over more workgroups;
+  // the slices' column sums are added in slice order by the next pass)
+  const int hk_begin = blockIdx.z * hk_per_slice;
+  const int hk_end = min(n_kv_heads, hk_begin + hk_per_slice);
+  for (int hk = hk_begin; hk < hk_end; ++hk) {
     for (int hc = 0; hc < rep; hc += CH) {
-      // Q operand for CH heads; the rows' log-sum-exp goes to LDS (+inf for rows past the tile's end)
+      const int nch = min(CH, rep - hc);  // heads in this pass (the last pass may be short)
+      // Q operand for up to CH heads; the rows' log-sum-exp goes to LDS (+inf for rows past the tile's end)
       bf16x8 qf[CH][8];
 #pragma unroll
       for (int j = 0; j < CH; ++j) {
-        const int head = hk * rep + hc + j;
+        const int head = hk * rep + min(hc + j, rep - 1);
         const bf16_t* qp = q + ((size_t)q_row * n_q_heads + head) * SDH + g * 8;
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) qf[j][ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 16);
@@ -102,8 +107,8 @@ __global__ void __launch_bounds__(256)
       if (g == 0) {
 #pragma unroll
         for (int j = 0; j < CH; ++j) {
-          const int head = hk * rep + hc + j;
-          s_l2[wave][j][lq] = (has_tile && lq < tl.nrows)
+          const int head = hk * rep + min(hc + j, rep - 1);
+          s_l2[wave][j][lq] = (has_tile && lq < tl.nrows && j < nch)
                                   ? lse[(size_t)(tl.row0 + lq) * n_q_heads + head] * 1.4426950408889634f
                                   : INFINITY;
         }
@@ -123,10 +128,13 @@ __global__ void __launch_bounds__(256)
             const uint16_t* krow = &s_k[cur * S_KEYS * S_KSTRIDE + (st * 32 + lq) * S_KSTRIDE + g * 8];
 #pragma unroll
             for (int ks = 0; ks < 8; ++ks) kf[ks] = *reinterpret_cast<const bf16x8*>(krow + ks * 16);
+            // only tiles that touch the diagonal (or the end of the key list) need the per-element test
+            const bool need_mask = (k0 + S_KEYS - 1 > tl.row0) || (k0 + S_KEYS > n_keys);
             const bool key_ok = key < n_keys;
             float csum = 0.f;
 #pragma unroll
             for (int j = 0; j < CH; ++j) {
+              if (j >= nch) break;
               f32x16 acc;
 #pragma unroll
               for (int e = 0; e < 16; ++e) acc[e] = 0.f;
@@ -141,8 +149,8 @@ __global__ void __launch_bounds__(256)
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                   const int row = tl.row0 + 8 * e4 + 4 * g + i;
-                  const float p = __builtin_amdgcn_exp2f(acc[4 * e4 + i] * scale_log2e - lv[i]);
-                  csum += (key <= row && key_ok) ? p : 0.f;
+                  const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(acc[4 * e4 + i], scale_log2e, -lv[i]));
+                  csum += (!need_mask || (key <= row && key_ok)) ? p : 0.f;
                 }
               }
             }
@@ -161,15 +169,15 @@ __global__ void __launch_bounds__(256)
 #undef SC_SSTORE1
   // column sums of this wave's row tile for the keys of the chunk
   if (has_tile) {
-    float* dst = colmass + (size_t)rt * col_ld + c0;
+    float* dst = colmass + ((size_t)blockIdx.z * n_rt + rt) * col_ld + c0;
     for (int i = lane; i < key_end - c0; i += 64) dst[i] = s_col[wave][i];
   }
 }
 
 // rtmass[rt, b] = sum of colmass[rt, keys of block b that the tile can see], for b before the tile's block
 __global__ void __launch_bounds__(256)
-    k_score_rt_reduce(const float* __restrict__ colmass, int col_ld, const RowTile* __restrict__ tiles, int n_rt,
-                      const int32_t* __restrict__ row_start, int m, float* __restrict__ rtmass) {
+    k_score_rt_reduce(const float* __restrict__ colmass, int col_ld, int n_slices, const RowTile* __restrict__ tiles,
+                      int n_rt, const int32_t* __restrict__ row_start, int m, float* __restrict__ rtmass) {
   const int lane = threadIdx.x & 63;
   const long w = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
   if (w >= (long)n_rt * m) return;
@@ -179,8 +187,10 @@ __global__ void __launch_bounds__(256)
   if (b < tl.slot) {
     const int last = tl.row0 + tl.nrows - 1;
     const int s0 = row_start[b], s1 = min(row_start[b + 1], last + 1);
-    const float* src = colmass + (size_t)rt * col_ld;
-    for (int s = s0 + lane; s < s1; s += 64) sum += src[s];
+    for (int z = 0; z < n_slices; ++z) {
+      const float* src = colmass + ((size_t)z * n_rt + rt) * col_ld;
+      for (int s = s0 + lane; s < s1; s += 64) sum += src[s];
+    }
   }
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off, 64);
@@ -236,24 +246,28 @@ void launch_score_mfma(const bf16_t* q, const bf16_t* kc, const float* lse, cons
   const int n_keys = h_row_start[m];
   const int rep = n_q_heads / n_kv_heads;
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)SDH);
-  const dim3 grid((n_rt + 3) / 4, (n_keys + S_CHUNK - 1) / S_CHUNK);
+  // KV-head slices: as many as it takes to have ~1024 workgroups, within the column-sum scratch
+  int n_slices = 1;
+  const long base_blocks = (long)((n_rt + 3) / 4) * ((n_keys + S_CHUNK - 1) / S_CHUNK);
+  while (n_slices < n_kv_heads && base_blocks * n_slices < 1024 && (long)(2 * n_slices) * n_rt <= cap &&
+         n_kv_heads % (2 * n_slices) == 0)
+    n_slices *= 2;
+  const int hk_per_slice = n_kv_heads / n_slices;
+  const dim3 grid((n_rt + 3) / 4, (n_keys + S_CHUNK - 1) / S_CHUNK, n_slices);
 #define GO(CH)                                                                                                      \
   hipLaunchKernelGGL(k_score_mfma<CH>, grid, dim3(256), 0, s, q, kc, lse, d_tiles, n_rt, n_keys, n_q_heads,         \
-                     n_kv_heads, scale_log2e, colmass, max_rows)
-  if (rep % 7 == 0)
-    GO(7);
-  else if (rep % 5 == 0)
-    GO(5);
-  else if (rep % 4 == 0)
-    GO(4);
-  else if (rep % 2 == 0)
+                     n_kv_heads, hk_per_slice, scale_log2e, colmass, max_rows)
+  // up to three query heads per pass keep two workgroups resident per CU (VALU of one overlaps MFMA of the other)
+  if (rep >= 3)
+    GO(3);
+  else if (rep == 2)
     GO(2);
   else
     GO(1);
 #undef GO
   const long waves = (long)n_rt * m;
-  hipLaunchKernelGGL(k_score_rt_reduce, dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, s, colmass, max_rows, d_tiles,
-                     n_rt, d_row_start, m, rtmass);
+  hipLaunchKernelGGL(k_score_rt_reduce, dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, s, colmass, max_rows,
+                     n_slices, d_tiles, n_rt, d_row_start, m, rtmass);
   hipLaunchKernelGGL(k_score_finish_tiles, dim3((m + 255) / 256, m + 1), dim3(256), 0, s, rtmass, d_tile_start,
                      d_row_start, m, n_q_heads, S);
 }
