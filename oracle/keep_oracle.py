@@ -240,7 +240,8 @@ def rows_of(groups: Sequence[int], group_len: Sequence[int], instr_len: int) -> 
 # ----------------------------------------------------------------------------
 def selective_layer(sh: Shape, w: Dict[str, np.ndarray], x: np.ndarray, groups: Sequence[int],
                     group_len: Sequence[int], instr_len: int, k_hat: np.ndarray, v_hat: np.ndarray,
-                    want_scores: bool = True, only_rows: Optional[np.ndarray] = None):
+                    want_scores: bool = True, only_rows: Optional[np.ndarray] = None,
+                    score_blocks: Optional[Sequence[int]] = None):
     """Recompute the KV of the memories in `groups` (and of the instruction) over the
     joined cache of this layer.
 
@@ -254,6 +255,12 @@ def selective_layer(sh: Shape, w: Dict[str, np.ndarray], x: np.ndarray, groups: 
     everything after it is evaluated for just those rows (K/V are still refreshed
     for all rows, since every later row attends to them) and x_out has that many
     rows.  S is then not available.
+
+    score_blocks: optional list of source blocks (indices into `groups`, or
+    len(groups) for the query); attention is then evaluated for all rows of just
+    those blocks and S comes back with only those rows filled (NaN elsewhere);
+    x_out and lse hold those blocks' rows in order.  For sampled checks at sizes
+    where the full matrix is too slow.
     """
     groups = sorted(int(g) for g in groups)
     assert instr_len >= 1 and min(group_len) >= 1      # a query is needed; blocks are non-empty
@@ -266,7 +273,16 @@ def selective_layer(sh: Shape, w: Dict[str, np.ndarray], x: np.ndarray, groups: 
     k_hat[pos] = round_to_storage(k, sh.storage)
     v_hat[pos] = round_to_storage(v, sh.storage)
 
-    if only_rows is not None:
+    m = len(groups)
+    block_starts = np.zeros(m + 2, dtype=np.int64)
+    block_starts[1:m + 1] = np.cumsum([group_len[g] for g in groups])
+    block_starts[m + 1] = block_starts[m] + instr_len
+    if score_blocks is not None:
+        assert only_rows is None and want_scores
+        score_blocks = sorted(int(b) for b in score_blocks)
+        only = np.concatenate([np.arange(block_starts[b], block_starts[b + 1]) for b in score_blocks])
+        q, pos_q, x_res = q[only], pos[only], x[only]
+    elif only_rows is not None:
         assert not want_scores
         q, pos_q, x_res = q[only_rows], pos[only_rows], x[only_rows]
     else:
@@ -277,13 +293,17 @@ def selective_layer(sh: Shape, w: Dict[str, np.ndarray], x: np.ndarray, groups: 
     o = np.empty_like(q)
     lse = np.empty((n, sh.n_q_heads), dtype=q.dtype)
 
-    # partition of the n_l rows and of the N keys into blocks, for the score sums
-    m = len(groups)
+    # partition of the evaluated rows and of the N keys into blocks, for the score sums
     if want_scores:
-        row_starts = np.zeros(m + 1, dtype=np.int64)
-        row_starts[1:] = np.cumsum([group_len[g] for g in groups])      # block m = instruction rows
+        if score_blocks is None:
+            row_starts = block_starts[:m + 1]                           # block m = instruction rows
+            n_row_blocks = m + 1
+        else:
+            lens = [block_starts[b + 1] - block_starts[b] for b in score_blocks]
+            row_starts = np.concatenate([[0], np.cumsum(lens)[:-1]]).astype(np.int64)
+            n_row_blocks = len(score_blocks)
         key_starts = off.copy()                                         # G group blocks, block G = instruction
-        mass = np.zeros((m + 1, len(group_len) + 1), dtype=q.dtype)
+        mass = np.zeros((n_row_blocks, len(group_len) + 1), dtype=q.dtype)
 
     for h in range(sh.n_q_heads):
         s = (q[:, h, :] @ k_hat[:, h // rep, :].T) / np.sqrt(float(sh.head_dim))
@@ -301,8 +321,14 @@ def selective_layer(sh: Shape, w: Dict[str, np.ndarray], x: np.ndarray, groups: 
 
     x_out = output_and_ffn(sh, w, x_res, o)
     scores = None
-    if want_scores:
+    if want_scores and score_blocks is None:
         scores = scores_from_mass(mass, groups, group_len, instr_len, sh.n_q_heads)
+    elif want_scores:
+        full = np.zeros((m + 1, len(group_len) + 1), dtype=mass.dtype)
+        full[score_blocks] = mass
+        scores = scores_from_mass(full, groups, group_len, instr_len, sh.n_q_heads)
+        missing = [b for b in range(m + 1) if b not in score_blocks]
+        scores[missing] = np.nan
     return x_out, lse, scores
 
 

@@ -5,7 +5,7 @@
 // whatever lies between the recomputed rows.  A workgroup owns one KV head and 128
 // "query rows" (a recomputed row paired with one of the query heads of that KV head);
 // each of its 4 waves owns 32 of them.  K/V tiles of 64 keys are staged through LDS
-// (two buffers, next tile prefetched into registers).
+// (two buffers; the next tile streams global -> LDS while the current one is used).
 //
 // The scores are computed transposed, S^T = K . Q^T, so that a lane owns one query row
 // (column l % 32 of the 32x32 MFMA result) and the keys sit in its registers: row max and
@@ -33,9 +33,7 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 constexpr int DH = 128;
 constexpr int KT_KEYS = 64;
-constexpr int KSTRIDE = 136;  // bf16 elements per K row in LDS (272 B: 16-byte reads of 16 rows hit 64 banks)
-constexpr int VSTRIDE = 144;  // bf16 elements per V row in LDS (288 B: 4 rows x 32 B of a transpose read are disjoint)
-constexpr int ATT_BUF = KT_KEYS * KSTRIDE + KT_KEYS * VSTRIDE;  // elements per buffer
+constexpr int ATT_BUF = 2 * KT_KEYS * DH;  // elements per LDS buffer: K tile then V tile
 
 typedef __attribute__((ext_vector_type(8))) short s16x8;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
@@ -91,50 +89,84 @@ __global__ void __launch_bounds__(256, 2)
     for (int e = 0; e < 16; ++e) oacc[nt][e] = 0.f;
   float m_run = M_FLOOR, l_run = 0.f;
 
-  // global -> LDS staging: 4 chunks of K and 4 of V per thread per tile
-  const int ld_row = tid >> 4, ld_c = tid & 15;  // rows ld_row + 16 i
-  uint4 kreg0, kreg1, kreg2, kreg3, vreg0, vreg1, vreg2, vreg3;
-#define ATT_GLOAD1(KR, VR, I, KT)                                                        \
-  {                                                                                      \
-    const int key_ = min((KT) * KT_KEYS + ld_row + 16 * (I), n_total - 1);               \
-    const size_t off_ = ((size_t)key_ * n_kv_heads + hk) * DH + ld_c * 8;                \
-    KR = *reinterpret_cast<const uint4*>(k_cache + off_);                                \
-    VR = *reinterpret_cast<const uint4*>(v_cache + off_);                                \
+  // ---- LDS tiles: per buffer K [64 keys][256 B] then V [64 keys][256 B], no padding; 16-byte chunks are
+  // XOR-swizzled so that operand reads are bank-conflict free: K chunk c of row r sits at c ^ (r % 16)
+  // (16 consecutive rows x one 16-byte chunk = all 64 banks), V chunk c of row r at c ^ (2 (r % 8))
+  // (the 4 rows x 32 bytes of one transpose read fall on disjoint banks).
+  // Global -> LDS goes through global_load_lds_dwordx4 (lane l's 16 bytes land at base + 16 l, so one
+  // instruction fills 4 rows); the swizzle is applied to the global address each lane fetches.
+  typedef const void __attribute__((address_space(1))) * gptr_t;
+  typedef void __attribute__((address_space(3))) * lptr_t;
+  typedef s16x4 __attribute__((address_space(3))) * lds_s16x4_ptr;
+  const int ld_row = wave * 16 + (lane >> 4);  // + 4 i, i < 4
+  const int ld_pc = lane & 15;
+#define ATT_STAGE(KT, BUFI)                                                                                     \
+  {                                                                                                             \
+    _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                                             \
+      const int row_ = ld_row + 4 * i;                                                                          \
+      const int key_ = min((KT) * KT_KEYS + row_, n_total - 1);                                                 \
+      const size_t g_ = ((size_t)key_ * n_kv_heads + hk) * DH;                                                  \
+      uint16_t* l_ = smem + (BUFI) * ATT_BUF + (wave * 16 + 4 * i) * DH;                                        \
+      __builtin_amdgcn_global_load_lds((gptr_t)(k_cache + g_ + ((ld_pc ^ (row_ & 15)) << 3)), (lptr_t)l_, 16, 0, 0); \
+      __builtin_amdgcn_global_load_lds((gptr_t)(v_cache + g_ + ((ld_pc ^ ((row_ & 7) << 1)) << 3)),             \
+                                       (lptr_t)(l_ + KT_KEYS * DH), 16, 0, 0);                                  \
+    }                                                                                                           \
   }
-#define ATT_GLOAD(KT) \
-  ATT_GLOAD1(kreg0, vreg0, 0, KT) ATT_GLOAD1(kreg1, vreg1, 1, KT) ATT_GLOAD1(kreg2, vreg2, 2, KT) ATT_GLOAD1(kreg3, vreg3, 3, KT)
-#define ATT_SSTORE1(KR, VR, I, BUFI)                                                                      \
-  {                                                                                                       \
-    uint16_t* sk_ = smem + (BUFI) * ATT_BUF;                                                              \
-    *reinterpret_cast<uint4*>(sk_ + (ld_row + 16 * (I)) * KSTRIDE + ld_c * 8) = KR;                       \
-    *reinterpret_cast<uint4*>(sk_ + KT_KEYS * KSTRIDE + (ld_row + 16 * (I)) * VSTRIDE + ld_c * 8) = VR;   \
+  // element offsets of this lane's operand chunks inside a tile
+  int koff[8];  // K row lq, logical chunk 2 ks + g
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) koff[ks] = lq * DH + (((2 * ks + g) ^ (lq & 15)) << 3);
+  int voff[4];  // V row 4 g + (lane % 16) / 4 of a 16-key step, 8 bytes of head-dim tile nt
+  {
+    const int vr = 4 * g + ((lane & 15) >> 2);
+    const int cl = 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);
+#pragma unroll
+    for (int nt = 0; nt < 4; ++nt) voff[nt] = vr * DH + (((4 * nt + cl) ^ ((vr & 7) << 1)) << 3) + 4 * (lane & 1);
   }
-#define ATT_SSTORE(BUFI) \
-  ATT_SSTORE1(kreg0, vreg0, 0, BUFI) ATT_SSTORE1(kreg1, vreg1, 1, BUFI) ATT_SSTORE1(kreg2, vreg2, 2, BUFI) ATT_SSTORE1(kreg3, vreg3, 3, BUFI)
-  ATT_GLOAD(kt0)
-  ATT_SSTORE(0)
+
+  ATT_STAGE(kt0, 0)
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): the tile has landed in LDS
   __syncthreads();
 
   for (int kt = kt0; kt < n_kt; ++kt) {
     const int cur = (kt - kt0) & 1;
     const int k0 = kt * KT_KEYS;
-    if (kt + 1 < n_kt) { ATT_GLOAD(kt + 1) }
+    // every wave finished reading the other buffer before the barrier that ended the last iteration
+    if (kt + 1 < n_kt) ATT_STAGE(kt + 1, cur ^ 1)
     if (k0 <= wmax) {
       const uint16_t* sk = smem + cur * ATT_BUF;
-      const uint16_t* sv = sk + KT_KEYS * KSTRIDE;
-      // ---- S^T = K . Q^T for the two 32-key halves of the tile
+      const uint16_t* sv = sk + KT_KEYS * DH;
+      // ---- S^T = K . Q^T for the two 32-key halves; K operands are read four k-steps ahead
       f32x16 sacc[2];
 #pragma unroll
-      for (int st = 0; st < 2; ++st) {
+      for (int st = 0; st < 2; ++st)
 #pragma unroll
         for (int e = 0; e < 16; ++e) sacc[st][e] = 0.f;
-        const uint16_t* krow = sk + (st * 32 + lq) * KSTRIDE + g * 8;
+      bf16x8 kfa[4], kfb[4];
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
-          const bf16x8 kf = *reinterpret_cast<const bf16x8*>(krow + ks * 16);
-          sacc[st] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], sacc[st], 0, 0, 0);
-        }
+      for (int i = 0; i < 4; ++i) kfa[i] = *reinterpret_cast<const bf16x8*>(sk + koff[i]);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) kfb[i] = *reinterpret_cast<const bf16x8*>(sk + koff[4 + i]);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) sacc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfa[i], qf[i], sacc[0], 0, 0, 0);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) kfa[i] = *reinterpret_cast<const bf16x8*>(sk + 32 * DH + koff[i]);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) sacc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfb[i], qf[4 + i], sacc[0], 0, 0, 0);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) kfb[i] = *reinterpret_cast<const bf16x8*>(sk + 32 * DH + koff[4 + i]);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) sacc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfa[i], qf[i], sacc[1], 0, 0, 0);
+      // V^T operands of the first 16-key step: in flight during the softmax arithmetic
+      s16x4 vlo[2][4], vhi[2][4];
+#pragma unroll
+      for (int nt = 0; nt < 4; ++nt) {
+        vlo[0][nt] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(sv + voff[nt]));
+        vhi[0][nt] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(sv + 8 * DH + voff[nt]));
       }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) sacc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfb[i], qf[4 + i], sacc[1], 0, 0, 0);
+
       // ---- causal mask, running max (raw scores; the scale is folded into the exponent's fma)
       const bool need_mask = k0 + KT_KEYS - 1 > wmin;
       if (need_mask) {
@@ -175,30 +207,33 @@ __global__ void __launch_bounds__(256, 2)
           pk[st][e >> 1] = pack_bf16x2(p0, p1);
         }
       l_run += psum;
-      // ---- O^T += V^T . P^T : 4 k-steps of 16 keys, 4 head-dim tiles of 32
+      // ---- O^T += V^T . P^T : 4 k-steps of 16 keys, 4 head-dim tiles of 32; the V^T operands of step
+      // s+1 are read while step s multiplies.  A operand slot (g, i) holds key base + 8*(i/4) + 4*g + i%4:
+      // exactly the keys of P^T's registers, so P needs no shuffle.
 #pragma unroll
-      for (int st = 0; st < 2; ++st)
-#pragma unroll
-        for (int hh = 0; hh < 2; ++hh) {
-          u32x4 pu;
-#pragma unroll
-          for (int i = 0; i < 4; ++i) pu[i] = pk[st][hh * 4 + i];
-          const bf16x8 pf = __builtin_bit_cast(bf16x8, pu);
-          // A operand slot (g, i) holds key base + 8*(i/4) + 4*g + i%4: the keys of P^T's registers
-          const int key_l = st * 32 + hh * 16 + 4 * g + ((lane & 15) >> 2);
-          const uint16_t* vbase = sv + key_l * VSTRIDE + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+      for (int step = 0; step < 4; ++step) {
+        const int st = step >> 1, hh = step & 1, vc = step & 1, vn = vc ^ 1;
+        if (step + 1 < 4) {
+          const uint16_t* vb = sv + (step + 1) * 16 * DH;
 #pragma unroll
           for (int nt = 0; nt < 4; ++nt) {
-            typedef s16x4 __attribute__((address_space(3))) * lds_s16x4_ptr;
-            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(vbase + nt * 32));
-            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(vbase + nt * 32 + 8 * VSTRIDE));
-            oacc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cat4(lo, hi), pf, oacc[nt], 0, 0, 0);
+            vlo[vn][nt] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(vb + voff[nt]));
+            vhi[vn][nt] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(vb + 8 * DH + voff[nt]));
           }
         }
+        u32x4 pu;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) pu[i] = pk[st][hh * 4 + i];
+        const bf16x8 pf = __builtin_bit_cast(bf16x8, pu);
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt)
+          oacc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cat4(vlo[vc][nt], vhi[vc][nt]), pf, oacc[nt], 0, 0, 0);
+      }
     }
-    if (kt + 1 < n_kt) { ATT_SSTORE(cur ^ 1) }
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): the next tile has landed
     __syncthreads();
   }
+#undef ATT_STAGE
 
   // ---- finish: combine the two lane halves' sums, then either normalise and write O and LSE, or
   // (cut tile) store the un-normalised partial with its max and sum for k_attn_combine
@@ -237,10 +272,6 @@ __global__ void __launch_bounds__(256, 2)
     }
   }
 }
-#undef ATT_GLOAD
-#undef ATT_GLOAD1
-#undef ATT_SSTORE
-#undef ATT_SSTORE1
 
 // Merge the partials of one cut tile and one KV head: rows q = 0..127, chunks in order.
 __global__ void __launch_bounds__(256)

@@ -21,6 +21,8 @@ CASES = {
     "rep5_multi_tile": (_shape(2, 640, 10, 2, 1280), [300, 257, 411, 128, 96, 350, 290, 333], 130),
     "rep7_one_kv_head": (_shape(1, 896, 7, 1, 640), [70, 5, 190], 3),
     "rep1_tiny_prompt": (_shape(1, 256, 2, 2, 256), [2], 1),
+    # large enough for the 256x256 GEMM tiles (gate/up), unsplit attention work items and a multi-chunk score pass
+    "rep4_dense_4k": (_shape(1, 1024, 8, 2, 16384), [1024, 1024, 1024, 1024], 256),
 }
 
 

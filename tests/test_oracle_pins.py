@@ -453,3 +453,18 @@ def test_bf16_storage_rounds_only_the_cache():
     np.testing.assert_array_equal(ks.f32_from_bf16_bits(bits).astype(np.float64), kh)   # already bf16 values
     assert ko.round_to_storage(np.array([1.00390625]), "bf16")[0] == 1.0                # tie to even
     assert ko.round_to_storage(np.array([1.01171875]), "bf16")[0] == 1.015625           # tie to even (up)
+
+
+def test_score_blocks_matches_full_scores():
+    shape = small_shape(n_layers=1)
+    sh, layers, embed, ids, kb, vb = small_problem(shape, GROUPS, LQ)
+    kh, vh = ko.realign_concat(sh, kb[0], vb[0], GROUPS, LQ)
+    groups = [0, 1, 3]
+    pos = ko.rows_of(groups, GROUPS, LQ)
+    x = np.random.default_rng(5).standard_normal((len(pos), shape.hidden))
+    xo, lse, S = ko.selective_layer(sh, layers[0], x, groups, GROUPS, LQ, kh.copy(), vh.copy())
+    xs, lse_s, Ss = ko.selective_layer(sh, layers[0], x, groups, GROUPS, LQ, kh.copy(), vh.copy(), score_blocks=[3, 1])
+    np.testing.assert_allclose(Ss[[1, 3]], S[[1, 3]], atol=1e-15)
+    assert np.isnan(Ss[[0, 2]]).all()
+    rows = np.concatenate([np.arange(5, 8), np.arange(12, 12 + LQ)])     # block 1 = group 1 (3 rows), block 3 = query
+    np.testing.assert_allclose(xs, xo[rows], atol=1e-12)
