@@ -32,6 +32,7 @@ def parse():
     ap.add_argument("--workload", default="qwen14b_32k")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--schedule", default=None, help="ratio schedule: linear (default of the workload) or const")
+    ap.add_argument("--ratio", type=float, default=None, help="mean recompute ratio (default: the workload's)")
     ap.add_argument("--budget", default=None, help="groups or tokens (default: the workload's)")
     ap.add_argument("--load-mode", type=int, default=2, help="0 serial, 1 next-layer, 2 layer-balanced")
     ap.add_argument("--layers-json", default=None, help="also write the per-layer timing report to this file")
@@ -175,6 +176,9 @@ def main():
         print("bench.py needs a GPU (no CPU fallback exists)", file=sys.stderr)
         sys.exit(3)
     w = ks.workload(a.workload)
+    if a.ratio is not None:
+        import dataclasses
+        w = dataclasses.replace(w, ratio=a.ratio)
     s = w.shape
     sched = a.schedule or w.schedule
     budget = a.budget or w.budget

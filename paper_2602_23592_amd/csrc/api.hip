@@ -681,30 +681,49 @@ struct Loader {
   size_t inflight = 0;
   uint64_t bytes_total = 0;
 
-  keep_status copy_group(int layer, int g) {
-    const size_t idx = (size_t)layer * pi->G + g;
-    if (loaded[idx]) return KEEP_OK;
-    const size_t nb = (size_t)p->group_len[g] * row_bytes;
-    const size_t dst = (size_t)layer * layer_bytes + (size_t)pi->off[g] * row_bytes;
-    if (!p->k_blocks[idx] || !p->v_blocks[idx])
-      return fail(c, KEEP_ERR_INVALID_ARG, "k_blocks/v_blocks entry of layer %d group %d is NULL", layer, g);
-    HIP_TRY(c, hipMemcpyAsync(k_cache + dst, p->k_blocks[idx], nb, hipMemcpyHostToDevice, c->s_copy));
-    HIP_TRY(c, hipMemcpyAsync(v_cache + dst, p->v_blocks[idx], nb, hipMemcpyHostToDevice, c->s_copy));
-    loaded[idx] = 1;
-    bytes_total += 2 * nb;
-    // flow control bookkeeping
-    const size_t slot = inflight_head % c->ev_chunk.size();
-    if (inflight_head - inflight_tail == c->ev_chunk.size()) {  // ring full: retire the oldest
-      HIP_TRY(c, hipEventSynchronize(c->ev_chunk[inflight_tail % c->ev_chunk.size()]));
-      inflight -= chunk_bytes[inflight_tail % c->ev_chunk.size()];
-      ++inflight_tail;
+  // Copy the blocks of groups [g0, g1) of one layer.  Consecutive groups are consecutive rows of the
+  // cache; when their host blocks are consecutive in host memory too (one pinned slab per layer, the
+  // usual case), the run goes out as ONE copy for K and one for V instead of two per group.
+  static constexpr size_t MAX_RUN_BYTES = 16u << 20;
+  keep_status copy_run(int layer, int g0, int g1) {
+    int g = g0;
+    while (g < g1) {
+      const size_t idx0 = (size_t)layer * pi->G + g;
+      if (loaded[idx0]) {
+        ++g;
+        continue;
+      }
+      if (!p->k_blocks[idx0] || !p->v_blocks[idx0])
+        return fail(c, KEEP_ERR_INVALID_ARG, "k_blocks/v_blocks entry of layer %d group %d is NULL", layer, g);
+      size_t nb = (size_t)p->group_len[g] * row_bytes;
+      int e = g + 1;
+      while (e < g1 && nb < MAX_RUN_BYTES && !loaded[(size_t)layer * pi->G + e] &&
+             (const char*)p->k_blocks[(size_t)layer * pi->G + e] == (const char*)p->k_blocks[idx0] + nb &&
+             (const char*)p->v_blocks[(size_t)layer * pi->G + e] == (const char*)p->v_blocks[idx0] + nb) {
+        nb += (size_t)p->group_len[e] * row_bytes;
+        ++e;
+      }
+      const size_t dst = (size_t)layer * layer_bytes + (size_t)pi->off[g] * row_bytes;
+      HIP_TRY(c, hipMemcpyAsync(k_cache + dst, p->k_blocks[idx0], nb, hipMemcpyHostToDevice, c->s_copy));
+      HIP_TRY(c, hipMemcpyAsync(v_cache + dst, p->v_blocks[idx0], nb, hipMemcpyHostToDevice, c->s_copy));
+      for (int i = g; i < e; ++i) loaded[(size_t)layer * pi->G + i] = 1;
+      bytes_total += 2 * nb;
+      // flow control bookkeeping
+      const size_t slot = inflight_head % c->ev_chunk.size();
+      if (inflight_head - inflight_tail == c->ev_chunk.size()) {  // ring full: retire the oldest
+        HIP_TRY(c, hipEventSynchronize(c->ev_chunk[inflight_tail % c->ev_chunk.size()]));
+        inflight -= chunk_bytes[inflight_tail % c->ev_chunk.size()];
+        ++inflight_tail;
+      }
+      HIP_TRY(c, hipEventRecord(c->ev_chunk[slot], c->s_copy));
+      chunk_bytes[slot] = 2 * nb;
+      inflight += 2 * nb;
+      ++inflight_head;
+      g = e;
     }
-    HIP_TRY(c, hipEventRecord(c->ev_chunk[slot], c->s_copy));
-    chunk_bytes[slot] = 2 * nb;
-    inflight += 2 * nb;
-    ++inflight_head;
     return KEEP_OK;
   }
+  keep_status copy_group(int layer, int g) { return copy_run(layer, g, g + 1); }
   void retire() {
     while (inflight_tail < inflight_head) {
       const size_t slot = inflight_tail % c->ev_chunk.size();
@@ -715,14 +734,14 @@ struct Loader {
   }
   // every group of `layer` outside `set` (ascending) that is not loaded yet
   keep_status copy_outside(int layer, const std::vector<int32_t>& set) {
-    size_t gi = 0;
-    for (int g = 0; g < pi->G; ++g) {
-      if (gi < set.size() && set[gi] == g) {
-        ++gi;
-        continue;
+    int g = 0;
+    for (size_t gi = 0; gi <= set.size(); ++gi) {
+      const int stop = gi < set.size() ? set[gi] : pi->G;  // groups [g, stop) are outside the set
+      if (stop > g) {
+        keep_status st = copy_run(layer, g, stop);
+        if (st != KEEP_OK) return st;
       }
-      keep_status st = copy_group(layer, g);
-      if (st != KEEP_OK) return st;
+      g = stop + 1;
     }
     return KEEP_OK;
   }
@@ -1033,12 +1052,19 @@ keep_status keep_prefill(keep_ctx* c, const keep_prompt* p, const float* ratios,
               preload_group = 0;
               continue;
             }
-            if (!ld.loaded[(size_t)preload_layer * pi.G + preload_group]) {
-              st = ld.copy_group(preload_layer, preload_group);
+            // the run of groups outside the set that starts at the cursor (at most 8 of them per chunk)
+            int run_end = preload_group + 1;
+            while (run_end < pi.G && run_end < preload_group + 8 &&
+                   !std::binary_search(cur.begin(), cur.end(), run_end))
+              ++run_end;
+            bool any = false;
+            for (int gg = preload_group; gg < run_end; ++gg) any |= !ld.loaded[(size_t)preload_layer * pi.G + gg];
+            if (any) {
+              st = ld.copy_run(preload_layer, preload_group, run_end);
               if (st != KEEP_OK) return st;
               issued = true;
             }
-            ++preload_group;
+            preload_group = run_end;
           }
         }
       }
