@@ -287,34 +287,38 @@ __global__ void __launch_bounds__(256)
   float m_all = M_FLOOR;
   for (int c = 0; c < sp.z; ++c) m_all = fmaxf(m_all, part_ml[((size_t)(sp.y + c) * n_kv_heads + hk) * 256 + ql]);
   float l_all = 0.f;
-  for (int c = 0; c < sp.z; ++c) {
+  float4 acc[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) acc[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int c = 0; c < sp.z; ++c) {  // chunks in key order
     const size_t slot = (size_t)(sp.y + c) * n_kv_heads + hk;
-    l_all += part_ml[slot * 256 + 128 + ql] * __builtin_amdgcn_exp2f(part_ml[slot * 256 + ql] - m_all);
+    const float w = __builtin_amdgcn_exp2f(part_ml[slot * 256 + ql] - m_all);
+    l_all += part_ml[slot * 256 + 128 + ql] * w;
+    const float* po = part_o + slot * PART_FLOATS + ((size_t)(half * 16) * 128 + ql) * 4;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const float4 v = *reinterpret_cast<const float4*>(po + (size_t)i * 128 * 4);
+      acc[i].x += w * v.x;
+      acc[i].y += w * v.y;
+      acc[i].z += w * v.z;
+      acc[i].w += w * v.w;
+    }
   }
   const float inv = 1.0f / l_all;
-  bf16_t* op = o + ((size_t)r * n_q_heads + head) * DH;
-  for (int d4 = half * 16; d4 < half * 16 + 16; ++d4) {
-    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int c = 0; c < sp.z; ++c) {
-      const size_t slot = (size_t)(sp.y + c) * n_kv_heads + hk;
-      const float w = __builtin_amdgcn_exp2f(part_ml[slot * 256 + ql] - m_all);
-      const float4 v = *reinterpret_cast<const float4*>(part_o + slot * PART_FLOATS + ((size_t)d4 * 128 + ql) * 4);
-      acc.x += w * v.x;
-      acc.y += w * v.y;
-      acc.z += w * v.z;
-      acc.w += w * v.w;
-    }
+  bf16_t* op = o + ((size_t)r * n_q_heads + head) * DH + half * 64;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
     uint2 u;
-    u.x = pack_bf16x2(acc.x * inv, acc.y * inv);
-    u.y = pack_bf16x2(acc.z * inv, acc.w * inv);
-    *reinterpret_cast<uint2*>(op + d4 * 4) = u;
+    u.x = pack_bf16x2(acc[i].x * inv, acc[i].y * inv);
+    u.y = pack_bf16x2(acc[i].z * inv, acc[i].w * inv);
+    *reinterpret_cast<uint2*>(op + i * 4) = u;
   }
   if (half == 0) lse[(size_t)r * n_q_heads + head] = 0.6931471805599453f * (m_all + log2f(l_all));
 }
 
 // ---- host-side work list ---------------------------------------------------
 constexpr int ATT_MAX_SLOTS = 4096;      // partial buffers (cut items x KV heads) the scratch can hold
-constexpr int ATT_TARGET_BLOCKS = 2048;  // cut long tiles until about this many workgroups exist
+constexpr int ATT_SLOTS = 512;           // resident workgroups: 2 per CU x 256 CUs
 constexpr int ATT_MIN_CHUNK = 16;        // never cut below 16 key tiles (1024 keys)
 
 static inline int att_max_tiles(int max_rows, int rep) { return (int)(((long)max_rows * rep + 127) / 128); }
@@ -359,19 +363,19 @@ void launch_attn_mfma(const bf16_t* q, const bf16_t* k_cache, const bf16_t* v_ca
     steps[t] = pos_of_row(x_last / rep) / KT_KEYS + 1;
     total_steps += steps[t];
   }
-  int chunk = 1 << 30;
-  if ((long)n_tiles * n_kv_heads < ATT_TARGET_BLOCKS) {
-    const long want_items = ATT_TARGET_BLOCKS / n_kv_heads;
-    chunk = (int)std::max<long>(ATT_MIN_CHUNK, (total_steps + want_items - 1) / want_items);
-    for (;;) {
-      long slots = 0;
-      for (int t = 0; t < n_tiles; ++t) {
-        const int nc = (steps[t] + chunk - 1) / chunk;
-        if (nc > 1) slots += nc;
-      }
-      if (slots * n_kv_heads <= ATT_MAX_SLOTS) break;
-      chunk *= 2;
+  // Two workgroups fit on each of the 256 CUs: 512 slots.  A key range longer than a slot's average
+  // share of the work would leave the chip waiting for it at the end (instruction rows see the whole
+  // cache while most recomputed memories sit early in the prompt), so such ranges are cut into chunks
+  // of about that length (never below ATT_MIN_CHUNK key tiles); everything shorter runs whole.
+  int chunk = (int)std::max<long>(ATT_MIN_CHUNK, (total_steps * n_kv_heads + ATT_SLOTS - 1) / ATT_SLOTS);
+  for (;;) {
+    long slots = 0;
+    for (int t = 0; t < n_tiles; ++t) {
+      const int nc = (steps[t] + chunk - 1) / chunk;
+      if (nc > 1) slots += nc;
     }
+    if (slots * n_kv_heads <= ATT_MAX_SLOTS) break;
+    chunk *= 2;
   }
   int n_items = 0, n_splits = 0, slot = 0;
   for (int t = n_tiles - 1; t >= 0; --t) {  // longest key ranges first
