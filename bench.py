@@ -247,6 +247,7 @@ def main():
     L = s.n_layers
     rows = np.array([reports[-1].rows[l] for l in range(L)], dtype=np.float64)
     re_rows = np.array([reports[-1].realign_rows[l] for l in range(L)], dtype=np.float64)
+    ffn_rows = np.array([reports[-1].ffn_rows[l] for l in range(L)], dtype=np.float64)
     vis = np.array(visible_keys(sets, glen, lq), dtype=np.float64)
 
     def mean_ms(name):
@@ -263,10 +264,10 @@ def main():
         kern[name] = {"ms_per_step": round(tot_ms, 3), "achieved": round(ach / scale, 2), "unit": unit,
                       "frac": round(ach / scale / peak, 4)}
 
-    add("gemm_gate_up_swiglu", mean_ms("ms_gateup"), 2.0 * rows * s.hidden * 2 * s.ffn_dim, "TFLOP/s", PEAK_BF16_TFLOPS)
-    add("gemm_down", mean_ms("ms_down"), 2.0 * rows * s.hidden * s.ffn_dim, "TFLOP/s", PEAK_BF16_TFLOPS)
+    add("gemm_gate_up_swiglu", mean_ms("ms_gateup"), 2.0 * ffn_rows * s.hidden * 2 * s.ffn_dim, "TFLOP/s", PEAK_BF16_TFLOPS)
+    add("gemm_down", mean_ms("ms_down"), 2.0 * ffn_rows * s.hidden * s.ffn_dim, "TFLOP/s", PEAK_BF16_TFLOPS)
     add("gemm_qkv", mean_ms("ms_qkv_gemm"), 2.0 * rows * s.hidden * (qd + 2 * kvd), "TFLOP/s", PEAK_BF16_TFLOPS)
-    add("gemm_out_proj", mean_ms("ms_oproj"), 2.0 * rows * qd * s.hidden, "TFLOP/s", PEAK_BF16_TFLOPS)
+    add("gemm_out_proj", mean_ms("ms_oproj"), 2.0 * ffn_rows * qd * s.hidden, "TFLOP/s", PEAK_BF16_TFLOPS)
     add("sparse_row_attention", mean_ms("ms_attn"), 4.0 * s.head_dim * s.n_q_heads * vis, "TFLOP/s", PEAK_BF16_TFLOPS)
     add("realign_concat", mean_ms("ms_realign"), 4.0 * re_rows * kvd * esz, "GB/s", PEAK_HBM_GBS)
     add("rope_scatter", mean_ms("ms_rope"), rows * ((qd + 2 * kvd) * 4.0 + (qd + 3 * kvd) * esz), "GB/s", PEAK_HBM_GBS)
@@ -294,7 +295,7 @@ def main():
                                % (w.name, L, s.hidden, s.n_q_heads, s.n_kv_heads, s.head_dim, s.ffn_dim, n_tokens, G,
                                   w.mem_tokens, lq, w.ratio, budget, sched, w.hops, w.kv_location),
                    "rows_per_layer_mean": round(float(np.mean(rows[1:])) if L > 1 else float(rows[0]), 1),
-                   "rows_layer0": int(rows[0]), "set_sizes": [len(x) for x in sets],
+                   "rows_layer0": int(rows[0]), "ffn_rows_layer0": int(ffn_rows[0]), "set_sizes": [len(x) for x in sets],
                    "group_caches": "random draws" if a.random_cache else "library dense prefill of each group alone",
                    "load_mode": a.load_mode, "setup_s": round(t_setup, 1)},
         "roofline": roofline,
@@ -302,7 +303,8 @@ def main():
     }
     if a.layers_json:
         from paper_2602_23592_amd.binding import _REPORT_MS
-        per_layer = {"rows": [int(v) for v in rows], "set_sizes": [len(x) for x in sets]}
+        per_layer = {"rows": [int(v) for v in rows], "ffn_rows": [int(v) for v in ffn_rows],
+                     "set_sizes": [len(x) for x in sets]}
         for name in _REPORT_MS:
             per_layer[name] = [round(float(v), 4) for v in mean_ms(name)]
         with open(a.layers_json, "w") as f:

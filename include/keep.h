@@ -119,6 +119,8 @@ typedef struct {
   int32_t set_size[KEEP_REPORT_MAX_LAYERS];    /* groups recomputed at each layer */
   int32_t hops_run[KEEP_REPORT_MAX_LAYERS];    /* selections run after each layer */
   int32_t realign_rows[KEEP_REPORT_MAX_LAYERS];/* cache rows re-aligned (groups outside the set) */
+  int32_t ffn_rows[KEEP_REPORT_MAX_LAYERS];    /* rows the output projection + FFN ran on: rows[l], or the
+                                                  next layer's rows when evaluation went first (see keep_prefill) */
   float ms_realign[KEEP_REPORT_MAX_LAYERS];    /* re-align + concatenate kernel */
   float ms_prep[KEEP_REPORT_MAX_LAYERS];       /* row table, gather, first RMSNorm */
   float ms_qkv_gemm[KEEP_REPORT_MAX_LAYERS];   /* QKV projection GEMM alone */
@@ -198,7 +200,10 @@ keep_status keep_select_groups(keep_ctx* ctx, const float* S, const int32_t* gro
 
 /* Whole selective prefill (Section 4.2 + 4.3 + 5): for l = 0..n_layers-1 recompute
  * the relevant set of layer l, evaluate importance beside the FFN, load what layer
- * l+1 needs.
+ * l+1 needs.  Evaluation runs beside the output projection and FFN (Section 4.2), except where the
+ * budget says that at most half of a layer's rows survive (typically after layer 0): there it runs
+ * first and the output projection and FFN are computed for the surviving rows only, which gives the
+ * same result because the hidden rows of dropped memories are discarded (Section 4.3).
  *   ratios: HOST [n_layers]; ratios[0] is 1 (recompute every memory at the first
  *           layer, Section 4.2) or 0 (pure reuse); ratios[1..] non-increasing (a memory
  *           dropped once is never recomputed, Section 4.3).

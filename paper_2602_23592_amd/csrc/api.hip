@@ -22,8 +22,9 @@ thread_local std::string g_init_error;
 
 constexpr double BUDGET_EPS = 1.0e-3;
 // events per layer: 0 begin, 1 re-align done, 2 rows/gather/norm done, 3 QKV GEMM done, 4 RoPE+scatter done,
-// 5 attention done, 6 output projection done, 7 second norm done, 8 gate/up done, 9 down done, 10/11 score begin/end
-constexpr int EV_PER_LAYER = 12;
+// 5 attention done, 6 output projection done, 7 second norm done, 8 gate/up done, 9 down done, 10/11 score begin/end,
+// 12 output projection begins
+constexpr int EV_PER_LAYER = 13;
 // Host->device pre-loads are enqueued only while fewer bytes than this are in flight,
 // so that the copies a layer is waiting for never queue behind a long run of pre-loads.
 constexpr size_t PRELOAD_INFLIGHT_CAP = 48u << 20;
@@ -403,7 +404,8 @@ keep_status layer_front(keep_ctx* c, const PromptInfo& pi, int layer, const Laye
 
 // Output projection + residual, RMSNorm, SwiGLU FFN + residual on the compute stream.
 template <typename T>
-keep_status layer_back(keep_ctx* c, int layer, int n, const void* x_in, void* x_out, hipEvent_t* evs) {
+keep_status layer_back(keep_ctx* c, int layer, int n, const void* o_rows, const void* x_in, void* x_out,
+                       hipEvent_t* evs) {
   const keep_model_desc& d = c->d;
   const keep_layer_weights& w = c->w[layer];
   hipStream_t s = c->s_comp;
@@ -413,9 +415,10 @@ keep_status layer_back(keep_ctx* c, int layer, int n, const void* x_in, void* x_
   GemmB bd{}; bd.n_parts = 1; bd.ptr[0] = w.wdown; bd.n_rows[0] = d.hidden;
 #define EV(i) \
   if (evs) HIP_TRY(c, hipEventRecord(evs[i], s))
+  EV(12);
   if (c->mfma) {
     auto B = [](const void* p) { return reinterpret_cast<const bf16_t*>(p); };
-    launch_gemm_mfma(B(c->o), n, qd, bo, nullptr, d.hidden, EPI_RESIDUAL_STORE, B(x_in), c->x1, s);
+    launch_gemm_mfma(B(o_rows), n, qd, bo, nullptr, d.hidden, EPI_RESIDUAL_STORE, B(x_in), c->x1, s);
     EV(6);
     launch_rmsnorm<bf16_t>(B(c->x1), B(w.ln2), n, d.hidden, d.rms_eps, reinterpret_cast<bf16_t*>(c->hbuf), s);
     EV(7);
@@ -423,7 +426,7 @@ keep_status layer_back(keep_ctx* c, int layer, int n, const void* x_in, void* x_
     EV(8);
     launch_gemm_mfma(B(c->act), n, d.ffn_dim, bd, nullptr, d.hidden, EPI_RESIDUAL_STORE, B(c->x1), x_out, s);
   } else {
-    launch_gemm_generic<T>(Typed<T>::p(c->o), n, qd, bo, nullptr, d.hidden, EPI_RESIDUAL_STORE, Typed<T>::p(x_in),
+    launch_gemm_generic<T>(Typed<T>::p(o_rows), n, qd, bo, nullptr, d.hidden, EPI_RESIDUAL_STORE, Typed<T>::p(x_in),
                            c->x1, s);
     EV(6);
     launch_rmsnorm<T>(Typed<T>::p(c->x1), Typed<T>::p(w.ln2), n, d.hidden, d.rms_eps, Typed<T>::p(c->hbuf), s);
@@ -782,7 +785,7 @@ keep_status keep_recompute_layer(keep_ctx* c, const keep_prompt* p, int32_t laye
     using T = std::remove_pointer_t<decltype(tag)>;
     keep_status s2 = layer_front<T>(c, pi, layer, plan, x_in, k_cache_l, v_cache_l, nullptr);
     if (s2 != KEEP_OK) return s2;
-    return layer_back<T>(c, layer, plan.n_rows, x_in ? x_in : c->xa, x_out, nullptr);
+    return layer_back<T>(c, layer, plan.n_rows, c->o, x_in ? x_in : c->xa, x_out, nullptr);
   });
   if (st != KEEP_OK) return st;
   Staging& sg = c->stage[layer];
@@ -1014,16 +1017,33 @@ keep_status keep_prefill(keep_ctx* c, const keep_prompt* p, const float* ratios,
         HIP_TRY(c, hipEventRecord(c->ev_eval, c->s_eval));
       }
     }
-    // ---- compute stream: output projection + FFN
-    st = by_dtype(c, [&](auto* tag) {
-      using T = std::remove_pointer_t<decltype(tag)>;
-      return layer_back<T>(c, l, plan.n_rows, x_cur, x_nxt, evs);
-    });
-    if (st != KEEP_OK) return st;
-    {
+    // ---- compute stream: output projection + FFN.
+    // Normally they run now, beside the evaluation (Section 4.2).  When the budget says that at most half
+    // of this layer's rows survive into the next set, evaluation goes first and the output projection
+    // and FFN then run on the surviving rows only: the hidden rows of dropped memories are discarded
+    // anyway (Section 4.3), so the result is the same.
+    bool eval_first = false;
+    if (kind == SEL_DEVICE) {
+      const long mem_rows = plan.n_rows - pi.Lq;
+      const long bound = budget_mode == KEEP_BUDGET_TOKENS ? std::min<long>(tok, mem_rows) + pi.Lq
+                                                            : mem_rows * k_count / std::max(1, m) + pi.Lq;
+      eval_first = bound * 2 <= plan.n_rows;
+    }
+    auto finish_layer = [&](int n_rows_back, const void* o_rows, const void* x_in_back, void* x_out_back) {
+      keep_status s2 = by_dtype(c, [&](auto* tag) {
+        using T = std::remove_pointer_t<decltype(tag)>;
+        return layer_back<T>(c, l, n_rows_back, o_rows, x_in_back, x_out_back, evs);
+      });
+      if (s2 != KEEP_OK) return s2;
+      if (report) report->ffn_rows[l] = n_rows_back;
       Staging& sg = c->stage[l];
       HIP_TRY(c, hipEventRecord(sg.done, c->s_comp));
       sg.used = true;
+      return KEEP_OK;
+    };
+    if (!eval_first) {
+      st = finish_layer(plan.n_rows, c->o, x_cur, x_nxt);
+      if (st != KEEP_OK) return st;
     }
     if (last) break;
 
@@ -1091,13 +1111,18 @@ keep_status keep_prefill(keep_ctx* c, const keep_prompt* p, const float* ratios,
       HIP_TRY(c, hipStreamWaitEvent(c->s_comp, c->ev_load, 0));
       if (report) report->bytes_loaded[l + 1] = ld.bytes_total - bytes_before;
     }
-    // ---- hidden rows of the next set: gather from this layer's output
-    if (nxt.size() == cur.size()) {
+    // ---- hidden rows of the next set
+    if (!eval_first && nxt.size() == cur.size()) {
       std::swap(x_cur, x_nxt);  // same rows: this layer's output is the next layer's input
       x_from_embed = false;
+    } else if (eval_first && nxt.size() == cur.size()) {
+      st = finish_layer(plan.n_rows, c->o, x_cur, x_nxt);
+      if (st != KEEP_OK) return st;
+      std::swap(x_cur, x_nxt);
+      x_from_embed = false;
     } else {
-      // source compact start of each kept block inside the current layout
-      Staging& sg = c->stage[l];  // gather_src of slot l is free: uploaded now, consumed by this gather
+      // compact start of each kept block in the current layout and in the next one
+      Staging& sg = c->stage[l];
       std::vector<int32_t> dst_start(nxt.size() + 2);
       int acc = 0;
       size_t ci = 0;
@@ -1111,22 +1136,39 @@ keep_status keep_prefill(keep_ctx* c, const keep_prompt* p, const float* ratios,
       dst_start[nxt.size()] = acc;
       acc += pi.Lq;
       dst_start[nxt.size() + 1] = acc;
-      // the destination starts are exactly the next layer's row_start: upload them into
-      // d_row_start after the FFN that still reads nothing from it (stream order)
+      // (the destination starts are the next layer's row_start; nothing still reads the old one)
       memcpy(sg.gather_dst, dst_start.data(), dst_start.size() * 4);
       HIP_TRY(c, hipMemcpyAsync(c->d_gather_src, sg.gather_src, (nxt.size() + 1) * 4, hipMemcpyHostToDevice, c->s_comp));
       HIP_TRY(c, hipMemcpyAsync(c->d_row_start, sg.gather_dst, dst_start.size() * 4, hipMemcpyHostToDevice, c->s_comp));
-      void* x_out_buf = x_nxt;  // this layer's output
-      void* x_dst = x_cur;      // this layer's input buffer is free once the layer is done
-      st = by_dtype(c, [&](auto* tag) {
-        using T = std::remove_pointer_t<decltype(tag)>;
-        launch_rows_gather<T>(Typed<T>::p(x_out_buf), c->d_gather_src, c->d_row_start, (int)nxt.size() + 1, acc,
-                              d.hidden, Typed<T>::p(x_dst), c->s_comp);
-        return KEEP_OK;
-      });
-      HIP_TRY(c, hipGetLastError());
-      HIP_TRY(c, hipEventRecord(sg.done, c->s_comp));
-      x_cur = x_dst;
+      const int n_blocks = (int)nxt.size() + 1;
+      if (!eval_first) {
+        void* x_out_buf = x_nxt;  // this layer's output
+        void* x_dst = x_cur;      // this layer's input buffer is free once the layer is done
+        st = by_dtype(c, [&](auto* tag) {
+          using T = std::remove_pointer_t<decltype(tag)>;
+          launch_rows_gather<T>(Typed<T>::p(x_out_buf), c->d_gather_src, c->d_row_start, n_blocks, acc, d.hidden,
+                                Typed<T>::p(x_dst), c->s_comp);
+          return KEEP_OK;
+        });
+        HIP_TRY(c, hipGetLastError());
+        HIP_TRY(c, hipEventRecord(sg.done, c->s_comp));
+        x_cur = x_dst;
+      } else {
+        // survivors first: gather their attention rows (into the q buffer, free now that the scores are
+        // done) and their input rows, then output projection + FFN on them alone
+        const int qd = d.n_q_heads * d.head_dim;
+        st = by_dtype(c, [&](auto* tag) {
+          using T = std::remove_pointer_t<decltype(tag)>;
+          launch_rows_gather<T>(Typed<T>::p(c->o), c->d_gather_src, c->d_row_start, n_blocks, acc, qd,
+                                Typed<T>::p(c->q), c->s_comp);
+          launch_rows_gather<T>(Typed<T>::p(x_cur), c->d_gather_src, c->d_row_start, n_blocks, acc, d.hidden,
+                                Typed<T>::p(x_nxt), c->s_comp);
+          return KEEP_OK;
+        });
+        HIP_TRY(c, hipGetLastError());
+        st = finish_layer(acc, c->q, x_nxt, x_cur);  // output lands in x_cur, already in the next layout
+        if (st != KEEP_OK) return st;
+      }
       x_from_embed = false;
     }
     cur.swap(nxt);
@@ -1148,7 +1190,7 @@ keep_status keep_prefill(keep_ctx* c, const keep_prompt* p, const float* ratios,
       (void)hipEventElapsedTime(&report->ms_qkv_gemm[l], e[2], e[3]);
       (void)hipEventElapsedTime(&report->ms_rope[l], e[3], e[4]);
       (void)hipEventElapsedTime(&report->ms_attn[l], e[4], e[5]);
-      (void)hipEventElapsedTime(&report->ms_oproj[l], e[5], e[6]);
+      (void)hipEventElapsedTime(&report->ms_oproj[l], e[12], e[6]);
       (void)hipEventElapsedTime(&report->ms_norm2[l], e[6], e[7]);
       (void)hipEventElapsedTime(&report->ms_gateup[l], e[7], e[8]);
       (void)hipEventElapsedTime(&report->ms_down[l], e[8], e[9]);

@@ -311,6 +311,10 @@ void launch_gemm_mfma(const bf16_t* A, int32_t M, int32_t K, const GemmB& B, con
 #define KEEP_EXP_CFG 256, 256, 4, 2, 64, 2
 #endif
     launch_cfg<KEEP_EXP_CFG>(A, M, K, b, b2, N, epilogue, residual, C, s);
+#ifdef KEEP_EXP_CFG_SMALL
+  else if (rows % 256 == 0 && aligned256)
+    launch_cfg<KEEP_EXP_CFG_SMALL>(A, M, K, b, b2, N, epilogue, residual, C, s);
+#endif
   else if (rows % 128 == 0)
     launch_cfg<128, 128, 2, 2, 64, 2>(A, M, K, b, b2, N, epilogue, residual, C, s);
   else
