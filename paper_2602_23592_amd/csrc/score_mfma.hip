@@ -25,7 +25,6 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 constexpr int SDH = 128;
 constexpr int S_KEYS = 64;      // keys per LDS tile
 constexpr int S_CHUNK = 1024;   // keys per workgroup
-constexpr int S_KSTRIDE = 136;  // bf16 per K row in LDS
 
 struct RowTile {
   int32_t row0, nrows, slot;
@@ -46,16 +45,158 @@ size_t score_mfma_stage_ints(int32_t max_rows, int32_t max_groups) {
   return (size_t)max_row_tiles(max_rows, max_groups) * 3 + (size_t)max_groups + 2;
 }
 
+typedef const void __attribute__((address_space(1))) * sc_gptr_t;
+typedef void __attribute__((address_space(3))) * sc_lptr_t;
+
+struct ScoreWave {       // wave-uniform state of one row tile
+  int row0, nrows, last_row;
+  bool has_tile;
+};
+
+// One pass over the chunk's keys for NCH query heads of KV head hk (heads hk*rep + hc ...).
+// K tiles stream global -> LDS with global_load_lds_dwordx4 (lane l's 16 bytes land at base + 16 l:
+// one instruction fills 4 rows of 256 B).  Chunk c of row r is kept at c ^ (r % 16), which makes the
+// 16-byte operand reads of 16 consecutive rows hit all 64 banks; the lane fetches the matching chunk.
+template <int NCH>
+__device__ __forceinline__ void score_pass(const bf16_t* __restrict__ q, const bf16_t* __restrict__ kc,
+                                           const float* __restrict__ lse, uint16_t* s_k, float* s_colw, float* s_l2w,
+                                           const ScoreWave sw, int q_row, int hk, int head0, int n_q_heads, int kv_dim,
+                                           int c0, int n_kt, int n_keys, float scale_log2e) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int g = lane >> 5, lq = lane & 31;
+  const int ld_row = wave * 16 + (lane >> 4);  // + 4 i, i < 4
+  const int ld_pc = lane & 15;
+#define SC_STAGE(KT, BUFI)                                                                       \
+  {                                                                                              \
+    _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                              \
+      const int row_ = ld_row + 4 * i;                                                           \
+      const int key_ = min(c0 + (KT) * S_KEYS + row_, n_keys - 1);                               \
+      __builtin_amdgcn_global_load_lds(                                                          \
+          (sc_gptr_t)(kc + (size_t)key_ * kv_dim + hk * SDH + ((ld_pc ^ (row_ & 15)) << 3)),     \
+          (sc_lptr_t)(s_k + (BUFI) * S_KEYS * SDH + (wave * 16 + 4 * i) * SDH), 16, 0, 0);       \
+    }                                                                                            \
+  }
+  int koff[8];  // K row lq, logical chunk 2 ks + g
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) koff[ks] = lq * SDH + (((2 * ks + g) ^ (lq & 15)) << 3);
+
+  bf16x8 qf[NCH][8];
+#pragma unroll
+  for (int j = 0; j < NCH; ++j) {
+    const bf16_t* qp = q + ((size_t)q_row * n_q_heads + head0 + j) * SDH + g * 8;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) qf[j][ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 16);
+  }
+  __syncthreads();  // previous users of the K buffers and of the log-sum-exp rows are done
+  if (g == 0) {     // +inf for rows past the tile's end: their probabilities come out as 0
+#pragma unroll
+    for (int j = 0; j < NCH; ++j)
+      s_l2w[j * 32 + lq] = (sw.has_tile && lq < sw.nrows)
+                               ? lse[(size_t)(sw.row0 + lq) * n_q_heads + head0 + j] * 1.4426950408889634f
+                               : INFINITY;
+  }
+  SC_STAGE(0, 0)
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): the tile has landed
+  __syncthreads();
+  for (int kt = 0; kt < n_kt; ++kt) {
+    const int cur = kt & 1;
+    if (kt + 1 < n_kt) SC_STAGE(kt + 1, cur ^ 1)
+    const int k0 = c0 + kt * S_KEYS;
+    if (sw.has_tile && k0 <= sw.last_row) {
+      const uint16_t* sk = s_k + cur * S_KEYS * SDH;
+      // only tiles that touch the diagonal (or the end of the key list) need the per-element test
+      const bool need_mask = (k0 + S_KEYS - 1 > sw.row0) || (k0 + S_KEYS > n_keys);
+      bf16x8 kf[8];  // K operands of a 32-key half
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) kf[ks] = *reinterpret_cast<const bf16x8*>(sk + koff[ks]);
+      // The tile is 2 * NCH units (32-key half, head).  The MFMAs of unit u + 1 are issued between the
+      // exponentials of unit u, so the matrix pipe and the vector ALU of this wave run side by side.
+      // registers 4*e4 .. 4*e4+3 of a unit are its rows 8*e4 + 4*g + {0..3}
+      constexpr int NU = 2 * NCH;
+      f32x16 acc[2];
+#define SC_ISSUE(UN)                                                                                          \
+  {                                                                                                           \
+    _Pragma("unroll") for (int e = 0; e < 16; ++e) acc[(UN) & 1][e] = 0.f;                                    \
+    _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) acc[(UN) & 1] =                                          \
+        __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[(UN) % NCH][ks], kf[ks], acc[(UN) & 1], 0, 0, 0);          \
+    if ((UN) == NCH - 1) { /* last use of the first half's operands: fetch the second half's */               \
+      _Pragma("unroll") for (int ks = 0; ks < 8; ++ks) kf[ks] =                                               \
+          *reinterpret_cast<const bf16x8*>(sk + 32 * SDH + koff[ks]);                                         \
+    }                                                                                                         \
+  }
+      SC_ISSUE(0)
+      float csum = 0.f;
+      if (!need_mask) {
+#pragma unroll
+        for (int u = 0; u < NU; ++u) {
+          const int j = u % NCH;
+          if (u + 1 < NU) SC_ISSUE(u + 1)
+          float4 l4[4];
+#pragma unroll
+          for (int e4 = 0; e4 < 4; ++e4) l4[e4] = *reinterpret_cast<const float4*>(&s_l2w[j * 32 + 8 * e4 + 4 * g]);
+#pragma unroll
+          for (int e4 = 0; e4 < 4; ++e4) {
+            csum += __builtin_amdgcn_exp2f(__builtin_fmaf(acc[u & 1][4 * e4 + 0], scale_log2e, -l4[e4].x));
+            csum += __builtin_amdgcn_exp2f(__builtin_fmaf(acc[u & 1][4 * e4 + 1], scale_log2e, -l4[e4].y));
+            csum += __builtin_amdgcn_exp2f(__builtin_fmaf(acc[u & 1][4 * e4 + 2], scale_log2e, -l4[e4].z));
+            csum += __builtin_amdgcn_exp2f(__builtin_fmaf(acc[u & 1][4 * e4 + 3], scale_log2e, -l4[e4].w));
+          }
+          if (u + 1 < NU) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+              __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one MFMA
+              __builtin_amdgcn_sched_group_barrier(0x402, 6, 0);  // six vector ALU / transcendental
+            }
+          }
+          if (j == NCH - 1) {  // all heads of this half are in: add the lane's key column to the chunk's sums
+            csum += __shfl_xor(csum, 32, 64);
+            if (g == 0) s_colw[kt * S_KEYS + (u / NCH) * 32 + lq] += csum;
+            csum = 0.f;
+          }
+        }
+      } else {
+#pragma unroll
+        for (int u = 0; u < NU; ++u) {
+          const int j = u % NCH;
+          if (u + 1 < NU) SC_ISSUE(u + 1)
+          const int key = k0 + (u / NCH) * 32 + lq;  // this lane's key column
+          // first tile-relative row that may see the key (none past the end of the key list)
+          const int first = (key < n_keys ? key - sw.row0 : 64) - 4 * g;
+#pragma unroll
+          for (int e4 = 0; e4 < 4; ++e4) {
+            const float4 l4 = *reinterpret_cast<const float4*>(&s_l2w[j * 32 + 8 * e4 + 4 * g]);
+            const float lv[4] = {l4.x, l4.y, l4.z, l4.w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(acc[u & 1][4 * e4 + i], scale_log2e, -lv[i]));
+              csum += (8 * e4 + i >= first) ? p : 0.f;
+            }
+          }
+          if (j == NCH - 1) {
+            csum += __shfl_xor(csum, 32, 64);
+            if (g == 0) s_colw[kt * S_KEYS + (u / NCH) * 32 + lq] += csum;
+            csum = 0.f;
+          }
+        }
+      }
+#undef SC_ISSUE
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): the next tile has landed
+    __syncthreads();
+  }
+#undef SC_STAGE
+}
+
 template <int CH>
 __global__ void __launch_bounds__(256, 2)
     k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ kc, const float* __restrict__ lse,
                  const RowTile* __restrict__ tiles, int n_rt, int n_keys, int n_q_heads, int n_kv_heads,
                  int hk_per_slice, float scale_log2e, float* __restrict__ colmass, int col_ld) {
-  __shared__ __attribute__((aligned(16))) uint16_t s_k[2 * S_KEYS * S_KSTRIDE];
+  __shared__ __attribute__((aligned(16))) uint16_t s_k[2 * S_KEYS * SDH];
   __shared__ float s_col[4][S_CHUNK];
-  __shared__ __attribute__((aligned(16))) float s_l2[4][CH][32];  // rows' log-sum-exp, log2 domain
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int g = lane >> 5, lq = lane & 31;
+  __shared__ __attribute__((aligned(16))) float s_l2[4][CH * 32];  // rows' log-sum-exp, log2 domain
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int lq = lane & 31;
   const int rep = n_q_heads / n_kv_heads;
   const int c0 = blockIdx.y * S_CHUNK;
   const int c1 = min(c0 + S_CHUNK, n_keys);
@@ -67,108 +208,38 @@ __global__ void __launch_bounds__(256, 2)
   const int n_kt = (key_end - c0 + S_KEYS - 1) / S_KEYS;
 
   const int rt = blockIdx.x * 4 + wave;
-  const bool has_tile = rt < n_rt;
-  const RowTile tl = tiles[has_tile ? rt : rt_last];
-  const int q_row = tl.row0 + min(lq, tl.nrows - 1);  // A operand row of this lane (clamped)
-  const int tile_last_row = tl.row0 + tl.nrows - 1;
+  ScoreWave sw;
+  sw.has_tile = rt < n_rt;
+  const RowTile tl = tiles[sw.has_tile ? rt : rt_last];
+  sw.row0 = __builtin_amdgcn_readfirstlane(tl.row0);   // the tile is the wave's: keep it in scalar registers
+  sw.nrows = __builtin_amdgcn_readfirstlane(tl.nrows);
+  sw.last_row = sw.row0 + sw.nrows - 1;
+  const int q_row = sw.row0 + min(lq, sw.nrows - 1);  // A operand row of this lane (clamped)
 
   for (int i = tid; i < 4 * S_CHUNK; i += 256) (&s_col[0][0])[i] = 0.f;
 
-  const int ld_row = tid >> 4, ld_c = tid & 15;
-  uint4 kreg0, kreg1, kreg2, kreg3;
-  const int kv_dim = n_kv_heads * SDH;
-#define SC_GLOAD1(KR, I, KT)                                                                     \
-  {                                                                                              \
-    const int key_ = min(c0 + (KT) * S_KEYS + ld_row + 16 * (I), n_keys - 1);                    \
-    KR = *reinterpret_cast<const uint4*>(kc + (size_t)key_ * kv_dim + hk * SDH + ld_c * 8);      \
-  }
-#define SC_GLOAD(KT) SC_GLOAD1(kreg0, 0, KT) SC_GLOAD1(kreg1, 1, KT) SC_GLOAD1(kreg2, 2, KT) SC_GLOAD1(kreg3, 3, KT)
-#define SC_SSTORE1(KR, I, BUFI) \
-  *reinterpret_cast<uint4*>(&s_k[(BUFI) * S_KEYS * S_KSTRIDE + (ld_row + 16 * (I)) * S_KSTRIDE + ld_c * 8]) = KR;
-#define SC_SSTORE(BUFI) SC_SSTORE1(kreg0, 0, BUFI) SC_SSTORE1(kreg1, 1, BUFI) SC_SSTORE1(kreg2, 2, BUFI) SC_SSTORE1(kreg3, 3, BUFI)
-
   // blockIdx.z selects a slice of the KV heads (small problems are spread over more workgroups;
   // the slices' column sums are added in slice order by the next pass)
+  const int kv_dim = n_kv_heads * SDH;
   const int hk_begin = blockIdx.z * hk_per_slice;
   const int hk_end = min(n_kv_heads, hk_begin + hk_per_slice);
   for (int hk = hk_begin; hk < hk_end; ++hk) {
     for (int hc = 0; hc < rep; hc += CH) {
       const int nch = min(CH, rep - hc);  // heads in this pass (the last pass may be short)
-      // Q operand for up to CH heads; the rows' log-sum-exp goes to LDS (+inf for rows past the tile's end)
-      bf16x8 qf[CH][8];
-#pragma unroll
-      for (int j = 0; j < CH; ++j) {
-        const int head = hk * rep + min(hc + j, rep - 1);
-        const bf16_t* qp = q + ((size_t)q_row * n_q_heads + head) * SDH + g * 8;
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks) qf[j][ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 16);
-      }
-      __syncthreads();  // previous users of the K buffers and of s_l2 are done
-      if (g == 0) {
-#pragma unroll
-        for (int j = 0; j < CH; ++j) {
-          const int head = hk * rep + min(hc + j, rep - 1);
-          s_l2[wave][j][lq] = (has_tile && lq < tl.nrows && j < nch)
-                                  ? lse[(size_t)(tl.row0 + lq) * n_q_heads + head] * 1.4426950408889634f
-                                  : INFINITY;
-        }
-      }
-      SC_GLOAD(0)
-      SC_SSTORE(0)
-      __syncthreads();
-      for (int kt = 0; kt < n_kt; ++kt) {
-        const int cur = kt & 1;
-        if (kt + 1 < n_kt) { SC_GLOAD(kt + 1) }
-        const int k0 = c0 + kt * S_KEYS;
-        if (has_tile && k0 <= tile_last_row) {
-#pragma unroll
-          for (int st = 0; st < 2; ++st) {
-            const int key = k0 + st * 32 + lq;  // this lane's key column
-            bf16x8 kf[8];
-            const uint16_t* krow = &s_k[cur * S_KEYS * S_KSTRIDE + (st * 32 + lq) * S_KSTRIDE + g * 8];
-#pragma unroll
-            for (int ks = 0; ks < 8; ++ks) kf[ks] = *reinterpret_cast<const bf16x8*>(krow + ks * 16);
-            // only tiles that touch the diagonal (or the end of the key list) need the per-element test
-            const bool need_mask = (k0 + S_KEYS - 1 > tl.row0) || (k0 + S_KEYS > n_keys);
-            const bool key_ok = key < n_keys;
-            float csum = 0.f;
-#pragma unroll
-            for (int j = 0; j < CH; ++j) {
-              if (j >= nch) break;
-              f32x16 acc;
-#pragma unroll
-              for (int e = 0; e < 16; ++e) acc[e] = 0.f;
-#pragma unroll
-              for (int ks = 0; ks < 8; ++ks)
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[j][ks], kf[ks], acc, 0, 0, 0);
-#pragma unroll
-              for (int e4 = 0; e4 < 4; ++e4) {
-                // registers 4*e4 .. 4*e4+3 are rows 8*e4 + 4*g + {0..3} of the tile
-                const float4 l4 = *reinterpret_cast<const float4*>(&s_l2[wave][j][8 * e4 + 4 * g]);
-                const float lv[4] = {l4.x, l4.y, l4.z, l4.w};
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                  const int row = tl.row0 + 8 * e4 + 4 * g + i;
-                  const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(acc[4 * e4 + i], scale_log2e, -lv[i]));
-                  csum += (!need_mask || (key <= row && key_ok)) ? p : 0.f;
-                }
-              }
-            }
-            csum += __shfl_xor(csum, 32, 64);
-            if (g == 0) s_col[wave][kt * S_KEYS + st * 32 + lq] += csum;
-          }
-        }
-        if (kt + 1 < n_kt) { SC_SSTORE(cur ^ 1) }
-        __syncthreads();
-      }
+      const int head0 = hk * rep + hc;
+      if (nch == CH)
+        score_pass<CH>(q, kc, lse, s_k, s_col[wave], s_l2[wave], sw, q_row, hk, head0, n_q_heads, kv_dim, c0, n_kt,
+                       n_keys, scale_log2e);
+      else if (nch == 2)
+        score_pass<2>(q, kc, lse, s_k, s_col[wave], s_l2[wave], sw, q_row, hk, head0, n_q_heads, kv_dim, c0, n_kt,
+                      n_keys, scale_log2e);
+      else
+        score_pass<1>(q, kc, lse, s_k, s_col[wave], s_l2[wave], sw, q_row, hk, head0, n_q_heads, kv_dim, c0, n_kt,
+                      n_keys, scale_log2e);
     }
   }
-#undef SC_GLOAD
-#undef SC_GLOAD1
-#undef SC_SSTORE
-#undef SC_SSTORE1
   // column sums of this wave's row tile for the keys of the chunk
-  if (has_tile) {
+  if (sw.has_tile) {
     float* dst = colmass + ((size_t)blockIdx.z * n_rt + rt) * col_ld + c0;
     for (int i = lane; i < key_end - c0; i += 64) dst[i] = s_col[wave][i];
   }
