@@ -24,6 +24,10 @@ PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 
 
+# (2.0 x FETCH_SIZE + 1.0 x WRITE_SIZE) of the gate/up GEMM launches of one step / 48 launches
+GATE_UP_TRAFFIC_BYTES_PER_LAUNCH = int(((39313940 + 4109788) * 2.0 + 4069440) * 1024 / 48)
+
+
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -38,6 +42,9 @@ def parse():
     ap.add_argument("--layers-json", default=None, help="also write the per-layer timing report to this file")
     ap.add_argument("--random-cache", action="store_true",
                     help="random group caches instead of caches prefilled by the library (faster set-up)")
+    ap.add_argument("--calib-copy-mib", type=int, default=0,
+                    help="launch one device copy of this many MiB before the warm-up: the known-size "
+                         "kernel that scales rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
     return ap.parse_args()
 
 
@@ -230,6 +237,13 @@ def main():
                            a.load_mode, want_report=report)
 
     gate.resume()
+    if a.calib_copy_mib > 0:
+        src = torch.empty(a.calib_copy_mib << 20, dtype=torch.uint8, device="cuda")
+        src.zero_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(a.warmup):
         step(False)
     torch.cuda.synchronize()
@@ -271,7 +285,13 @@ def main():
     add("sparse_row_attention", mean_ms("ms_attn"), 4.0 * s.head_dim * s.n_q_heads * vis, "TFLOP/s", PEAK_BF16_TFLOPS)
     add("realign_concat", mean_ms("ms_realign"), 4.0 * re_rows * kvd * esz, "GB/s", PEAK_HBM_GBS)
     add("rope_scatter", mean_ms("ms_rope"), rows * ((qd + 2 * kvd) * 4.0 + (qd + 3 * kvd) * esz), "GB/s", PEAK_HBM_GBS)
-    add("score_select", mean_ms("ms_score"), np.zeros(L), "GB/s", PEAK_HBM_GBS)
+    # score pass: Q.K^T of every recomputed row against the recomputed memory keys at or before it
+    # (the same compact list), then the reductions and the selector; layers whose budget keeps all
+    # or none of the candidates run no pass
+    ms_sc = mean_ms("ms_score")
+    mem = np.maximum(rows - lq, 0.0)
+    pairs = np.where(ms_sc > 0, mem * (mem + 1) / 2 + lq * mem, 0.0)
+    add("score_select", ms_sc, 2.0 * s.head_dim * s.n_q_heads * pairs, "TFLOP/s", PEAK_BF16_TFLOPS)
     # attention in bytes too: one pass over the visible K and V per (row tile, KV head) is the algorithmic
     # minimum only when rows share tiles; report the cache-size figure (K_hat + V_hat of the layer, once)
     att_ms = float(np.sum(mean_ms("ms_attn")))
@@ -279,9 +299,15 @@ def main():
 
     gu = kern["gemm_gate_up_swiglu"]
     n_launch = L
-    roofline = {"kernel": "k_gemm_mfma<256,256,2,2,SWIGLU> (gate/up projection with fused SiLU*mul)",
+    # L2-miss bytes per launch from the two rocprofv3 counter runs summarised in
+    # profiles/keep_prefill_qwen14b_32k_hbm_traffic.md; they hold for that workload at its default settings only
+    default_run = (a.workload == "qwen14b_32k" and a.schedule is None and a.ratio is None and a.budget is None
+                   and not a.random_cache)
+    traffic = GATE_UP_TRAFFIC_BYTES_PER_LAUNCH if default_run else None
+    roofline = {"kernel": "k_gemm_mfma<...,SWIGLU> (gate/up projection with fused SiLU*mul; 256x256 tiles, "
+                          "128x128 for launches of fewer than 1024 such tiles)",
                 "bound": "mfma", "achieved": gu["achieved"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": gu["frac"], "traffic": None,
+                "frac": gu["frac"], "traffic": traffic,
                 "avg_launch_ms": round(gu["ms_per_step"] / n_launch, 4), "launches_per_step": n_launch}
 
     out = {
