@@ -42,6 +42,8 @@ def parse():
     ap.add_argument("--layers-json", default=None, help="also write the per-layer timing report to this file")
     ap.add_argument("--random-cache", action="store_true",
                     help="random group caches instead of caches prefilled by the library (faster set-up)")
+    ap.add_argument("--memory-update", action="store_true",
+                    help="measure the cost of one memory update on the workload's model shape instead of the prefill")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="launch one device copy of this many MiB before the warm-up: the known-size "
                          "kernel that scales rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
@@ -74,31 +76,67 @@ class ProfilerGate:
 
 def precompute_group_caches(ctx, w, glen, ids, torch):
     """Group caches made by the library's own dense path on each group alone, at group-local
-    positions (a lone group recomputed at every layer is a dense prefill of that group)."""
-    from paper_2602_23592_amd import KeepPrompt
+    positions (Section 4.1: every static group and every dynamic segment is cached on its own)."""
     s = w.shape
     L, n_mem = s.n_layers, int(np.sum(glen))
     dt = torch.bfloat16 if s.storage == "bf16" else torch.float32
     kb_all = torch.empty((L, n_mem, s.n_kv_heads, s.head_dim), dtype=dt, device="cuda")
     vb_all = torch.empty_like(kb_all)
     off = np.concatenate([[0], np.cumsum(glen)])
-    ones = [1.0] * L
     scratch = {}
     for g, n in enumerate(glen):
         n = int(n)
         if n not in scratch:
-            scratch[n] = (torch.empty((L, n + 1, s.n_kv_heads, s.head_dim), dtype=dt, device="cuda"),
-                          torch.empty((L, n + 1, s.n_kv_heads, s.head_dim), dtype=dt, device="cuda"),
-                          torch.empty((1, s.hidden), dtype=dt, device="cuda"))
-        kc, vc, xf = scratch[n]
-        tok = np.concatenate([ids[off[g]:off[g + 1]], ids[-1:]])
-        dummy = [[kc[l] for _ in range(1)] for l in range(L)]          # never read: the group is always in the set
-        pr = KeepPrompt([n], 1, tok, dummy, dummy, L)
-        ctx.prefill(pr, ones, 1, kc, vc, xf)
-        kb_all[:, off[g]:off[g + 1]] = kc[:, :n]
-        vb_all[:, off[g]:off[g + 1]] = vc[:, :n]
+            scratch[n] = (torch.empty((L, n, s.n_kv_heads, s.head_dim), dtype=dt, device="cuda"),
+                          torch.empty((L, n, s.n_kv_heads, s.head_dim), dtype=dt, device="cuda"))
+        kc, vc = scratch[n]
+        ctx.precompute_group(ids[off[g]:off[g + 1]], kc, vc)
+        kb_all[:, off[g]:off[g + 1]] = kc
+        vb_all[:, off[g]:off[g + 1]] = vc
     torch.cuda.synchronize()
     return kb_all, vb_all
+
+
+def memory_update_cost(ctx, w, torch, steps, warmup):
+    """Cost of one memory update (Section 4.1) on this model shape: the KV computation that the
+    static-dynamic store asks for after (a) an update of one dynamic segment, (b) a static group that
+    turned dynamic (each segment on its own), (c) a dynamic group that turned static (jointly)."""
+    s = w.shape
+    dt = torch.bfloat16 if s.storage == "bf16" else torch.float32
+    seg, nseg = 64, 16
+    rng = np.random.default_rng(3)
+    toks = rng.integers(0, s.vocab, size=seg * nseg).astype(np.int32)
+    k1 = torch.empty((s.n_layers, seg, s.n_kv_heads, s.head_dim), dtype=dt, device="cuda")
+    v1 = torch.empty_like(k1)
+    kg = torch.empty((s.n_layers, seg * nseg, s.n_kv_heads, s.head_dim), dtype=dt, device="cuda")
+    vg = torch.empty_like(kg)
+
+    def one_segment():
+        ctx.precompute_group(toks[:seg], k1, v1)
+
+    def every_segment():
+        for i in range(nseg):
+            ctx.precompute_group(toks[i * seg:(i + 1) * seg], k1, v1)
+
+    def whole_group():
+        ctx.precompute_group(toks, kg, vg)
+
+    out = {}
+    for name, fn, ntok in (("dynamic_segment_update", one_segment, seg),
+                           ("static_to_dynamic", every_segment, seg * nseg),
+                           ("dynamic_to_static", whole_group, seg * nseg)):
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / steps
+        out[name] = {"ms": round(ms, 3), "tokens": ntok, "tokens_per_s": round(ntok / (ms * 1e-3), 1)}
+    return {"metric": "memory update cost (KV computation the static-dynamic store triggers)",
+            "segment_tokens": seg, "segments_per_group": nseg, "layers": s.n_layers, "n_gpus": 1,
+            "steps": steps, "warmup": warmup, "dtype": s.storage, "data": "synthetic", "cases": out}
 
 
 def visible_keys(sets, glen, lq):
@@ -203,6 +241,10 @@ def main():
     streams = [torch.cuda.Stream() for _ in range(3)]
     torch.cuda.synchronize()
     ctx = KeepContext(s, layers, embed, n_tokens, G, kb.KEEP_KERNELS_AUTO, *streams)
+    if a.memory_update:
+        gate.resume()
+        print(json.dumps(memory_update_cost(ctx, w, torch, a.steps, a.warmup)))
+        return
     if a.random_cache:
         kb_all = torch.empty((s.n_layers, w.mem_tokens, s.n_kv_heads, s.head_dim), dtype=dt, device="cuda")
         vb_all = torch.empty_like(kb_all)

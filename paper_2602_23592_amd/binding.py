@@ -24,7 +24,10 @@ KEEP_KERNELS_AUTO, KEEP_KERNELS_GENERIC = 0, 1
 KEEP_REPORT_MAX_LAYERS = 128
 
 EXPORTED = ("keep_init", "keep_destroy", "keep_last_error", "keep_uses_mfma", "keep_workspace_bytes", "keep_recompute_layer",
-            "keep_score_groups", "keep_select_groups", "keep_prefill")
+            "keep_score_groups", "keep_select_groups", "keep_prefill",
+            "keep_precompute_group", "keep_memory_create", "keep_memory_destroy", "keep_memory_last_error",
+            "keep_memory_put", "keep_memory_remove", "keep_memory_end_step", "keep_memory_unit_count",
+            "keep_memory_unit_info", "keep_memory_unit_tokens", "keep_memory_mark_computed")
 
 
 class KeepError(RuntimeError):
@@ -68,6 +71,15 @@ class Report(C.Structure):
 _lib = None
 
 
+class MemoryUnit(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("kind", "id", "group", "n_segments", "n_tokens", "dirty")]
+
+
+class MemoryStepReport(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("step", "n_static", "n_dynamic", "n_to_dynamic", "n_to_static",
+                                         "dirty_units")] + [("dirty_tokens", C.c_int64)]
+
+
 def load_library() -> C.CDLL:
     """dlopen the HIP library; raises if it has not been built (no fallback)."""
     global _lib
@@ -98,6 +110,28 @@ def load_library() -> C.CDLL:
     lib.keep_prefill.restype = i32
     lib.keep_prefill.argtypes = [vp, C.POINTER(Prompt), C.POINTER(f32), i32, i32, i32, vp, vp, vp, pi32, pi32,
                                  C.POINTER(Report)]
+    lib.keep_precompute_group.restype = i32
+    lib.keep_precompute_group.argtypes = [vp, pi32, i32, vp, vp, C.POINTER(Report)]
+    lib.keep_memory_create.restype = i32
+    lib.keep_memory_create.argtypes = [i32, C.POINTER(vp)]
+    lib.keep_memory_destroy.restype = i32
+    lib.keep_memory_destroy.argtypes = [vp]
+    lib.keep_memory_last_error.restype = C.c_char_p
+    lib.keep_memory_last_error.argtypes = [vp]
+    lib.keep_memory_put.restype = i32
+    lib.keep_memory_put.argtypes = [vp, i32, i32, pi32, i32, pi32]
+    lib.keep_memory_remove.restype = i32
+    lib.keep_memory_remove.argtypes = [vp, i32]
+    lib.keep_memory_end_step.restype = i32
+    lib.keep_memory_end_step.argtypes = [vp, C.POINTER(MemoryStepReport), pi32, i32, pi32, i32]
+    lib.keep_memory_unit_count.restype = i32
+    lib.keep_memory_unit_count.argtypes = [vp]
+    lib.keep_memory_unit_info.restype = i32
+    lib.keep_memory_unit_info.argtypes = [vp, i32, C.POINTER(MemoryUnit)]
+    lib.keep_memory_unit_tokens.restype = i32
+    lib.keep_memory_unit_tokens.argtypes = [vp, i32, pi32, i32, pi32]
+    lib.keep_memory_mark_computed.restype = i32
+    lib.keep_memory_mark_computed.argtypes = [vp, i32]
     _lib = lib
     return lib
 
@@ -254,3 +288,75 @@ class KeepContext:
             cnt.ctypes.data_as(C.POINTER(C.c_int32)), C.byref(rep) if want_report else None))
         sets = [[int(v) for v in sel[l * G:l * G + cnt[l]]] for l in range(L)]
         return sets, rep
+
+    def precompute_group(self, token_ids: Sequence[int], k_blocks: torch.Tensor, v_blocks: torch.Tensor,
+                         want_report: bool = False):
+        """KV blocks [n_layers][n, n_kv_heads, head_dim] of one memory unit computed on its own."""
+        ids, ip = _i32_array(token_ids)
+        rep = Report() if want_report else None
+        self._check(self.lib.keep_precompute_group(self.handle, ip, len(ids), k_blocks.data_ptr(), v_blocks.data_ptr(),
+                                                   C.byref(rep) if want_report else None))
+        return rep
+
+
+class KeepMemory:
+    """Static-dynamic memory store of the library (host-side bookkeeping; marshalling only)."""
+
+    def __init__(self, window_t: int):
+        self.lib = load_library()
+        h = C.c_void_p()
+        st = self.lib.keep_memory_create(window_t, C.byref(h))
+        if st != KEEP_OK:
+            raise KeepError(st, "keep_memory_create failed")
+        self.handle = h
+
+    def close(self):
+        if self.handle:
+            self.lib.keep_memory_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, st: int):
+        if st != KEEP_OK:
+            raise KeepError(st, self.lib.keep_memory_last_error(self.handle).decode())
+
+    def put(self, group: int, segment: int, tokens: Sequence[int]) -> bool:
+        ids, ip = _i32_array(tokens if len(tokens) else [0])
+        changed = C.c_int32(0)
+        self._check(self.lib.keep_memory_put(self.handle, group, segment, ip, len(tokens), C.byref(changed)))
+        return bool(changed.value)
+
+    def remove(self, segment: int):
+        self._check(self.lib.keep_memory_remove(self.handle, segment))
+
+    def end_step(self, cap: int = 4096):
+        rep = MemoryStepReport()
+        td = np.zeros(cap, dtype=np.int32)
+        ts = np.zeros(cap, dtype=np.int32)
+        p32 = C.POINTER(C.c_int32)
+        self._check(self.lib.keep_memory_end_step(self.handle, C.byref(rep), td.ctypes.data_as(p32), cap,
+                                                  ts.ctypes.data_as(p32), cap))
+        return rep, [int(v) for v in td[:rep.n_to_dynamic]], [int(v) for v in ts[:rep.n_to_static]]
+
+    def units(self):
+        out = []
+        for i in range(self.lib.keep_memory_unit_count(self.handle)):
+            u = MemoryUnit()
+            self._check(self.lib.keep_memory_unit_info(self.handle, i, C.byref(u)))
+            out.append(u)
+        return out
+
+    def unit_tokens(self, unit: int, cap: int):
+        buf = np.zeros(max(1, cap), dtype=np.int32)
+        n = C.c_int32(0)
+        self._check(self.lib.keep_memory_unit_tokens(self.handle, unit, buf.ctypes.data_as(C.POINTER(C.c_int32)), cap,
+                                                     C.byref(n)))
+        return [int(v) for v in buf[:n.value]]
+
+    def mark_computed(self, unit: int):
+        self._check(self.lib.keep_memory_mark_computed(self.handle, unit))

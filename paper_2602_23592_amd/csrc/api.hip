@@ -13,6 +13,7 @@
 #include <vector>
 
 #include "keep_internal.h"
+#include "keep_memory.h"
 
 using namespace keep;
 
@@ -61,7 +62,7 @@ struct keep_ctx {
   int32_t *d_set_off = nullptr, *d_row_start = nullptr, *d_gather_src = nullptr, *d_cand_len = nullptr;
   RealignSeg* d_segs = nullptr;
   void *xa = nullptr, *xb = nullptr, *hbuf = nullptr, *q = nullptr, *kc = nullptr, *o = nullptr, *x1 = nullptr,
-       *act = nullptr, *attn_scratch = nullptr;
+       *act = nullptr, *attn_scratch = nullptr, *skinny_ws = nullptr;
   float *qkv_raw = nullptr, *lse = nullptr, *score_scratch = nullptr, *S = nullptr, *sel_work = nullptr;
   int32_t *sel_iwork = nullptr, *sel_out = nullptr;
 
@@ -195,6 +196,7 @@ uint64_t workspace_bytes(const keep_model_desc* d) {
   t += align256(z.M * (size_t)d->n_q_heads * sizeof(float));           // lse
   t += align256(score_scratch_bytes(d));
   if (wants_mfma(d)) t += align256(attn_mfma_scratch_bytes((int32_t)z.M, d->n_q_heads, d->n_kv_heads));
+  if (wants_mfma(d)) t += align256(gemm_skinny_ws_bytes());
   t += align256((z.G + 1) * z.G * sizeof(float));                      // S
   t += align256(((z.G + 1) * z.G + 2 * z.G) * sizeof(float));          // sel_work
   t += align256(4 * z.G * sizeof(int32_t)) + align256((z.G + 2) * sizeof(int32_t));
@@ -381,7 +383,7 @@ keep_status layer_front(keep_ctx* c, const PromptInfo& pi, int layer, const Laye
   const int n_qkv = b.n_rows[0] + 2 * b.n_rows[1];
   if (c->mfma)
     launch_gemm_mfma(reinterpret_cast<const bf16_t*>(c->hbuf), n, d.hidden, b, nullptr, n_qkv, EPI_STORE_F32, nullptr,
-                     c->qkv_raw, s);
+                     c->qkv_raw, s, c->skinny_ws);
   else
     launch_gemm_generic<T>(Typed<T>::p(c->hbuf), n, d.hidden, b, nullptr, n_qkv, EPI_STORE_F32, nullptr, c->qkv_raw, s);
   if (evs) HIP_TRY(c, hipEventRecord(evs[3], s));
@@ -418,13 +420,13 @@ keep_status layer_back(keep_ctx* c, int layer, int n, const void* o_rows, const 
   EV(12);
   if (c->mfma) {
     auto B = [](const void* p) { return reinterpret_cast<const bf16_t*>(p); };
-    launch_gemm_mfma(B(o_rows), n, qd, bo, nullptr, d.hidden, EPI_RESIDUAL_STORE, B(x_in), c->x1, s);
+    launch_gemm_mfma(B(o_rows), n, qd, bo, nullptr, d.hidden, EPI_RESIDUAL_STORE, B(x_in), c->x1, s, c->skinny_ws);
     EV(6);
     launch_rmsnorm<bf16_t>(B(c->x1), B(w.ln2), n, d.hidden, d.rms_eps, reinterpret_cast<bf16_t*>(c->hbuf), s);
     EV(7);
-    launch_gemm_mfma(B(c->hbuf), n, d.hidden, bg, w.wup, d.ffn_dim, EPI_SWIGLU_STORE, nullptr, c->act, s);
+    launch_gemm_mfma(B(c->hbuf), n, d.hidden, bg, w.wup, d.ffn_dim, EPI_SWIGLU_STORE, nullptr, c->act, s, c->skinny_ws);
     EV(8);
-    launch_gemm_mfma(B(c->act), n, d.ffn_dim, bd, nullptr, d.hidden, EPI_RESIDUAL_STORE, B(c->x1), x_out, s);
+    launch_gemm_mfma(B(c->act), n, d.ffn_dim, bd, nullptr, d.hidden, EPI_RESIDUAL_STORE, B(c->x1), x_out, s, c->skinny_ws);
   } else {
     launch_gemm_generic<T>(Typed<T>::p(o_rows), n, qd, bo, nullptr, d.hidden, EPI_RESIDUAL_STORE, Typed<T>::p(x_in),
                            c->x1, s);
@@ -499,6 +501,12 @@ keep_status by_dtype(keep_ctx* c, F&& f) {
 // ===========================================================================
 // public functions
 // ===========================================================================
+namespace {
+keep_status prefill_impl(keep_ctx* c, const keep_prompt* p, const float* ratios, int32_t hops, int32_t budget_mode,
+                         int32_t load_mode, void* k_cache, void* v_cache, void* x_final, int32_t* sel_groups,
+                         int32_t* sel_counts, keep_report* report);
+}  // namespace
+
 extern "C" {
 
 const char* keep_last_error(const keep_ctx* ctx) { return ctx ? ctx->err.c_str() : g_init_error.c_str(); }
@@ -600,9 +608,11 @@ keep_status keep_init(const keep_model_desc* desc, const keep_layer_weights* lay
   TRY_INIT(dev_alloc(c, &c->qkv_raw, z.M * (z.qd + 2 * z.kvd) * sizeof(float)));
   TRY_INIT(dev_alloc(c, &c->lse, z.M * (size_t)desc->n_q_heads * sizeof(float)));
   TRY_INIT(dev_alloc(c, &c->score_scratch, score_scratch_bytes(desc)));
-  if (c->mfma)
+  if (c->mfma) {
     TRY_INIT(dev_alloc(c, reinterpret_cast<char**>(&c->attn_scratch),
                        attn_mfma_scratch_bytes((int32_t)z.M, desc->n_q_heads, desc->n_kv_heads)));
+    TRY_INIT(dev_alloc(c, reinterpret_cast<char**>(&c->skinny_ws), gemm_skinny_ws_bytes()));
+  }
   TRY_INIT(dev_alloc(c, &c->S, (z.G + 1) * z.G * sizeof(float)));
   TRY_INIT(dev_alloc(c, &c->sel_work, ((z.G + 1) * z.G + 2 * z.G) * sizeof(float)));
   TRY_INIT(dev_alloc(c, &c->sel_iwork, 4 * z.G * 4));
@@ -917,11 +927,43 @@ keep_status keep_prefill(keep_ctx* c, const keep_prompt* p, const float* ratios,
                          int32_t load_mode, void* k_cache, void* v_cache, void* x_final, int32_t* sel_groups,
                          int32_t* sel_counts, keep_report* report) {
   if (!c) return KEEP_ERR_INVALID_ARG;
+  if (!x_final) return fail(c, KEEP_ERR_INVALID_ARG, "x_final is NULL");
+  return prefill_impl(c, p, ratios, hops, budget_mode, load_mode, k_cache, v_cache, x_final, sel_groups, sel_counts,
+                      report);
+}
+
+keep_status keep_precompute_group(keep_ctx* c, const int32_t* token_ids, int32_t n_tokens, void* k_blocks,
+                                  void* v_blocks, keep_report* report) {
+  if (!c) return KEEP_ERR_INVALID_ARG;
+  if (!token_ids || !k_blocks || !v_blocks) return fail(c, KEEP_ERR_INVALID_ARG, "token_ids / k_blocks / v_blocks is NULL");
+  if (n_tokens < 1) return fail(c, KEEP_ERR_INVALID_ARG, "a unit needs at least one token");
+  // A prompt without memories whose "instruction" is the unit: every row is recomputed at every layer
+  // over its own causal prefix at positions 0..n-1, which is the dense prefill of the unit on its own;
+  // the joined cache of that prompt is the unit's block of every layer.
+  keep_prompt pr;
+  memset(&pr, 0, sizeof pr);
+  pr.n_groups = 0;
+  pr.instr_len = n_tokens;
+  pr.token_ids = token_ids;
+  pr.kv_location = KEEP_KV_DEVICE;
+  std::vector<float> ratios((size_t)c->d.n_layers, 0.f);
+  return prefill_impl(c, &pr, ratios.data(), 1, KEEP_BUDGET_GROUP_COUNT, KEEP_LOAD_SERIAL, k_blocks, v_blocks, nullptr,
+                      nullptr, nullptr, report);
+}
+
+}  // extern "C"
+
+namespace {
+
+// x_final may be NULL (the hidden rows are not wanted).
+keep_status prefill_impl(keep_ctx* c, const keep_prompt* p, const float* ratios, int32_t hops, int32_t budget_mode,
+                         int32_t load_mode, void* k_cache, void* v_cache, void* x_final, int32_t* sel_groups,
+                         int32_t* sel_counts, keep_report* report) {
   const auto t_begin = std::chrono::steady_clock::now();
   const keep_model_desc& d = c->d;
   const int L = d.n_layers;
-  if (!ratios || !k_cache || !v_cache || !x_final)
-    return fail(c, KEEP_ERR_INVALID_ARG, "ratios / k_cache / v_cache / x_final is NULL");
+  if (!ratios || !k_cache || !v_cache)
+    return fail(c, KEEP_ERR_INVALID_ARG, "ratios / k_cache / v_cache is NULL");
   if (budget_mode != KEEP_BUDGET_GROUP_COUNT && budget_mode != KEEP_BUDGET_TOKENS)
     return fail(c, KEEP_ERR_INVALID_ARG, "unknown budget_mode");
   if (load_mode < KEEP_LOAD_SERIAL || load_mode > KEEP_LOAD_LAYER_BALANCED)
@@ -1174,7 +1216,7 @@ keep_status keep_prefill(keep_ctx* c, const keep_prompt* p, const float* ratios,
     cur.swap(nxt);
   }
   // final hidden rows of the instruction
-  {
+  if (x_final) {
     const char* src = (const char*)x_nxt + (size_t)(plan.n_rows - pi.Lq) * d.hidden * c->esz;
     HIP_TRY(c, hipMemcpyAsync(x_final, src, (size_t)pi.Lq * d.hidden * c->esz, hipMemcpyDeviceToDevice, c->s_comp));
   }
@@ -1200,4 +1242,4 @@ keep_status keep_prefill(keep_ctx* c, const keep_prompt* p, const float* ratios,
   return KEEP_OK;
 }
 
-}  // extern "C"
+}  // namespace

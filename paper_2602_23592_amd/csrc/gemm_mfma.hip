@@ -286,8 +286,12 @@ static void launch_cfg(const bf16_t* A, int M, int K, const MfmaB& b, const bf16
 }
 
 void launch_gemm_mfma(const bf16_t* A, int32_t M, int32_t K, const GemmB& B, const void* B2, int32_t N, int epilogue,
-                      const bf16_t* residual, void* C, hipStream_t s) {
+                      const bf16_t* residual, void* C, hipStream_t s, void* skinny_ws) {
   if (M <= 0 || N <= 0) return;
+  if (skinny_ws && gemm_skinny_fits(M, K, B, N, epilogue)) {
+    launch_gemm_skinny(A, M, K, B, B2, N, epilogue, residual, C, skinny_ws, s);
+    return;
+  }
   MfmaB b;
   b.n_parts = B.n_parts;
   int acc = 0;

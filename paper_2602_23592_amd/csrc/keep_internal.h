@@ -125,8 +125,14 @@ void launch_score_finish(const float* rowmass, const int32_t* d_row_start, int32
                          hipStream_t s);
 
 // MFMA (bf16, head_dim 128) kernels
+// skinny_ws: device scratch of gemm_skinny_ws_bytes() for launches of at most 64 rows (weight-streaming
+// kernel with K slices), or NULL to always use the tiled kernels.
 void launch_gemm_mfma(const bf16_t* A, int32_t M, int32_t K, const GemmB& B, const void* B2, int32_t N, int epilogue,
-                      const bf16_t* residual, void* C, hipStream_t s);
+                      const bf16_t* residual, void* C, hipStream_t s, void* skinny_ws = nullptr);
+size_t gemm_skinny_ws_bytes();
+bool gemm_skinny_fits(int32_t M, int32_t K, const GemmB& B, int32_t N, int epilogue);
+void launch_gemm_skinny(const bf16_t* A, int32_t M, int32_t K, const GemmB& B, const void* B2, int32_t N, int epilogue,
+                        const bf16_t* residual, void* C, void* ws, hipStream_t s);
 // h_row_start / h_set_off / m / instr_off: the host copy of the layer's row layout (as for
 // launch_build_rows), from which the work list is planned; h_stage: pinned host ints
 // (attn_mfma_stage_ints), d_scratch: device bytes (attn_mfma_scratch_bytes).
