@@ -30,7 +30,9 @@ PyTorch-CPU expression; ratio 1 == dense causal prefill; ratio 0 == re-rotated
 concatenation; lone group reproduces its cache; RoPE composition and the
 relative-position property; first-group and layer-0 invariances; attention-mass
 conservation; harmonic closed form under uniform attention; brute-force top-k
-and token-budget walks; hand-built propagation chains.
+and token-budget walks; hand-built propagation chains; decoding one token over
+a cache == the last row of a dense prefill of the longer sequence; logits vs an
+independent PyTorch-CPU expression; argmax tie rule.
 Parity unpinned: whether the selected memories are the ones a trained model
 needs (task success rate) -- that needs the paper's datasets and weights.
 """
@@ -503,3 +505,64 @@ def keep_prefill(sh: Shape, layers, embed: np.ndarray, token_ids: np.ndarray, gr
         cur, pos = nxt, pos_next
     return {"k_hat": k_hat, "v_hat": v_hat, "x_final": x[len(x) - instr_len:], "sets": sets,
             "scores": scores, "hops_run": hops_run}
+
+
+# ----------------------------------------------------------------------------
+# first token and short greedy decoding over the joined cache
+# (Section 1: the planner emits a short action after the long prompt;
+#  Section 5: `prefill_layer` leaves "the updated KV cache for decoding")
+# ----------------------------------------------------------------------------
+def lm_logits(sh: Shape, final_norm: np.ndarray, lm_head: np.ndarray, x: np.ndarray) -> np.ndarray:
+    """Final RMSNorm and vocabulary projection of hidden rows x [n, hidden] -> [n, vocab]."""
+    return rmsnorm(x, final_norm, sh.rms_eps) @ lm_head.T
+
+
+def greedy_token(logits_row: np.ndarray) -> int:
+    """reading: greedy decoding, the lowest token id among equal maxima."""
+    return int(np.argmax(logits_row))
+
+
+def decode_layer(sh: Shape, w: Dict[str, np.ndarray], x_row: np.ndarray, position: int,
+                 k_cache_l: np.ndarray, v_cache_l: np.ndarray):
+    """One new token at `position` through one layer: its K/V go to cache row `position` (rounded to the
+    cache format), it attends to rows 0..position, then output projection and FFN.
+    k_cache_l, v_cache_l: [rows >= position + 1, n_kv_heads, head_dim], updated in place."""
+    x = x_row.reshape(1, -1)
+    q, k, v = project_qkv(sh, w, x, np.array([position]))
+    k_cache_l[position] = round_to_storage(k, sh.storage)[0]
+    v_cache_l[position] = round_to_storage(v, sh.storage)[0]
+    rep = sh.n_q_heads // sh.n_kv_heads
+    o = np.empty_like(q)
+    for h in range(sh.n_q_heads):
+        kk = k_cache_l[:position + 1, h // rep, :]
+        s = (kk @ q[0, h, :]) / np.sqrt(float(sh.head_dim))
+        p = np.exp(s - s.max())
+        p = p / p.sum()
+        o[0, h, :] = p @ v_cache_l[:position + 1, h // rep, :]
+    return output_and_ffn(sh, w, x, o)[0]
+
+
+def greedy_decode(sh: Shape, layers, embed: np.ndarray, final_norm: np.ndarray, lm_head: np.ndarray,
+                  x_last: np.ndarray, k_cache: Sequence[np.ndarray], v_cache: Sequence[np.ndarray], n_ctx: int,
+                  n_new: int, forced_tokens: Optional[Sequence[int]] = None, dtype=np.float64):
+    """n_new greedy tokens after a prompt of n_ctx tokens whose last hidden row is x_last.
+
+    Token 0 comes from x_last; token t > 0 from running token t-1 at position n_ctx + t - 1 through every
+    layer over the cache (which gains that token's K/V).  forced_tokens[t], if given, replaces the choice
+    fed forward (teacher forcing for parity tests); the logits are those of the free choice either way.
+    k_cache[l], v_cache[l]: [rows >= n_ctx + n_new - 1, n_kv_heads, head_dim], updated in place.
+    Returns (tokens [n_new], logits [n_new, vocab])."""
+    tokens, logits = [], []
+    x = np.asarray(x_last, dtype=dtype)
+    for t in range(n_new):
+        lg = lm_logits(sh, final_norm, lm_head, x.reshape(1, -1))[0]
+        logits.append(lg)
+        tok = greedy_token(lg)
+        tokens.append(tok)
+        if t + 1 == n_new:
+            break
+        fed = tok if forced_tokens is None else int(forced_tokens[t])
+        x = embed[fed].astype(dtype)
+        for l in range(sh.n_layers):
+            x = decode_layer(sh, layers[l], x, n_ctx + t, k_cache[l], v_cache[l])
+    return tokens, np.stack(logits)
