@@ -42,6 +42,9 @@ def parse():
     ap.add_argument("--layers-json", default=None, help="also write the per-layer timing report to this file")
     ap.add_argument("--random-cache", action="store_true",
                     help="random group caches instead of caches prefilled by the library (faster set-up)")
+    ap.add_argument("--decode-tokens", type=int, default=0,
+                    help="instead of the prefill benchmark: prefill once, then time the first token and this many "
+                         "greedy decode steps over the joined cache")
     ap.add_argument("--memory-update", action="store_true",
                     help="measure the cost of one memory update on the workload's model shape instead of the prefill")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
@@ -95,6 +98,50 @@ def precompute_group_caches(ctx, w, glen, ids, torch):
         vb_all[:, off[g]:off[g + 1]] = vc
     torch.cuda.synchronize()
     return kb_all, vb_all
+
+
+def decode_bench(ctx, prompt, ratios, w, s, n_tokens, budget_mode, a, torch, dt):
+    """First token and short greedy decoding after the joined prefill (Section 1: the planner's answer is
+    a short action).  Per decoded token the path reads every layer's weights, the vocabulary projection and
+    the whole joined cache once: an HBM-bound regime."""
+    k = a.decode_tokens
+    cap = n_tokens + k + 1
+    kc = torch.empty((s.n_layers, cap, s.n_kv_heads, s.head_dim), dtype=dt, device="cuda")
+    vc = torch.empty_like(kc)
+    xf = torch.empty((w.instr_len, s.hidden), dtype=dt, device="cuda")
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(11)
+    fn = torch.ones(s.hidden, dtype=dt, device="cuda")
+    lm = (0.02 * torch.randn((s.vocab, s.hidden), generator=gen, device="cuda")).to(dt)
+    ctx.prefill(prompt, ratios, w.hops, kc, vc, xf, budget_mode, a.load_mode, cache_rows=cap)
+
+    def timed(n_new):
+        for _ in range(a.warmup):
+            ctx.decode(fn, lm, xf[-1], kc, vc, n_tokens, n_new)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(a.steps):
+            toks = ctx.decode(fn, lm, xf[-1], kc, vc, n_tokens, n_new)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / a.steps, toks
+
+    ms_first, _ = timed(1)
+    ms_all, toks = timed(k + 1)
+    ms_tok = (ms_all - ms_first) / k
+    esz = 2 if s.storage == "bf16" else 4
+    qd, kvd = s.n_q_heads * s.head_dim, s.n_kv_heads * s.head_dim
+    w_layer = (s.hidden * (qd + 2 * kvd) + qd * s.hidden + 3 * s.hidden * s.ffn_dim) * esz
+    head = s.vocab * s.hidden * esz
+    cache = 2.0 * (n_tokens + k / 2.0) * kvd * esz
+    bytes_tok = s.n_layers * (w_layer + cache) + head
+    return {"metric": "greedy decode over the joined cache", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+            "context_tokens": n_tokens, "decoded_tokens": k, "first_token_ms": round(ms_first, 3),
+            "ms_per_token": round(ms_tok, 3), "tokens_per_s": round(1e3 / ms_tok, 1),
+            "bytes_per_token": int(bytes_tok), "hbm": {"bound": "hbm", "achieved": round(bytes_tok / (ms_tok * 1e-3) / 1e9, 1),
+                                                       "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                                                       "frac": round(bytes_tok / (ms_tok * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)},
+            "first_token_gbs": round(head / (ms_first * 1e-3) / 1e9, 1), "dtype": s.storage, "data": "synthetic",
+            "tokens": toks[:8]}
 
 
 def memory_update_cost(ctx, w, torch, steps, warmup):
@@ -240,7 +287,7 @@ def main():
     ids = ks.make_token_ids(n_tokens, s.vocab, 0)
     streams = [torch.cuda.Stream() for _ in range(3)]
     torch.cuda.synchronize()
-    ctx = KeepContext(s, layers, embed, n_tokens, G, kb.KEEP_KERNELS_AUTO, *streams)
+    ctx = KeepContext(s, layers, embed, n_tokens + a.decode_tokens + 1, G, kb.KEEP_KERNELS_AUTO, *streams)
     if a.memory_update:
         gate.resume()
         print(json.dumps(memory_update_cost(ctx, w, torch, a.steps, a.warmup)))
@@ -277,6 +324,11 @@ def main():
     def step(report):
         return ctx.prefill(prompt, ratios, w.hops, k_cache, v_cache, x_final, budget_mode,
                            a.load_mode, want_report=report)
+
+    if a.decode_tokens > 0:
+        gate.resume()
+        print(json.dumps(decode_bench(ctx, prompt, ratios, w, s, n_tokens, budget_mode, a, torch, dt)))
+        return
 
     gate.resume()
     if a.calib_copy_mib > 0:

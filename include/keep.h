@@ -217,6 +217,34 @@ keep_status keep_prefill(keep_ctx* ctx, const keep_prompt* prompt, const float* 
                          int32_t budget_mode, int32_t load_mode, void* k_cache, void* v_cache, void* x_final,
                          int32_t* sel_groups, int32_t* sel_counts, keep_report* report);
 
+/* keep_prefill into caches with room for decoded tokens: as keep_prefill, but layer l of k_cache / v_cache
+ * starts at row l * cache_rows (cache_rows >= N); rows N..cache_rows-1 of every layer are left untouched.
+ * Errors: as keep_prefill, INVALID_ARG if cache_rows < N. */
+keep_status keep_prefill_padded(keep_ctx* ctx, const keep_prompt* prompt, const float* ratios, int32_t hops,
+                                int32_t budget_mode, int32_t load_mode, void* k_cache, void* v_cache,
+                                int32_t cache_rows, void* x_final, int32_t* sel_groups, int32_t* sel_counts,
+                                keep_report* report);
+
+#define KEEP_DECODE_MAX_TOKENS 64
+/* First token and short greedy decoding over the joined cache (Section 1: after the long prompt the
+ * planner emits a short action; Section 5: prefill_layer leaves "the updated KV cache for decoding").
+ * Token 0 = argmax over the vocabulary of lm_head . RMSNorm(x_last); token t > 0 comes from running
+ * token t-1 at position n_ctx + t - 1 through every layer: its K/V are written to row n_ctx + t - 1 of
+ * the caches and it attends to rows 0 .. n_ctx + t - 1.  Equal logits: the lowest token id.
+ *   final_norm: DEVICE [hidden]; lm_head: DEVICE [vocab, hidden] (row-major, as torch.nn.Linear).
+ *   x_last: DEVICE [hidden]: hidden row of the last prompt token (last row of keep_prefill's x_final).
+ *   k_cache, v_cache: DEVICE [n_layers][cache_rows, n_kv_heads, head_dim], rows 0..n_ctx-1 valid
+ *     (keep_prefill_padded's output); rows n_ctx .. n_ctx + n_new - 2 are written.
+ *   n_new: 1..KEEP_DECODE_MAX_TOKENS.  tokens_out: HOST [n_new], valid on return.
+ *   logits_out: DEVICE [n_new, vocab] fp32 or NULL.
+ *   forced_tokens: HOST [n_new - 1] or NULL; when given, forced_tokens[t] is fed forward instead of
+ *     token t (tokens_out still holds the greedy choices).
+ * Errors: INVALID_ARG (NULL, n_new out of range, n_ctx < 1, n_ctx + n_new - 1 above cache_rows),
+ * WORKSPACE (n_ctx + n_new - 1 above the context's max_tokens), HIP. */
+keep_status keep_decode(keep_ctx* ctx, const void* final_norm, const void* lm_head, const void* x_last,
+                        void* k_cache, void* v_cache, int32_t cache_rows, int32_t n_ctx, int32_t n_new,
+                        int32_t* tokens_out, float* logits_out, const int32_t* forced_tokens);
+
 #ifdef __cplusplus
 }
 #endif

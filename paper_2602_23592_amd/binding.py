@@ -25,7 +25,7 @@ KEEP_REPORT_MAX_LAYERS = 128
 
 EXPORTED = ("keep_init", "keep_destroy", "keep_last_error", "keep_uses_mfma", "keep_workspace_bytes", "keep_recompute_layer",
             "keep_score_groups", "keep_select_groups", "keep_prefill",
-            "keep_precompute_group", "keep_memory_create", "keep_memory_destroy", "keep_memory_last_error",
+            "keep_prefill_padded", "keep_decode", "keep_precompute_group", "keep_memory_create", "keep_memory_destroy", "keep_memory_last_error",
             "keep_memory_put", "keep_memory_remove", "keep_memory_end_step", "keep_memory_unit_count",
             "keep_memory_unit_info", "keep_memory_unit_tokens", "keep_memory_mark_computed")
 
@@ -110,6 +110,11 @@ def load_library() -> C.CDLL:
     lib.keep_prefill.restype = i32
     lib.keep_prefill.argtypes = [vp, C.POINTER(Prompt), C.POINTER(f32), i32, i32, i32, vp, vp, vp, pi32, pi32,
                                  C.POINTER(Report)]
+    lib.keep_prefill_padded.restype = i32
+    lib.keep_prefill_padded.argtypes = [vp, C.POINTER(Prompt), C.POINTER(f32), i32, i32, i32, vp, vp, i32, vp, pi32, pi32,
+                                        C.POINTER(Report)]
+    lib.keep_decode.restype = i32
+    lib.keep_decode.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, pi32, vp, pi32]
     lib.keep_precompute_group.restype = i32
     lib.keep_precompute_group.argtypes = [vp, pi32, i32, vp, vp, C.POINTER(Report)]
     lib.keep_memory_create.restype = i32
@@ -276,18 +281,40 @@ class KeepContext:
 
     def prefill(self, prompt: KeepPrompt, ratios: Sequence[float], hops: int, k_cache: torch.Tensor,
                 v_cache: torch.Tensor, x_final: torch.Tensor, budget_mode: int = KEEP_BUDGET_GROUP_COUNT,
-                load_mode: int = KEEP_LOAD_LAYER_BALANCED, want_report: bool = False):
+                load_mode: int = KEEP_LOAD_LAYER_BALANCED, want_report: bool = False,
+                cache_rows: Optional[int] = None):
+        """cache_rows: rows per layer of k_cache / v_cache when they leave room for decoded tokens."""
         L, G = self.shape.n_layers, prompt.n_groups
         r = np.ascontiguousarray(np.asarray(ratios, dtype=np.float32))
         sel = np.zeros(max(1, L * G), dtype=np.int32)
         cnt = np.zeros(L, dtype=np.int32)
         rep = Report() if want_report else None
-        self._check(self.lib.keep_prefill(
-            self.handle, C.byref(prompt.c), r.ctypes.data_as(C.POINTER(C.c_float)), hops, budget_mode, load_mode,
-            k_cache.data_ptr(), v_cache.data_ptr(), x_final.data_ptr(), sel.ctypes.data_as(C.POINTER(C.c_int32)),
-            cnt.ctypes.data_as(C.POINTER(C.c_int32)), C.byref(rep) if want_report else None))
+        if cache_rows is None:
+            self._check(self.lib.keep_prefill(
+                self.handle, C.byref(prompt.c), r.ctypes.data_as(C.POINTER(C.c_float)), hops, budget_mode, load_mode,
+                k_cache.data_ptr(), v_cache.data_ptr(), x_final.data_ptr(), sel.ctypes.data_as(C.POINTER(C.c_int32)),
+                cnt.ctypes.data_as(C.POINTER(C.c_int32)), C.byref(rep) if want_report else None))
+        else:
+            self._check(self.lib.keep_prefill_padded(
+                self.handle, C.byref(prompt.c), r.ctypes.data_as(C.POINTER(C.c_float)), hops, budget_mode, load_mode,
+                k_cache.data_ptr(), v_cache.data_ptr(), cache_rows, x_final.data_ptr(),
+                sel.ctypes.data_as(C.POINTER(C.c_int32)), cnt.ctypes.data_as(C.POINTER(C.c_int32)),
+                C.byref(rep) if want_report else None))
         sets = [[int(v) for v in sel[l * G:l * G + cnt[l]]] for l in range(L)]
         return sets, rep
+
+    def decode(self, final_norm: torch.Tensor, lm_head: torch.Tensor, x_last: torch.Tensor, k_cache: torch.Tensor,
+               v_cache: torch.Tensor, n_ctx: int, n_new: int, logits_out: Optional[torch.Tensor] = None,
+               forced_tokens: Optional[Sequence[int]] = None):
+        """Greedy tokens after a prompt of n_ctx tokens; caches are [n_layers, cache_rows, Hkv, dh]."""
+        out = np.zeros(max(1, n_new), dtype=np.int32)
+        fp = None
+        if forced_tokens is not None:
+            f, fp = _i32_array(list(forced_tokens) if len(forced_tokens) else [0])
+        self._check(self.lib.keep_decode(self.handle, final_norm.data_ptr(), lm_head.data_ptr(), x_last.data_ptr(),
+                                         k_cache.data_ptr(), v_cache.data_ptr(), k_cache.shape[1], n_ctx, n_new,
+                                         out.ctypes.data_as(C.POINTER(C.c_int32)), _ptr(logits_out), fp))
+        return [int(v) for v in out[:n_new]]
 
     def precompute_group(self, token_ids: Sequence[int], k_blocks: torch.Tensor, v_blocks: torch.Tensor,
                          want_report: bool = False):

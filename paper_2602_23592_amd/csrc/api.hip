@@ -69,6 +69,9 @@ struct keep_ctx {
   // pinned host
   std::vector<Staging> stage;       // one slot per layer
   int32_t* h_sel_out = nullptr;     // [max_groups + 2]
+  int32_t* h_dec = nullptr;         // pinned [4 * KEEP_DECODE_MAX_TOKENS]: positions, fed tokens, results
+  int32_t* d_dec = nullptr;         // device mirror
+  float* dec_logits = nullptr;      // [vocab]
   float* h_S = nullptr;             // [(max_groups+1) * max_groups]
   int32_t* h_token_ids = nullptr;   // [max_tokens]
 
@@ -200,6 +203,7 @@ uint64_t workspace_bytes(const keep_model_desc* d) {
   t += align256((z.G + 1) * z.G * sizeof(float));                      // S
   t += align256(((z.G + 1) * z.G + 2 * z.G) * sizeof(float));          // sel_work
   t += align256(4 * z.G * sizeof(int32_t)) + align256((z.G + 2) * sizeof(int32_t));
+  t += align256(4 * KEEP_DECODE_MAX_TOKENS * 4) + align256((size_t)d->vocab * sizeof(float));  // decode
   return t;
 }
 
@@ -496,6 +500,106 @@ keep_status by_dtype(keep_ctx* c, F&& f) {
   return c->d.dtype == KEEP_BF16 ? f((bf16_t*)nullptr) : f((float*)nullptr);
 }
 
+
+// Greedy decoding of n_new tokens over the joined cache.  The whole chain is enqueued on the compute
+// stream without a host round trip: each token id stays on the device (argmax output -> embedding gather).
+// For the attention the new token is a one-row "instruction" behind n_ctx + t - 1 cached tokens.
+template <typename T>
+keep_status decode_impl(keep_ctx* c, const void* final_norm, const void* lm_head, const void* x_last, void* k_cache,
+                        void* v_cache, int32_t cache_rows, int32_t n_ctx, int32_t n_new, int32_t* tokens_out,
+                        float* logits_out, const int32_t* forced_tokens) {
+  const keep_model_desc& d = c->d;
+  hipStream_t s = c->s_comp;
+  constexpr int CAP = KEEP_DECODE_MAX_TOKENS;
+  // pinned / device ints: [0, CAP) positions, [CAP, 2 CAP) fed tokens (forced), [2 CAP, 3 CAP) results, [3 CAP] zero
+  int32_t* h = c->h_dec;
+  for (int t = 0; t < CAP; ++t) {
+    h[t] = n_ctx + t;
+    h[CAP + t] = (forced_tokens && t + 1 < n_new) ? forced_tokens[t] : 0;
+    h[2 * CAP + t] = 0;
+  }
+  h[3 * CAP] = 0;
+  HIP_TRY(c, hipMemcpyAsync(c->d_dec, h, (size_t)(3 * CAP + 1) * 4, hipMemcpyHostToDevice, s));
+  const size_t row_bytes = (size_t)d.n_kv_heads * d.head_dim * c->esz;
+  const size_t layer_bytes = (size_t)cache_rows * row_bytes;
+  GemmB bh{};
+  bh.n_parts = 1;
+  bh.ptr[0] = lm_head;
+  bh.n_rows[0] = d.vocab;
+  PromptInfo pi;
+  pi.G = 0;
+  pi.Lq = 1;
+  pi.off.assign(1, 0);
+  LayerPlan plan;
+  plan.m = 0;
+  plan.n_rows = 1;
+  plan.row_start = {0, 1};
+  const void* x = x_last;
+  for (int t = 0; t < n_new; ++t) {
+    // vocabulary projection of the newest hidden row, greedy choice
+    float* lg = logits_out ? logits_out + (size_t)t * d.vocab : c->dec_logits;
+    launch_rmsnorm<T>(Typed<T>::p(x), Typed<T>::p(final_norm), 1, d.hidden, d.rms_eps, Typed<T>::p(c->hbuf), s);
+    if (c->mfma)
+      launch_gemm_mfma(reinterpret_cast<const bf16_t*>(c->hbuf), 1, d.hidden, bh, nullptr, d.vocab, EPI_STORE_F32,
+                       nullptr, lg, s, c->skinny_ws);
+    else
+      launch_gemm_generic<T>(Typed<T>::p(c->hbuf), 1, d.hidden, bh, nullptr, d.vocab, EPI_STORE_F32, nullptr, lg, s);
+    launch_argmax(lg, d.vocab, c->d_dec + 2 * CAP + t, s);
+    HIP_TRY(c, hipGetLastError());
+    if (t + 1 == n_new) break;
+    // the chosen (or forced) token at position n_ctx + t through every layer
+    const int32_t* d_tok = c->d_dec + (forced_tokens ? CAP : 2 * CAP) + t;
+    const int32_t* d_pos = c->d_dec + t;
+    pi.n_mem = n_ctx + t;
+    pi.N = n_ctx + t + 1;
+    launch_embed_gather<T>(Typed<T>::p(c->embed), d_tok, c->d_dec + 3 * CAP, 1, d.hidden, Typed<T>::p(c->xa), s);
+    void* x_cur = c->xa;
+    void* x_nxt = c->xb;
+    for (int l = 0; l < d.n_layers; ++l) {
+      const keep_layer_weights& w = c->w[l];
+      char* kl = (char*)k_cache + (size_t)l * layer_bytes;
+      char* vl = (char*)v_cache + (size_t)l * layer_bytes;
+      Staging& sg = c->stage[l];
+      if (sg.used) HIP_TRY(c, hipEventSynchronize(sg.done));  // the slot's last upload has been consumed
+      launch_rmsnorm<T>(Typed<T>::p(x_cur), Typed<T>::p(w.ln1), 1, d.hidden, d.rms_eps, Typed<T>::p(c->hbuf), s);
+      GemmB b;
+      b.n_parts = 3;
+      b.ptr[0] = w.wq; b.ptr[1] = w.wk; b.ptr[2] = w.wv;
+      b.bias[0] = w.bq; b.bias[1] = w.bk; b.bias[2] = w.bv;
+      b.n_rows[0] = d.n_q_heads * d.head_dim;
+      b.n_rows[1] = b.n_rows[2] = d.n_kv_heads * d.head_dim;
+      const int n_qkv = b.n_rows[0] + 2 * b.n_rows[1];
+      if (c->mfma)
+        launch_gemm_mfma(reinterpret_cast<const bf16_t*>(c->hbuf), 1, d.hidden, b, nullptr, n_qkv, EPI_STORE_F32,
+                         nullptr, c->qkv_raw, s, c->skinny_ws);
+      else
+        launch_gemm_generic<T>(Typed<T>::p(c->hbuf), 1, d.hidden, b, nullptr, n_qkv, EPI_STORE_F32, nullptr, c->qkv_raw, s);
+      launch_rope_scatter<T>(c->qkv_raw, Typed<T>::p(w.bq), Typed<T>::p(w.bk), Typed<T>::p(w.bv), d_pos, 1, d.n_q_heads,
+                             d.n_kv_heads, d.head_dim, c->rope_cos, c->rope_sin, Typed<T>::p(c->q), Typed<T>::p(c->kc),
+                             Typed<T>::p(kl), Typed<T>::p(vl), s);
+      if (c->mfma)
+        launch_attn_mfma(reinterpret_cast<const bf16_t*>(c->q), reinterpret_cast<const bf16_t*>(kl),
+                         reinterpret_cast<const bf16_t*>(vl), d_pos, plan.row_start.data(), sg.set_off, 0, pi.n_mem, 1,
+                         pi.N, d.n_q_heads, d.n_kv_heads, d.max_tokens, sg.attn_items, c->attn_scratch,
+                         reinterpret_cast<bf16_t*>(c->o), c->lse, s);
+      else
+        launch_attn_generic<T>(Typed<T>::p(c->q), Typed<T>::p(kl), Typed<T>::p(vl), d_pos, 1, d.n_q_heads, d.n_kv_heads,
+                               d.head_dim, Typed<T>::p(c->o), c->lse, s);
+      HIP_TRY(c, hipGetLastError());
+      HIP_TRY(c, hipEventRecord(sg.done, s));
+      sg.used = true;
+      keep_status st = layer_back<T>(c, l, 1, c->o, x_cur, x_nxt, nullptr);
+      if (st != KEEP_OK) return st;
+      std::swap(x_cur, x_nxt);
+    }
+    x = x_cur;
+  }
+  HIP_TRY(c, hipMemcpyAsync(h + 2 * CAP, c->d_dec + 2 * CAP, (size_t)n_new * 4, hipMemcpyDeviceToHost, s));
+  HIP_TRY(c, hipStreamSynchronize(s));
+  for (int t = 0; t < n_new; ++t) tokens_out[t] = h[2 * CAP + t];
+  return KEEP_OK;
+}
+
 }  // namespace
 
 // ===========================================================================
@@ -503,8 +607,8 @@ keep_status by_dtype(keep_ctx* c, F&& f) {
 // ===========================================================================
 namespace {
 keep_status prefill_impl(keep_ctx* c, const keep_prompt* p, const float* ratios, int32_t hops, int32_t budget_mode,
-                         int32_t load_mode, void* k_cache, void* v_cache, void* x_final, int32_t* sel_groups,
-                         int32_t* sel_counts, keep_report* report);
+                         int32_t load_mode, void* k_cache, void* v_cache, int32_t cache_rows, void* x_final,
+                         int32_t* sel_groups, int32_t* sel_counts, keep_report* report);
 }  // namespace
 
 extern "C" {
@@ -537,6 +641,7 @@ keep_status keep_destroy(keep_ctx* c) {
     if (st.done) (void)hipEventDestroy(st.done);
   }
   if (c->h_sel_out) (void)hipHostFree(c->h_sel_out);
+  if (c->h_dec) (void)hipHostFree(c->h_dec);
   if (c->h_S) (void)hipHostFree(c->h_S);
   if (c->h_token_ids) (void)hipHostFree(c->h_token_ids);
   for (hipEvent_t e : c->ev) (void)hipEventDestroy(e);
@@ -657,6 +762,9 @@ keep_status keep_init(const keep_model_desc* desc, const keep_layer_weights* lay
     TRY_INIT(mk());
   }
   TRY_INIT(pin_alloc(c, &c->h_sel_out, (z.G + 2) * 4));
+  TRY_INIT(pin_alloc(c, &c->h_dec, 4 * KEEP_DECODE_MAX_TOKENS * 4));
+  TRY_INIT(dev_alloc(c, &c->d_dec, 4 * KEEP_DECODE_MAX_TOKENS * 4));
+  TRY_INIT(dev_alloc(c, &c->dec_logits, (size_t)desc->vocab * sizeof(float)));
   TRY_INIT(pin_alloc(c, &c->h_S, (z.G + 1) * z.G * sizeof(float)));
   TRY_INIT(pin_alloc(c, &c->h_token_ids, z.M * 4));
   auto mk_events = [&]() -> keep_status {
@@ -928,8 +1036,45 @@ keep_status keep_prefill(keep_ctx* c, const keep_prompt* p, const float* ratios,
                          int32_t* sel_counts, keep_report* report) {
   if (!c) return KEEP_ERR_INVALID_ARG;
   if (!x_final) return fail(c, KEEP_ERR_INVALID_ARG, "x_final is NULL");
-  return prefill_impl(c, p, ratios, hops, budget_mode, load_mode, k_cache, v_cache, x_final, sel_groups, sel_counts,
-                      report);
+  return prefill_impl(c, p, ratios, hops, budget_mode, load_mode, k_cache, v_cache, 0, x_final, sel_groups,
+                      sel_counts, report);
+}
+
+keep_status keep_prefill_padded(keep_ctx* c, const keep_prompt* p, const float* ratios, int32_t hops,
+                                int32_t budget_mode, int32_t load_mode, void* k_cache, void* v_cache,
+                                int32_t cache_rows, void* x_final, int32_t* sel_groups, int32_t* sel_counts,
+                                keep_report* report) {
+  if (!c) return KEEP_ERR_INVALID_ARG;
+  if (!x_final) return fail(c, KEEP_ERR_INVALID_ARG, "x_final is NULL");
+  if (cache_rows < 1) return fail(c, KEEP_ERR_INVALID_ARG, "cache_rows must be positive");
+  return prefill_impl(c, p, ratios, hops, budget_mode, load_mode, k_cache, v_cache, cache_rows, x_final, sel_groups,
+                      sel_counts, report);
+}
+
+keep_status keep_decode(keep_ctx* c, const void* final_norm, const void* lm_head, const void* x_last, void* k_cache,
+                        void* v_cache, int32_t cache_rows, int32_t n_ctx, int32_t n_new, int32_t* tokens_out,
+                        float* logits_out, const int32_t* forced_tokens) {
+  if (!c) return KEEP_ERR_INVALID_ARG;
+  if (!final_norm || !lm_head || !x_last || !k_cache || !v_cache || !tokens_out)
+    return fail(c, KEEP_ERR_INVALID_ARG, "final_norm / lm_head / x_last / k_cache / v_cache / tokens_out is NULL");
+  if (n_new < 1 || n_new > KEEP_DECODE_MAX_TOKENS)
+    return fail(c, KEEP_ERR_INVALID_ARG, "n_new %d outside [1, %d]", n_new, KEEP_DECODE_MAX_TOKENS);
+  if (n_ctx < 1) return fail(c, KEEP_ERR_INVALID_ARG, "n_ctx must be at least 1");
+  if ((int64_t)n_ctx + n_new - 1 > cache_rows)
+    return fail(c, KEEP_ERR_INVALID_ARG, "n_ctx + n_new - 1 = %lld rows do not fit cache_rows %d",
+                (long long)n_ctx + n_new - 1, cache_rows);
+  if ((int64_t)n_ctx + n_new - 1 > c->d.max_tokens)
+    return fail(c, KEEP_ERR_WORKSPACE, "n_ctx + n_new - 1 above max_tokens %d", c->d.max_tokens);
+  if (forced_tokens)
+    for (int t = 0; t + 1 < n_new; ++t)
+      if (forced_tokens[t] < 0 || forced_tokens[t] >= c->d.vocab)
+        return fail(c, KEEP_ERR_INVALID_ARG, "forced_tokens[%d] = %d outside the vocabulary", t, forced_tokens[t]);
+  c->last_layer = -1;
+  return by_dtype(c, [&](auto* tag) {
+    using T = std::remove_pointer_t<decltype(tag)>;
+    return decode_impl<T>(c, final_norm, lm_head, x_last, k_cache, v_cache, cache_rows, n_ctx, n_new, tokens_out,
+                          logits_out, forced_tokens);
+  });
 }
 
 keep_status keep_precompute_group(keep_ctx* c, const int32_t* token_ids, int32_t n_tokens, void* k_blocks,
@@ -947,7 +1092,7 @@ keep_status keep_precompute_group(keep_ctx* c, const int32_t* token_ids, int32_t
   pr.token_ids = token_ids;
   pr.kv_location = KEEP_KV_DEVICE;
   std::vector<float> ratios((size_t)c->d.n_layers, 0.f);
-  return prefill_impl(c, &pr, ratios.data(), 1, KEEP_BUDGET_GROUP_COUNT, KEEP_LOAD_SERIAL, k_blocks, v_blocks, nullptr,
+  return prefill_impl(c, &pr, ratios.data(), 1, KEEP_BUDGET_GROUP_COUNT, KEEP_LOAD_SERIAL, k_blocks, v_blocks, 0, nullptr,
                       nullptr, nullptr, report);
 }
 
@@ -955,10 +1100,10 @@ keep_status keep_precompute_group(keep_ctx* c, const int32_t* token_ids, int32_t
 
 namespace {
 
-// x_final may be NULL (the hidden rows are not wanted).
+// x_final may be NULL (the hidden rows are not wanted).  cache_rows: rows per layer of the caches, 0 = N.
 keep_status prefill_impl(keep_ctx* c, const keep_prompt* p, const float* ratios, int32_t hops, int32_t budget_mode,
-                         int32_t load_mode, void* k_cache, void* v_cache, void* x_final, int32_t* sel_groups,
-                         int32_t* sel_counts, keep_report* report) {
+                         int32_t load_mode, void* k_cache, void* v_cache, int32_t cache_rows, void* x_final,
+                         int32_t* sel_groups, int32_t* sel_counts, keep_report* report) {
   const auto t_begin = std::chrono::steady_clock::now();
   const keep_model_desc& d = c->d;
   const int L = d.n_layers;
@@ -982,7 +1127,9 @@ keep_status prefill_impl(keep_ctx* c, const keep_prompt* p, const float* ratios,
   c->last_layer = -1;
   const bool host_kv = p->kv_location == KEEP_KV_PINNED_HOST;
   const size_t row_bytes = (size_t)d.n_kv_heads * d.head_dim * c->esz;
-  const size_t layer_bytes = (size_t)pi.N * row_bytes;
+  if (cache_rows != 0 && cache_rows < pi.N)
+    return fail(c, KEEP_ERR_INVALID_ARG, "cache_rows %d below the prompt's %d tokens", cache_rows, pi.N);
+  const size_t layer_bytes = (size_t)(cache_rows ? cache_rows : pi.N) * row_bytes;
   if (report) {
     memset(report, 0, sizeof *report);
     report->n_layers = L;

@@ -273,53 +273,52 @@ __global__ void __launch_bounds__(256, 2)
   }
 }
 
-// Merge the partials of one cut tile and one KV head: rows q = 0..127, chunks in order.
+// Merge the partials of one cut tile and one KV head, chunks in key order.  A thread owns one query row
+// and 4 of the 128 output dimensions (blockIdx.y picks which), so that even a tile with a single valid
+// row (decoding) spreads over 32 threads and the loop over chunks is a stream of independent loads.
 __global__ void __launch_bounds__(256)
     k_attn_combine(const int4* __restrict__ splits, const float* __restrict__ part_o, const float* __restrict__ part_ml,
                    int n_rows, int n_q_heads, int n_kv_heads, bf16_t* __restrict__ o, float* __restrict__ lse) {
   const int hk = blockIdx.x % n_kv_heads;
   const int4 sp = splits[blockIdx.x / n_kv_heads];  // {tile, first slot, chunks, -}
   const int rep = n_q_heads / n_kv_heads;
-  const int ql = threadIdx.x & 127, half = threadIdx.x >> 7;
+  const int ql = threadIdx.x & 127;
+  const int d4 = blockIdx.y * 2 + (threadIdx.x >> 7);  // 0..31
   const int x = sp.x * 128 + ql;
   if (x >= n_rows * rep) return;
   const int r = x / rep, head = hk * rep + x % rep;
+  const float* ml = part_ml + ((size_t)sp.y * n_kv_heads + hk) * 256 + ql;
+  const size_t ml_step = (size_t)n_kv_heads * 256;
   float m_all = M_FLOOR;
-  for (int c = 0; c < sp.z; ++c) m_all = fmaxf(m_all, part_ml[((size_t)(sp.y + c) * n_kv_heads + hk) * 256 + ql]);
+#pragma unroll 8
+  for (int c = 0; c < sp.z; ++c) m_all = fmaxf(m_all, ml[c * ml_step]);
   float l_all = 0.f;
-  float4 acc[16];
-#pragma unroll
-  for (int i = 0; i < 16; ++i) acc[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-  for (int c = 0; c < sp.z; ++c) {  // chunks in key order
-    const size_t slot = (size_t)(sp.y + c) * n_kv_heads + hk;
-    const float w = __builtin_amdgcn_exp2f(part_ml[slot * 256 + ql] - m_all);
-    l_all += part_ml[slot * 256 + 128 + ql] * w;
-    const float* po = part_o + slot * PART_FLOATS + ((size_t)(half * 16) * 128 + ql) * 4;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const float4 v = *reinterpret_cast<const float4*>(po + (size_t)i * 128 * 4);
-      acc[i].x += w * v.x;
-      acc[i].y += w * v.y;
-      acc[i].z += w * v.z;
-      acc[i].w += w * v.w;
-    }
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  const float* po = part_o + ((size_t)sp.y * n_kv_heads + hk) * PART_FLOATS + ((size_t)d4 * 128 + ql) * 4;
+  const size_t po_step = (size_t)n_kv_heads * PART_FLOATS;
+#pragma unroll 8
+  for (int c = 0; c < sp.z; ++c) {
+    const float w = __builtin_amdgcn_exp2f(ml[c * ml_step] - m_all);
+    l_all += ml[c * ml_step + 128] * w;
+    const float4 v = *reinterpret_cast<const float4*>(po + c * po_step);
+    acc.x += w * v.x;
+    acc.y += w * v.y;
+    acc.z += w * v.z;
+    acc.w += w * v.w;
   }
   const float inv = 1.0f / l_all;
-  bf16_t* op = o + ((size_t)r * n_q_heads + head) * DH + half * 64;
-#pragma unroll
-  for (int i = 0; i < 16; ++i) {
-    uint2 u;
-    u.x = pack_bf16x2(acc[i].x * inv, acc[i].y * inv);
-    u.y = pack_bf16x2(acc[i].z * inv, acc[i].w * inv);
-    *reinterpret_cast<uint2*>(op + i * 4) = u;
-  }
-  if (half == 0) lse[(size_t)r * n_q_heads + head] = 0.6931471805599453f * (m_all + log2f(l_all));
+  uint2 u;
+  u.x = pack_bf16x2(acc.x * inv, acc.y * inv);
+  u.y = pack_bf16x2(acc.z * inv, acc.w * inv);
+  *reinterpret_cast<uint2*>(o + ((size_t)r * n_q_heads + head) * DH + d4 * 4) = u;
+  if (d4 == 0) lse[(size_t)r * n_q_heads + head] = 0.6931471805599453f * (m_all + log2f(l_all));
 }
 
 // ---- host-side work list ---------------------------------------------------
 constexpr int ATT_MAX_SLOTS = 4096;      // partial buffers (cut items x KV heads) the scratch can hold
 constexpr int ATT_SLOTS = 512;           // resident workgroups: 2 per CU x 256 CUs
-constexpr int ATT_MIN_CHUNK = 16;        // never cut below 16 key tiles (1024 keys)
+constexpr int ATT_MIN_CHUNK = 16;        // never cut below 16 key tiles (1024 keys) ...
+constexpr int ATT_MIN_CHUNK_SMALL = 4;   // ... unless the whole launch is small (a few rows over a long cache)
 
 static inline int att_max_tiles(int max_rows, int rep) { return (int)(((long)max_rows * rep + 127) / 128); }
 
@@ -367,7 +366,11 @@ void launch_attn_mfma(const bf16_t* q, const bf16_t* k_cache, const bf16_t* v_ca
   // share of the work would leave the chip waiting for it at the end (instruction rows see the whole
   // cache while most recomputed memories sit early in the prompt), so such ranges are cut into chunks
   // of about that length (never below ATT_MIN_CHUNK key tiles); everything shorter runs whole.
-  int chunk = (int)std::max<long>(ATT_MIN_CHUNK, (total_steps * n_kv_heads + ATT_SLOTS - 1) / ATT_SLOTS);
+  // A launch with less work than 16 key tiles per slot (decoding: one row over the whole cache) is bound
+  // by memory latency per workgroup, not by the matrix cores: it is cut finer, into about 1024 items.
+  const bool small = total_steps * n_kv_heads < (long)ATT_MIN_CHUNK * ATT_SLOTS;
+  int chunk = small ? (int)std::max<long>(ATT_MIN_CHUNK_SMALL, (total_steps * n_kv_heads + 2 * ATT_SLOTS - 1) / (2 * ATT_SLOTS))
+                    : (int)std::max<long>(ATT_MIN_CHUNK, (total_steps * n_kv_heads + ATT_SLOTS - 1) / ATT_SLOTS);
   for (;;) {
     long slots = 0;
     for (int t = 0; t < n_tiles; ++t) {
@@ -411,7 +414,7 @@ void launch_attn_mfma(const bf16_t* q, const bf16_t* k_cache, const bf16_t* v_ca
   hipLaunchKernelGGL(k_attn_mfma, dim3(n_items * n_kv_heads), dim3(256), sh, s, q, k_cache, v_cache, d_row_pos, n_rows,
                      n_total, n_q_heads, n_kv_heads, d_items, scale_log2e, o, lse, part_o, part_ml);
   if (n_splits)
-    hipLaunchKernelGGL(k_attn_combine, dim3(n_splits * n_kv_heads), dim3(256), 0, s, d_splits, part_o, part_ml, n_rows,
+    hipLaunchKernelGGL(k_attn_combine, dim3(n_splits * n_kv_heads, 16), dim3(256), 0, s, d_splits, part_o, part_ml, n_rows,
                        n_q_heads, n_kv_heads, o, lse);
 }
 

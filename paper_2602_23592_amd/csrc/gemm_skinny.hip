@@ -10,7 +10,7 @@
 // row and 64 of one activation row per step, the two half-waves together consume whole 128-byte
 // lines.  Which K index feeds which MFMA slot is free as long as A and B agree, so the lane's 32
 // K values are simply its four 16-byte chunks in order.  The four waves' partial tiles are added
-// through LDS and written as fp32 partials [S][64][ld]; a second kernel adds the S slices in
+// through LDS and written as fp32 partials [S][M][ld]; a second kernel adds the S slices in
 // order (no atomics: reproducible) and applies the epilogue.
 #include <algorithm>
 
@@ -28,7 +28,7 @@ struct SkinnyB {
 
 constexpr int SK_BN = 64;       // weight rows per workgroup
 constexpr int SK_KSTEP = 64;    // K per wave step
-constexpr size_t SK_MAX_PART_FLOATS = (size_t)64 * 65536;  // partials never exceed this
+constexpr size_t SK_MAX_PART_FLOATS = (size_t)64 * 65536;  // capacity of the partials workspace
 
 size_t gemm_skinny_ws_bytes() { return SK_MAX_PART_FLOATS * sizeof(float); }
 
@@ -123,7 +123,7 @@ __global__ void __launch_bounds__(256, 2)
 #pragma unroll
       for (int e = 0; e < 16; ++e) s_red[wave][rt * 32 + 8 * (e >> 2) + 4 * g + (e & 3)][ct * 32 + lq] = acc[rt][ct][e];
   __syncthreads();
-  float* dst = part + (size_t)z * (MT * 32) * ld;
+  float* dst = part + (size_t)z * M * ld;
   for (int i = tid; i < MT * 32 * SK_BN; i += 256) {
     const int r = i / SK_BN, cidx = i % SK_BN;
     const float v = (s_red[0][r][cidx] + s_red[1][r][cidx]) + (s_red[2][r][cidx] + s_red[3][r][cidx]);
@@ -134,14 +134,14 @@ __global__ void __launch_bounds__(256, 2)
 // C = epilogue(sum over the K slices, in slice order)
 template <int EPI>
 __global__ void __launch_bounds__(256)
-    k_skinny_finish(const float* __restrict__ part, int n_splits, int m_pad, int ld, int M, int N,
+    k_skinny_finish(const float* __restrict__ part, int n_splits, int ld, int M, int N,
                     const bf16_t* __restrict__ residual, void* __restrict__ Cv) {
   const int n = blockIdx.x * 256 + threadIdx.x;
   const int m = blockIdx.y;
   if (n >= N || m >= M) return;
   float s0 = 0.f, s1 = 0.f;
   for (int z = 0; z < n_splits; ++z) {
-    const float* p = part + ((size_t)z * m_pad + m) * ld;
+    const float* p = part + ((size_t)z * M + m) * ld;
     s0 += p[n];
     if (EPI == EPI_SWIGLU_STORE) s1 += p[N + n];
   }
@@ -157,8 +157,9 @@ __global__ void __launch_bounds__(256)
 
 bool gemm_skinny_fits(int32_t M, int32_t K, const GemmB& B, int32_t N, int epilogue) {
   const long rows = epilogue == EPI_SWIGLU_STORE ? 2L * N : N;
-  return M >= 1 && M <= 64 && K % SK_KSTEP == 0 && K >= SK_KSTEP && rows <= 65536 &&
-         (epilogue != EPI_SWIGLU_STORE || B.n_parts == 1);
+  const long ld = (rows + SK_BN - 1) / SK_BN * SK_BN;
+  return M >= 1 && M <= 64 && K % SK_KSTEP == 0 && K >= SK_KSTEP && rows < (1L << 24) &&
+         (size_t)M * (size_t)ld <= SK_MAX_PART_FLOATS && (epilogue != EPI_SWIGLU_STORE || B.n_parts == 1);
 }
 
 void launch_gemm_skinny(const bf16_t* A, int32_t M, int32_t K, const GemmB& B, const void* B2, int32_t N, int epilogue,
@@ -185,7 +186,7 @@ void launch_gemm_skinny(const bf16_t* A, int32_t M, int32_t K, const GemmB& B, c
   // enough K slices for ~2048 waves (8 per CU), at least 4 steps per workgroup, partials within the workspace
   int splits = (512 + tiles - 1) / tiles;
   splits = std::min(splits, std::max(1, steps / 4));
-  splits = std::min<long>(splits, (long)(SK_MAX_PART_FLOATS / ((size_t)mt * 32 * ld)));
+  splits = std::min<long>(splits, (long)(SK_MAX_PART_FLOATS / ((size_t)M * ld)));
   splits = std::max(splits, 1);
   float* part = reinterpret_cast<float*>(ws);
   const dim3 grid(tiles, splits);
@@ -195,11 +196,11 @@ void launch_gemm_skinny(const bf16_t* A, int32_t M, int32_t K, const GemmB& B, c
     hipLaunchKernelGGL(k_gemm_skinny<2>, grid, dim3(256), 0, s, A, M, K, b, rows, splits, part, ld);
   const dim3 fgrid((N + 255) / 256, M);
   if (epilogue == EPI_STORE_F32)
-    hipLaunchKernelGGL(k_skinny_finish<EPI_STORE_F32>, fgrid, dim3(256), 0, s, part, splits, mt * 32, ld, M, N, residual, C);
+    hipLaunchKernelGGL(k_skinny_finish<EPI_STORE_F32>, fgrid, dim3(256), 0, s, part, splits, ld, M, N, residual, C);
   else if (epilogue == EPI_RESIDUAL_STORE)
-    hipLaunchKernelGGL(k_skinny_finish<EPI_RESIDUAL_STORE>, fgrid, dim3(256), 0, s, part, splits, mt * 32, ld, M, N, residual, C);
+    hipLaunchKernelGGL(k_skinny_finish<EPI_RESIDUAL_STORE>, fgrid, dim3(256), 0, s, part, splits, ld, M, N, residual, C);
   else
-    hipLaunchKernelGGL(k_skinny_finish<EPI_SWIGLU_STORE>, fgrid, dim3(256), 0, s, part, splits, mt * 32, ld, M, N, residual, C);
+    hipLaunchKernelGGL(k_skinny_finish<EPI_SWIGLU_STORE>, fgrid, dim3(256), 0, s, part, splits, ld, M, N, residual, C);
 }
 
 }  // namespace keep

@@ -107,6 +107,9 @@ void launch_rope_scatter(const float* qkv_raw /*[n_rows, q_dim + 2 kv_dim]*/, co
                          int32_t head_dim, const float* rope_cos, const float* rope_sin, T* q, T* k_compact,
                          T* k_cache, T* v_cache, hipStream_t s);
 
+// out[0] = index of the largest of logits[0..n), the lowest index among equal values
+void launch_argmax(const float* logits, int32_t n, int32_t* out, hipStream_t s);
+
 // generic (scalar FMA) kernels
 template <typename T>
 void launch_gemm_generic(const T* A, int32_t M, int32_t K, const GemmB& B, const void* B2, int32_t N, int epilogue,

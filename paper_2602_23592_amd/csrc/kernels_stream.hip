@@ -346,6 +346,44 @@ void launch_rope_scatter(const float* qkv_raw, const T* bq, const T* bk, const T
                      n_kv_heads, head_dim, rope_cos, rope_sin, q, k_compact, k_cache, v_cache);
 }
 
+// Greedy choice over one row of logits: the largest value, the lowest index among equal ones.
+// One workgroup; every thread scans a strided slice (ascending, so it keeps the first of equal
+// values), then a fixed tree over (value, index) pairs.
+__global__ void __launch_bounds__(1024) k_argmax(const float* __restrict__ logits, int n, int32_t* __restrict__ out) {
+  __shared__ float s_v[1024];
+  __shared__ int s_i[1024];
+  float best = -INFINITY;
+  int bi = 0x7fffffff;
+  for (int i = threadIdx.x; i < n; i += 1024) {
+    const float v = logits[i];
+    if (v > best || bi == 0x7fffffff) {
+      best = v;
+      bi = i;
+    }
+  }
+  s_v[threadIdx.x] = best;
+  s_i[threadIdx.x] = bi;
+  __syncthreads();
+  for (int w = 512; w > 0; w >>= 1) {
+    if ((int)threadIdx.x < w) {
+      const float v2 = s_v[threadIdx.x + w];
+      const int i2 = s_i[threadIdx.x + w];
+      const float v1 = s_v[threadIdx.x];
+      const int i1 = s_i[threadIdx.x];
+      if (i2 != 0x7fffffff && (i1 == 0x7fffffff || v2 > v1 || (v2 == v1 && i2 < i1))) {
+        s_v[threadIdx.x] = v2;
+        s_i[threadIdx.x] = i2;
+      }
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) *out = s_i[0];
+}
+
+void launch_argmax(const float* logits, int32_t n, int32_t* out, hipStream_t s) {
+  hipLaunchKernelGGL(k_argmax, dim3(1), dim3(1024), 0, s, logits, n, out);
+}
+
 // explicit instantiations
 #define INST(T)                                                                                                       \
   template void launch_embed_gather<T>(const T*, const int32_t*, const int32_t*, int32_t, int32_t, T*, hipStream_t); \
