@@ -42,6 +42,9 @@ def parse():
     ap.add_argument("--layers-json", default=None, help="also write the per-layer timing report to this file")
     ap.add_argument("--random-cache", action="store_true",
                     help="random group caches instead of caches prefilled by the library (faster set-up)")
+    ap.add_argument("--sparse-rows", type=int, default=0,
+                    help="diagnostic: pure reuse (ratio 0 at every layer) with an instruction of this many rows, "
+                         "the regime where the sparse-row attention is bound by reading the cache once")
     ap.add_argument("--decode-tokens", type=int, default=0,
                     help="instead of the prefill benchmark: prefill once, then time the first token and this many "
                          "greedy decode steps over the joined cache")
@@ -271,6 +274,9 @@ def main():
     if a.ratio is not None:
         import dataclasses
         w = dataclasses.replace(w, ratio=a.ratio)
+    if a.sparse_rows > 0:
+        import dataclasses
+        w = dataclasses.replace(w, instr_len=a.sparse_rows, ratio=0.0)
     s = w.shape
     sched = a.schedule or w.schedule
     budget = a.budget or w.budget
@@ -315,6 +321,8 @@ def main():
     prompt = KeepPrompt(glen, lq, ids, k_blocks, v_blocks, s.n_layers,
                         kb.KEEP_KV_PINNED_HOST if host else kb.KEEP_KV_DEVICE, kinds)
     ratios = ks.ratio_schedule(w.ratio, s.n_layers, sched)
+    if a.sparse_rows > 0:
+        ratios[:] = 0.0
     k_cache = torch.empty((s.n_layers, n_tokens, s.n_kv_heads, s.head_dim), dtype=dt, device="cuda")
     v_cache = torch.empty_like(k_cache)
     x_final = torch.empty((lq, s.hidden), dtype=dt, device="cuda")
@@ -396,7 +404,7 @@ def main():
     # L2-miss bytes per launch from the two rocprofv3 counter runs summarised in
     # profiles/keep_prefill_qwen14b_32k_hbm_traffic.md; they hold for that workload at its default settings only
     default_run = (a.workload == "qwen14b_32k" and a.schedule is None and a.ratio is None and a.budget is None
-                   and not a.random_cache)
+                   and not a.random_cache and a.sparse_rows == 0)
     traffic = GATE_UP_TRAFFIC_BYTES_PER_LAUNCH if default_run else None
     roofline = {"kernel": "k_gemm_mfma<...,SWIGLU> (gate/up projection with fused SiLU*mul; 256x256 tiles, "
                           "128x128 for launches of fewer than 1024 such tiles)",

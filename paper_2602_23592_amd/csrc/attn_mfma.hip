@@ -254,7 +254,7 @@ __global__ void __launch_bounds__(256, 2)
         }
       if (g == 0) lse[(size_t)r * n_q_heads + head] = 0.6931471805599453f * (m_run + log2f(l_tot));
     }
-  } else {
+  } else if (valid) {  // rows past the end of the list are never read back
     const size_t slot = (size_t)item.w * n_kv_heads + hk;
     float* po = part_o + slot * PART_FLOATS;
     const int ql = wave * 32 + lq;
@@ -381,15 +381,43 @@ void launch_attn_mfma(const bf16_t* q, const bf16_t* k_cache, const bf16_t* v_ca
     chunk *= 2;
   }
   int n_items = 0, n_splits = 0, slot = 0;
-  for (int t = n_tiles - 1; t >= 0; --t) {  // longest key ranges first
-    const int nc = (steps[t] + chunk - 1) / chunk;
-    if (nc <= 1) {
-      h_items[n_items++] = make_int4(t, 0, steps[t], -1);
-    } else {
-      const int len = (steps[t] + nc - 1) / nc;
-      h_splits[n_splits++] = make_int4(t, slot, nc, 0);
-      for (int c = 0; c < nc; ++c) h_items[n_items++] = make_int4(t, c * len, std::min(steps[t], (c + 1) * len), slot + c);
-      slot += nc;
+  int min_steps = steps[0];
+  for (int t = 1; t < n_tiles; ++t) min_steps = std::min(min_steps, steps[t]);
+  if (n_tiles > 1 && (long)min_steps * 10 >= (long)steps[n_tiles - 1] * 9) {
+    // Every query tile reads (nearly) the whole cache: a few instruction rows over a long prompt.  Items go
+    // out chunk by chunk on one grid of key ranges, so the query tiles that read the same K/V range are
+    // neighbours in the launch order, run at the same time on the XCD of their KV head and find the range
+    // in its L2 instead of fetching it once per query tile.
+    int max_nc = 1;
+    static thread_local std::vector<int> slot_base;
+    slot_base.resize(n_tiles);
+    for (int t = n_tiles - 1; t >= 0; --t) {
+      const int nc = (steps[t] + chunk - 1) / chunk;
+      max_nc = std::max(max_nc, nc);
+      slot_base[t] = -1;
+      if (nc > 1) {
+        h_splits[n_splits++] = make_int4(t, slot, nc, 0);
+        slot_base[t] = slot;
+        slot += nc;
+      }
+    }
+    for (int c = 0; c < max_nc; ++c)
+      for (int t = n_tiles - 1; t >= 0; --t) {
+        if (c * chunk >= steps[t]) continue;
+        h_items[n_items++] = make_int4(t, c * chunk, std::min(steps[t], (c + 1) * chunk),
+                                       slot_base[t] < 0 ? -1 : slot_base[t] + c);
+      }
+  } else {
+    for (int t = n_tiles - 1; t >= 0; --t) {  // longest key ranges first, each cut into equal pieces
+      const int nc = (steps[t] + chunk - 1) / chunk;
+      if (nc <= 1) {
+        h_items[n_items++] = make_int4(t, 0, steps[t], -1);
+      } else {
+        const int len = (steps[t] + nc - 1) / nc;
+        h_splits[n_splits++] = make_int4(t, slot, nc, 0);
+        for (int c = 0; c < nc; ++c) h_items[n_items++] = make_int4(t, c * len, std::min(steps[t], (c + 1) * len), slot + c);
+        slot += nc;
+      }
     }
   }
   char* base = reinterpret_cast<char*>(d_scratch);

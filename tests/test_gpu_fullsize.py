@@ -79,3 +79,42 @@ def test_fullsize_selective_layer_sampled():
     # the device's selection is the oracle's selection applied to the device's scores
     want, want_runs = ko.select_multihop(S, groups, glist, float(ratios[2]), w.hops, ko.BUDGET_TOKENS)
     assert nxt == want and runs == want_runs
+
+
+def test_decode_attention_over_the_full_cache_matches_oracle():
+    """One new token over the 33 024-row cache of the bench workload's shape (one layer, random cache):
+    the launch configuration the decode benchmark times.  The oracle computes the single row directly."""
+    import keep_synth as ks
+    from oracle import keep_oracle as ko
+    from oracle_util import layer_to_numpy, oracle_shape
+    from paper_2602_23592_amd import KeepContext
+    full = ks.workload("qwen14b_32k").shape
+    shape = ks.ModelShape(1, full.hidden, full.n_q_heads, full.n_kv_heads, full.head_dim, full.ffn_dim, 4099,
+                          full.rope_theta, full.rms_eps, "bf16")
+    n_ctx = 33024
+    w_t = ks.make_layer_weights(shape, 0, "cpu")
+    embed_t = ks.make_embedding(shape, "cpu")
+    g = torch.Generator().manual_seed(5)
+    kc = torch.randn((1, n_ctx + 2, shape.n_kv_heads, shape.head_dim), generator=g).to(torch.bfloat16)
+    vc = torch.randn((1, n_ctx + 2, shape.n_kv_heads, shape.head_dim), generator=g).to(torch.bfloat16)
+    fn = torch.ones(shape.hidden, dtype=torch.bfloat16)
+    lm = (0.02 * torch.randn((shape.vocab, shape.hidden), generator=g)).to(torch.bfloat16)
+    x_last = (0.5 * torch.randn(shape.hidden, generator=g)).to(torch.bfloat16)
+    ctx = KeepContext(shape, [{k: (None if v is None else v.cuda()) for k, v in w_t.items()}], embed_t.cuda(),
+                      n_ctx + 2, 1, 0)
+    assert ctx.uses_mfma
+    kd, vd = kc.cuda(), vc.cuda()
+    logits = torch.empty((2, shape.vocab), dtype=torch.float32, device="cuda")
+    toks = ctx.decode(fn.cuda(), lm.cuda(), x_last.cuda(), kd, vd, n_ctx, 2, logits_out=logits)
+    torch.cuda.synchronize()
+    sh = oracle_shape(shape)
+    kr, vr = [ks.to_numpy_f64(kc[0])], [ks.to_numpy_f64(vc[0])]
+    _, rlg = ko.greedy_decode(sh, [layer_to_numpy(w_t)], ks.to_numpy_f64(embed_t), ks.to_numpy_f64(fn),
+                              ks.to_numpy_f64(lm), ks.to_numpy_f64(x_last), kr, vr, n_ctx, 2, forced_tokens=toks)
+    lg = logits.cpu().double().numpy()
+    for t in range(2):
+        e = np.abs(lg[t] - rlg[t]).max() / np.abs(rlg[t]).max()
+        print("full-size decode step", t, "logits err %.2e" % e)
+        assert e < 2e-2
+    assert np.abs(kd[0, n_ctx].cpu().double().numpy() - kr[0][n_ctx]).max() / np.abs(kr[0][n_ctx]).max() < 2e-2
+    assert np.abs(vd[0, n_ctx].cpu().double().numpy() - vr[0][n_ctx]).max() / np.abs(vr[0][n_ctx]).max() < 2e-2
