@@ -199,7 +199,7 @@ uint64_t workspace_bytes(const keep_model_desc* d) {
   t += align256(z.M * (size_t)d->n_q_heads * sizeof(float));           // lse
   t += align256(score_scratch_bytes(d));
   if (wants_mfma(d)) t += align256(attn_mfma_scratch_bytes((int32_t)z.M, d->n_q_heads, d->n_kv_heads));
-  if (wants_mfma(d)) t += align256(gemm_skinny_ws_bytes());
+  if (wants_mfma(d)) t += align256(gemm_ws_bytes());
   t += align256((z.G + 1) * z.G * sizeof(float));                      // S
   t += align256(((z.G + 1) * z.G + 2 * z.G) * sizeof(float));          // sel_work
   t += align256(4 * z.G * sizeof(int32_t)) + align256((z.G + 2) * sizeof(int32_t));
@@ -716,7 +716,7 @@ keep_status keep_init(const keep_model_desc* desc, const keep_layer_weights* lay
   if (c->mfma) {
     TRY_INIT(dev_alloc(c, reinterpret_cast<char**>(&c->attn_scratch),
                        attn_mfma_scratch_bytes((int32_t)z.M, desc->n_q_heads, desc->n_kv_heads)));
-    TRY_INIT(dev_alloc(c, reinterpret_cast<char**>(&c->skinny_ws), gemm_skinny_ws_bytes()));
+    TRY_INIT(dev_alloc(c, reinterpret_cast<char**>(&c->skinny_ws), gemm_ws_bytes()));
   }
   TRY_INIT(dev_alloc(c, &c->S, (z.G + 1) * z.G * sizeof(float)));
   TRY_INIT(dev_alloc(c, &c->sel_work, ((z.G + 1) * z.G + 2 * z.G) * sizeof(float)));

@@ -12,6 +12,8 @@
 // Epilogues: plain fp32 store (QKV), residual add (output and down projections), and
 // SwiGLU: the B tile interleaves rows of W_gate and W_up so that one lane holds
 // gate[m, n] and up[m, n] in matching accumulator registers.
+#include <algorithm>
+
 #include "keep_internal.h"
 
 namespace keep {
@@ -39,10 +41,26 @@ __device__ __forceinline__ int lds_off(int row, int chunk) {
 // s_waitcnt vmcnt(n) with the other counters left alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14)
 __device__ __forceinline__ constexpr int vmcnt_imm(int n) { return 0x0F70 | (n & 15) | ((n >> 4) << 14); }
 
+// Position t of the tile list -> tile coordinates: panels of GM tile rows, walked column by column.
+template <int BM>
+__device__ __forceinline__ void gemm_tile_of(int t, int tiles_m, int tiles_n, int& tile_m, int& tile_n) {
+#ifdef KEEP_EXP_GM
+  constexpr int GM = KEEP_EXP_GM;
+#else
+  constexpr int GM = (BM >= 256) ? 4 : 8;
+#endif
+  const int panel = t / (GM * tiles_n);
+  const int panel_rows = min(GM, tiles_m - panel * GM);
+  const int within = t - panel * GM * tiles_n;
+  tile_m = panel * GM + within % panel_rows;
+  tile_n = within / panel_rows;
+}
+
 template <int BM, int BN, int WM, int WN, int EPI, int GBK, int NST>
 __global__ void __launch_bounds__(WM* WN * 64)
     k_gemm_mfma(const bf16_t* __restrict__ A, int M, int K, MfmaB B, const bf16_t* __restrict__ B2, int N,
-                const bf16_t* __restrict__ residual, void* __restrict__ Cv, int tiles_m, int tiles_n) {
+                const bf16_t* __restrict__ residual, void* __restrict__ Cv, int tiles_m, int tiles_n,
+                int full_per_xcd, int split_s, float* __restrict__ part) {
   constexpr int T = WM * WN * 64;
   constexpr int TM = BM / WM, TN = BN / WN;
   constexpr int MI = TM / 32, NI = TN / 32;
@@ -58,20 +76,23 @@ __global__ void __launch_bounds__(WM* WN * 64)
   // XCD x therefore takes the x-th eighth of the tile list, and the list walks panels of GM tile rows
   // column by column, so the ~32 workgroups resident on one XCD cover a GM x (32/GM) patch of C and
   // share their A and B slices through that XCD's L2.
-#ifdef KEEP_EXP_GM
-  constexpr int GM = KEEP_EXP_GM;
-#else
-  constexpr int GM = (BM >= 256) ? 4 : 8;
-#endif
+  //
+  // The tail of each XCD's list, the tiles that would form a last, partly filled round of workgroups,
+  // is cut along K instead: split_s workgroups share a tile, each multiplies its slice of K and writes
+  // an fp32 partial tile; k_gemm_fixup adds the slices in order and applies the epilogue.
   const int n_tiles = tiles_m * tiles_n;
   const int per_xcd = (n_tiles + 7) >> 3;
-  const int t = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
-  if (t >= min(n_tiles, ((int)(blockIdx.x & 7) + 1) * per_xcd)) return;
-  const int panel = t / (GM * tiles_n);
-  const int panel_rows = min(GM, tiles_m - panel * GM);
-  const int within = t - panel * GM * tiles_n;
-  const int tile_m = panel * GM + within % panel_rows;
-  const int tile_n = within / panel_rows;
+  const int xcd = (int)(blockIdx.x & 7), j_x = (int)(blockIdx.x >> 3);
+  int tl = j_x, piece = 0, pieces = 1;
+  if (j_x >= full_per_xcd) {
+    tl = full_per_xcd + (j_x - full_per_xcd) / split_s;
+    piece = (j_x - full_per_xcd) % split_s;
+    pieces = split_s;
+  }
+  const int t = xcd * per_xcd + tl;
+  if (tl >= per_xcd || t >= n_tiles) return;
+  int tile_m, tile_n;
+  gemm_tile_of<BM>(t, tiles_m, tiles_n, tile_m, tile_n);
   const int m0 = tile_m * BM;
   const int n0 = tile_n * BN;  // in B-tile rows (for SwiGLU: BN/2 output columns per block)
 
@@ -147,9 +168,10 @@ __global__ void __launch_bounds__(WM* WN * 64)
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
   // NST LDS stages: slices kt+1 .. kt+NST-1 are in flight (or landed) while slice kt is multiplied
-  const int KT = K / GBK;
+  const int kt_begin = (int)((long)piece * (K / GBK) / pieces);
+  const int KT = (int)((long)(piece + 1) * (K / GBK) / pieces);  // end of this workgroup's K slices
 #pragma unroll
-  for (int p = 0; p < NST - 1; ++p) GEMM_STAGE(min(p, KT - 1), p)
+  for (int p = 0; p < NST - 1; ++p) GEMM_STAGE(min(kt_begin + p, KT - 1), p)
   __builtin_amdgcn_s_waitcnt(vmcnt_imm((NST - 2) * LD));  // slice 0 has landed in LDS
   __syncthreads();
 
@@ -174,7 +196,7 @@ __global__ void __launch_bounds__(WM* WN * 64)
   for (int j = 0; j < NI; ++j) bfr[0][j] = *reinterpret_cast<const bf16x8*>(smem + b_off[0] + j * 32 * GBK);
 
   int stage = 0;
-  for (int kt = 0; kt < KT; ++kt) {
+  for (int kt = kt_begin; kt < KT; ++kt) {
     // The stage that held slice kt-1 was last read before the previous barrier, so slice kt+NST-1
     // can stream into it now.  (Past the end the last slice is fetched again: harmless, and it keeps
     // the loop body one straight-line block for the instruction scheduler.)
@@ -225,6 +247,19 @@ __global__ void __launch_bounds__(WM* WN * 64)
   // ---- epilogue.  acc[i][j][e]: row = i*32 + 8*(e/4) + 4*(lane/32) + e%4, col = j*32 + lane%32
   const int col_l = lane & 31;
   const int row_l = 4 * (lane >> 5);
+  if (pieces > 1) {  // partial tile [BM][BN] in tile coordinates
+    const int rem_per_xcd = per_xcd - full_per_xcd;
+    float* pt = part + ((size_t)(xcd * rem_per_xcd + (tl - full_per_xcd)) * split_s + piece) * (BM * BN);
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int r = wm * TM + i * 32 + 8 * (e >> 2) + row_l + (e & 3);
+#pragma unroll
+        for (int j = 0; j < NI; ++j) pt[(size_t)r * BN + wn * TN + j * 32 + col_l] = acc[i][j][e];
+      }
+    return;
+  }
 #pragma unroll
   for (int i = 0; i < MI; ++i) {
 #pragma unroll
@@ -257,24 +292,91 @@ __global__ void __launch_bounds__(WM* WN * 64)
   }
 }
 
+// Epilogue of the tiles that were cut along K: partial slices added in slice order (reproducible).
+template <int BM, int BN, int WM, int WN, int EPI>
+__global__ void __launch_bounds__(256)
+    k_gemm_fixup(const float* __restrict__ part, int M, int N, const bf16_t* __restrict__ residual,
+                 void* __restrict__ Cv, int tiles_m, int tiles_n, int full_per_xcd, int split_s) {
+  constexpr int TN = BN / WN;
+  constexpr int OUT_N = EPI == EPI_SWIGLU_STORE ? BN / 2 : BN;  // output columns per tile
+  const int n_tiles = tiles_m * tiles_n;
+  const int per_xcd = (n_tiles + 7) >> 3;
+  const int rem_per_xcd = per_xcd - full_per_xcd;
+  const int xcd = blockIdx.x / rem_per_xcd, ri = blockIdx.x % rem_per_xcd;
+  const int t = xcd * per_xcd + full_per_xcd + ri;
+  if (t >= n_tiles) return;
+  int tile_m, tile_n;
+  gemm_tile_of<BM>(t, tiles_m, tiles_n, tile_m, tile_n);
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
+  const float* pt = part + (size_t)blockIdx.x * split_s * (BM * BN);
+  for (int i = blockIdx.y * 256 + threadIdx.x; i < BM * OUT_N; i += gridDim.y * 256) {
+    const int r = i / OUT_N, c = i % OUT_N;
+    const int gm = m0 + r;
+    if (gm >= M) continue;
+    if (EPI == EPI_SWIGLU_STORE) {
+      // output column c of the tile: gate in tile column w*TN + col, up in w*TN + TN/2 + col
+      const int w = c / (TN / 2), col = c % (TN / 2);
+      float g = 0.f, u = 0.f;
+      for (int z = 0; z < split_s; ++z) {
+        const float* p = pt + (size_t)z * (BM * BN) + (size_t)r * BN + w * TN + col;
+        g += p[0];
+        u += p[TN / 2];
+      }
+      const float v = g / (1.0f + __expf(-g)) * u;
+      reinterpret_cast<bf16_t*>(Cv)[(size_t)gm * N + n0 / 2 + c].bits = f32_to_bf16_bits(v);
+    } else {
+      float a = 0.f;
+      for (int z = 0; z < split_s; ++z) a += pt[(size_t)z * (BM * BN) + (size_t)r * BN + c];
+      const size_t idx = (size_t)gm * N + n0 + c;
+      if (EPI == EPI_STORE_F32)
+        reinterpret_cast<float*>(Cv)[idx] = a;
+      else
+        reinterpret_cast<bf16_t*>(Cv)[idx].bits = f32_to_bf16_bits(bf16_bits_to_f32(residual[idx].bits) + a);
+    }
+  }
+}
+
+constexpr size_t GEMM_SPLIT_WS_BYTES = (size_t)256 * 256 * 256 * sizeof(float);  // 256 partial tiles of 256 x 256
+
 template <int BM, int BN, int WM, int WN, int GBK, int NST>
 static void launch_cfg(const bf16_t* A, int M, int K, const MfmaB& b, const bf16_t* B2, int N, int epilogue,
-                       const bf16_t* residual, void* C, hipStream_t s) {
+                       const bf16_t* residual, void* C, hipStream_t s, void* ws) {
   const size_t sh = (size_t)NST * (BM + BN) * GBK * sizeof(uint16_t);
   const dim3 block(WM * WN * 64);
   const int n_tile_rows = epilogue == EPI_SWIGLU_STORE ? 2 * N : N;  // B-tile rows to cover
   const int tiles_n = n_tile_rows / BN, tiles_m = (M + BM - 1) / BM;
-  const dim3 grid(8 * ((tiles_m * tiles_n + 7) / 8));
+  const int per_xcd = (tiles_m * tiles_n + 7) / 8;
+  // Workgroups resident per XCD (32 CUs): one per CU for the 256 x 256 tile (128 KB of LDS), two otherwise.
+  // What would be a last, partly filled round is cut along K so that it fills the XCD once.
+  const int slots = sh > 80 * 1024 ? 32 : 64;
+  int full = per_xcd, split = 1;
+  if (ws && BM >= 128) {
+    const int f = per_xcd / slots * slots, rem = per_xcd - f;
+    if (rem > 0) {
+      int sp = std::min(16, slots / rem);
+      sp = std::min(sp, (K / GBK) / 4);  // at least four K slices per workgroup
+      if (sp >= 2 && (size_t)8 * rem * sp * BM * BN * sizeof(float) <= GEMM_SPLIT_WS_BYTES) {
+        full = f;
+        split = sp;
+      }
+    }
+  }
+  const int rem = per_xcd - full;
+  const dim3 grid(8 * (full + rem * split));
+  float* part = reinterpret_cast<float*>(ws);
 #define GO(E)                                                                                              \
   do {                                                                                                     \
-    auto kern = k_gemm_mfma<BM, BN, WM, WN, E, GBK, NST>;                                                            \
+    auto kern = k_gemm_mfma<BM, BN, WM, WN, E, GBK, NST>;                                                  \
     static bool attr_set = false;                                                                          \
     if (!attr_set) {                                                                                       \
       (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, \
                                 (int)sh);                                                                  \
       attr_set = true;                                                                                     \
     }                                                                                                      \
-    hipLaunchKernelGGL(kern, grid, block, sh, s, A, M, K, b, B2, N, residual, C, tiles_m, tiles_n);                          \
+    hipLaunchKernelGGL(kern, grid, block, sh, s, A, M, K, b, B2, N, residual, C, tiles_m, tiles_n, full, split, part); \
+    if (split > 1)                                                                                         \
+      hipLaunchKernelGGL((k_gemm_fixup<BM, BN, WM, WN, E>), dim3(8 * rem, BM * BN / 4096), dim3(256), 0, s, part, M, N, \
+                         residual, C, tiles_m, tiles_n, full, split);                                      \
   } while (0)
   if (epilogue == EPI_STORE_F32)
     GO(EPI_STORE_F32);
@@ -284,6 +386,8 @@ static void launch_cfg(const bf16_t* A, int M, int K, const MfmaB& b, const bf16
     GO(EPI_SWIGLU_STORE);
 #undef GO
 }
+
+size_t gemm_ws_bytes() { return std::max(GEMM_SPLIT_WS_BYTES, gemm_skinny_ws_bytes()); }
 
 void launch_gemm_mfma(const bf16_t* A, int32_t M, int32_t K, const GemmB& B, const void* B2, int32_t N, int epilogue,
                       const bf16_t* residual, void* C, hipStream_t s, void* skinny_ws) {
@@ -307,22 +411,23 @@ void launch_gemm_mfma(const bf16_t* A, int32_t M, int32_t K, const GemmB& B, con
   b.begin[3] = acc;
   const bf16_t* b2 = reinterpret_cast<const bf16_t*>(B2);
   const int rows = epilogue == EPI_SWIGLU_STORE ? 2 * N : N;
-  // 256x256 tiles (8 waves, 64x128 each) when there are enough of them to fill the 256 CUs several
-  // times over; otherwise 128x128 tiles, whose finer grain loses less to the last partial wave of tiles.
+  // 256x256 tiles (8 waves, 64x128 each) unless the launch is so small that their start-up cost shows
+  // (fewer than ~10000 tile K-slices in all); 128x128 tiles then, and where the row counts are not
+  // multiples of 256.  A last, partly filled round of workgroups is cut along K in either case.
   const long tiles256 = (long)((M + 255) / 256) * (rows / 256);
-  if (aligned256 && rows % 256 == 0 && tiles256 >= 1024)
+  if (aligned256 && rows % 256 == 0 && tiles256 * (K / 64) >= 10000)
 #ifndef KEEP_EXP_CFG
 #define KEEP_EXP_CFG 256, 256, 4, 2, 64, 2
 #endif
-    launch_cfg<KEEP_EXP_CFG>(A, M, K, b, b2, N, epilogue, residual, C, s);
+    launch_cfg<KEEP_EXP_CFG>(A, M, K, b, b2, N, epilogue, residual, C, s, skinny_ws);
 #ifdef KEEP_EXP_CFG_SMALL
   else if (rows % 256 == 0 && aligned256)
-    launch_cfg<KEEP_EXP_CFG_SMALL>(A, M, K, b, b2, N, epilogue, residual, C, s);
+    launch_cfg<KEEP_EXP_CFG_SMALL>(A, M, K, b, b2, N, epilogue, residual, C, s, skinny_ws);
 #endif
   else if (rows % 128 == 0)
-    launch_cfg<128, 128, 2, 2, 64, 2>(A, M, K, b, b2, N, epilogue, residual, C, s);
+    launch_cfg<128, 128, 2, 2, 64, 2>(A, M, K, b, b2, N, epilogue, residual, C, s, skinny_ws);
   else
-    launch_cfg<64, 64, 1, 1, 64, 2>(A, M, K, b, b2, N, epilogue, residual, C, s);
+    launch_cfg<64, 64, 1, 1, 64, 2>(A, M, K, b, b2, N, epilogue, residual, C, s, skinny_ws);
 }
 
 }  // namespace keep

@@ -128,8 +128,9 @@ void launch_score_finish(const float* rowmass, const int32_t* d_row_start, int32
                          hipStream_t s);
 
 // MFMA (bf16, head_dim 128) kernels
-// skinny_ws: device scratch of gemm_skinny_ws_bytes() for launches of at most 64 rows (weight-streaming
-// kernel with K slices), or NULL to always use the tiled kernels.
+// skinny_ws: device scratch of gemm_ws_bytes(): partials of the weight-streaming kernel for launches of at
+// most 64 rows, and of the tiles that are cut along K to fill the last round of workgroups.  NULL: neither.
+size_t gemm_ws_bytes();
 void launch_gemm_mfma(const bf16_t* A, int32_t M, int32_t K, const GemmB& B, const void* B2, int32_t N, int epilogue,
                       const bf16_t* residual, void* C, hipStream_t s, void* skinny_ws = nullptr);
 size_t gemm_skinny_ws_bytes();
