@@ -170,9 +170,13 @@ __global__ void __launch_bounds__(WM* WN * 64)
   // NST LDS stages: slices kt+1 .. kt+NST-1 are in flight (or landed) while slice kt is multiplied
   const int kt_begin = (int)((long)piece * (K / GBK) / pieces);
   const int KT = (int)((long)(piece + 1) * (K / GBK) / pieces);  // end of this workgroup's K slices
+  // With two stages the slice after next is requested as soon as the barrier inside the loop has shown
+  // that every wave is done reading the current stage (its last operands are in registers by then): the
+  // loads get a whole iteration to land instead of the part of it that follows the loop top.
+  constexpr bool EARLY = NST == 2;
 #pragma unroll
-  for (int p = 0; p < NST - 1; ++p) GEMM_STAGE(min(kt_begin + p, KT - 1), p)
-  __builtin_amdgcn_s_waitcnt(vmcnt_imm((NST - 2) * LD));  // slice 0 has landed in LDS
+  for (int p = 0; p < (EARLY ? 2 : NST - 1); ++p) GEMM_STAGE(min(kt_begin + p, KT - 1), p)
+  __builtin_amdgcn_s_waitcnt(vmcnt_imm(EARLY ? LD : (NST - 2) * LD));  // slice 0 has landed in LDS
   __syncthreads();
 
   const int a_row0 = wm * TM + (lane & 31);
@@ -201,7 +205,7 @@ __global__ void __launch_bounds__(WM* WN * 64)
     // can stream into it now.  (Past the end the last slice is fetched again: harmless, and it keeps
     // the loop body one straight-line block for the instruction scheduler.)
     const int free_stage = stage == 0 ? NST - 1 : stage - 1;
-    GEMM_STAGE(min(kt + NST - 1, KT - 1), free_stage)
+    if (!EARLY) GEMM_STAGE(min(kt + NST - 1, KT - 1), free_stage)
     const int next_stage = stage + 1 == NST ? 0 : stage + 1;
     const uint16_t* cbuf = smem + stage * BUF;
     const uint16_t* nbuf = smem + next_stage * BUF;
@@ -219,8 +223,9 @@ __global__ void __launch_bounds__(WM* WN * 64)
         // Last k-step of the slice: its operands are already in registers, so the workgroup waits for
         // slice kt+1 and synchronises BEFORE these MFMAs; the first operand reads of the next slice
         // are then in flight while they run.
-        __builtin_amdgcn_s_waitcnt(vmcnt_imm((NST - 2) * LD));
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm(EARLY ? 0 : (NST - 2) * LD));
         __syncthreads();
+        if (EARLY) GEMM_STAGE(min(kt + 2, KT - 1), stage)
 #pragma unroll
         for (int i = 0; i < MI; ++i) af[fn][i] = *reinterpret_cast<const bf16x8*>(nbuf + a_off[0] + i * 32 * GBK);
 #pragma unroll
