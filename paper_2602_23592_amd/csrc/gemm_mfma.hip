@@ -170,13 +170,12 @@ __global__ void __launch_bounds__(WM* WN * 64)
   // NST LDS stages: slices kt+1 .. kt+NST-1 are in flight (or landed) while slice kt is multiplied
   const int kt_begin = (int)((long)piece * (K / GBK) / pieces);
   const int KT = (int)((long)(piece + 1) * (K / GBK) / pieces);  // end of this workgroup's K slices
-  // With two stages the slice after next is requested as soon as the barrier inside the loop has shown
-  // that every wave is done reading the current stage (its last operands are in registers by then): the
-  // loads get a whole iteration to land instead of the part of it that follows the loop top.
-  constexpr bool EARLY = NST == 2;
+  // All NST stages are kept in flight: slice kt+NST is requested as soon as the barrier inside iteration kt
+  // has shown that every wave is done reading the current stage (its last operands are in registers by
+  // then), so the loads get NST-1 whole iterations to land.
 #pragma unroll
-  for (int p = 0; p < (EARLY ? 2 : NST - 1); ++p) GEMM_STAGE(min(kt_begin + p, KT - 1), p)
-  __builtin_amdgcn_s_waitcnt(vmcnt_imm(EARLY ? LD : (NST - 2) * LD));  // slice 0 has landed in LDS
+  for (int p = 0; p < NST; ++p) GEMM_STAGE(min(kt_begin + p, KT - 1), p)
+  __builtin_amdgcn_s_waitcnt(vmcnt_imm((NST - 1) * LD));  // slice 0 has landed in LDS
   __syncthreads();
 
   const int a_row0 = wm * TM + (lane & 31);
@@ -201,11 +200,8 @@ __global__ void __launch_bounds__(WM* WN * 64)
 
   int stage = 0;
   for (int kt = kt_begin; kt < KT; ++kt) {
-    // The stage that held slice kt-1 was last read before the previous barrier, so slice kt+NST-1
-    // can stream into it now.  (Past the end the last slice is fetched again: harmless, and it keeps
-    // the loop body one straight-line block for the instruction scheduler.)
-    const int free_stage = stage == 0 ? NST - 1 : stage - 1;
-    if (!EARLY) GEMM_STAGE(min(kt + NST - 1, KT - 1), free_stage)
+    // (Past the end the last slice is fetched again into the stage just freed: harmless, and it keeps the
+    // loop body one straight-line block for the instruction scheduler.)
     const int next_stage = stage + 1 == NST ? 0 : stage + 1;
     const uint16_t* cbuf = smem + stage * BUF;
     const uint16_t* nbuf = smem + next_stage * BUF;
@@ -223,9 +219,9 @@ __global__ void __launch_bounds__(WM* WN * 64)
         // Last k-step of the slice: its operands are already in registers, so the workgroup waits for
         // slice kt+1 and synchronises BEFORE these MFMAs; the first operand reads of the next slice
         // are then in flight while they run.
-        __builtin_amdgcn_s_waitcnt(vmcnt_imm(EARLY ? 0 : (NST - 2) * LD));
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm((NST - 2) * LD));
         __syncthreads();
-        if (EARLY) GEMM_STAGE(min(kt + 2, KT - 1), stage)
+        GEMM_STAGE(min(kt + NST, KT - 1), stage)
 #pragma unroll
         for (int i = 0; i < MI; ++i) af[fn][i] = *reinterpret_cast<const bf16x8*>(nbuf + a_off[0] + i * 32 * GBK);
 #pragma unroll
@@ -248,6 +244,7 @@ __global__ void __launch_bounds__(WM* WN * 64)
     stage = next_stage;
   }
 #undef GEMM_STAGE
+  __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));  // no LDS write of this workgroup may outlive it
 
   // ---- epilogue.  acc[i][j][e]: row = i*32 + 8*(e/4) + 4*(lane/32) + e%4, col = j*32 + lane%32
   const int col_l = lane & 31;
