@@ -311,29 +311,45 @@ __global__ void __launch_bounds__(256)
   gemm_tile_of<BM>(t, tiles_m, tiles_n, tile_m, tile_n);
   const int m0 = tile_m * BM, n0 = tile_n * BN;
   const float* pt = part + (size_t)blockIdx.x * split_s * (BM * BN);
-  for (int i = blockIdx.y * 256 + threadIdx.x; i < BM * OUT_N; i += gridDim.y * 256) {
-    const int r = i / OUT_N, c = i % OUT_N;
-    const int gm = m0 + r;
-    if (gm >= M) continue;
-    if (EPI == EPI_SWIGLU_STORE) {
-      // output column c of the tile: gate in tile column w*TN + col, up in w*TN + TN/2 + col
-      const int w = c / (TN / 2), col = c % (TN / 2);
-      float g = 0.f, u = 0.f;
-      for (int z = 0; z < split_s; ++z) {
-        const float* p = pt + (size_t)z * (BM * BN) + (size_t)r * BN + w * TN + col;
-        g += p[0];
-        u += p[TN / 2];
-      }
-      const float v = g / (1.0f + __expf(-g)) * u;
-      reinterpret_cast<bf16_t*>(Cv)[(size_t)gm * N + n0 / 2 + c].bits = f32_to_bf16_bits(v);
+  // one thread per 4 consecutive output columns of one row; the slices' loads are independent
+  const int i = (blockIdx.y * 256 + threadIdx.x) * 4;
+  if (i >= BM * OUT_N) return;
+  const int r = i / OUT_N, c = i % OUT_N;
+  const int gm = m0 + r;
+  if (gm >= M) return;
+  if (EPI == EPI_SWIGLU_STORE) {
+    // output column c of the tile: gate in tile column w*TN + col, up in w*TN + TN/2 + col
+    const int w = c / (TN / 2), col = c % (TN / 2);
+    const float* p = pt + (size_t)r * BN + w * TN + col;
+    float4 g = make_float4(0.f, 0.f, 0.f, 0.f), u = g;
+#pragma unroll 4
+    for (int z = 0; z < split_s; ++z) {
+      const float4 gz = *reinterpret_cast<const float4*>(p + (size_t)z * (BM * BN));
+      const float4 uz = *reinterpret_cast<const float4*>(p + (size_t)z * (BM * BN) + TN / 2);
+      g.x += gz.x; g.y += gz.y; g.z += gz.z; g.w += gz.w;
+      u.x += uz.x; u.y += uz.y; u.z += uz.z; u.w += uz.w;
+    }
+    uint2 o;
+    o.x = pack_bf16x2(g.x / (1.0f + __expf(-g.x)) * u.x, g.y / (1.0f + __expf(-g.y)) * u.y);
+    o.y = pack_bf16x2(g.z / (1.0f + __expf(-g.z)) * u.z, g.w / (1.0f + __expf(-g.w)) * u.w);
+    *reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(Cv) + (size_t)gm * N + n0 / 2 + c) = o;
+  } else {
+    const float* p = pt + (size_t)r * BN + c;
+    float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll 4
+    for (int z = 0; z < split_s; ++z) {
+      const float4 v = *reinterpret_cast<const float4*>(p + (size_t)z * (BM * BN));
+      a.x += v.x; a.y += v.y; a.z += v.z; a.w += v.w;
+    }
+    const size_t idx = (size_t)gm * N + n0 + c;
+    if (EPI == EPI_STORE_F32) {
+      *reinterpret_cast<float4*>(reinterpret_cast<float*>(Cv) + idx) = a;
     } else {
-      float a = 0.f;
-      for (int z = 0; z < split_s; ++z) a += pt[(size_t)z * (BM * BN) + (size_t)r * BN + c];
-      const size_t idx = (size_t)gm * N + n0 + c;
-      if (EPI == EPI_STORE_F32)
-        reinterpret_cast<float*>(Cv)[idx] = a;
-      else
-        reinterpret_cast<bf16_t*>(Cv)[idx].bits = f32_to_bf16_bits(bf16_bits_to_f32(residual[idx].bits) + a);
+      const uint2 rv = *reinterpret_cast<const uint2*>(residual + idx);
+      uint2 o;
+      o.x = pack_bf16x2(bf16_bits_to_f32((uint16_t)(rv.x & 0xffff)) + a.x, bf16_bits_to_f32((uint16_t)(rv.x >> 16)) + a.y);
+      o.y = pack_bf16x2(bf16_bits_to_f32((uint16_t)(rv.y & 0xffff)) + a.z, bf16_bits_to_f32((uint16_t)(rv.y >> 16)) + a.w);
+      *reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(Cv) + idx) = o;
     }
   }
 }
@@ -377,7 +393,7 @@ static void launch_cfg(const bf16_t* A, int M, int K, const MfmaB& b, const bf16
     }                                                                                                      \
     hipLaunchKernelGGL(kern, grid, block, sh, s, A, M, K, b, B2, N, residual, C, tiles_m, tiles_n, full, split, part); \
     if (split > 1)                                                                                         \
-      hipLaunchKernelGGL((k_gemm_fixup<BM, BN, WM, WN, E>), dim3(8 * rem, BM * BN / 4096), dim3(256), 0, s, part, M, N, \
+      hipLaunchKernelGGL((k_gemm_fixup<BM, BN, WM, WN, E>), dim3(8 * rem, BM * BN / 1024), dim3(256), 0, s, part, M, N, \
                          residual, C, tiles_m, tiles_n, full, split);                                      \
   } while (0)
   if (epilogue == EPI_STORE_F32)
