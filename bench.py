@@ -81,24 +81,15 @@ class ProfilerGate:
 
 
 def precompute_group_caches(ctx, w, glen, ids, torch):
-    """Group caches made by the library's own dense path on each group alone, at group-local
-    positions (Section 4.1: every static group and every dynamic segment is cached on its own)."""
+    """Group caches made by the library's own dense path on each unit alone, at unit-local positions
+    (Section 4.1: every static group and every dynamic segment is cached on its own), all units in one
+    batched pass."""
     s = w.shape
     L, n_mem = s.n_layers, int(np.sum(glen))
     dt = torch.bfloat16 if s.storage == "bf16" else torch.float32
     kb_all = torch.empty((L, n_mem, s.n_kv_heads, s.head_dim), dtype=dt, device="cuda")
     vb_all = torch.empty_like(kb_all)
-    off = np.concatenate([[0], np.cumsum(glen)])
-    scratch = {}
-    for g, n in enumerate(glen):
-        n = int(n)
-        if n not in scratch:
-            scratch[n] = (torch.empty((L, n, s.n_kv_heads, s.head_dim), dtype=dt, device="cuda"),
-                          torch.empty((L, n, s.n_kv_heads, s.head_dim), dtype=dt, device="cuda"))
-        kc, vc = scratch[n]
-        ctx.precompute_group(ids[off[g]:off[g + 1]], kc, vc)
-        kb_all[:, off[g]:off[g + 1]] = kc
-        vb_all[:, off[g]:off[g + 1]] = vc
+    ctx.precompute_groups([int(n) for n in glen], ids[:n_mem], kb_all, vb_all)
     torch.cuda.synchronize()
     return kb_all, vb_all
 
@@ -168,12 +159,16 @@ def memory_update_cost(ctx, w, torch, steps, warmup):
         for i in range(nseg):
             ctx.precompute_group(toks[i * seg:(i + 1) * seg], k1, v1)
 
+    def every_segment_one_pass():
+        ctx.precompute_groups([seg] * nseg, toks, kg, vg)
+
     def whole_group():
         ctx.precompute_group(toks, kg, vg)
 
     out = {}
     for name, fn, ntok in (("dynamic_segment_update", one_segment, seg),
-                           ("static_to_dynamic", every_segment, seg * nseg),
+                           ("static_to_dynamic_one_by_one", every_segment, seg * nseg),
+                           ("static_to_dynamic", every_segment_one_pass, seg * nseg),
                            ("dynamic_to_static", whole_group, seg * nseg)):
         for _ in range(warmup):
             fn()

@@ -93,6 +93,17 @@ keep_status keep_memory_mark_computed(keep_memory* mem, int32_t unit);
 keep_status keep_precompute_group(keep_ctx* ctx, const int32_t* token_ids, int32_t n_tokens, void* k_blocks,
                                   void* v_blocks, keep_report* report);
 
+/* The same for several units in one pass (a static group that turned dynamic needs every segment cached
+ * on its own; a first build of the memory needs every unit): unit u's tokens follow unit u-1's in
+ * token_ids, and its blocks follow in k_blocks / v_blocks, so layer l of unit u starts at row
+ * (l * total + off_u) with off_u = unit_len[0] + ... + unit_len[u-1], total = sum of unit_len.  Every unit
+ * is rotated at its own local positions and attends to its own tokens only, as if computed alone.
+ *   unit_len: HOST [n_units], each >= 1; token_ids: HOST [total].
+ *   k_blocks, v_blocks: DEVICE [n_layers][total, n_kv_heads, head_dim], written in full.
+ * Errors: INVALID_ARG, WORKSPACE (total above the context's max_tokens), HIP. */
+keep_status keep_precompute_groups(keep_ctx* ctx, int32_t n_units, const int32_t* unit_len, const int32_t* token_ids,
+                                   void* k_blocks, void* v_blocks, keep_report* report);
+
 #ifdef __cplusplus
 }
 #endif

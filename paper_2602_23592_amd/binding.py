@@ -25,7 +25,8 @@ KEEP_REPORT_MAX_LAYERS = 128
 
 EXPORTED = ("keep_init", "keep_destroy", "keep_last_error", "keep_uses_mfma", "keep_workspace_bytes", "keep_recompute_layer",
             "keep_score_groups", "keep_select_groups", "keep_prefill",
-            "keep_prefill_padded", "keep_decode", "keep_precompute_group", "keep_memory_create", "keep_memory_destroy", "keep_memory_last_error",
+            "keep_prefill_padded", "keep_decode", "keep_precompute_group", "keep_precompute_groups",
+            "keep_memory_create", "keep_memory_destroy", "keep_memory_last_error",
             "keep_memory_put", "keep_memory_remove", "keep_memory_end_step", "keep_memory_unit_count",
             "keep_memory_unit_info", "keep_memory_unit_tokens", "keep_memory_mark_computed")
 
@@ -117,6 +118,8 @@ def load_library() -> C.CDLL:
     lib.keep_decode.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, pi32, vp, pi32]
     lib.keep_precompute_group.restype = i32
     lib.keep_precompute_group.argtypes = [vp, pi32, i32, vp, vp, C.POINTER(Report)]
+    lib.keep_precompute_groups.restype = i32
+    lib.keep_precompute_groups.argtypes = [vp, i32, pi32, pi32, vp, vp, C.POINTER(Report)]
     lib.keep_memory_create.restype = i32
     lib.keep_memory_create.argtypes = [i32, C.POINTER(vp)]
     lib.keep_memory_destroy.restype = i32
@@ -302,6 +305,16 @@ class KeepContext:
                 C.byref(rep) if want_report else None))
         sets = [[int(v) for v in sel[l * G:l * G + cnt[l]]] for l in range(L)]
         return sets, rep
+
+    def precompute_groups(self, unit_len: Sequence[int], token_ids: Sequence[int], k_blocks: torch.Tensor,
+                          v_blocks: torch.Tensor, want_report: bool = False):
+        """KV blocks [n_layers][sum(unit_len), n_kv_heads, head_dim] of several units, each computed on its own."""
+        ul, ulp = _i32_array(unit_len)
+        ids, ip = _i32_array(token_ids)
+        rep = Report() if want_report else None
+        self._check(self.lib.keep_precompute_groups(self.handle, len(ul), ulp, ip, k_blocks.data_ptr(),
+                                                    v_blocks.data_ptr(), C.byref(rep) if want_report else None))
+        return rep
 
     def decode(self, final_norm: torch.Tensor, lm_head: torch.Tensor, x_last: torch.Tensor, k_cache: torch.Tensor,
                v_cache: torch.Tensor, n_ctx: int, n_new: int, logits_out: Optional[torch.Tensor] = None,

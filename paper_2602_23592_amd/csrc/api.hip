@@ -69,6 +69,9 @@ struct keep_ctx {
   // pinned host
   std::vector<Staging> stage;       // one slot per layer
   int32_t* h_sel_out = nullptr;     // [max_groups + 2]
+  int32_t* h_row_lo = nullptr;      // pinned [max_tokens]: first visible key per row (batched unit caching)
+  int32_t* d_row_lo = nullptr;
+  bool units_mode = false;          // rows attend only from their unit's first row on
   int32_t* h_dec = nullptr;         // pinned [4 * KEEP_DECODE_MAX_TOKENS]: positions, fed tokens, results
   int32_t* d_dec = nullptr;         // device mirror
   float* dec_logits = nullptr;      // [vocab]
@@ -204,6 +207,7 @@ uint64_t workspace_bytes(const keep_model_desc* d) {
   t += align256(((z.G + 1) * z.G + 2 * z.G) * sizeof(float));          // sel_work
   t += align256(4 * z.G * sizeof(int32_t)) + align256((z.G + 2) * sizeof(int32_t));
   t += align256(4 * KEEP_DECODE_MAX_TOKENS * 4) + align256((size_t)d->vocab * sizeof(float));  // decode
+  t += align256(z.M * sizeof(int32_t));                                // row_lo
   return t;
 }
 
@@ -393,16 +397,19 @@ keep_status layer_front(keep_ctx* c, const PromptInfo& pi, int layer, const Laye
   if (evs) HIP_TRY(c, hipEventRecord(evs[3], s));
   launch_rope_scatter<T>(c->qkv_raw, Typed<T>::p(w.bq), Typed<T>::p(w.bk), Typed<T>::p(w.bv), c->d_row_pos, n,
                          d.n_q_heads, d.n_kv_heads, d.head_dim, c->rope_cos, c->rope_sin, Typed<T>::p(c->q),
-                         Typed<T>::p(c->kc), Typed<T>::p(k_cache_l), Typed<T>::p(v_cache_l), s);
+                         Typed<T>::p(c->kc), Typed<T>::p(k_cache_l), Typed<T>::p(v_cache_l), s,
+                         c->units_mode ? c->d_row_lo : nullptr);
   if (evs) HIP_TRY(c, hipEventRecord(evs[4], s));
   if (c->mfma)
     launch_attn_mfma(reinterpret_cast<const bf16_t*>(c->q), reinterpret_cast<const bf16_t*>(k_cache_l),
                      reinterpret_cast<const bf16_t*>(v_cache_l), c->d_row_pos, plan.row_start.data(),
                      c->stage[layer].set_off, plan.m, pi.n_mem, n, pi.N, d.n_q_heads, d.n_kv_heads, d.max_tokens,
-                     c->stage[layer].attn_items, c->attn_scratch, reinterpret_cast<bf16_t*>(c->o), c->lse, s);
+                     c->stage[layer].attn_items, c->attn_scratch, reinterpret_cast<bf16_t*>(c->o), c->lse, s,
+                     c->units_mode ? c->h_row_lo : nullptr, c->units_mode ? c->d_row_lo : nullptr);
   else
     launch_attn_generic<T>(Typed<T>::p(c->q), Typed<T>::p(k_cache_l), Typed<T>::p(v_cache_l), c->d_row_pos, n,
-                           d.n_q_heads, d.n_kv_heads, d.head_dim, Typed<T>::p(c->o), c->lse, s);
+                           d.n_q_heads, d.n_kv_heads, d.head_dim, Typed<T>::p(c->o), c->lse, s,
+                           c->units_mode ? c->d_row_lo : nullptr);
   if (evs) HIP_TRY(c, hipEventRecord(evs[5], s));
   HIP_TRY(c, hipGetLastError());
   return KEEP_OK;
@@ -642,6 +649,7 @@ keep_status keep_destroy(keep_ctx* c) {
   }
   if (c->h_sel_out) (void)hipHostFree(c->h_sel_out);
   if (c->h_dec) (void)hipHostFree(c->h_dec);
+  if (c->h_row_lo) (void)hipHostFree(c->h_row_lo);
   if (c->h_S) (void)hipHostFree(c->h_S);
   if (c->h_token_ids) (void)hipHostFree(c->h_token_ids);
   for (hipEvent_t e : c->ev) (void)hipEventDestroy(e);
@@ -763,6 +771,8 @@ keep_status keep_init(const keep_model_desc* desc, const keep_layer_weights* lay
   }
   TRY_INIT(pin_alloc(c, &c->h_sel_out, (z.G + 2) * 4));
   TRY_INIT(pin_alloc(c, &c->h_dec, 4 * KEEP_DECODE_MAX_TOKENS * 4));
+  TRY_INIT(pin_alloc(c, &c->h_row_lo, z.M * 4));
+  TRY_INIT(dev_alloc(c, &c->d_row_lo, z.M * 4));
   TRY_INIT(dev_alloc(c, &c->d_dec, 4 * KEEP_DECODE_MAX_TOKENS * 4));
   TRY_INIT(dev_alloc(c, &c->dec_logits, (size_t)desc->vocab * sizeof(float)));
   TRY_INIT(pin_alloc(c, &c->h_S, (z.G + 1) * z.G * sizeof(float)));
@@ -1094,6 +1104,42 @@ keep_status keep_precompute_group(keep_ctx* c, const int32_t* token_ids, int32_t
   std::vector<float> ratios((size_t)c->d.n_layers, 0.f);
   return prefill_impl(c, &pr, ratios.data(), 1, KEEP_BUDGET_GROUP_COUNT, KEEP_LOAD_SERIAL, k_blocks, v_blocks, 0, nullptr,
                       nullptr, nullptr, report);
+}
+
+keep_status keep_precompute_groups(keep_ctx* c, int32_t n_units, const int32_t* unit_len, const int32_t* token_ids,
+                                   void* k_blocks, void* v_blocks, keep_report* report) {
+  if (!c) return KEEP_ERR_INVALID_ARG;
+  if (!unit_len || !token_ids || !k_blocks || !v_blocks)
+    return fail(c, KEEP_ERR_INVALID_ARG, "unit_len / token_ids / k_blocks / v_blocks is NULL");
+  if (n_units < 1) return fail(c, KEEP_ERR_INVALID_ARG, "n_units must be at least 1");
+  int64_t total = 0;
+  for (int u = 0; u < n_units; ++u) {
+    if (unit_len[u] < 1) return fail(c, KEEP_ERR_INVALID_ARG, "unit_len[%d] = %d, must be >= 1", u, unit_len[u]);
+    total += unit_len[u];
+    if (total > c->d.max_tokens) return fail(c, KEEP_ERR_WORKSPACE, "units longer than max_tokens %d", c->d.max_tokens);
+  }
+  // One pass for all the units: the rows are every token in order, row t of unit u sits at cache row
+  // off_u + t, is rotated at its local position t and attends to rows off_u .. off_u + t only.
+  // (The bounds sit in pinned memory until the upload has run: wait for the stream's earlier work first.)
+  HIP_TRY(c, hipStreamSynchronize(c->s_comp));
+  int row = 0;
+  for (int u = 0; u < n_units; ++u) {
+    const int start = row;
+    for (int t = 0; t < unit_len[u]; ++t) c->h_row_lo[row++] = start;
+  }
+  HIP_TRY(c, hipMemcpyAsync(c->d_row_lo, c->h_row_lo, (size_t)total * 4, hipMemcpyHostToDevice, c->s_comp));
+  keep_prompt pr;
+  memset(&pr, 0, sizeof pr);
+  pr.n_groups = 0;
+  pr.instr_len = (int32_t)total;
+  pr.token_ids = token_ids;
+  pr.kv_location = KEEP_KV_DEVICE;
+  std::vector<float> ratios((size_t)c->d.n_layers, 0.f);
+  c->units_mode = true;
+  const keep_status st = prefill_impl(c, &pr, ratios.data(), 1, KEEP_BUDGET_GROUP_COUNT, KEEP_LOAD_SERIAL, k_blocks,
+                                      v_blocks, 0, nullptr, nullptr, nullptr, report);
+  c->units_mode = false;
+  return st;
 }
 
 }  // extern "C"

@@ -47,9 +47,10 @@ constexpr int PART_FLOATS = 128 * DH;  // partial O of one (item, KV head): [dh/
 
 __global__ void __launch_bounds__(256, 2)
     k_attn_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k_cache, const bf16_t* __restrict__ v_cache,
-                const int32_t* __restrict__ row_pos, int n_rows, int n_total, int n_q_heads, int n_kv_heads,
-                const int4* __restrict__ items, float scale_log2e, bf16_t* __restrict__ o, float* __restrict__ lse,
-                float* __restrict__ part_o, float* __restrict__ part_ml) {
+                const int32_t* __restrict__ row_pos, const int32_t* __restrict__ row_lo, int n_rows, int n_total,
+                int n_q_heads, int n_kv_heads, const int4* __restrict__ items, float scale_log2e,
+                bf16_t* __restrict__ o, float* __restrict__ lse, float* __restrict__ part_o,
+                float* __restrict__ part_ml) {
   extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int g = lane >> 5, lq = lane & 31;
@@ -66,11 +67,14 @@ __global__ void __launch_bounds__(256, 2)
   const int r = valid ? x / rep : 0;
   const int head = hk * rep + (valid ? x % rep : 0);
   const int pos = valid ? row_pos[r] : 0;
-  int wmax = pos, wmin = pos;
+  const int lo = (valid && row_lo) ? row_lo[r] : 0;  // first key the row may see
+  int wmax = pos, wmin = pos, wlo_max = lo, wlo_min = valid ? lo : 0x7fffffff;
 #pragma unroll
   for (int off = 16; off > 0; off >>= 1) {
     wmax = max(wmax, __shfl_xor(wmax, off, 64));
     wmin = min(wmin, __shfl_xor(wmin, off, 64));
+    wlo_max = max(wlo_max, __shfl_xor(wlo_max, off, 64));
+    wlo_min = min(wlo_min, __shfl_xor(wlo_min, off, 64));
   }
   const int kt0 = item.y, n_kt = item.z;
 
@@ -133,7 +137,7 @@ __global__ void __launch_bounds__(256, 2)
     const int k0 = kt * KT_KEYS;
     // every wave finished reading the other buffer before the barrier that ended the last iteration
     if (kt + 1 < n_kt) ATT_STAGE(kt + 1, cur ^ 1)
-    if (k0 <= wmax) {
+    if (k0 <= wmax && k0 + KT_KEYS > wlo_min) {
       const uint16_t* sk = smem + cur * ATT_BUF;
       const uint16_t* sv = sk + KT_KEYS * DH;
       // ---- S^T = K . Q^T for the two 32-key halves; K operands are read four k-steps ahead
@@ -168,14 +172,14 @@ __global__ void __launch_bounds__(256, 2)
       for (int i = 0; i < 4; ++i) sacc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfb[i], qf[4 + i], sacc[1], 0, 0, 0);
 
       // ---- causal mask, running max (raw scores; the scale is folded into the exponent's fma)
-      const bool need_mask = k0 + KT_KEYS - 1 > wmin;
+      const bool need_mask = k0 + KT_KEYS - 1 > wmin || k0 < wlo_max;
       if (need_mask) {
 #pragma unroll
         for (int st = 0; st < 2; ++st)
 #pragma unroll
           for (int e = 0; e < 16; ++e) {
             const int key = k0 + st * 32 + 8 * (e >> 2) + 4 * g + (e & 3);
-            sacc[st][e] = key <= pos ? sacc[st][e] : -INFINITY;
+            sacc[st][e] = (key <= pos && key >= lo) ? sacc[st][e] : -INFINITY;
           }
       }
       float tmax = -INFINITY;
@@ -334,7 +338,8 @@ size_t attn_mfma_scratch_bytes(int32_t max_rows, int32_t n_q_heads, int32_t n_kv
 void launch_attn_mfma(const bf16_t* q, const bf16_t* k_cache, const bf16_t* v_cache, const int32_t* d_row_pos,
                       const int32_t* h_row_start, const int32_t* h_set_off, int32_t m, int32_t instr_off,
                       int32_t n_rows, int32_t n_total, int32_t n_q_heads, int32_t n_kv_heads, int32_t max_rows,
-                      int32_t* h_stage, void* d_scratch, bf16_t* o, float* lse, hipStream_t s) {
+                      int32_t* h_stage, void* d_scratch, bf16_t* o, float* lse, hipStream_t s,
+                      const int32_t* h_row_lo, const int32_t* d_row_lo) {
   if (n_rows <= 0) return;
   const int rep = n_q_heads / n_kv_heads;
   const int n_tiles = (n_rows * rep + 127) / 128;
@@ -355,12 +360,16 @@ void launch_attn_mfma(const bf16_t* q, const bf16_t* k_cache, const bf16_t* v_ca
   int4* h_splits = reinterpret_cast<int4*>(h_stage + (size_t)4 * (mt + ATT_MAX_SLOTS));
   long total_steps = 0;
   // steps of tile t are kept in h_splits[t].w for the second pass (overwritten afterwards is fine: separate array)
-  static thread_local std::vector<int> steps;
+  // tile t needs the key tiles [first[t], steps[t]): from the first key its first row may see (0 unless
+  // h_row_lo says otherwise; bounds do not decrease along the rows) to the position of its last row
+  static thread_local std::vector<int> steps, first;
   steps.resize(n_tiles);
+  first.resize(n_tiles);
   for (int t = 0; t < n_tiles; ++t) {
     const int x_last = std::min(n_rows * rep, (t + 1) * 128) - 1;
     steps[t] = pos_of_row(x_last / rep) / KT_KEYS + 1;
-    total_steps += steps[t];
+    first[t] = h_row_lo ? h_row_lo[(t * 128) / rep] / KT_KEYS : 0;
+    total_steps += steps[t] - first[t];
   }
   // Two workgroups fit on each of the 256 CUs: 512 slots.  A key range longer than a slot's average
   // share of the work would leave the chip waiting for it at the end (instruction rows see the whole
@@ -374,7 +383,7 @@ void launch_attn_mfma(const bf16_t* q, const bf16_t* k_cache, const bf16_t* v_ca
   for (;;) {
     long slots = 0;
     for (int t = 0; t < n_tiles; ++t) {
-      const int nc = (steps[t] + chunk - 1) / chunk;
+      const int nc = (steps[t] - first[t] + chunk - 1) / chunk;
       if (nc > 1) slots += nc;
     }
     if (slots * n_kv_heads <= ATT_MAX_SLOTS) break;
@@ -383,7 +392,7 @@ void launch_attn_mfma(const bf16_t* q, const bf16_t* k_cache, const bf16_t* v_ca
   int n_items = 0, n_splits = 0, slot = 0;
   int min_steps = steps[0];
   for (int t = 1; t < n_tiles; ++t) min_steps = std::min(min_steps, steps[t]);
-  if (n_tiles > 1 && (long)min_steps * 10 >= (long)steps[n_tiles - 1] * 9) {
+  if (!h_row_lo && n_tiles > 1 && (long)min_steps * 10 >= (long)steps[n_tiles - 1] * 9) {
     // Every query tile reads (nearly) the whole cache: a few instruction rows over a long prompt.  Items go
     // out chunk by chunk on one grid of key ranges, so the query tiles that read the same K/V range are
     // neighbours in the launch order, run at the same time on the XCD of their KV head and find the range
@@ -409,13 +418,15 @@ void launch_attn_mfma(const bf16_t* q, const bf16_t* k_cache, const bf16_t* v_ca
       }
   } else {
     for (int t = n_tiles - 1; t >= 0; --t) {  // longest key ranges first, each cut into equal pieces
-      const int nc = (steps[t] + chunk - 1) / chunk;
+      const int span = steps[t] - first[t];
+      const int nc = (span + chunk - 1) / chunk;
       if (nc <= 1) {
-        h_items[n_items++] = make_int4(t, 0, steps[t], -1);
+        h_items[n_items++] = make_int4(t, first[t], steps[t], -1);
       } else {
-        const int len = (steps[t] + nc - 1) / nc;
+        const int len = (span + nc - 1) / nc;
         h_splits[n_splits++] = make_int4(t, slot, nc, 0);
-        for (int c = 0; c < nc; ++c) h_items[n_items++] = make_int4(t, c * len, std::min(steps[t], (c + 1) * len), slot + c);
+        for (int c = 0; c < nc; ++c)
+          h_items[n_items++] = make_int4(t, first[t] + c * len, std::min(steps[t], first[t] + (c + 1) * len), slot + c);
         slot += nc;
       }
     }
@@ -439,7 +450,7 @@ void launch_attn_mfma(const bf16_t* q, const bf16_t* k_cache, const bf16_t* v_ca
     attr_set = true;
   }
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)DH);
-  hipLaunchKernelGGL(k_attn_mfma, dim3(n_items * n_kv_heads), dim3(256), sh, s, q, k_cache, v_cache, d_row_pos, n_rows,
+  hipLaunchKernelGGL(k_attn_mfma, dim3(n_items * n_kv_heads), dim3(256), sh, s, q, k_cache, v_cache, d_row_pos, d_row_lo, n_rows,
                      n_total, n_q_heads, n_kv_heads, d_items, scale_log2e, o, lse, part_o, part_ml);
   if (n_splits)
     hipLaunchKernelGGL(k_attn_combine, dim3(n_splits * n_kv_heads, 16), dim3(256), 0, s, d_splits, part_o, part_ml, n_rows,

@@ -105,7 +105,7 @@ template <typename T>
 void launch_rope_scatter(const float* qkv_raw /*[n_rows, q_dim + 2 kv_dim]*/, const T* bq, const T* bk, const T* bv,
                          const int32_t* d_row_pos, int32_t n_rows, int32_t n_q_heads, int32_t n_kv_heads,
                          int32_t head_dim, const float* rope_cos, const float* rope_sin, T* q, T* k_compact,
-                         T* k_cache, T* v_cache, hipStream_t s);
+                         T* k_cache, T* v_cache, hipStream_t s, const int32_t* d_row_lo = nullptr);
 
 // out[0] = index of the largest of logits[0..n), the lowest index among equal values
 void launch_argmax(const float* logits, int32_t n, int32_t* out, hipStream_t s);
@@ -116,7 +116,8 @@ void launch_gemm_generic(const T* A, int32_t M, int32_t K, const GemmB& B, const
                          const T* residual, void* C, hipStream_t s);
 template <typename T>
 void launch_attn_generic(const T* q, const T* k_cache, const T* v_cache, const int32_t* d_row_pos, int32_t n_rows,
-                         int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, T* o, float* lse, hipStream_t s);
+                         int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, T* o, float* lse, hipStream_t s,
+                         const int32_t* d_row_lo = nullptr);
 // rowmass[t, j] = sum over heads and over the keys s of candidate j (compact rows
 // key_start[j]..key_start[j+1]) with s <= t of exp(q_t.k_s/sqrt(dh) - lse[t,h])
 template <typename T>
@@ -145,7 +146,10 @@ size_t attn_mfma_scratch_bytes(int32_t max_rows, int32_t n_q_heads, int32_t n_kv
 void launch_attn_mfma(const bf16_t* q, const bf16_t* k_cache, const bf16_t* v_cache, const int32_t* d_row_pos,
                       const int32_t* h_row_start, const int32_t* h_set_off, int32_t m, int32_t instr_off,
                       int32_t n_rows, int32_t n_total, int32_t n_q_heads, int32_t n_kv_heads, int32_t max_rows,
-                      int32_t* h_stage, void* d_scratch, bf16_t* o, float* lse, hipStream_t s);
+                      int32_t* h_stage, void* d_scratch, bf16_t* o, float* lse, hipStream_t s,
+                      const int32_t* h_row_lo = nullptr, const int32_t* d_row_lo = nullptr);
+// h_row_lo / d_row_lo (host and device copies, both or neither): first key each row may see (default 0);
+// used where several units are cached in one pass, each attending to itself only.
 // group-score matrix S[(m+1), m] of the layer whose q / compact k / lse are given.
 // h_stage: pinned host ints (score_mfma_stage_ints of them), d_scratch: device bytes
 // (score_mfma_scratch_bytes), both sized with the same max_rows / max_groups.

@@ -134,8 +134,8 @@ void launch_gemm_generic(const T* A, int32_t M, int32_t K, const GemmB& B, const
 template <typename T>
 __global__ void __launch_bounds__(256)
     k_attn_generic(const T* __restrict__ q, const T* __restrict__ k_cache, const T* __restrict__ v_cache,
-                   const int32_t* __restrict__ row_pos, int n_q_heads, int n_kv_heads, int head_dim,
-                   T* __restrict__ o, float* __restrict__ lse) {
+                   const int32_t* __restrict__ row_pos, const int32_t* __restrict__ row_lo, int n_q_heads,
+                   int n_kv_heads, int head_dim, T* __restrict__ o, float* __restrict__ lse) {
   extern __shared__ float smem[];
   float* s_q = smem;              // [head_dim]
   float* s_p = s_q + head_dim;    // [256]
@@ -144,6 +144,7 @@ __global__ void __launch_bounds__(256)
   const int r = blockIdx.x, h = blockIdx.y;
   const int hk = h / (n_q_heads / n_kv_heads);
   const int p_row = row_pos[r];
+  const int p_lo = row_lo ? row_lo[r] : 0;  // first visible key (a unit cached on its own sees only itself)
   const int kv_dim = n_kv_heads * head_dim;
   const int tid = threadIdx.x;
   const float scale = 1.0f / sqrtf((float)head_dim);
@@ -154,7 +155,7 @@ __global__ void __launch_bounds__(256)
   const int part = tid / head_dim, d_out = tid - part * head_dim;
   const bool pv_active = part < n_parts && head_dim <= 256;
   float m_run = -INFINITY, l_run = 0.f, acc = 0.f;
-  for (int c0 = 0; c0 <= p_row; c0 += 256) {
+  for (int c0 = p_lo; c0 <= p_row; c0 += 256) {
     const int key = c0 + tid;
     float sc = -INFINITY;
     if (key <= p_row) {
@@ -200,11 +201,12 @@ __global__ void __launch_bounds__(256)
 
 template <typename T>
 void launch_attn_generic(const T* q, const T* k_cache, const T* v_cache, const int32_t* d_row_pos, int32_t n_rows,
-                         int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, T* o, float* lse, hipStream_t s) {
+                         int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, T* o, float* lse, hipStream_t s,
+                         const int32_t* d_row_lo) {
   if (n_rows <= 0) return;
   const size_t sh = (size_t)(head_dim + 256 + 8 + 256) * sizeof(float);
   hipLaunchKernelGGL(k_attn_generic<T>, dim3(n_rows, n_q_heads), dim3(256), sh, s, q, k_cache, v_cache, d_row_pos,
-                     n_q_heads, n_kv_heads, head_dim, o, lse);
+                     d_row_lo, n_q_heads, n_kv_heads, head_dim, o, lse);
 }
 
 // ---------------------------------------------------------------------------
@@ -302,7 +304,7 @@ void launch_score_finish(const float* rowmass, const int32_t* d_row_start, int32
   template void launch_gemm_generic<T>(const T*, int32_t, int32_t, const GemmB&, const void*, int32_t, int,       \
                                        const T*, void*, hipStream_t);                                              \
   template void launch_attn_generic<T>(const T*, const T*, const T*, const int32_t*, int32_t, int32_t, int32_t,   \
-                                       int32_t, T*, float*, hipStream_t);                                          \
+                                       int32_t, T*, float*, hipStream_t, const int32_t*);                          \
   template void launch_score_rows_generic<T>(const T*, const T*, const float*, const int32_t*, int32_t, int32_t,  \
                                              int32_t, int32_t, int32_t, float*, hipStream_t);
 INST(float)

@@ -272,8 +272,9 @@ __device__ inline void store4<bf16_t>(bf16_t* p, const float* f) {
 template <typename T>
 __global__ void __launch_bounds__(256)
     k_rope_scatter(const float* __restrict__ qkv_raw, const T* __restrict__ bq, const T* __restrict__ bk,
-                   const T* __restrict__ bv, const int32_t* __restrict__ row_pos, int n_q_heads, int n_kv_heads,
-                   int head_dim, const float* __restrict__ rope_cos, const float* __restrict__ rope_sin,
+                   const T* __restrict__ bv, const int32_t* __restrict__ row_pos, const int32_t* __restrict__ row_lo,
+                   int n_q_heads, int n_kv_heads, int head_dim, const float* __restrict__ rope_cos,
+                   const float* __restrict__ rope_sin,
                    T* __restrict__ q, T* __restrict__ k_compact, T* __restrict__ k_cache, T* __restrict__ v_cache) {
   const int r = blockIdx.x;
   const int pos = row_pos[r];
@@ -284,8 +285,10 @@ __global__ void __launch_bounds__(256)
   const int per_head = half / 4;
   const int rot_items = (n_q_heads + n_kv_heads) * per_head;
   const int v_items = kv_dim / 4;
-  const float* cs = rope_cos + (size_t)pos * half;
-  const float* sn = rope_sin + (size_t)pos * half;
+  // a unit cached on its own is rotated at its local positions: cache row minus the unit's first row
+  const int rpos = pos - (row_lo ? row_lo[r] : 0);
+  const float* cs = rope_cos + (size_t)rpos * half;
+  const float* sn = rope_sin + (size_t)rpos * half;
   for (int it = threadIdx.x; it < rot_items + v_items; it += 256) {
     if (it < rot_items) {
       const int h = it / per_head, c = (it - h * per_head) * 4;
@@ -340,10 +343,11 @@ template <typename T>
 void launch_rope_scatter(const float* qkv_raw, const T* bq, const T* bk, const T* bv, const int32_t* d_row_pos,
                          int32_t n_rows, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
                          const float* rope_cos, const float* rope_sin, T* q, T* k_compact, T* k_cache, T* v_cache,
-                         hipStream_t s) {
+                         hipStream_t s,
+                         const int32_t* d_row_lo) {
   if (n_rows <= 0) return;
-  hipLaunchKernelGGL(k_rope_scatter<T>, dim3(n_rows), dim3(256), 0, s, qkv_raw, bq, bk, bv, d_row_pos, n_q_heads,
-                     n_kv_heads, head_dim, rope_cos, rope_sin, q, k_compact, k_cache, v_cache);
+  hipLaunchKernelGGL(k_rope_scatter<T>, dim3(n_rows), dim3(256), 0, s, qkv_raw, bq, bk, bv, d_row_pos, d_row_lo,
+                     n_q_heads, n_kv_heads, head_dim, rope_cos, rope_sin, q, k_compact, k_cache, v_cache);
 }
 
 // Greedy choice over one row of logits: the largest value, the lowest index among equal ones.
@@ -393,7 +397,8 @@ void launch_argmax(const float* logits, int32_t n, int32_t* out, hipStream_t s) 
                                   T*, T*, hipStream_t);                                                               \
   template void launch_rmsnorm<T>(const T*, const T*, int32_t, int32_t, float, T*, hipStream_t);                     \
   template void launch_rope_scatter<T>(const float*, const T*, const T*, const T*, const int32_t*, int32_t, int32_t, \
-                                       int32_t, int32_t, const float*, const float*, T*, T*, T*, T*, hipStream_t);
+                                       int32_t, int32_t, const float*, const float*, T*, T*, T*, T*, hipStream_t,   \
+                                       const int32_t*);
 INST(float)
 INST(bf16_t)
 #undef INST

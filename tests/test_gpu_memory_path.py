@@ -118,3 +118,33 @@ def test_update_loop_end_to_end_fp32():
             assert max_rel(to_np(vc[l]), ref["v_hat"][l]) < 1e-4
         assert max_rel(to_np(xf), ref["x_final"]) < 1e-4
     assert seen_static
+
+
+@pytest.mark.parametrize("shape,tol", [(F32, 1e-4), (BF16, 2e-2)], ids=["f32", "bf16_mfma"])
+def test_units_cached_in_one_pass_match_each_unit_alone(shape, tol):
+    """Several units through keep_precompute_groups: every unit's blocks against the oracle's dense prefill of
+    that unit on its own (local positions, attention inside the unit only).  Lengths straddle the 64-key tiles
+    and the query tiles of the kernels."""
+    pb = Problem(shape, [1], 1, seed=2, std=0.05, bias=True)
+    lens = [1, 33, 64, 65, 200, 7, 130, 2, 300]
+    total = sum(lens)
+    ctx = pb.context(max_tokens=total, max_groups=4)
+    rng = np.random.default_rng(13)
+    tokens = [int(t) for t in rng.integers(0, shape.vocab, size=total)]
+    dt = ks.torch_dtype(shape.storage)
+    k = torch.empty((shape.n_layers, total, shape.n_kv_heads, shape.head_dim), dtype=dt, device="cuda")
+    v = torch.empty_like(k)
+    ctx.precompute_groups(lens, tokens, k, v)
+    torch.cuda.synchronize()
+    off = 0
+    for n in lens:
+        kr, vr, _ = ko.dense_prefill(pb.sh, pb.layers, pb.embed, np.asarray(tokens[off:off + n]))
+        for l in range(shape.n_layers):
+            ek = max_rel(to_np(k[l, off:off + n]), kr[l])
+            ev = max_rel(to_np(v[l, off:off + n]), vr[l])
+            assert ek < tol and ev < tol, (n, l, ek, ev)
+        off += n
+    # the next ordinary call is back to whole-prompt attention and global positions
+    k1, v1 = unit_cache(ctx, shape, tokens[:40])
+    kr, vr, _ = ko.dense_prefill(pb.sh, pb.layers, pb.embed, np.asarray(tokens[:40]))
+    assert max_rel(to_np(k1[-1]), kr[-1]) < tol and max_rel(to_np(v1[-1]), vr[-1]) < tol
