@@ -52,7 +52,7 @@ __global__ void __launch_bounds__(256, 2)
                 bf16_t* __restrict__ o, float* __restrict__ lse, float* __restrict__ part_o,
                 float* __restrict__ part_ml) {
   extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int g = lane >> 5, lq = lane & 31;
   const int rep = n_q_heads / n_kv_heads;
   const int hk = blockIdx.x % n_kv_heads;
@@ -76,6 +76,12 @@ __global__ void __launch_bounds__(256, 2)
     wlo_max = max(wlo_max, __shfl_xor(wlo_max, off, 64));
     wlo_min = min(wlo_min, __shfl_xor(wlo_min, off, 64));
   }
+  // (the butterflies cover 32 lanes; fold the two halves and keep the wave's bounds in scalar registers,
+  // so that the tests on them below are uniform branches)
+  wmax = __builtin_amdgcn_readfirstlane(max(wmax, __shfl_xor(wmax, 32, 64)));
+  wmin = __builtin_amdgcn_readfirstlane(min(wmin, __shfl_xor(wmin, 32, 64)));
+  wlo_max = __builtin_amdgcn_readfirstlane(max(wlo_max, __shfl_xor(wlo_max, 32, 64)));
+  wlo_min = __builtin_amdgcn_readfirstlane(min(wlo_min, __shfl_xor(wlo_min, 32, 64)));
   const int kt0 = item.y, n_kt = item.z;
 
   // Q^T operand: 8 k-steps of 16 head-dim elements
