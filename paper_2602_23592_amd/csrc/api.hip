@@ -542,6 +542,7 @@ keep_status decode_impl(keep_ctx* c, const void* final_norm, const void* lm_head
   plan.n_rows = 1;
   plan.row_start = {0, 1};
   const void* x = x_last;
+  AttnPlan att_plan;
   for (int t = 0; t < n_new; ++t) {
     // vocabulary projection of the newest hidden row, greedy choice
     float* lg = logits_out ? logits_out + (size_t)t * d.vocab : c->dec_logits;
@@ -566,8 +567,13 @@ keep_status decode_impl(keep_ctx* c, const void* final_norm, const void* lm_head
       const keep_layer_weights& w = c->w[l];
       char* kl = (char*)k_cache + (size_t)l * layer_bytes;
       char* vl = (char*)v_cache + (size_t)l * layer_bytes;
-      Staging& sg = c->stage[l];
-      if (sg.used) HIP_TRY(c, hipEventSynchronize(sg.done));  // the slot's last upload has been consumed
+      // The work list of the attention depends on the position only: layer 0 of the step plans and uploads
+      // it (through staging slot t % n_layers, free again once its event has fired), the other layers reuse it.
+      Staging& sg = c->stage[t % d.n_layers];
+      if (l == 0) {
+        if (sg.used) HIP_TRY(c, hipEventSynchronize(sg.done));
+        att_plan.valid = false;
+      }
       launch_rmsnorm<T>(Typed<T>::p(x_cur), Typed<T>::p(w.ln1), 1, d.hidden, d.rms_eps, Typed<T>::p(c->hbuf), s);
       GemmB b;
       b.n_parts = 3;
@@ -588,13 +594,15 @@ keep_status decode_impl(keep_ctx* c, const void* final_norm, const void* lm_head
         launch_attn_mfma(reinterpret_cast<const bf16_t*>(c->q), reinterpret_cast<const bf16_t*>(kl),
                          reinterpret_cast<const bf16_t*>(vl), d_pos, plan.row_start.data(), sg.set_off, 0, pi.n_mem, 1,
                          pi.N, d.n_q_heads, d.n_kv_heads, d.max_tokens, sg.attn_items, c->attn_scratch,
-                         reinterpret_cast<bf16_t*>(c->o), c->lse, s);
+                         reinterpret_cast<bf16_t*>(c->o), c->lse, s, nullptr, nullptr, &att_plan);
       else
         launch_attn_generic<T>(Typed<T>::p(c->q), Typed<T>::p(kl), Typed<T>::p(vl), d_pos, 1, d.n_q_heads, d.n_kv_heads,
                                d.head_dim, Typed<T>::p(c->o), c->lse, s);
       HIP_TRY(c, hipGetLastError());
-      HIP_TRY(c, hipEventRecord(sg.done, s));
-      sg.used = true;
+      if (l == 0) {
+        HIP_TRY(c, hipEventRecord(sg.done, s));
+        sg.used = true;
+      }
       keep_status st = layer_back<T>(c, l, 1, c->o, x_cur, x_nxt, nullptr);
       if (st != KEEP_OK) return st;
       std::swap(x_cur, x_nxt);

@@ -341,12 +341,46 @@ size_t attn_mfma_scratch_bytes(int32_t max_rows, int32_t n_q_heads, int32_t n_kv
          (size_t)ATT_MAX_SLOTS * (PART_FLOATS + 256) * sizeof(float);
 }
 
+// The two launches, given a work list that is already in d_scratch.
+static void launch_attn_planned(const bf16_t* q, const bf16_t* k_cache, const bf16_t* v_cache, const int32_t* d_row_pos,
+                                const int32_t* d_row_lo, int32_t n_rows, int32_t n_total, int32_t n_q_heads,
+                                int32_t n_kv_heads, int32_t max_rows, void* d_scratch, int n_items, int n_splits,
+                                bf16_t* o, float* lse, hipStream_t s) {
+  const int rep = n_q_heads / n_kv_heads;
+  const int mt = att_max_tiles(max_rows, rep);
+  char* base = reinterpret_cast<char*>(d_scratch);
+  int4* d_items = reinterpret_cast<int4*>(base);
+  int4* d_splits = d_items + (mt + ATT_MAX_SLOTS);
+  size_t off = attn_mfma_stage_ints(max_rows, n_q_heads, n_kv_heads) * sizeof(int32_t);
+  off = (off + 255) & ~(size_t)255;
+  float* part_o = reinterpret_cast<float*>(base + off);
+  float* part_ml = part_o + (size_t)ATT_MAX_SLOTS * PART_FLOATS;
+  const size_t sh = (size_t)2 * ATT_BUF * sizeof(uint16_t);
+  static bool attr_set = false;
+  if (!attr_set) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_attn_mfma), hipFuncAttributeMaxDynamicSharedMemorySize,
+                              (int)sh);
+    attr_set = true;
+  }
+  const float scale_log2e = 1.4426950408889634f / sqrtf((float)DH);
+  hipLaunchKernelGGL(k_attn_mfma, dim3(n_items * n_kv_heads), dim3(256), sh, s, q, k_cache, v_cache, d_row_pos, d_row_lo,
+                     n_rows, n_total, n_q_heads, n_kv_heads, d_items, scale_log2e, o, lse, part_o, part_ml);
+  if (n_splits)
+    hipLaunchKernelGGL(k_attn_combine, dim3(n_splits * n_kv_heads, 16), dim3(256), 0, s, d_splits, part_o, part_ml,
+                       n_rows, n_q_heads, n_kv_heads, o, lse);
+}
+
 void launch_attn_mfma(const bf16_t* q, const bf16_t* k_cache, const bf16_t* v_cache, const int32_t* d_row_pos,
                       const int32_t* h_row_start, const int32_t* h_set_off, int32_t m, int32_t instr_off,
                       int32_t n_rows, int32_t n_total, int32_t n_q_heads, int32_t n_kv_heads, int32_t max_rows,
                       int32_t* h_stage, void* d_scratch, bf16_t* o, float* lse, hipStream_t s,
-                      const int32_t* h_row_lo, const int32_t* d_row_lo) {
+                      const int32_t* h_row_lo, const int32_t* d_row_lo, AttnPlan* plan) {
   if (n_rows <= 0) return;
+  if (plan && plan->valid) {  // same row layout as the launch that made the plan: the work list is on the device
+    launch_attn_planned(q, k_cache, v_cache, d_row_pos, d_row_lo, n_rows, n_total, n_q_heads, n_kv_heads, max_rows,
+                        d_scratch, plan->n_items, plan->n_splits, o, lse, s);
+    return;
+  }
   const int rep = n_q_heads / n_kv_heads;
   const int n_tiles = (n_rows * rep + 127) / 128;
   const int mt = att_max_tiles(max_rows, rep);
@@ -440,27 +474,16 @@ void launch_attn_mfma(const bf16_t* q, const bf16_t* k_cache, const bf16_t* v_ca
   char* base = reinterpret_cast<char*>(d_scratch);
   int4* d_items = reinterpret_cast<int4*>(base);
   int4* d_splits = d_items + (mt + ATT_MAX_SLOTS);
-  size_t off = attn_mfma_stage_ints(max_rows, n_q_heads, n_kv_heads) * sizeof(int32_t);
-  off = (off + 255) & ~(size_t)255;
-  float* part_o = reinterpret_cast<float*>(base + off);
-  float* part_ml = part_o + (size_t)ATT_MAX_SLOTS * PART_FLOATS;
   (void)hipMemcpyAsync(d_items, h_items, (size_t)n_items * sizeof(int4), hipMemcpyHostToDevice, s);
   if (n_splits)
     (void)hipMemcpyAsync(d_splits, h_splits, (size_t)n_splits * sizeof(int4), hipMemcpyHostToDevice, s);
-
-  const size_t sh = (size_t)2 * ATT_BUF * sizeof(uint16_t);
-  static bool attr_set = false;
-  if (!attr_set) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_attn_mfma), hipFuncAttributeMaxDynamicSharedMemorySize,
-                              (int)sh);
-    attr_set = true;
+  if (plan) {
+    plan->valid = true;
+    plan->n_items = n_items;
+    plan->n_splits = n_splits;
   }
-  const float scale_log2e = 1.4426950408889634f / sqrtf((float)DH);
-  hipLaunchKernelGGL(k_attn_mfma, dim3(n_items * n_kv_heads), dim3(256), sh, s, q, k_cache, v_cache, d_row_pos, d_row_lo, n_rows,
-                     n_total, n_q_heads, n_kv_heads, d_items, scale_log2e, o, lse, part_o, part_ml);
-  if (n_splits)
-    hipLaunchKernelGGL(k_attn_combine, dim3(n_splits * n_kv_heads, 16), dim3(256), 0, s, d_splits, part_o, part_ml, n_rows,
-                       n_q_heads, n_kv_heads, o, lse);
+  launch_attn_planned(q, k_cache, v_cache, d_row_pos, d_row_lo, n_rows, n_total, n_q_heads, n_kv_heads, max_rows,
+                      d_scratch, n_items, n_splits, o, lse, s);
 }
 
 }  // namespace keep

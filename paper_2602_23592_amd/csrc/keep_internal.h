@@ -143,11 +143,17 @@ void launch_gemm_skinny(const bf16_t* A, int32_t M, int32_t K, const GemmB& B, c
 // (attn_mfma_stage_ints), d_scratch: device bytes (attn_mfma_scratch_bytes).
 size_t attn_mfma_stage_ints(int32_t max_rows, int32_t n_q_heads, int32_t n_kv_heads);
 size_t attn_mfma_scratch_bytes(int32_t max_rows, int32_t n_q_heads, int32_t n_kv_heads);
+// A work list already uploaded to d_scratch: launches with the same row layout (the layers of one decode
+// step) pass the same AttnPlan and skip the planning and the upload after the first.
+struct AttnPlan {
+  bool valid = false;
+  int n_items = 0, n_splits = 0;
+};
 void launch_attn_mfma(const bf16_t* q, const bf16_t* k_cache, const bf16_t* v_cache, const int32_t* d_row_pos,
                       const int32_t* h_row_start, const int32_t* h_set_off, int32_t m, int32_t instr_off,
                       int32_t n_rows, int32_t n_total, int32_t n_q_heads, int32_t n_kv_heads, int32_t max_rows,
                       int32_t* h_stage, void* d_scratch, bf16_t* o, float* lse, hipStream_t s,
-                      const int32_t* h_row_lo = nullptr, const int32_t* d_row_lo = nullptr);
+                      const int32_t* h_row_lo = nullptr, const int32_t* d_row_lo = nullptr, AttnPlan* plan = nullptr);
 // h_row_lo / d_row_lo (host and device copies, both or neither): first key each row may see (default 0);
 // used where several units are cached in one pass, each attending to itself only.
 // group-score matrix S[(m+1), m] of the layer whose q / compact k / lse are given.
