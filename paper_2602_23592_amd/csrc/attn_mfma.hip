@@ -415,11 +415,11 @@ void launch_attn_mfma(const bf16_t* q, const bf16_t* k_cache, const bf16_t* v_ca
   // share of the work would leave the chip waiting for it at the end (instruction rows see the whole
   // cache while most recomputed memories sit early in the prompt), so such ranges are cut into chunks
   // of about that length (never below ATT_MIN_CHUNK key tiles); everything shorter runs whole.
-  // A launch with less work than 16 key tiles per slot (decoding: one row over the whole cache) is bound
-  // by memory latency per workgroup, not by the matrix cores: it is cut finer, into about 1024 items.
+  // A launch with less work than 16 key tiles per slot (decoding: one row over the whole cache) streams the
+  // cache once and is bound by memory: it is cut finer (down to 4 key tiles), still into one round of items.
   const bool small = total_steps * n_kv_heads < (long)ATT_MIN_CHUNK * ATT_SLOTS;
-  int chunk = small ? (int)std::max<long>(ATT_MIN_CHUNK_SMALL, (total_steps * n_kv_heads + 2 * ATT_SLOTS - 1) / (2 * ATT_SLOTS))
-                    : (int)std::max<long>(ATT_MIN_CHUNK, (total_steps * n_kv_heads + ATT_SLOTS - 1) / ATT_SLOTS);
+  int chunk = (int)std::max<long>(small ? ATT_MIN_CHUNK_SMALL : ATT_MIN_CHUNK,
+                                  (total_steps * n_kv_heads + ATT_SLOTS - 1) / ATT_SLOTS);
   for (;;) {
     long slots = 0;
     for (int t = 0; t < n_tiles; ++t) {
