@@ -457,14 +457,16 @@ keep_status layer_back(keep_ctx* c, int layer, int n, const void* o_rows, const 
 }
 
 // Score matrix of the layer whose q / k / lse are in the workspace, on stream s.
+// h_want (MFMA family only): flags of the source blocks whose rows of S are wanted, NULL = all.
 template <typename T>
-keep_status score_matrix(keep_ctx* c, int layer, const LayerPlan& plan, hipStream_t s) {
+keep_status score_matrix(keep_ctx* c, int layer, const LayerPlan& plan, hipStream_t s, const uint8_t* h_want = nullptr) {
   const keep_model_desc& d = c->d;
   if (plan.m == 0) return KEEP_OK;
   if (c->mfma) {
     launch_score_mfma(reinterpret_cast<const bf16_t*>(c->q), reinterpret_cast<const bf16_t*>(c->kc), c->lse,
                       plan.row_start.data(), c->d_row_start, plan.m, plan.n_rows, d.n_q_heads, d.n_kv_heads,
-                      c->stage[layer].score_tiles, c->score_scratch, d.max_tokens, std::max(1, d.max_groups), c->S, s);
+                      c->stage[layer].score_tiles, c->score_scratch, d.max_tokens, std::max(1, d.max_groups), c->S, s,
+                      h_want);
   } else {
     launch_score_rows_generic<T>(Typed<T>::p(c->q), Typed<T>::p(c->kc), c->lse, c->d_row_start, plan.m, plan.n_rows,
                                  d.n_q_heads, d.n_kv_heads, d.head_dim, c->score_scratch, s);
@@ -478,6 +480,7 @@ keep_status score_matrix(keep_ctx* c, int layer, const LayerPlan& plan, hipStrea
 // or none of the candidates.  Otherwise enqueues the selection on stream s and the
 // read-back of its result into c->h_sel_out; the caller waits and calls finish_select.
 enum SelectKind { SEL_ALL, SEL_NONE, SEL_DEVICE };
+constexpr int LAZY_MIN_CANDIDATES = 64;  // below this the whole score matrix is cheap
 SelectKind classify_budget(const PromptInfo& pi, const keep_prompt* p, const int32_t* groups, int m, float ratio,
                            int mode, int* k_count, int* tok_budget) {
   *k_count = budget_count(ratio, pi.G, m);
@@ -1208,6 +1211,8 @@ keep_status prefill_impl(keep_ctx* c, const keep_prompt* p, const float* ratios,
   bool x_from_embed = true;
   LayerPlan plan;
   int preload_layer = 2, preload_group = 0;  // cursor of the layer-balanced pre-loader
+  bool lazy = false;                          // this layer's scores are formed hop by hop
+  std::vector<uint8_t> want, have;
 
   if (host_kv) {  // what layer 0 needs must be there before it starts
     st = ld.copy_outside(0, cur);
@@ -1233,6 +1238,7 @@ keep_status prefill_impl(keep_ctx* c, const keep_prompt* p, const float* ratios,
       report->realign_rows[l] = plan.n_realign_rows;
     }
     const bool last = l + 1 == L;
+    lazy = false;
     const void* x_in = x_from_embed ? nullptr : x_cur;
     // ---- compute stream: everything up to attention
     st = by_dtype(c, [&](auto* tag) {
@@ -1249,12 +1255,23 @@ keep_status prefill_impl(keep_ctx* c, const keep_prompt* p, const float* ratios,
         HIP_TRY(c, hipEventRecord(c->ev_attn, c->s_comp));
         HIP_TRY(c, hipStreamWaitEvent(c->s_eval, c->ev_attn, 0));
         if (evs) HIP_TRY(c, hipEventRecord(evs[10], c->s_eval));
+        // With many candidates only a few rows of S are ever read: the query's, and those of the memories
+        // that enter a relevant set during the hops (Section 4.2: propagation averages the rows of the
+        // current relevant set).  They are computed hop by hop, as the sets become known; the other rows
+        // are never formed.  The selector re-runs hops 1..h each time, so the result is that of one run.
+        lazy = c->mfma && m >= LAZY_MIN_CANDIDATES && hops > 1;
+        if (lazy) {
+          want.assign((size_t)m + 1, 0);
+          have.assign((size_t)m + 1, 0);
+          want[m] = have[m] = 1;
+          HIP_TRY(c, hipMemsetAsync(c->S, 0, (size_t)(m + 1) * m * sizeof(float), c->s_eval));
+        }
         st = by_dtype(c, [&](auto* tag) {
           using T = std::remove_pointer_t<decltype(tag)>;
-          return score_matrix<T>(c, l, plan, c->s_eval);
+          return score_matrix<T>(c, l, plan, c->s_eval, lazy ? want.data() : nullptr);
         });
         if (st != KEEP_OK) return st;
-        st = enqueue_select(c, m, k_count, tok, budget_mode, hops, c->s_eval);
+        st = enqueue_select(c, m, k_count, tok, budget_mode, lazy ? 1 : hops, c->s_eval);
         if (st != KEEP_OK) return st;
         if (evs) HIP_TRY(c, hipEventRecord(evs[11], c->s_eval));
         HIP_TRY(c, hipEventRecord(c->ev_eval, c->s_eval));
@@ -1332,6 +1349,33 @@ keep_status prefill_impl(keep_ctx* c, const keep_prompt* p, const float* ratios,
         }
       }
       HIP_TRY(c, hipEventSynchronize(c->ev_eval));
+      if (lazy) {
+        std::vector<int32_t> prev_set;
+        for (int h = 1; h < hops; ++h) {
+          // the set repeated: converged (the selector would stop here as well)
+          std::vector<int32_t> this_set(c->h_sel_out + 2, c->h_sel_out + 2 + c->h_sel_out[0]);
+          if (c->h_sel_out[1] < h || (h > 1 && this_set == prev_set)) break;
+          prev_set.swap(this_set);
+          // rows of the memories selected at hop h that are not there yet
+          bool any = false;
+          std::fill(want.begin(), want.end(), 0);
+          for (int i = 0; i < c->h_sel_out[0]; ++i) {
+            const int a = c->h_sel_out[2 + i];
+            if (!have[a]) want[a] = have[a] = 1, any = true;
+          }
+          if (any) {
+            st = by_dtype(c, [&](auto* tag) {
+              using T = std::remove_pointer_t<decltype(tag)>;
+              return score_matrix<T>(c, l, plan, c->s_eval, want.data());
+            });
+            if (st != KEEP_OK) return st;
+          }
+          st = enqueue_select(c, m, k_count, tok, budget_mode, h + 1, c->s_eval);
+          if (st != KEEP_OK) return st;
+          if (evs) HIP_TRY(c, hipEventRecord(evs[11], c->s_eval));
+          HIP_TRY(c, hipStreamSynchronize(c->s_eval));
+        }
+      }
       nxt.clear();
       const int nn = c->h_sel_out[0];
       for (int i = 0; i < nn; ++i) nxt.push_back(cur[c->h_sel_out[2 + i]]);

@@ -164,7 +164,9 @@ size_t score_mfma_stage_ints(int32_t max_rows, int32_t max_groups);
 void launch_score_mfma(const bf16_t* q, const bf16_t* k_compact, const float* lse, const int32_t* h_row_start,
                        const int32_t* d_row_start, int32_t m, int32_t n_rows, int32_t n_q_heads, int32_t n_kv_heads,
                        int32_t* h_stage, void* d_scratch, int32_t max_rows, int32_t max_groups, float* S,
-                       hipStream_t s);
+                       hipStream_t s, const uint8_t* h_want = nullptr);
+// h_want: HOST [m + 1] flags or NULL: compute only the rows S[a, .] of the flagged source blocks (block m is
+// the instruction); the other rows of S are left untouched.
 
 // multi-hop selection on the device; d_out: [0] = n_next, [1] = hops_run, [2..] = slots kept (ascending)
 void launch_select(const float* S, int32_t m, const int32_t* d_cand_len, int32_t k_count, int32_t token_budget,

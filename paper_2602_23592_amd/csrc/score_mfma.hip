@@ -270,10 +270,12 @@ __global__ void __launch_bounds__(256)
 
 __global__ void k_score_finish_tiles(const float* __restrict__ rtmass, const int32_t* __restrict__ tile_start,
                                      const int32_t* __restrict__ row_start, int m, int n_q_heads,
-                                     float* __restrict__ S) {
+                                     float* __restrict__ S, int only_rows_with_tiles) {
   const int b = blockIdx.x * blockDim.x + threadIdx.x;
   const int a = blockIdx.y;
   if (b >= m) return;
+  // rows of blocks that were left out of this pass keep what an earlier pass wrote
+  if (only_rows_with_tiles && tile_start[a] == tile_start[a + 1]) return;
   float v = 0.f;
   if (b < a) {
     float sum = 0.f;
@@ -287,15 +289,20 @@ __global__ void k_score_finish_tiles(const float* __restrict__ rtmass, const int
 void launch_score_mfma(const bf16_t* q, const bf16_t* kc, const float* lse, const int32_t* h_row_start,
                        const int32_t* d_row_start, int32_t m, int32_t n_rows, int32_t n_q_heads, int32_t n_kv_heads,
                        int32_t* h_stage, void* d_scratch, int32_t max_rows, int32_t max_groups, float* S,
-                       hipStream_t s) {
+                       hipStream_t s, const uint8_t* h_want) {
   if (m <= 0) return;
   // row tiles: <= 32 rows, never across a block boundary; blocks 0..m-1 memories, m the instruction
   const int32_t cap = max_row_tiles(max_rows, max_groups);
   RowTile* ht = reinterpret_cast<RowTile*>(h_stage);
   int32_t* h_tile_start = h_stage + (size_t)cap * 3;
-  int n_rt = 0;
+  // h_want (NULL = every block): the source blocks a whose rows S[a, .] are wanted.  The other blocks get no
+  // row tiles and their rows of S are left as they are.  Everything that shapes the arithmetic (the slice
+  // count below) is derived from the full tile count, so a row comes out bit-identical either way.
+  int n_rt = 0, full_n_rt = 0;
   for (int a = 0; a <= m; ++a) {
     h_tile_start[a] = n_rt;
+    full_n_rt += (h_row_start[a + 1] - h_row_start[a] + 31) / 32;
+    if (h_want && !h_want[a]) continue;
     for (int t0 = h_row_start[a]; t0 < h_row_start[a + 1]; t0 += 32) {
       ht[n_rt].row0 = t0;
       ht[n_rt].nrows = std::min(32, h_row_start[a + 1] - t0);
@@ -304,6 +311,7 @@ void launch_score_mfma(const bf16_t* q, const bf16_t* kc, const float* lse, cons
     }
   }
   h_tile_start[m + 1] = n_rt;
+  if (n_rt == 0) return;
   char* base = reinterpret_cast<char*>(d_scratch);
   RowTile* d_tiles = reinterpret_cast<RowTile*>(base);
   int32_t* d_tile_start = reinterpret_cast<int32_t*>(base) + (size_t)cap * 3;
@@ -319,8 +327,8 @@ void launch_score_mfma(const bf16_t* q, const bf16_t* kc, const float* lse, cons
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)SDH);
   // KV-head slices: as many as it takes to have ~1024 workgroups, within the column-sum scratch
   int n_slices = 1;
-  const long base_blocks = (long)((n_rt + 3) / 4) * ((n_keys + S_CHUNK - 1) / S_CHUNK);
-  while (n_slices < n_kv_heads && base_blocks * n_slices < 1024 && (long)(2 * n_slices) * n_rt <= cap &&
+  const long base_blocks = (long)((full_n_rt + 3) / 4) * ((n_keys + S_CHUNK - 1) / S_CHUNK);
+  while (n_slices < n_kv_heads && base_blocks * n_slices < 1024 && (long)(2 * n_slices) * full_n_rt <= cap &&
          n_kv_heads % (2 * n_slices) == 0)
     n_slices *= 2;
   const int hk_per_slice = n_kv_heads / n_slices;
@@ -340,7 +348,7 @@ void launch_score_mfma(const bf16_t* q, const bf16_t* kc, const float* lse, cons
   hipLaunchKernelGGL(k_score_rt_reduce, dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, s, colmass, max_rows,
                      n_slices, d_tiles, n_rt, d_row_start, m, rtmass);
   hipLaunchKernelGGL(k_score_finish_tiles, dim3((m + 255) / 256, m + 1), dim3(256), 0, s, rtmass, d_tile_start,
-                     d_row_start, m, n_q_heads, S);
+                     d_row_start, m, n_q_heads, S, h_want ? 1 : 0);
 }
 
 }  // namespace keep

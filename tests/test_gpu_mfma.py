@@ -98,3 +98,35 @@ def test_mfma_prefill_end_to_end_teacher_forced_sets():
         assert max_rel(to_np(vc[l]), ref["v_hat"][l]) < TOL
     assert max_rel(to_np(xf), ref["x_final"]) < TOL
     assert overlap >= 0.75          # 4 of 8 groups kept: at most one near-tie may flip
+
+
+def test_prefill_with_many_candidates_selects_like_the_full_score_matrix():
+    """With 64 or more candidates keep_prefill forms only the rows of S that the hops read.  The sets must be
+    those of the selector run on the complete matrix (same device arithmetic row by row, so bit-exact), and
+    the caches those of the oracle teacher-forced to these sets."""
+    shape = _shape(2, 512, 8, 2, 1024)
+    rng = np.random.default_rng(31)
+    glen = [int(v) for v in rng.integers(8, 41, size=72)]
+    lq = 20
+    pb = Problem(shape, glen, lq, seed=9, std=0.05, bias=True)
+    ctx, pr = pb.context(), pb.prompt()
+    G = len(glen)
+    for hops, ratio in ((3, 0.15), (4, 0.3), (2, 0.05)):
+        ratios = [1.0, ratio]
+        kc, vc = pb.empty_cache()
+        xf = torch.empty((lq, shape.hidden), dtype=torch.bfloat16, device="cuda")
+        sets, rep = ctx.prefill(pr, ratios, hops, kc, vc, xf, want_report=True)
+        # the same layer through the two-call interface, which always forms the whole matrix
+        kc2, vc2 = pb.empty_cache(1)
+        x_out = torch.empty((pr.n_rows(list(range(G))), shape.hidden), dtype=torch.bfloat16, device="cuda")
+        ctx.recompute_layer(pr, 0, list(range(G)), None, x_out, kc2[0], vc2[0])
+        nxt, runs, S = ctx.score_groups(pr, 0, list(range(G)), ratio, hops)
+        torch.cuda.synchronize()
+        print("hops", hops, "ratio", ratio, "set", sets[1], "runs", rep.hops_run[0], runs)
+        assert sets[1] == nxt and rep.hops_run[0] == runs
+        want, want_runs = ko.select_multihop(S, list(range(G)), glen, ratio, hops)
+        assert nxt == want and runs == want_runs
+        ref = ko.keep_prefill(pb.sh, pb.layers, pb.embed, pb.ids, glen, lq, pb.kb, pb.vb, ratios, hops, forced_sets=sets)
+        for l in range(2):
+            assert max_rel(to_np(kc[l]), ref["k_hat"][l]) < TOL and max_rel(to_np(vc[l]), ref["v_hat"][l]) < TOL
+        assert max_rel(to_np(xf), ref["x_final"]) < TOL
