@@ -140,7 +140,7 @@ typedef struct {
  * the FFN, Section 4.2 "System advantage") and host->device loading (Section 5,
  * the three pipelined threads).  All must be at the default priority.
  * Errors: INVALID_ARG (NULL, non-positive sizes, n_q_heads not a multiple of
- * n_kv_heads, odd head_dim), SHAPE (head_dim > 256, n_layers > 128), HIP. */
+ * n_kv_heads, odd head_dim), SHAPE (head_dim > 256, n_layers > 128, max_groups > 6000), HIP. */
 keep_status keep_init(const keep_model_desc* desc, const keep_layer_weights* layers, const void* embed_table,
                       void* stream_compute, void* stream_eval, void* stream_copy, keep_ctx** out);
 

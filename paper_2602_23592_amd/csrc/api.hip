@@ -129,6 +129,10 @@ keep_status check_desc(const keep_model_desc* d, const char** why) {
     *why = "n_q_heads must be a multiple of n_kv_heads";
     return KEEP_ERR_INVALID_ARG;
   }
+  if (d->max_groups > 6000) {
+    *why = "max_groups above 6000 (the selector keeps its per-memory arrays in LDS)";
+    return KEEP_ERR_SHAPE;
+  }
   if (d->dtype != KEEP_F32 && d->dtype != KEEP_BF16) {
     *why = "dtype must be KEEP_F32 or KEEP_BF16";
     return KEEP_ERR_INVALID_ARG;

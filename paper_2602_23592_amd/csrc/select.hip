@@ -12,8 +12,8 @@ constexpr int SEL_THREADS = 1024;
 
 // rank every candidate by (importance descending, index ascending) and mark the
 // ones taken: the first k of the order (count mode) or a walk of the order that
-// takes a memory iff it still fits the token budget (token mode).
-__device__ void take(const float* imp, int m, const int32_t* cand_len, int k_count, int token_budget, int mode,
+// takes a memory iff it still fits the token budget (token mode).  All arrays in LDS.
+__device__ void take(const float* imp, int m, const int32_t* len, int k_count, int token_budget, int mode,
                      int32_t* order, int32_t* taken) {
   for (int b = threadIdx.x; b < m; b += SEL_THREADS) {
     const float v = imp[b];
@@ -31,37 +31,43 @@ __device__ void take(const float* imp, int m, const int32_t* cand_len, int k_cou
       int used = 0;
       for (int i = 0; i < m; ++i) {
         const int b = order[i];
-        const int fits = used + cand_len[b] <= token_budget;
+        const int fits = used + len[b] <= token_budget;
         taken[b] = fits;
-        if (fits) used += cand_len[b];
+        if (fits) used += len[b];
       }
     }
     __syncthreads();
   }
 }
 
+// The normalised score of (a, b) is S[a, b] / total_a with total_a the sum of row a in ascending order
+// (0 where the row is empty); it is formed where it is used, only the row totals are kept.
 __global__ void __launch_bounds__(SEL_THREADS)
     k_select(const float* __restrict__ S, int m, const int32_t* __restrict__ cand_len, int k_count, int token_budget,
              int mode, int hops, float* __restrict__ work, int32_t* __restrict__ iwork, int32_t* __restrict__ out) {
-  float* norm = work;                     // [(m+1) * m]
-  float* imp = work + (size_t)(m + 1) * m;  // [m]
-  float* imp2 = imp + m;                  // [m]
-  int32_t* order = iwork;                 // [m]
-  int32_t* rel = iwork + m;               // [m]
-  int32_t* rel2 = iwork + 2 * m;          // [m]
+  extern __shared__ float sel_smem[];
+  float* tot = sel_smem;                                   // [m + 1] row totals
+  float* imp = tot + (m + 1);                              // [m]
+  int32_t* order = reinterpret_cast<int32_t*>(imp + m);    // [m]
+  int32_t* rel = order + m;                                // [m]
+  int32_t* rel2 = rel + m;                                 // [m]
+  int32_t* len = rel2 + m;                                 // [m]
   __shared__ int s_same, s_cnt;
+  (void)work;
+  (void)iwork;
 
-  // row-normalise over the candidate targets
   for (int a = threadIdx.x; a <= m; a += SEL_THREADS) {
     const float* row = S + (size_t)a * m;
     float total = 0.f;
     for (int b = 0; b < m; ++b) total = total + row[b];
-    for (int b = 0; b < m; ++b) norm[(size_t)a * m + b] = total > 0.f ? row[b] / total : 0.f;
+    tot[a] = total;
   }
+  for (int b = threadIdx.x; b < m; b += SEL_THREADS) len[b] = cand_len[b];
   __syncthreads();
-  for (int b = threadIdx.x; b < m; b += SEL_THREADS) imp[b] = norm[(size_t)m * m + b];
+  const float tq = tot[m];
+  for (int b = threadIdx.x; b < m; b += SEL_THREADS) imp[b] = tq > 0.f ? S[(size_t)m * m + b] / tq : 0.f;
   __syncthreads();
-  take(imp, m, cand_len, k_count, token_budget, mode, order, rel);
+  take(imp, m, len, k_count, token_budget, mode, order, rel);
   int runs = 1;
   const int max_runs = hops > 1 ? hops : 1;
   while (runs < max_runs) {
@@ -73,13 +79,16 @@ __global__ void __launch_bounds__(SEL_THREADS)
     __syncthreads();
     const float denom = (float)(1 + s_cnt);
     for (int b = threadIdx.x; b < m; b += SEL_THREADS) {
-      float acc = norm[(size_t)m * m + b];
+      float acc = tq > 0.f ? S[(size_t)m * m + b] / tq : 0.f;
       for (int a = 0; a < m; ++a)
-        if (rel[a]) acc = acc + norm[(size_t)a * m + b];
-      imp2[b] = acc / denom;
+        if (rel[a]) {
+          const float ta = tot[a];
+          acc = acc + (ta > 0.f ? S[(size_t)a * m + b] / ta : 0.f);
+        }
+      imp[b] = acc / denom;
     }
     __syncthreads();
-    take(imp2, m, cand_len, k_count, token_budget, mode, order, rel2);
+    take(imp, m, len, k_count, token_budget, mode, order, rel2);
     ++runs;
     if (threadIdx.x == 0) {
       int same = 1;
@@ -104,7 +113,14 @@ __global__ void __launch_bounds__(SEL_THREADS)
 
 void launch_select(const float* S, int32_t m, const int32_t* d_cand_len, int32_t k_count, int32_t token_budget,
                    int32_t mode, int32_t hops, float* d_work, int32_t* d_iwork, int32_t* d_out, hipStream_t s) {
-  hipLaunchKernelGGL(k_select, dim3(1), dim3(SEL_THREADS), 0, s, S, m, d_cand_len, k_count, token_budget, mode, hops,
+  const size_t sh = ((size_t)(m + 1) + m) * sizeof(float) + (size_t)4 * m * sizeof(int32_t);  // <= 160 KB: m <= 6000
+  static bool attr_set = false;
+  if (!attr_set) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_select), hipFuncAttributeMaxDynamicSharedMemorySize,
+                              160 * 1024 - 256);
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(k_select, dim3(1), dim3(SEL_THREADS), sh, s, S, m, d_cand_len, k_count, token_budget, mode, hops,
                      d_work, d_iwork, d_out);
 }
 
