@@ -1263,7 +1263,14 @@ keep_status prefill_impl(keep_ctx* c, const keep_prompt* p, const float* ratios,
         // that enter a relevant set during the hops (Section 4.2: propagation averages the rows of the
         // current relevant set).  They are computed hop by hop, as the sets become known; the other rows
         // are never formed.  The selector re-runs hops 1..h each time, so the result is that of one run.
-        lazy = c->mfma && m >= LAZY_MIN_CANDIDATES && hops > 1;
+        // (worth it only where the budget keeps at most half of the candidates' rows: otherwise nearly every
+        // row is read anyway and the hop-by-hop round trips are pure overhead)
+        {
+          const long mem_rows = plan.n_rows - pi.Lq;
+          const long keep_rows = budget_mode == KEEP_BUDGET_TOKENS ? std::min<long>(tok, mem_rows)
+                                                                   : mem_rows * k_count / std::max(1, m);
+          lazy = c->mfma && m >= LAZY_MIN_CANDIDATES && hops > 1 && keep_rows * 2 <= mem_rows;
+        }
         if (lazy) {
           want.assign((size_t)m + 1, 0);
           have.assign((size_t)m + 1, 0);
