@@ -45,6 +45,10 @@ struct Staging {  // pinned host mirror of the small per-layer device arrays
 
 }  // namespace
 
+// Layout of the per-layer table block: three int arrays of G + 2, then G re-align segments (16-byte aligned).
+static inline size_t table_seg_offset_ints(size_t G) { return (3 * (G + 2) + 3) & ~(size_t)3; }
+static inline size_t table_block_bytes(size_t G) { return table_seg_offset_ints(G) * 4 + G * sizeof(keep::RealignSeg); }
+
 struct keep_ctx {
   keep_model_desc d;
   std::vector<keep_layer_weights> w;
@@ -357,12 +361,10 @@ keep_status stage_layer(keep_ctx* c, const keep_prompt* p, const PromptInfo& pi,
   plan->n_segs = ns;
   plan->n_realign_rows = rows;
   hipStream_t s = c->s_comp;
-  if (m > 0) {
-    HIP_TRY(c, hipMemcpyAsync(c->d_set_off, st.set_off, (size_t)m * 4, hipMemcpyHostToDevice, s));
-    HIP_TRY(c, hipMemcpyAsync(c->d_cand_len, st.cand_len, (size_t)m * 4, hipMemcpyHostToDevice, s));
-  }
-  HIP_TRY(c, hipMemcpyAsync(c->d_row_start, st.row_start, (size_t)(m + 2) * 4, hipMemcpyHostToDevice, s));
-  if (ns > 0) HIP_TRY(c, hipMemcpyAsync(c->d_segs, st.segs, (size_t)ns * sizeof(RealignSeg), hipMemcpyHostToDevice, s));
+  // one upload: the three int arrays and the segments that are in use
+  const size_t G_cap = (size_t)std::max(1, c->d.max_groups);
+  HIP_TRY(c, hipMemcpyAsync(c->d_set_off, st.set_off, table_seg_offset_ints(G_cap) * 4 + (size_t)ns * sizeof(RealignSeg),
+                            hipMemcpyHostToDevice, s));
   return KEEP_OK;
 }
 
@@ -652,14 +654,11 @@ keep_status keep_destroy(keep_ctx* c) {
   (void)hipStreamSynchronize(c->s_copy);
   for (void* p : c->allocs) (void)hipFree(p);
   for (Staging& st : c->stage) {
-    if (st.set_off) (void)hipHostFree(st.set_off);
-    if (st.row_start) (void)hipHostFree(st.row_start);
+    if (st.set_off) (void)hipHostFree(st.set_off);  // the block also holds cand_len, row_start and segs
     if (st.gather_src) (void)hipHostFree(st.gather_src);
     if (st.gather_dst) (void)hipHostFree(st.gather_dst);
-    if (st.cand_len) (void)hipHostFree(st.cand_len);
     if (st.score_tiles) (void)hipHostFree(st.score_tiles);
     if (st.attn_items) (void)hipHostFree(st.attn_items);
-    if (st.segs) (void)hipHostFree(st.segs);
     if (st.done) (void)hipEventDestroy(st.done);
   }
   if (c->h_sel_out) (void)hipHostFree(c->h_sel_out);
@@ -720,11 +719,11 @@ keep_status keep_init(const keep_model_desc* desc, const keep_layer_weights* lay
   TRY_INIT(dev_alloc(c, &c->d_token_ids, z.M * 4));
   TRY_INIT(dev_alloc(c, &c->d_row_pos, z.M * 4));
   TRY_INIT(dev_alloc(c, &c->d_row_slot, z.M * 4));
-  TRY_INIT(dev_alloc(c, &c->d_set_off, (z.G + 2) * 4));
-  TRY_INIT(dev_alloc(c, &c->d_row_start, (z.G + 2) * 4));
+  TRY_INIT(dev_alloc(c, &c->d_set_off, table_block_bytes(z.G)));
+  c->d_cand_len = c->d_set_off + (z.G + 2);
+  c->d_row_start = c->d_cand_len + (z.G + 2);
+  c->d_segs = reinterpret_cast<RealignSeg*>(c->d_set_off + table_seg_offset_ints(z.G));
   TRY_INIT(dev_alloc(c, &c->d_gather_src, (z.G + 2) * 4));
-  TRY_INIT(dev_alloc(c, &c->d_cand_len, (z.G + 2) * 4));
-  TRY_INIT(dev_alloc(c, &c->d_segs, z.G * sizeof(RealignSeg)));
   TRY_INIT(dev_alloc(c, &c->xa, z.M * z.d * z.esz));
   TRY_INIT(dev_alloc(c, &c->xb, z.M * z.d * z.esz));
   TRY_INIT(dev_alloc(c, &c->hbuf, z.M * z.d * z.esz));
@@ -768,16 +767,17 @@ keep_status keep_init(const keep_model_desc* desc, const keep_layer_weights* lay
   c->stage.resize(desc->n_layers);
   for (Staging& sg : c->stage) {
     sg = Staging{};
-    TRY_INIT(pin_alloc(c, &sg.set_off, (z.G + 2) * 4));
-    TRY_INIT(pin_alloc(c, &sg.row_start, (z.G + 2) * 4));
+    // set_off | cand_len | row_start | segs share one block, mirrored on the device: one upload per layer
+    TRY_INIT(pin_alloc(c, &sg.set_off, table_block_bytes(z.G)));
+    sg.cand_len = sg.set_off + (z.G + 2);
+    sg.row_start = sg.cand_len + (z.G + 2);
+    sg.segs = reinterpret_cast<RealignSeg*>(sg.set_off + table_seg_offset_ints(z.G));
     TRY_INIT(pin_alloc(c, &sg.gather_src, (z.G + 2) * 4));
     TRY_INIT(pin_alloc(c, &sg.gather_dst, (z.G + 2) * 4));
-    TRY_INIT(pin_alloc(c, &sg.cand_len, (z.G + 2) * 4));
     if (c->mfma) {
       TRY_INIT(pin_alloc(c, &sg.score_tiles, score_mfma_stage_ints((int32_t)z.M, (int32_t)z.G) * 4));
       TRY_INIT(pin_alloc(c, &sg.attn_items, attn_mfma_stage_ints((int32_t)z.M, desc->n_q_heads, desc->n_kv_heads) * 4));
     }
-    TRY_INIT(pin_alloc(c, &sg.segs, z.G * sizeof(RealignSeg)));
     auto mk = [&]() -> keep_status {
       HIP_TRY(c, hipEventCreateWithFlags(&sg.done, hipEventDisableTiming));
       return KEEP_OK;

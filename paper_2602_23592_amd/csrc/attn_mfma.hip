@@ -474,9 +474,11 @@ void launch_attn_mfma(const bf16_t* q, const bf16_t* k_cache, const bf16_t* v_ca
   char* base = reinterpret_cast<char*>(d_scratch);
   int4* d_items = reinterpret_cast<int4*>(base);
   int4* d_splits = d_items + (mt + ATT_MAX_SLOTS);
-  (void)hipMemcpyAsync(d_items, h_items, (size_t)n_items * sizeof(int4), hipMemcpyHostToDevice, s);
-  if (n_splits)
-    (void)hipMemcpyAsync(d_splits, h_splits, (size_t)n_splits * sizeof(int4), hipMemcpyHostToDevice, s);
+  // one upload: the item list, or (when tiles were cut) everything up to the end of the split list, which
+  // sits behind the item area in both buffers
+  (void)d_splits;
+  const size_t up_bytes = n_splits ? ((size_t)(mt + ATT_MAX_SLOTS) + n_splits) * sizeof(int4) : (size_t)n_items * sizeof(int4);
+  (void)hipMemcpyAsync(d_items, h_items, up_bytes, hipMemcpyHostToDevice, s);
   if (plan) {
     plan->valid = true;
     plan->n_items = n_items;
