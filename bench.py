@@ -203,8 +203,8 @@ def visible_keys(sets, glen, lq):
 def cpu_baseline(w, glen, rows_per_layer, n_tokens):
     """The CPU oracle as it stands, timed on a bounded sample: one selective layer of this
     workload (layer 1, seeded random set of the layer's budget, random-draw caches and
-    hidden rows), K/V refresh of all its rows, attention + projections + FFN of 128 and of
-    256 sampled rows.  Whole-prefill tokens/s is extrapolated by row count."""
+    hidden rows), K/V refresh of all its rows, attention + projections + FFN of 256 and of
+    768 sampled rows.  Whole-prefill tokens/s is extrapolated by row count."""
     import keep_synth as ks
     from oracle import keep_oracle as ko
     s = w.shape
@@ -231,14 +231,14 @@ def cpu_baseline(w, glen, rows_per_layer, n_tokens):
     n_l = sum(glist[g] for g in groups) + w.instr_len
     x = ks.to_numpy_f64(ks.make_random_rows(n_l, s.hidden, s.storage, seed=11))
     times = []
-    for n_s in (128, 256):
+    for n_s in (256, 768):
         pick = np.sort(rng.choice(n_l, size=min(n_s, n_l), replace=False))
         t0 = time.perf_counter()
         ko.selective_layer(sh, lw, x, groups, glist, w.instr_len, kh.copy(), vh.copy(), want_scores=False,
                            only_rows=pick)
         times.append(time.perf_counter() - t0)
-    per_row = max((times[1] - times[0]) / 128.0, 1e-9)
-    fixed = max(times[0] - 128 * per_row, 0.0)
+    per_row = max((times[1] - times[0]) / 512.0, 1e-9)
+    fixed = max(times[0] - 256 * per_row, 0.0)
     row_cost = per_row + fixed / n_l
     total_rows = int(np.sum(rows_per_layer))
     est = total_rows * row_cost
@@ -246,7 +246,7 @@ def cpu_baseline(w, glen, rows_per_layer, n_tokens):
     threads = int(os.environ.get("OMP_NUM_THREADS", cores))
     return {"value": n_tokens / est, "unit": "tokens/s", "cores": min(cores, threads), "kind": "oracle",
             "sample": "oracle selective_layer, layer 1 of %d, %d rows over the %d-token cache: K/V refresh of all rows "
-                      "+ attention/FFN of 128 and 256 sampled rows (%.1f s + %.1f s); whole prefill extrapolated by "
+                      "+ attention/FFN of 256 and 768 sampled rows (%.1f s + %.1f s); whole prefill extrapolated by "
                       "row count (%d rows over all layers)" % (s.n_layers, n_l, n_tokens, times[0], times[1], total_rows),
             "seconds": times[0] + times[1], "extrapolated": True}
 
@@ -401,8 +401,8 @@ def main():
     default_run = (a.workload == "qwen14b_32k" and a.schedule is None and a.ratio is None and a.budget is None
                    and not a.random_cache and a.sparse_rows == 0)
     traffic = GATE_UP_TRAFFIC_BYTES_PER_LAUNCH if default_run else None
-    roofline = {"kernel": "k_gemm_mfma<...,SWIGLU> (gate/up projection with fused SiLU*mul; 256x256 tiles, "
-                          "128x128 for launches of fewer than 1024 such tiles)",
+    roofline = {"kernel": "k_gemm_mfma<256,256,...,SWIGLU> + k_gemm_fixup (gate/up projection with fused SiLU*mul; "
+                          "256x256 tiles, the last partly filled round cut along K)",
                 "bound": "mfma", "achieved": gu["achieved"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                 "frac": gu["frac"], "traffic": traffic,
                 "avg_launch_ms": round(gu["ms_per_step"] / n_launch, 4), "launches_per_step": n_launch}
