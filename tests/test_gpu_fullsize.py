@@ -118,3 +118,47 @@ def test_decode_attention_over_the_full_cache_matches_oracle():
         assert e < 2e-2
     assert np.abs(kd[0, n_ctx].cpu().double().numpy() - kr[0][n_ctx]).max() / np.abs(kr[0][n_ctx]).max() < 2e-2
     assert np.abs(vd[0, n_ctx].cpu().double().numpy() - vr[0][n_ctx]).max() / np.abs(vr[0][n_ctx]).max() < 2e-2
+
+
+def test_fullsize_prefill_layer0_selection_equals_full_matrix_selection():
+    """The bench workload's layer 0 -> 1 decision at full size (272 candidates, 33 024 rows, token budget,
+    3 hops), where keep_prefill forms the score rows hop by hop: the set must be the one the selector gives
+    on the complete score matrix of the same layer (keep_recompute_layer + keep_score_groups), which in turn
+    must be the oracle's selection applied to that matrix."""
+    from paper_2602_23592_amd import KeepContext, KeepPrompt
+    from paper_2602_23592_amd.binding import KEEP_BUDGET_TOKENS
+    w = ks.workload("qwen14b_32k")
+    s = w.shape
+    two = ks.ModelShape(2, s.hidden, s.n_q_heads, s.n_kv_heads, s.head_dim, s.ffn_dim, 4099, s.rope_theta,
+                        s.rms_eps, s.storage)
+    glen, kinds = ks.group_lengths(w)
+    glist = [int(v) for v in glen]
+    G, lq = len(glist), w.instr_len
+    n_tokens = w.mem_tokens + lq
+    dev = "cuda"
+    layers = [ks.make_layer_weights(two, l, dev) for l in range(2)]
+    embed = ks.make_embedding(two, dev)
+    ids = ks.make_token_ids(n_tokens, two.vocab, 0)
+    ctx = KeepContext(two, layers, embed, n_tokens, G)
+    assert ctx.uses_mfma
+    kb = torch.empty((2, w.mem_tokens, s.n_kv_heads, s.head_dim), dtype=torch.bfloat16, device=dev)
+    vb = torch.empty_like(kb)
+    ctx.precompute_groups(glist, ids[:w.mem_tokens], kb, vb)          # group caches by the library's own dense path
+    off = np.concatenate([[0], np.cumsum(glist)]).astype(np.int64)
+    k_blocks = [[kb[l, off[g]:off[g + 1]] for g in range(G)] for l in range(2)]
+    v_blocks = [[vb[l, off[g]:off[g + 1]] for g in range(G)] for l in range(2)]
+    pr = KeepPrompt(glist, lq, ids, k_blocks, v_blocks, 2, group_kind=kinds)
+    ratio1 = float(ks.ratio_schedule(w.ratio, s.n_layers, w.schedule)[1])
+    kc = torch.empty((2, n_tokens, s.n_kv_heads, s.head_dim), dtype=torch.bfloat16, device=dev)
+    vc = torch.empty_like(kc)
+    xf = torch.empty((lq, s.hidden), dtype=torch.bfloat16, device=dev)
+    sets, rep = ctx.prefill(pr, [1.0, ratio1], w.hops, kc, vc, xf, KEEP_BUDGET_TOKENS, want_report=True)
+    x_out = torch.empty((n_tokens, s.hidden), dtype=torch.bfloat16, device=dev)
+    ctx.recompute_layer(pr, 0, list(range(G)), None, x_out, kc[0], vc[0])
+    nxt, runs, S = ctx.score_groups(pr, 0, list(range(G)), ratio1, w.hops, KEEP_BUDGET_TOKENS)
+    torch.cuda.synchronize()
+    print("full size layer 0 -> 1: set", sets[1], "hops run", rep.hops_run[0], "| full matrix:", nxt, runs)
+    assert sets[1] == nxt and rep.hops_run[0] == runs
+    want, want_runs = ko.select_multihop(S, list(range(G)), glist, ratio1, w.hops, ko.BUDGET_TOKENS)
+    assert nxt == want and runs == want_runs
+    assert rep.ffn_rows[0] == sum(glist[g] for g in nxt) + lq       # evaluation went first: FFN on the survivors only
