@@ -359,7 +359,10 @@ def main():
     rows = np.array([reports[-1].rows[l] for l in range(L)], dtype=np.float64)
     re_rows = np.array([reports[-1].realign_rows[l] for l in range(L)], dtype=np.float64)
     ffn_rows = np.array([reports[-1].ffn_rows[l] for l in range(L)], dtype=np.float64)
-    vis = np.array(visible_keys(sets, glen, lq), dtype=np.float64)
+    # keys seen by the rows the attention actually ran on (at an evaluation-first layer only the rows whose
+    # scores or outputs are read are attended)
+    vis = np.array([reports[-1].attn_keys[l] for l in range(L)], dtype=np.float64)
+    attn_rows = [int(reports[-1].attn_rows[l]) for l in range(L)]
 
     def mean_ms(name):
         return np.mean([[getattr(r, name)[l] for l in range(L)] for r in reports], axis=0)
@@ -418,7 +421,7 @@ def main():
                                % (w.name, L, s.hidden, s.n_q_heads, s.n_kv_heads, s.head_dim, s.ffn_dim, n_tokens, G,
                                   w.mem_tokens, lq, w.ratio, budget, sched, w.hops, w.kv_location),
                    "rows_per_layer_mean": round(float(np.mean(rows[1:])) if L > 1 else float(rows[0]), 1),
-                   "rows_layer0": int(rows[0]), "ffn_rows_layer0": int(ffn_rows[0]), "set_sizes": [len(x) for x in sets],
+                   "attn_rows_layer0": attn_rows[0], "rows_layer0": int(rows[0]), "ffn_rows_layer0": int(ffn_rows[0]), "set_sizes": [len(x) for x in sets],
                    "group_caches": "random draws" if a.random_cache else "library dense prefill of each group alone",
                    "load_mode": a.load_mode, "setup_s": round(t_setup, 1)},
         "roofline": roofline,

@@ -64,7 +64,8 @@ _REPORT_MS = ("ms_realign", "ms_prep", "ms_qkv_gemm", "ms_rope", "ms_attn", "ms_
 class Report(C.Structure):
     _fields_ = ([("n_layers", C.c_int32), ("used_mfma", C.c_int32), ("ms_total", C.c_float),
                  ("rows", C.c_int32 * _L), ("set_size", C.c_int32 * _L), ("hops_run", C.c_int32 * _L),
-                 ("realign_rows", C.c_int32 * _L), ("ffn_rows", C.c_int32 * _L)]
+                 ("realign_rows", C.c_int32 * _L), ("ffn_rows", C.c_int32 * _L),
+                 ("attn_rows", C.c_int32 * _L), ("attn_keys", C.c_uint64 * _L)]
                 + [(_n, C.c_float * _L) for _n in _REPORT_MS]
                 + [("bytes_loaded", C.c_uint64 * _L)])
 

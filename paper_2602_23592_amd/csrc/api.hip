@@ -73,6 +73,9 @@ struct keep_ctx {
   // pinned host
   std::vector<Staging> stage;       // one slot per layer
   int32_t* h_sel_out = nullptr;     // [max_groups + 2]
+  int32_t* h_row_list = nullptr;    // pinned [max_tokens]: rows of an attention launch on part of a layer
+  int32_t* d_row_list = nullptr;
+  hipEvent_t ev_part[16] = {};      // begin / end pairs of such launches (timing)
   int32_t* h_row_lo = nullptr;      // pinned [max_tokens]: first visible key per row (batched unit caching)
   int32_t* d_row_lo = nullptr;
   bool units_mode = false;          // rows attend only from their unit's first row on
@@ -215,7 +218,7 @@ uint64_t workspace_bytes(const keep_model_desc* d) {
   t += align256(((z.G + 1) * z.G + 2 * z.G) * sizeof(float));          // sel_work
   t += align256(4 * z.G * sizeof(int32_t)) + align256((z.G + 2) * sizeof(int32_t));
   t += align256(4 * KEEP_DECODE_MAX_TOKENS * 4) + align256((size_t)d->vocab * sizeof(float));  // decode
-  t += align256(z.M * sizeof(int32_t));                                // row_lo
+  t += 2 * align256(z.M * sizeof(int32_t));                            // row_lo, row_list
   return t;
 }
 
@@ -371,7 +374,7 @@ keep_status stage_layer(keep_ctx* c, const keep_prompt* p, const PromptInfo& pi,
 // Steps of one layer on the compute stream, up to and including attention.
 template <typename T>
 keep_status layer_front(keep_ctx* c, const PromptInfo& pi, int layer, const LayerPlan& plan, const void* x_in,
-                        void* k_cache_l, void* v_cache_l, hipEvent_t* evs) {
+                        void* k_cache_l, void* v_cache_l, hipEvent_t* evs, bool skip_attention = false) {
   const keep_model_desc& d = c->d;
   const keep_layer_weights& w = c->w[layer];
   hipStream_t s = c->s_comp;
@@ -406,6 +409,11 @@ keep_status layer_front(keep_ctx* c, const PromptInfo& pi, int layer, const Laye
                          Typed<T>::p(c->kc), Typed<T>::p(k_cache_l), Typed<T>::p(v_cache_l), s,
                          c->units_mode ? c->d_row_lo : nullptr);
   if (evs) HIP_TRY(c, hipEventRecord(evs[4], s));
+  if (skip_attention) {  // the caller attends the rows as they turn out to be needed
+    if (evs) HIP_TRY(c, hipEventRecord(evs[5], s));
+    HIP_TRY(c, hipGetLastError());
+    return KEEP_OK;
+  }
   if (c->mfma)
     launch_attn_mfma(reinterpret_cast<const bf16_t*>(c->q), reinterpret_cast<const bf16_t*>(k_cache_l),
                      reinterpret_cast<const bf16_t*>(v_cache_l), c->d_row_pos, plan.row_start.data(),
@@ -417,6 +425,38 @@ keep_status layer_front(keep_ctx* c, const PromptInfo& pi, int layer, const Laye
                            d.n_q_heads, d.n_kv_heads, d.head_dim, Typed<T>::p(c->o), c->lse, s,
                            c->units_mode ? c->d_row_lo : nullptr);
   if (evs) HIP_TRY(c, hipEventRecord(evs[5], s));
+  HIP_TRY(c, hipGetLastError());
+  return KEEP_OK;
+}
+
+// Attention of the rows of the flagged blocks only (blocks 0..m-1 the layer's memories, m the instruction),
+// on the compute stream; MFMA family.  The caller has made sure that no earlier upload from h_row_list is
+// still pending.  rows_out / keys_out: how many rows were attended and how many keys they see in all.
+keep_status attend_blocks(keep_ctx* c, const PromptInfo& pi, int layer, const LayerPlan& plan, const uint8_t* flags,
+                          void* k_cache_l, void* v_cache_l, hipEvent_t ev_begin, hipEvent_t ev_end, int* rows_out,
+                          uint64_t* keys_out) {
+  const keep_model_desc& d = c->d;
+  hipStream_t s = c->s_comp;
+  int n = 0;
+  uint64_t keys = 0;
+  for (int a = 0; a <= plan.m; ++a)
+    if (flags[a]) {
+      const int64_t first = a < plan.m ? c->stage[layer].set_off[a] : pi.n_mem;  // position of the block's first row
+      const int64_t len = plan.row_start[a + 1] - plan.row_start[a];
+      keys += (uint64_t)(len * (2 * first + len + 1) / 2);
+      for (int r = plan.row_start[a]; r < plan.row_start[a + 1]; ++r) c->h_row_list[n++] = r;
+    }
+  *rows_out = n;
+  *keys_out = keys;
+  if (n == 0) return KEEP_OK;
+  HIP_TRY(c, hipMemcpyAsync(c->d_row_list, c->h_row_list, (size_t)n * 4, hipMemcpyHostToDevice, s));
+  if (ev_begin) HIP_TRY(c, hipEventRecord(ev_begin, s));
+  launch_attn_mfma(reinterpret_cast<const bf16_t*>(c->q), reinterpret_cast<const bf16_t*>(k_cache_l),
+                   reinterpret_cast<const bf16_t*>(v_cache_l), c->d_row_pos, plan.row_start.data(),
+                   c->stage[layer].set_off, plan.m, pi.n_mem, plan.n_rows, pi.N, d.n_q_heads, d.n_kv_heads, d.max_tokens,
+                   c->stage[layer].attn_items, c->attn_scratch, reinterpret_cast<bf16_t*>(c->o), c->lse, s, nullptr,
+                   nullptr, nullptr, c->h_row_list, c->d_row_list, n);
+  if (ev_end) HIP_TRY(c, hipEventRecord(ev_end, s));
   HIP_TRY(c, hipGetLastError());
   return KEEP_OK;
 }
@@ -664,6 +704,9 @@ keep_status keep_destroy(keep_ctx* c) {
   if (c->h_sel_out) (void)hipHostFree(c->h_sel_out);
   if (c->h_dec) (void)hipHostFree(c->h_dec);
   if (c->h_row_lo) (void)hipHostFree(c->h_row_lo);
+  if (c->h_row_list) (void)hipHostFree(c->h_row_list);
+  for (hipEvent_t e : c->ev_part)
+    if (e) (void)hipEventDestroy(e);
   if (c->h_S) (void)hipHostFree(c->h_S);
   if (c->h_token_ids) (void)hipHostFree(c->h_token_ids);
   for (hipEvent_t e : c->ev) (void)hipEventDestroy(e);
@@ -787,6 +830,15 @@ keep_status keep_init(const keep_model_desc* desc, const keep_layer_weights* lay
   TRY_INIT(pin_alloc(c, &c->h_sel_out, (z.G + 2) * 4));
   TRY_INIT(pin_alloc(c, &c->h_dec, 4 * KEEP_DECODE_MAX_TOKENS * 4));
   TRY_INIT(pin_alloc(c, &c->h_row_lo, z.M * 4));
+  TRY_INIT(pin_alloc(c, &c->h_row_list, z.M * 4));
+  TRY_INIT(dev_alloc(c, &c->d_row_list, z.M * 4));
+  {
+    auto mk = [&]() -> keep_status {
+      for (hipEvent_t& e : c->ev_part) HIP_TRY(c, hipEventCreate(&e));
+      return KEEP_OK;
+    };
+    TRY_INIT(mk());
+  }
   TRY_INIT(dev_alloc(c, &c->d_row_lo, z.M * 4));
   TRY_INIT(dev_alloc(c, &c->d_dec, 4 * KEEP_DECODE_MAX_TOKENS * 4));
   TRY_INIT(dev_alloc(c, &c->dec_logits, (size_t)desc->vocab * sizeof(float)));
@@ -1216,6 +1268,7 @@ keep_status prefill_impl(keep_ctx* c, const keep_prompt* p, const float* ratios,
   LayerPlan plan;
   int preload_layer = 2, preload_group = 0;  // cursor of the layer-balanced pre-loader
   bool lazy = false;                          // this layer's scores are formed hop by hop
+  std::vector<float> part_attn_ms((size_t)L, 0.f);  // attention launches on parts of a layer
   std::vector<uint8_t> want, have;
 
   if (host_kv) {  // what layer 0 needs must be there before it starts
@@ -1244,61 +1297,86 @@ keep_status prefill_impl(keep_ctx* c, const keep_prompt* p, const float* ratios,
     const bool last = l + 1 == L;
     lazy = false;
     const void* x_in = x_from_embed ? nullptr : x_cur;
-    // ---- compute stream: everything up to attention
-    st = by_dtype(c, [&](auto* tag) {
-      using T = std::remove_pointer_t<decltype(tag)>;
-      return layer_front<T>(c, pi, l, plan, x_in, kl, vl, evs);
-    });
-    if (st != KEEP_OK) return st;
-    // ---- eval stream: scores + selection beside the FFN
+    // ---- what the budget of the next layer implies for this one
     int k_count = 0, tok = 0;
     SelectKind kind = SEL_NONE;
+    // Output projection + FFN normally run beside the evaluation (Section 4.2).  When the budget says that at
+    // most half of this layer's rows survive into the next set, evaluation goes first and they run on the
+    // surviving rows only: the hidden rows of dropped memories are discarded anyway (Section 4.3).
+    bool eval_first = false;
+    // With many candidates only a few rows of S are ever read: the query's, and those of the memories that
+    // enter a relevant set during the hops (Section 4.2: propagation averages the rows of the current
+    // relevant set).  They are computed hop by hop, as the sets become known; the other rows are never
+    // formed.  The selector re-runs hops 1..h each time, so the result is that of one run.  (Worth it only
+    // where the budget keeps at most half of the candidates' rows: otherwise nearly every row is read anyway
+    // and the hop-by-hop round trips are pure overhead.)
+    // Where both hold, the attention itself is needed only for the rows whose scores are read and for the
+    // rows that survive: it is run for the instruction first and for each hop's new memories after that.
+    bool lazy_attn = false;
     if (!last) {
       kind = classify_budget(pi, p, cur.data(), m, ratios[l + 1], budget_mode, &k_count, &tok);
       if (kind == SEL_DEVICE) {
-        HIP_TRY(c, hipEventRecord(c->ev_attn, c->s_comp));
-        HIP_TRY(c, hipStreamWaitEvent(c->s_eval, c->ev_attn, 0));
-        if (evs) HIP_TRY(c, hipEventRecord(evs[10], c->s_eval));
-        // With many candidates only a few rows of S are ever read: the query's, and those of the memories
-        // that enter a relevant set during the hops (Section 4.2: propagation averages the rows of the
-        // current relevant set).  They are computed hop by hop, as the sets become known; the other rows
-        // are never formed.  The selector re-runs hops 1..h each time, so the result is that of one run.
-        // (worth it only where the budget keeps at most half of the candidates' rows: otherwise nearly every
-        // row is read anyway and the hop-by-hop round trips are pure overhead)
-        {
-          const long mem_rows = plan.n_rows - pi.Lq;
-          const long keep_rows = budget_mode == KEEP_BUDGET_TOKENS ? std::min<long>(tok, mem_rows)
-                                                                   : mem_rows * k_count / std::max(1, m);
-          lazy = c->mfma && m >= LAZY_MIN_CANDIDATES && hops > 1 && keep_rows * 2 <= mem_rows;
-        }
-        if (lazy) {
-          want.assign((size_t)m + 1, 0);
-          have.assign((size_t)m + 1, 0);
-          want[m] = have[m] = 1;
-          HIP_TRY(c, hipMemsetAsync(c->S, 0, (size_t)(m + 1) * m * sizeof(float), c->s_eval));
-        }
-        st = by_dtype(c, [&](auto* tag) {
-          using T = std::remove_pointer_t<decltype(tag)>;
-          return score_matrix<T>(c, l, plan, c->s_eval, lazy ? want.data() : nullptr);
-        });
-        if (st != KEEP_OK) return st;
-        st = enqueue_select(c, m, k_count, tok, budget_mode, lazy ? 1 : hops, c->s_eval);
-        if (st != KEEP_OK) return st;
-        if (evs) HIP_TRY(c, hipEventRecord(evs[11], c->s_eval));
-        HIP_TRY(c, hipEventRecord(c->ev_eval, c->s_eval));
+        const long mem_rows = plan.n_rows - pi.Lq;
+        const long keep_rows = budget_mode == KEEP_BUDGET_TOKENS ? std::min<long>(tok, mem_rows)
+                                                                 : mem_rows * k_count / std::max(1, m);
+        eval_first = (keep_rows + pi.Lq) * 2 <= plan.n_rows;
+        lazy = c->mfma && m >= LAZY_MIN_CANDIDATES && hops > 1 && keep_rows * 2 <= mem_rows;
+        lazy_attn = lazy && eval_first;
       }
     }
-    // ---- compute stream: output projection + FFN.
-    // Normally they run now, beside the evaluation (Section 4.2).  When the budget says that at most half
-    // of this layer's rows survive into the next set, evaluation goes first and the output projection
-    // and FFN then run on the surviving rows only: the hidden rows of dropped memories are discarded
-    // anyway (Section 4.3), so the result is the same.
-    bool eval_first = false;
+    int part_launches = 0;  // attention launches on parts of the layer (timed with c->ev_part)
+    long attn_rows = plan.n_rows;
+    uint64_t attn_keys = (uint64_t)((int64_t)pi.Lq * (2 * (int64_t)pi.n_mem + pi.Lq + 1) / 2);
+    for (int i = 0; i < m; ++i) {
+      const int64_t first = pi.off[cur[i]], len = p->group_len[cur[i]];
+      attn_keys += (uint64_t)(len * (2 * first + len + 1) / 2);
+    }
+    // ---- compute stream: everything up to attention
+    st = by_dtype(c, [&](auto* tag) {
+      using T = std::remove_pointer_t<decltype(tag)>;
+      return layer_front<T>(c, pi, l, plan, x_in, kl, vl, evs, lazy_attn);
+    });
+    if (st != KEEP_OK) return st;
+    auto attend = [&](const uint8_t* flags) -> keep_status {
+      int n_att = 0;
+      uint64_t n_keys = 0;
+      const int slot = std::min(part_launches, 7);
+      keep_status s2 = attend_blocks(c, pi, l, plan, flags, kl, vl, evs ? c->ev_part[2 * slot] : nullptr,
+                                     evs ? c->ev_part[2 * slot + 1] : nullptr, &n_att, &n_keys);
+      if (s2 != KEEP_OK) return s2;
+      if (n_att > 0) {
+        attn_rows += n_att;
+        attn_keys += n_keys;
+        if (part_launches < 8) ++part_launches;
+      }
+      return KEEP_OK;
+    };
+    // ---- eval stream: scores + selection
     if (kind == SEL_DEVICE) {
-      const long mem_rows = plan.n_rows - pi.Lq;
-      const long bound = budget_mode == KEEP_BUDGET_TOKENS ? std::min<long>(tok, mem_rows) + pi.Lq
-                                                            : mem_rows * k_count / std::max(1, m) + pi.Lq;
-      eval_first = bound * 2 <= plan.n_rows;
+      if (lazy) {
+        want.assign((size_t)m + 1, 0);
+        have.assign((size_t)m + 1, 0);
+        want[m] = have[m] = 1;
+      }
+      if (lazy_attn) {
+        attn_rows = 0;
+        attn_keys = 0;
+        st = attend(want.data());  // the instruction's rows
+        if (st != KEEP_OK) return st;
+      }
+      HIP_TRY(c, hipEventRecord(c->ev_attn, c->s_comp));
+      HIP_TRY(c, hipStreamWaitEvent(c->s_eval, c->ev_attn, 0));
+      if (evs) HIP_TRY(c, hipEventRecord(evs[10], c->s_eval));
+      if (lazy) HIP_TRY(c, hipMemsetAsync(c->S, 0, (size_t)(m + 1) * m * sizeof(float), c->s_eval));
+      st = by_dtype(c, [&](auto* tag) {
+        using T = std::remove_pointer_t<decltype(tag)>;
+        return score_matrix<T>(c, l, plan, c->s_eval, lazy ? want.data() : nullptr);
+      });
+      if (st != KEEP_OK) return st;
+      st = enqueue_select(c, m, k_count, tok, budget_mode, lazy ? 1 : hops, c->s_eval);
+      if (st != KEEP_OK) return st;
+      if (evs) HIP_TRY(c, hipEventRecord(evs[11], c->s_eval));
+      HIP_TRY(c, hipEventRecord(c->ev_eval, c->s_eval));
     }
     auto finish_layer = [&](int n_rows_back, const void* o_rows, const void* x_in_back, void* x_out_back) {
       keep_status s2 = by_dtype(c, [&](auto* tag) {
@@ -1315,6 +1393,10 @@ keep_status prefill_impl(keep_ctx* c, const keep_prompt* p, const float* ratios,
     if (!eval_first) {
       st = finish_layer(plan.n_rows, c->o, x_cur, x_nxt);
       if (st != KEEP_OK) return st;
+    }
+    if (report && !lazy_attn) {
+      report->attn_rows[l] = (int32_t)attn_rows;
+      report->attn_keys[l] = attn_keys;
     }
     if (last) break;
 
@@ -1375,6 +1457,12 @@ keep_status prefill_impl(keep_ctx* c, const keep_prompt* p, const float* ratios,
             if (!have[a]) want[a] = have[a] = 1, any = true;
           }
           if (any) {
+            if (lazy_attn) {  // their attention first: the scores need its log-sum-exp
+              st = attend(want.data());
+              if (st != KEEP_OK) return st;
+              HIP_TRY(c, hipEventRecord(c->ev_attn, c->s_comp));
+              HIP_TRY(c, hipStreamWaitEvent(c->s_eval, c->ev_attn, 0));
+            }
             st = by_dtype(c, [&](auto* tag) {
               using T = std::remove_pointer_t<decltype(tag)>;
               return score_matrix<T>(c, l, plan, c->s_eval, want.data());
@@ -1391,6 +1479,30 @@ keep_status prefill_impl(keep_ctx* c, const keep_prompt* p, const float* ratios,
       const int nn = c->h_sel_out[0];
       for (int i = 0; i < nn; ++i) nxt.push_back(cur[c->h_sel_out[2 + i]]);
       if (report) report->hops_run[l] = c->h_sel_out[1];
+      if (lazy_attn) {  // members of the final set that no hop has needed yet: their outputs are needed now
+        bool any = false;
+        std::fill(want.begin(), want.end(), 0);
+        for (int i = 0; i < nn; ++i) {
+          const int a = c->h_sel_out[2 + i];
+          if (!have[a]) want[a] = have[a] = 1, any = true;
+        }
+        if (any) {
+          st = attend(want.data());
+          if (st != KEEP_OK) return st;
+        }
+        if (report) {
+          report->attn_rows[l] = (int32_t)attn_rows;
+          report->attn_keys[l] = attn_keys;
+        }
+        if (report && part_launches > 0) {  // the events are reused by later layers: read them now
+          HIP_TRY(c, hipEventSynchronize(c->ev_part[2 * (part_launches - 1) + 1]));
+          for (int i = 0; i < part_launches; ++i) {
+            float ms = 0.f;
+            (void)hipEventElapsedTime(&ms, c->ev_part[2 * i], c->ev_part[2 * i + 1]);
+            part_attn_ms[l] += ms;
+          }
+        }
+      }
     } else if (kind == SEL_ALL) {
       nxt = cur;
     } else {
@@ -1488,6 +1600,7 @@ keep_status prefill_impl(keep_ctx* c, const keep_prompt* p, const float* ratios,
       (void)hipEventElapsedTime(&report->ms_qkv_gemm[l], e[2], e[3]);
       (void)hipEventElapsedTime(&report->ms_rope[l], e[3], e[4]);
       (void)hipEventElapsedTime(&report->ms_attn[l], e[4], e[5]);
+      report->ms_attn[l] += part_attn_ms[l];
       (void)hipEventElapsedTime(&report->ms_oproj[l], e[12], e[6]);
       (void)hipEventElapsedTime(&report->ms_norm2[l], e[6], e[7]);
       (void)hipEventElapsedTime(&report->ms_gateup[l], e[7], e[8]);

@@ -47,7 +47,8 @@ constexpr int PART_FLOATS = 128 * DH;  // partial O of one (item, KV head): [dh/
 
 __global__ void __launch_bounds__(256, 2)
     k_attn_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k_cache, const bf16_t* __restrict__ v_cache,
-                const int32_t* __restrict__ row_pos, const int32_t* __restrict__ row_lo, int n_rows, int n_total,
+                const int32_t* __restrict__ row_pos, const int32_t* __restrict__ row_lo,
+                const int32_t* __restrict__ row_list, int n_rows, int n_total,
                 int n_q_heads, int n_kv_heads, const int4* __restrict__ items, float scale_log2e,
                 bf16_t* __restrict__ o, float* __restrict__ lse, float* __restrict__ part_o,
                 float* __restrict__ part_ml) {
@@ -64,7 +65,8 @@ __global__ void __launch_bounds__(256, 2)
   // this lane's query row
   const int x = tile * 128 + wave * 32 + lq;
   const bool valid = x < QR;
-  const int r = valid ? x / rep : 0;
+  // n_rows counts the listed rows when a list is given: entry x / rep names the row of q / o / lse / row_pos
+  const int r = valid ? (row_list ? row_list[x / rep] : x / rep) : 0;
   const int head = hk * rep + (valid ? x % rep : 0);
   const int pos = valid ? row_pos[r] : 0;
   const int lo = (valid && row_lo) ? row_lo[r] : 0;  // first key the row may see
@@ -288,7 +290,8 @@ __global__ void __launch_bounds__(256, 2)
 // row (decoding) spreads over 32 threads and the loop over chunks is a stream of independent loads.
 __global__ void __launch_bounds__(256)
     k_attn_combine(const int4* __restrict__ splits, const float* __restrict__ part_o, const float* __restrict__ part_ml,
-                   int n_rows, int n_q_heads, int n_kv_heads, bf16_t* __restrict__ o, float* __restrict__ lse) {
+                   const int32_t* __restrict__ row_list, int n_rows, int n_q_heads, int n_kv_heads,
+                   bf16_t* __restrict__ o, float* __restrict__ lse) {
   const int hk = blockIdx.x % n_kv_heads;
   const int4 sp = splits[blockIdx.x / n_kv_heads];  // {tile, first slot, chunks, -}
   const int rep = n_q_heads / n_kv_heads;
@@ -296,7 +299,7 @@ __global__ void __launch_bounds__(256)
   const int d4 = blockIdx.y * 2 + (threadIdx.x >> 7);  // 0..31
   const int x = sp.x * 128 + ql;
   if (x >= n_rows * rep) return;
-  const int r = x / rep, head = hk * rep + x % rep;
+  const int r = row_list ? row_list[x / rep] : x / rep, head = hk * rep + x % rep;
   const float* ml = part_ml + ((size_t)sp.y * n_kv_heads + hk) * 256 + ql;
   const size_t ml_step = (size_t)n_kv_heads * 256;
   float m_all = M_FLOOR;
@@ -343,7 +346,7 @@ size_t attn_mfma_scratch_bytes(int32_t max_rows, int32_t n_q_heads, int32_t n_kv
 
 // The two launches, given a work list that is already in d_scratch.
 static void launch_attn_planned(const bf16_t* q, const bf16_t* k_cache, const bf16_t* v_cache, const int32_t* d_row_pos,
-                                const int32_t* d_row_lo, int32_t n_rows, int32_t n_total, int32_t n_q_heads,
+                                const int32_t* d_row_lo, const int32_t* d_row_list, int32_t n_rows, int32_t n_total, int32_t n_q_heads,
                                 int32_t n_kv_heads, int32_t max_rows, void* d_scratch, int n_items, int n_splits,
                                 bf16_t* o, float* lse, hipStream_t s) {
   const int rep = n_q_heads / n_kv_heads;
@@ -364,20 +367,26 @@ static void launch_attn_planned(const bf16_t* q, const bf16_t* k_cache, const bf
   }
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)DH);
   hipLaunchKernelGGL(k_attn_mfma, dim3(n_items * n_kv_heads), dim3(256), sh, s, q, k_cache, v_cache, d_row_pos, d_row_lo,
-                     n_rows, n_total, n_q_heads, n_kv_heads, d_items, scale_log2e, o, lse, part_o, part_ml);
+                     d_row_list, n_rows, n_total, n_q_heads, n_kv_heads, d_items, scale_log2e, o, lse, part_o, part_ml);
   if (n_splits)
     hipLaunchKernelGGL(k_attn_combine, dim3(n_splits * n_kv_heads, 16), dim3(256), 0, s, d_splits, part_o, part_ml,
-                       n_rows, n_q_heads, n_kv_heads, o, lse);
+                       d_row_list, n_rows, n_q_heads, n_kv_heads, o, lse);
 }
 
 void launch_attn_mfma(const bf16_t* q, const bf16_t* k_cache, const bf16_t* v_cache, const int32_t* d_row_pos,
                       const int32_t* h_row_start, const int32_t* h_set_off, int32_t m, int32_t instr_off,
                       int32_t n_rows, int32_t n_total, int32_t n_q_heads, int32_t n_kv_heads, int32_t max_rows,
                       int32_t* h_stage, void* d_scratch, bf16_t* o, float* lse, hipStream_t s,
-                      const int32_t* h_row_lo, const int32_t* d_row_lo, AttnPlan* plan) {
+                      const int32_t* h_row_lo, const int32_t* d_row_lo, AttnPlan* plan, const int32_t* h_row_list,
+                      const int32_t* d_row_list, int32_t n_list) {
+  // With a row list only the listed rows (ascending ids into q / o / lse / row_pos) are attended; n_rows then
+  // stands for the length of the list everywhere below.
+  const int32_t n_all_rows = n_rows;
+  (void)n_all_rows;
+  if (h_row_list) n_rows = n_list;
   if (n_rows <= 0) return;
   if (plan && plan->valid) {  // same row layout as the launch that made the plan: the work list is on the device
-    launch_attn_planned(q, k_cache, v_cache, d_row_pos, d_row_lo, n_rows, n_total, n_q_heads, n_kv_heads, max_rows,
+    launch_attn_planned(q, k_cache, v_cache, d_row_pos, d_row_lo, d_row_list, n_rows, n_total, n_q_heads, n_kv_heads, max_rows,
                         d_scratch, plan->n_items, plan->n_splits, o, lse, s);
     return;
   }
@@ -386,6 +395,7 @@ void launch_attn_mfma(const bf16_t* q, const bf16_t* k_cache, const bf16_t* v_ca
   const int mt = att_max_tiles(max_rows, rep);
   // key tiles each query tile needs: up to the position of its last row
   auto pos_of_row = [&](int r) {
+    if (h_row_list) r = h_row_list[r];
     int lo = 0, hi = m;  // blocks 0..m
     while (lo < hi) {
       const int mid = (lo + hi + 1) >> 1;
@@ -484,8 +494,8 @@ void launch_attn_mfma(const bf16_t* q, const bf16_t* k_cache, const bf16_t* v_ca
     plan->n_items = n_items;
     plan->n_splits = n_splits;
   }
-  launch_attn_planned(q, k_cache, v_cache, d_row_pos, d_row_lo, n_rows, n_total, n_q_heads, n_kv_heads, max_rows,
-                      d_scratch, n_items, n_splits, o, lse, s);
+  launch_attn_planned(q, k_cache, v_cache, d_row_pos, d_row_lo, d_row_list, n_rows, n_total, n_q_heads, n_kv_heads,
+                      max_rows, d_scratch, n_items, n_splits, o, lse, s);
 }
 
 }  // namespace keep

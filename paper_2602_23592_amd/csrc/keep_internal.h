@@ -153,7 +153,9 @@ void launch_attn_mfma(const bf16_t* q, const bf16_t* k_cache, const bf16_t* v_ca
                       const int32_t* h_row_start, const int32_t* h_set_off, int32_t m, int32_t instr_off,
                       int32_t n_rows, int32_t n_total, int32_t n_q_heads, int32_t n_kv_heads, int32_t max_rows,
                       int32_t* h_stage, void* d_scratch, bf16_t* o, float* lse, hipStream_t s,
-                      const int32_t* h_row_lo = nullptr, const int32_t* d_row_lo = nullptr, AttnPlan* plan = nullptr);
+                      const int32_t* h_row_lo = nullptr, const int32_t* d_row_lo = nullptr, AttnPlan* plan = nullptr,
+                      const int32_t* h_row_list = nullptr, const int32_t* d_row_list = nullptr, int32_t n_list = 0);
+// h_row_list / d_row_list (host and device copies) of n_list ascending row ids: attend only these rows.
 // h_row_lo / d_row_lo (host and device copies, both or neither): first key each row may see (default 0);
 // used where several units are cached in one pass, each attending to itself only.
 // group-score matrix S[(m+1), m] of the layer whose q / compact k / lse are given.
