@@ -111,7 +111,10 @@ typedef struct {
 /* Filled by keep_prefill when a report is asked for (caller-allocated, HOST).
  * Times are device times between HIP events recorded on the stream the kernels run
  * on (compute stream; eval stream for ms_score), in milliseconds, per layer. */
+#define KEEP_REPORT_EVENTS_ALL 0     /* events around every kernel: all ms_* fields are filled */
+#define KEEP_REPORT_EVENTS_GATE_UP 1 /* events around the gate/up GEMM only (ms_gateup): ~2 ms less intrusive at 48 layers */
 typedef struct {
+  int32_t events_in;                           /* IN: KEEP_REPORT_EVENTS_*; the only field read by the library */
   int32_t n_layers;
   int32_t used_mfma;                           /* 1 if the MFMA kernel family ran */
   float ms_total;                              /* whole call, host clock */

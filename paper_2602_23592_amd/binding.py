@@ -62,7 +62,7 @@ _REPORT_MS = ("ms_realign", "ms_prep", "ms_qkv_gemm", "ms_rope", "ms_attn", "ms_
 
 
 class Report(C.Structure):
-    _fields_ = ([("n_layers", C.c_int32), ("used_mfma", C.c_int32), ("ms_total", C.c_float),
+    _fields_ = ([("events_in", C.c_int32), ("n_layers", C.c_int32), ("used_mfma", C.c_int32), ("ms_total", C.c_float),
                  ("rows", C.c_int32 * _L), ("set_size", C.c_int32 * _L), ("hops_run", C.c_int32 * _L),
                  ("realign_rows", C.c_int32 * _L), ("ffn_rows", C.c_int32 * _L),
                  ("attn_rows", C.c_int32 * _L), ("attn_keys", C.c_uint64 * _L)]
@@ -286,13 +286,16 @@ class KeepContext:
     def prefill(self, prompt: KeepPrompt, ratios: Sequence[float], hops: int, k_cache: torch.Tensor,
                 v_cache: torch.Tensor, x_final: torch.Tensor, budget_mode: int = KEEP_BUDGET_GROUP_COUNT,
                 load_mode: int = KEEP_LOAD_LAYER_BALANCED, want_report: bool = False,
-                cache_rows: Optional[int] = None):
-        """cache_rows: rows per layer of k_cache / v_cache when they leave room for decoded tokens."""
+                cache_rows: Optional[int] = None, gate_up_events_only: bool = False):
+        """cache_rows: rows per layer of k_cache / v_cache when they leave room for decoded tokens.
+        gate_up_events_only: with a report, time only the gate/up GEMM (far fewer HIP events in the stream)."""
         L, G = self.shape.n_layers, prompt.n_groups
         r = np.ascontiguousarray(np.asarray(ratios, dtype=np.float32))
         sel = np.zeros(max(1, L * G), dtype=np.int32)
         cnt = np.zeros(L, dtype=np.int32)
         rep = Report() if want_report else None
+        if want_report:
+            rep.events_in = 1 if gate_up_events_only else 0
         if cache_rows is None:
             self._check(self.lib.keep_prefill(
                 self.handle, C.byref(prompt.c), r.ctypes.data_as(C.POINTER(C.c_float)), hops, budget_mode, load_mode,

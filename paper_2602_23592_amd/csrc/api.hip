@@ -78,6 +78,7 @@ struct keep_ctx {
   hipEvent_t ev_part[16] = {};      // begin / end pairs of such launches (timing)
   int32_t* h_row_lo = nullptr;      // pinned [max_tokens]: first visible key per row (batched unit caching)
   int32_t* d_row_lo = nullptr;
+  bool ev_light = false;            // record only the events around the gate/up GEMM (keep_report.events_in = 1)
   bool units_mode = false;          // rows attend only from their unit's first row on
   int32_t* h_dec = nullptr;         // pinned [4 * KEEP_DECODE_MAX_TOKENS]: positions, fed tokens, results
   int32_t* d_dec = nullptr;         // device mirror
@@ -379,10 +380,10 @@ keep_status layer_front(keep_ctx* c, const PromptInfo& pi, int layer, const Laye
   const keep_layer_weights& w = c->w[layer];
   hipStream_t s = c->s_comp;
   const int n = plan.n_rows;
-  if (evs) HIP_TRY(c, hipEventRecord(evs[0], s));
+  if (evs && !c->ev_light) HIP_TRY(c, hipEventRecord(evs[0], s));
   launch_realign<T>(c->d_segs, plan.n_segs, plan.n_realign_rows, d.n_kv_heads, d.head_dim, c->rope_cos, c->rope_sin,
                     Typed<T>::p(k_cache_l), Typed<T>::p(v_cache_l), s);
-  if (evs) HIP_TRY(c, hipEventRecord(evs[1], s));
+  if (evs && !c->ev_light) HIP_TRY(c, hipEventRecord(evs[1], s));
   launch_build_rows(c->d_set_off, c->d_row_start, plan.m, pi.n_mem, n, c->d_row_pos, c->d_row_slot, s);
   const T* x = Typed<T>::p(x_in);
   if (!x) {
@@ -390,7 +391,7 @@ keep_status layer_front(keep_ctx* c, const PromptInfo& pi, int layer, const Laye
     x = Typed<T>::p(c->xa);
   }
   launch_rmsnorm<T>(x, Typed<T>::p(w.ln1), n, d.hidden, d.rms_eps, Typed<T>::p(c->hbuf), s);
-  if (evs) HIP_TRY(c, hipEventRecord(evs[2], s));
+  if (evs && !c->ev_light) HIP_TRY(c, hipEventRecord(evs[2], s));
   GemmB b;
   b.n_parts = 3;
   b.ptr[0] = w.wq; b.ptr[1] = w.wk; b.ptr[2] = w.wv;
@@ -403,14 +404,14 @@ keep_status layer_front(keep_ctx* c, const PromptInfo& pi, int layer, const Laye
                      c->qkv_raw, s, c->skinny_ws);
   else
     launch_gemm_generic<T>(Typed<T>::p(c->hbuf), n, d.hidden, b, nullptr, n_qkv, EPI_STORE_F32, nullptr, c->qkv_raw, s);
-  if (evs) HIP_TRY(c, hipEventRecord(evs[3], s));
+  if (evs && !c->ev_light) HIP_TRY(c, hipEventRecord(evs[3], s));
   launch_rope_scatter<T>(c->qkv_raw, Typed<T>::p(w.bq), Typed<T>::p(w.bk), Typed<T>::p(w.bv), c->d_row_pos, n,
                          d.n_q_heads, d.n_kv_heads, d.head_dim, c->rope_cos, c->rope_sin, Typed<T>::p(c->q),
                          Typed<T>::p(c->kc), Typed<T>::p(k_cache_l), Typed<T>::p(v_cache_l), s,
                          c->units_mode ? c->d_row_lo : nullptr);
-  if (evs) HIP_TRY(c, hipEventRecord(evs[4], s));
+  if (evs && !c->ev_light) HIP_TRY(c, hipEventRecord(evs[4], s));
   if (skip_attention) {  // the caller attends the rows as they turn out to be needed
-    if (evs) HIP_TRY(c, hipEventRecord(evs[5], s));
+    if (evs && !c->ev_light) HIP_TRY(c, hipEventRecord(evs[5], s));
     HIP_TRY(c, hipGetLastError());
     return KEEP_OK;
   }
@@ -424,7 +425,7 @@ keep_status layer_front(keep_ctx* c, const PromptInfo& pi, int layer, const Laye
     launch_attn_generic<T>(Typed<T>::p(c->q), Typed<T>::p(k_cache_l), Typed<T>::p(v_cache_l), c->d_row_pos, n,
                            d.n_q_heads, d.n_kv_heads, d.head_dim, Typed<T>::p(c->o), c->lse, s,
                            c->units_mode ? c->d_row_lo : nullptr);
-  if (evs) HIP_TRY(c, hipEventRecord(evs[5], s));
+  if (evs && !c->ev_light) HIP_TRY(c, hipEventRecord(evs[5], s));
   HIP_TRY(c, hipGetLastError());
   return KEEP_OK;
 }
@@ -473,7 +474,7 @@ keep_status layer_back(keep_ctx* c, int layer, int n, const void* o_rows, const 
   GemmB bg{}; bg.n_parts = 1; bg.ptr[0] = w.wgate; bg.n_rows[0] = d.ffn_dim;
   GemmB bd{}; bd.n_parts = 1; bd.ptr[0] = w.wdown; bd.n_rows[0] = d.hidden;
 #define EV(i) \
-  if (evs) HIP_TRY(c, hipEventRecord(evs[i], s))
+  if (evs && (!c->ev_light || (i) == 7 || (i) == 8)) HIP_TRY(c, hipEventRecord(evs[i], s))
   EV(12);
   if (c->mfma) {
     auto B = [](const void* p) { return reinterpret_cast<const bf16_t*>(p); };
@@ -1243,8 +1244,12 @@ keep_status prefill_impl(keep_ctx* c, const keep_prompt* p, const float* ratios,
   if (cache_rows != 0 && cache_rows < pi.N)
     return fail(c, KEEP_ERR_INVALID_ARG, "cache_rows %d below the prompt's %d tokens", cache_rows, pi.N);
   const size_t layer_bytes = (size_t)(cache_rows ? cache_rows : pi.N) * row_bytes;
+  c->ev_light = false;
   if (report) {
+    c->ev_light = report->events_in == KEEP_REPORT_EVENTS_GATE_UP;
+    const int32_t events_in = report->events_in;
     memset(report, 0, sizeof *report);
+    report->events_in = events_in;
     report->n_layers = L;
     report->used_mfma = c->mfma ? 1 : 0;
   }
@@ -1341,8 +1346,8 @@ keep_status prefill_impl(keep_ctx* c, const keep_prompt* p, const float* ratios,
       int n_att = 0;
       uint64_t n_keys = 0;
       const int slot = std::min(part_launches, 7);
-      keep_status s2 = attend_blocks(c, pi, l, plan, flags, kl, vl, evs ? c->ev_part[2 * slot] : nullptr,
-                                     evs ? c->ev_part[2 * slot + 1] : nullptr, &n_att, &n_keys);
+      keep_status s2 = attend_blocks(c, pi, l, plan, flags, kl, vl, (evs && !c->ev_light) ? c->ev_part[2 * slot] : nullptr,
+                                     (evs && !c->ev_light) ? c->ev_part[2 * slot + 1] : nullptr, &n_att, &n_keys);
       if (s2 != KEEP_OK) return s2;
       if (n_att > 0) {
         attn_rows += n_att;
@@ -1366,7 +1371,7 @@ keep_status prefill_impl(keep_ctx* c, const keep_prompt* p, const float* ratios,
       }
       HIP_TRY(c, hipEventRecord(c->ev_attn, c->s_comp));
       HIP_TRY(c, hipStreamWaitEvent(c->s_eval, c->ev_attn, 0));
-      if (evs) HIP_TRY(c, hipEventRecord(evs[10], c->s_eval));
+      if (evs && !c->ev_light) HIP_TRY(c, hipEventRecord(evs[10], c->s_eval));
       if (lazy) HIP_TRY(c, hipMemsetAsync(c->S, 0, (size_t)(m + 1) * m * sizeof(float), c->s_eval));
       st = by_dtype(c, [&](auto* tag) {
         using T = std::remove_pointer_t<decltype(tag)>;
@@ -1375,7 +1380,7 @@ keep_status prefill_impl(keep_ctx* c, const keep_prompt* p, const float* ratios,
       if (st != KEEP_OK) return st;
       st = enqueue_select(c, m, k_count, tok, budget_mode, lazy ? 1 : hops, c->s_eval);
       if (st != KEEP_OK) return st;
-      if (evs) HIP_TRY(c, hipEventRecord(evs[11], c->s_eval));
+      if (evs && !c->ev_light) HIP_TRY(c, hipEventRecord(evs[11], c->s_eval));
       HIP_TRY(c, hipEventRecord(c->ev_eval, c->s_eval));
     }
     auto finish_layer = [&](int n_rows_back, const void* o_rows, const void* x_in_back, void* x_out_back) {
@@ -1471,7 +1476,7 @@ keep_status prefill_impl(keep_ctx* c, const keep_prompt* p, const float* ratios,
           }
           st = enqueue_select(c, m, k_count, tok, budget_mode, h + 1, c->s_eval);
           if (st != KEEP_OK) return st;
-          if (evs) HIP_TRY(c, hipEventRecord(evs[11], c->s_eval));
+          if (evs && !c->ev_light) HIP_TRY(c, hipEventRecord(evs[11], c->s_eval));
           HIP_TRY(c, hipStreamSynchronize(c->s_eval));
         }
       }
@@ -1494,7 +1499,7 @@ keep_status prefill_impl(keep_ctx* c, const keep_prompt* p, const float* ratios,
           report->attn_rows[l] = (int32_t)attn_rows;
           report->attn_keys[l] = attn_keys;
         }
-        if (report && part_launches > 0) {  // the events are reused by later layers: read them now
+        if (report && !c->ev_light && part_launches > 0) {  // the events are reused by later layers: read them now
           HIP_TRY(c, hipEventSynchronize(c->ev_part[2 * (part_launches - 1) + 1]));
           for (int i = 0; i < part_launches; ++i) {
             float ms = 0.f;
@@ -1595,6 +1600,8 @@ keep_status prefill_impl(keep_ctx* c, const keep_prompt* p, const float* ratios,
     report->ms_total = std::chrono::duration<float, std::milli>(std::chrono::steady_clock::now() - t_begin).count();
     for (int l = 0; l < L; ++l) {
       hipEvent_t* e = &c->ev[(size_t)l * EV_PER_LAYER];
+      (void)hipEventElapsedTime(&report->ms_gateup[l], e[7], e[8]);
+      if (c->ev_light) continue;
       (void)hipEventElapsedTime(&report->ms_realign[l], e[0], e[1]);
       (void)hipEventElapsedTime(&report->ms_prep[l], e[1], e[2]);
       (void)hipEventElapsedTime(&report->ms_qkv_gemm[l], e[2], e[3]);
@@ -1603,7 +1610,6 @@ keep_status prefill_impl(keep_ctx* c, const keep_prompt* p, const float* ratios,
       report->ms_attn[l] += part_attn_ms[l];
       (void)hipEventElapsedTime(&report->ms_oproj[l], e[12], e[6]);
       (void)hipEventElapsedTime(&report->ms_norm2[l], e[6], e[7]);
-      (void)hipEventElapsedTime(&report->ms_gateup[l], e[7], e[8]);
       (void)hipEventElapsedTime(&report->ms_down[l], e[8], e[9]);
       if (report->hops_run[l] > 0) (void)hipEventElapsedTime(&report->ms_score[l], e[10], e[11]);
     }
