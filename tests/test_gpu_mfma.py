@@ -130,3 +130,33 @@ def test_prefill_with_many_candidates_selects_like_the_full_score_matrix():
         for l in range(2):
             assert max_rel(to_np(kc[l]), ref["k_hat"][l]) < TOL and max_rel(to_np(vc[l]), ref["v_hat"][l]) < TOL
         assert max_rel(to_np(xf), ref["x_final"]) < TOL
+
+
+def test_many_candidates_with_host_resident_caches_in_every_load_mode():
+    """Hop-by-hop scoring and attention on demand together with caches in pinned host memory: the three
+    loading modes and the device-resident run must give bit-identical caches, rows and sets."""
+    from paper_2602_23592_amd.binding import KEEP_LOAD_SERIAL, KEEP_LOAD_NEXT_LAYER, KEEP_LOAD_LAYER_BALANCED
+    shape = _shape(3, 512, 8, 2, 1024)
+    rng = np.random.default_rng(41)
+    glen = [int(v) for v in rng.integers(8, 41, size=80)]
+    lq = 17
+    pb = Problem(shape, glen, lq, seed=12, std=0.05, bias=True, random_cache=True)
+    ctx = pb.context()
+    ratios = [1.0, 0.2, 0.1]
+    outs = []
+    for pinned, mode in ((False, KEEP_LOAD_LAYER_BALANCED), (True, KEEP_LOAD_SERIAL), (True, KEEP_LOAD_NEXT_LAYER),
+                         (True, KEEP_LOAD_LAYER_BALANCED)):
+        pr = pb.prompt(pinned_host=pinned)
+        kc, vc = pb.empty_cache()
+        xf = torch.empty((lq, shape.hidden), dtype=torch.bfloat16, device="cuda")
+        sets, rep = ctx.prefill(pr, ratios, 3, kc, vc, xf, load_mode=mode, want_report=True)
+        torch.cuda.synchronize()
+        assert rep.attn_rows[0] < rep.rows[0]          # layer 0 attended only part of its rows
+        outs.append((sets, kc.clone(), vc.clone(), xf.clone()))
+    for o in outs[1:]:
+        assert o[0] == outs[0][0]
+        assert torch.equal(o[1], outs[0][1]) and torch.equal(o[2], outs[0][2]) and torch.equal(o[3], outs[0][3])
+    ref = ko.keep_prefill(pb.sh, pb.layers, pb.embed, pb.ids, glen, lq, pb.kb, pb.vb, ratios, 3, forced_sets=outs[0][0])
+    for l in range(3):
+        assert max_rel(to_np(outs[0][1][l]), ref["k_hat"][l]) < TOL and max_rel(to_np(outs[0][2][l]), ref["v_hat"][l]) < TOL
+    assert max_rel(to_np(outs[0][3]), ref["x_final"]) < TOL
