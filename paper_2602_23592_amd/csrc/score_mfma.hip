@@ -24,7 +24,7 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 constexpr int SDH = 128;
 constexpr int S_KEYS = 64;      // keys per LDS tile
-constexpr int S_CHUNK = 1024;   // keys per workgroup
+constexpr int S_CHUNK = 1024;   // keys per workgroup at most (launches with few row tiles take shorter chunks)
 
 struct RowTile {
   int32_t row0, nrows, slot;
@@ -191,15 +191,15 @@ template <int CH>
 __global__ void __launch_bounds__(256, 2)
     k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ kc, const float* __restrict__ lse,
                  const RowTile* __restrict__ tiles, int n_rt, int n_keys, int n_q_heads, int n_kv_heads,
-                 int hk_per_slice, float scale_log2e, float* __restrict__ colmass, int col_ld) {
+                 int hk_per_slice, int chunk, float scale_log2e, float* __restrict__ colmass, int col_ld) {
   __shared__ __attribute__((aligned(16))) uint16_t s_k[2 * S_KEYS * SDH];
   __shared__ float s_col[4][S_CHUNK];
   __shared__ __attribute__((aligned(16))) float s_l2[4][CH * 32];  // rows' log-sum-exp, log2 domain
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lq = lane & 31;
   const int rep = n_q_heads / n_kv_heads;
-  const int c0 = blockIdx.y * S_CHUNK;
-  const int c1 = min(c0 + S_CHUNK, n_keys);
+  const int c0 = blockIdx.y * chunk;
+  const int c1 = min(c0 + chunk, n_keys);
   // rows of the workgroup's last tile bound the keys that can be visible
   const int rt_last = min(n_rt, (int)blockIdx.x * 4 + 4) - 1;
   const int blk_last_row = tiles[rt_last].row0 + tiles[rt_last].nrows - 1;
@@ -216,7 +216,7 @@ __global__ void __launch_bounds__(256, 2)
   sw.last_row = sw.row0 + sw.nrows - 1;
   const int q_row = sw.row0 + min(lq, sw.nrows - 1);  // A operand row of this lane (clamped)
 
-  for (int i = tid; i < 4 * S_CHUNK; i += 256) (&s_col[0][0])[i] = 0.f;
+  for (int i = tid; i < 4 * chunk; i += 256) s_col[i / chunk][i % chunk] = 0.f;
 
   // blockIdx.z selects a slice of the KV heads (small problems are spread over more workgroups;
   // the slices' column sums are added in slice order by the next pass)
@@ -332,10 +332,25 @@ void launch_score_mfma(const bf16_t* q, const bf16_t* kc, const float* lse, cons
          n_kv_heads % (2 * n_slices) == 0)
     n_slices *= 2;
   const int hk_per_slice = n_kv_heads / n_slices;
-  const dim3 grid((n_rt + 3) / 4, (n_keys + S_CHUNK - 1) / S_CHUNK, n_slices);
+  // Keys per workgroup.  A key's column sum is formed by one wave over its rows and heads in a fixed order
+  // whatever the chunk, so the chunk length shapes the launch only, never a result.  Every pass over a chunk
+  // starts with exposed loads of the rows' Q, so long chunks are the efficient ones (measured: 256-key chunks
+  // cost 20 % more time on a launch that fills the chip either way); shorter ones are taken only while the
+  // workgroups with visible keys would not even occupy the chip once (a few hundred rows against a long
+  // key list: 0.61 -> 0.18 ms for the 256 instruction rows of the 33 024-token workload).
+  int chunk = S_CHUNK;
+  for (; chunk > 2 * S_KEYS; chunk /= 2) {
+    long active = 0;
+    for (int x = 0; x < (n_rt + 3) / 4; ++x) {
+      const RowTile& lt = ht[std::min(4 * x + 3, n_rt - 1)];
+      active += std::min((n_keys + chunk - 1) / chunk, (lt.row0 + lt.nrows - 1) / chunk + 1);
+    }
+    if (active * n_slices >= 512) break;
+  }
+  const dim3 grid((n_rt + 3) / 4, (n_keys + chunk - 1) / chunk, n_slices);
 #define GO(CH)                                                                                                      \
   hipLaunchKernelGGL(k_score_mfma<CH>, grid, dim3(256), 0, s, q, kc, lse, d_tiles, n_rt, n_keys, n_q_heads,         \
-                     n_kv_heads, hk_per_slice, scale_log2e, colmass, max_rows)
+                     n_kv_heads, hk_per_slice, chunk, scale_log2e, colmass, max_rows)
   // up to three query heads per pass keep two workgroups resident per CU (VALU of one overlaps MFMA of the other)
   if (rep >= 3)
     GO(3);
