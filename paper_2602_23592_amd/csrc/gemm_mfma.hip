@@ -44,11 +44,7 @@ __device__ __forceinline__ constexpr int vmcnt_imm(int n) { return 0x0F70 | (n &
 // Position t of the tile list -> tile coordinates: panels of GM tile rows, walked column by column.
 template <int BM>
 __device__ __forceinline__ void gemm_tile_of(int t, int tiles_m, int tiles_n, int& tile_m, int& tile_n) {
-#ifdef KEEP_EXP_GM
-  constexpr int GM = KEEP_EXP_GM;
-#else
   constexpr int GM = (BM >= 256) ? 4 : 8;
-#endif
   const int panel = t / (GM * tiles_n);
   const int panel_rows = min(GM, tiles_m - panel * GM);
   const int within = t - panel * GM * tiles_n;
@@ -115,11 +111,7 @@ __global__ void __launch_bounds__(WM* WN * 64)
 #pragma unroll
   for (int i = 0; i < A_LD; ++i) {
     const int r = (wave * A_LD + i) * RPI + lane / CPR, c = (lane % CPR) ^ ((r / RPL) & (CPR - 1));
-#ifdef KEEP_EXP_A_WRAP
-    const int gm = min(m0 + r, M - 1) % KEEP_EXP_A_WRAP;
-#else
     const int gm = min(m0 + r, M - 1);
-#endif
     a_src[i] = A + (size_t)gm * K + c * 8;
   }
 #pragma unroll
@@ -434,14 +426,7 @@ void launch_gemm_mfma(const bf16_t* A, int32_t M, int32_t K, const GemmB& B, con
   // multiples of 256.  A last, partly filled round of workgroups is cut along K in either case.
   const long tiles256 = (long)((M + 255) / 256) * (rows / 256);
   if (aligned256 && rows % 256 == 0 && tiles256 * (K / 64) >= 10000)
-#ifndef KEEP_EXP_CFG
-#define KEEP_EXP_CFG 256, 256, 4, 2, 64, 2
-#endif
-    launch_cfg<KEEP_EXP_CFG>(A, M, K, b, b2, N, epilogue, residual, C, s, skinny_ws);
-#ifdef KEEP_EXP_CFG_SMALL
-  else if (rows % 256 == 0 && aligned256)
-    launch_cfg<KEEP_EXP_CFG_SMALL>(A, M, K, b, b2, N, epilogue, residual, C, s, skinny_ws);
-#endif
+    launch_cfg<256, 256, 4, 2, 64, 2>(A, M, K, b, b2, N, epilogue, residual, C, s, skinny_ws);
   else if (rows % 128 == 0)
     launch_cfg<128, 128, 2, 2, 64, 2>(A, M, K, b, b2, N, epilogue, residual, C, s, skinny_ws);
   else
