@@ -4,7 +4,7 @@ This package is the only code shared by the CPU oracle's tests and the HIP
 path's tests/bench.  It holds workload shapes and random-number recipes and
 none of the method's arithmetic (no RoPE, no attention, no projections, no
 selection): every array it returns is a plain random draw, a reshaping of
-one, or a storage-format conversion (fp32 <-> bf16 bit patterns).
+one, or a storage-format conversion (fp32 <-> bf16 bit patterns, 4-bit codes <-> packed bytes).
 """
 from .configs import ModelShape, Workload, WORKLOADS, workload, ratio_schedule
 from .gen import (
@@ -20,4 +20,9 @@ from .gen import (
     make_token_ids,
     make_random_group_cache,
     make_random_rows,
+    INT4_GROUP,
+    INT4_MATS,
+    pack_int4_codes,
+    make_int4_matrix,
+    make_int4_layer,
 )

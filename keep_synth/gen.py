@@ -135,6 +135,48 @@ def make_weights(s: ModelShape, device: str = "cpu", std: float = 0.02, bias: bo
 
 
 # ----------------------------------------------------------------------------
+# INT4 weight-only matrices: random codes, zero points and scales (no dequantisation here)
+# ----------------------------------------------------------------------------
+INT4_GROUP = 128   # input features that share one scale and one zero point
+INT4_MATS = ("wq", "wk", "wv", "wo", "wgate", "wup", "wdown")
+
+
+def pack_int4_codes(q: np.ndarray) -> np.ndarray:
+    """Storage packing of 4-bit codes [rows, K] -> bytes [rows, K/2].
+
+    Within each run of 8 consecutive input features, byte t (t < 4) holds feature t in its low
+    nibble and feature t + 4 in its high nibble."""
+    rows, k = q.shape
+    assert k % 8 == 0
+    q8 = q.reshape(rows, k // 8, 8).astype(np.uint8)
+    return (q8[:, :, 0:4] | (q8[:, :, 4:8] << np.uint8(4))).reshape(rows, k // 2)
+
+
+def make_int4_matrix(rows: int, k: int, seed: int, std: float = 0.02) -> Dict[str, np.ndarray]:
+    """Random group-quantised matrix: codes ~ Binomial(15, 1/2), zero point 7 or 8, bf16 scale drawn so
+    that (code - zero) * scale has a standard deviation near `std`.
+
+    Returns the raw draws (`q` [rows, K] uint8, `zero` [rows, K/128] uint8, `scale_bits` [rows, K/128]
+    uint16 bf16 patterns) and their storage form: `codes` [rows, K/2] uint8 (pack_int4_codes) and
+    `scale_zero` [rows, K/128] uint32 = scale_bits | zero << 16."""
+    assert k % INT4_GROUP == 0
+    rng = np.random.Generator(np.random.PCG64(seed))
+    q = rng.binomial(15, 0.5, size=(rows, k)).astype(np.uint8)
+    zero = rng.integers(7, 9, size=(rows, k // INT4_GROUP)).astype(np.uint8)
+    scale = (std / 1.94) * rng.uniform(0.75, 1.25, size=(rows, k // INT4_GROUP))
+    scale_bits = bf16_bits_from_f32(scale.astype(np.float32))
+    scale_zero = scale_bits.astype(np.uint32) | (zero.astype(np.uint32) << np.uint32(16))
+    return {"q": q, "zero": zero, "scale_bits": scale_bits, "codes": pack_int4_codes(q), "scale_zero": scale_zero}
+
+
+def make_int4_layer(s: ModelShape, layer: int, std: float = 0.02) -> Dict[str, Dict[str, np.ndarray]]:
+    """The seven projection matrices of one layer as random INT4 matrices (seed 5000 + 16 * layer + index)."""
+    shapes = layer_weight_shapes(s)
+    return {name: make_int4_matrix(shapes[name][0], shapes[name][1], 5000 + 16 * layer + i, std)
+            for i, name in enumerate(INT4_MATS)}
+
+
+# ----------------------------------------------------------------------------
 # random stand-ins for cached K/V blocks and hidden rows (teacher-forced layer tests)
 # ----------------------------------------------------------------------------
 def make_random_group_cache(s: ModelShape, group_len: Sequence[int], layer: int, seed: int = 7,
