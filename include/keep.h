@@ -254,6 +254,44 @@ keep_status keep_decode(keep_ctx* ctx, const void* final_norm, const void* lm_he
                         void* k_cache, void* v_cache, int32_t cache_rows, int32_t n_ctx, int32_t n_new,
                         int32_t* tokens_out, float* logits_out, const int32_t* forced_tokens);
 
+/* ---- INT4 weight-only matrices (Section 6.1: the 32B model is run with INT4 weight-only quantisation) ----
+ * Format of one matrix W[rows, K] (K a multiple of 128), all DEVICE memory, caller-owned:
+ *   codes       [rows, K/2] bytes: 4-bit codes q in 0..15; within each run of 8 consecutive input
+ *               features, byte t (t < 4) holds feature t in its low nibble and feature t + 4 in its high one;
+ *   scale_zero  [rows, K/128] uint32: bits 0..15 the bfloat16 pattern of the group's scale s, bits 16..19
+ *               its zero point z, other bits 0.
+ * The weight the model computes with is  w = bf16((q - z) * s), rounded to nearest even: the 4-bit form is
+ * a compact storage of exactly those bfloat16 values.  The calibration that chooses q, z, s is not part of
+ * this library (weights arrive quantised). */
+typedef struct {
+  const void* codes;
+  const void* scale_zero;
+} keep_int4_matrix;
+
+/* The seven projections of one layer, shapes as in keep_layer_weights. */
+typedef struct {
+  keep_int4_matrix wq, wk, wv, wo, wgate, wup, wdown;
+} keep_layer_weights_int4;
+
+/* out[rows, K] (DEVICE, bfloat16) = the weights of an INT4 matrix.  With these as the keep_layer_weights
+ * of keep_init, the launches that are bound by the matrix cores (many rows) run on the expanded copy.
+ *   stream: hipStream_t or NULL (default stream); the call does not wait for the kernel.
+ * Errors: INVALID_ARG (NULL, rows < 1, K not a positive multiple of 128), HIP.  Needs no context:
+ * the message of a failure is at keep_last_error(NULL). */
+keep_status keep_dequantize_int4(const void* codes, const void* scale_zero, int32_t rows, int32_t K, void* out,
+                                 void* stream);
+
+/* Registers the INT4 form of every layer's projections with a context whose keep_layer_weights are their
+ * bfloat16 expansion (keep_dequantize_int4).  From then on the launches that are bound by reading the
+ * weights (at most 64 rows: keep_decode, keep_precompute_group of a short segment, prompts of a few rows)
+ * read the 4-bit form, a quarter of the bytes, and expand it in registers to the same bfloat16 values, so
+ * results differ from the bfloat16 launches only by the order of the fp32 accumulation.
+ *   layers: HOST array [n_layers] of DEVICE pointers, borrowed until keep_destroy; NULL detaches.
+ *   The LM head of keep_decode stays bfloat16.
+ * Errors: INVALID_ARG (a NULL pointer inside), UNSUPPORTED (context not on the bf16 MFMA path),
+ * SHAPE (hidden or ffn_dim not a multiple of 128). */
+keep_status keep_attach_int4(keep_ctx* ctx, const keep_layer_weights_int4* layers);
+
 #ifdef __cplusplus
 }
 #endif

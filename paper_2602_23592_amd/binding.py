@@ -26,6 +26,7 @@ KEEP_REPORT_MAX_LAYERS = 128
 EXPORTED = ("keep_init", "keep_destroy", "keep_last_error", "keep_uses_mfma", "keep_workspace_bytes", "keep_recompute_layer",
             "keep_score_groups", "keep_select_groups", "keep_prefill",
             "keep_prefill_padded", "keep_decode", "keep_precompute_group", "keep_precompute_groups",
+            "keep_dequantize_int4", "keep_attach_int4",
             "keep_memory_create", "keep_memory_destroy", "keep_memory_last_error",
             "keep_memory_put", "keep_memory_remove", "keep_memory_end_step", "keep_memory_unit_count",
             "keep_memory_unit_info", "keep_memory_unit_tokens", "keep_memory_mark_computed")
@@ -48,6 +49,17 @@ _W_NAMES = ("ln1", "wq", "wk", "wv", "bq", "bk", "bv", "wo", "ln2", "wgate", "wu
 
 class LayerWeights(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in _W_NAMES]
+
+
+_W4_NAMES = ("wq", "wk", "wv", "wo", "wgate", "wup", "wdown")
+
+
+class Int4Matrix(C.Structure):
+    _fields_ = [("codes", C.c_void_p), ("scale_zero", C.c_void_p)]
+
+
+class LayerWeightsInt4(C.Structure):
+    _fields_ = [(n, Int4Matrix) for n in _W4_NAMES]
 
 
 class Prompt(C.Structure):
@@ -117,6 +129,10 @@ def load_library() -> C.CDLL:
                                         C.POINTER(Report)]
     lib.keep_decode.restype = i32
     lib.keep_decode.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, pi32, vp, pi32]
+    lib.keep_dequantize_int4.restype = i32
+    lib.keep_dequantize_int4.argtypes = [vp, vp, i32, i32, vp, vp]
+    lib.keep_attach_int4.restype = i32
+    lib.keep_attach_int4.argtypes = [vp, C.POINTER(LayerWeightsInt4)]
     lib.keep_precompute_group.restype = i32
     lib.keep_precompute_group.argtypes = [vp, pi32, i32, vp, vp, C.POINTER(Report)]
     lib.keep_precompute_groups.restype = i32
@@ -200,6 +216,21 @@ class KeepPrompt:
         return sum(self.group_len[g] for g in groups) + self.instr_len
 
 
+def dequantize_int4(codes: torch.Tensor, scale_zero: torch.Tensor, stream=None) -> torch.Tensor:
+    """keep_dequantize_int4: codes [rows, K/2] uint8, scale_zero [rows, K/128] int32/uint32 words (device) ->
+    the bfloat16 weights [rows, K] (new device tensor; the allocation is the only thing done here)."""
+    lib = load_library()
+    assert codes.is_cuda and codes.is_contiguous() and codes.dtype == torch.uint8
+    assert scale_zero.is_cuda and scale_zero.is_contiguous() and scale_zero.element_size() == 4
+    rows, k = codes.shape[0], codes.shape[1] * 2
+    out = torch.empty((rows, k), dtype=torch.bfloat16, device=codes.device)
+    st = lib.keep_dequantize_int4(codes.data_ptr(), scale_zero.data_ptr(), rows, k, out.data_ptr(),
+                                  _stream_handle(stream if stream is not None else torch.cuda.current_stream()))
+    if st != KEEP_OK:
+        raise KeepError(st, lib.keep_last_error(None).decode())
+    return out
+
+
 class KeepContext:
     """keep_ctx handle.  Weights: list of dicts name -> device tensor (or None for absent biases)."""
 
@@ -239,6 +270,23 @@ class KeepContext:
             self.close()
         except Exception:
             pass
+
+    def attach_int4(self, layers4: Optional[List[dict]]):
+        """keep_attach_int4.  layers4: per layer a dict name -> (codes, scale_zero) device tensors for the seven
+        projections, or None to detach.  The tensors are kept alive by this object."""
+        if layers4 is None:
+            self._check(self.lib.keep_attach_int4(self.handle, None))
+            self._keep4 = None
+            return
+        arr = (LayerWeightsInt4 * self.shape.n_layers)()
+        for l, w in enumerate(layers4):
+            for n in _W4_NAMES:
+                codes, sz = w[n]
+                assert codes.is_cuda and codes.is_contiguous() and sz.is_cuda and sz.is_contiguous(), n
+                getattr(arr[l], n).codes = codes.data_ptr()
+                getattr(arr[l], n).scale_zero = sz.data_ptr()
+        self._check(self.lib.keep_attach_int4(self.handle, arr))
+        self._keep4 = layers4
 
     @property
     def uses_mfma(self) -> bool:

@@ -52,6 +52,7 @@ static inline size_t table_block_bytes(size_t G) { return table_seg_offset_ints(
 struct keep_ctx {
   keep_model_desc d;
   std::vector<keep_layer_weights> w;
+  std::vector<keep_layer_weights_int4> w4;  // empty: no INT4 form attached
   const void* embed = nullptr;
   hipStream_t s_comp = nullptr, s_eval = nullptr, s_copy = nullptr;
   bool mfma = false;
@@ -121,6 +122,17 @@ keep_status fail(keep_ctx* c, keep_status st, const char* fmt, ...) {
     if (e__ != hipSuccess)                                                                           \
       return fail((c), KEEP_ERR_HIP, "%s failed: %s (%s:%d)", #expr, hipGetErrorString(e__), __FILE__, __LINE__); \
   } while (0)
+
+// INT4 form of a GEMM's weight parts, where the context has one
+inline void set_w4(GemmB& b, int part, const keep_int4_matrix& m) {
+  b.has_w4 = true;
+  b.w4_codes[part] = m.codes;
+  b.w4_scale_zero[part] = m.scale_zero;
+}
+inline void set_w4_b2(GemmB& b, const keep_int4_matrix& m) {
+  b.w4_codes_b2 = m.codes;
+  b.w4_scale_zero_b2 = m.scale_zero;
+}
 
 keep_status check_desc(const keep_model_desc* d, const char** why) {
   *why = "";
@@ -392,12 +404,17 @@ keep_status layer_front(keep_ctx* c, const PromptInfo& pi, int layer, const Laye
   }
   launch_rmsnorm<T>(x, Typed<T>::p(w.ln1), n, d.hidden, d.rms_eps, Typed<T>::p(c->hbuf), s);
   if (evs && !c->ev_light) HIP_TRY(c, hipEventRecord(evs[2], s));
-  GemmB b;
+  GemmB b{};
   b.n_parts = 3;
   b.ptr[0] = w.wq; b.ptr[1] = w.wk; b.ptr[2] = w.wv;
   b.bias[0] = w.bq; b.bias[1] = w.bk; b.bias[2] = w.bv;
   b.n_rows[0] = d.n_q_heads * d.head_dim;
   b.n_rows[1] = b.n_rows[2] = d.n_kv_heads * d.head_dim;
+  if (!c->w4.empty()) {
+    set_w4(b, 0, c->w4[layer].wq);
+    set_w4(b, 1, c->w4[layer].wk);
+    set_w4(b, 2, c->w4[layer].wv);
+  }
   const int n_qkv = b.n_rows[0] + 2 * b.n_rows[1];
   if (c->mfma)
     launch_gemm_mfma(reinterpret_cast<const bf16_t*>(c->hbuf), n, d.hidden, b, nullptr, n_qkv, EPI_STORE_F32, nullptr,
@@ -473,6 +490,12 @@ keep_status layer_back(keep_ctx* c, int layer, int n, const void* o_rows, const 
   GemmB bo{}; bo.n_parts = 1; bo.ptr[0] = w.wo; bo.n_rows[0] = d.hidden;
   GemmB bg{}; bg.n_parts = 1; bg.ptr[0] = w.wgate; bg.n_rows[0] = d.ffn_dim;
   GemmB bd{}; bd.n_parts = 1; bd.ptr[0] = w.wdown; bd.n_rows[0] = d.hidden;
+  if (!c->w4.empty()) {
+    set_w4(bo, 0, c->w4[layer].wo);
+    set_w4(bg, 0, c->w4[layer].wgate);
+    set_w4_b2(bg, c->w4[layer].wup);
+    set_w4(bd, 0, c->w4[layer].wdown);
+  }
 #define EV(i) \
   if (evs && (!c->ev_light || (i) == 7 || (i) == 8)) HIP_TRY(c, hipEventRecord(evs[i], s))
   EV(12);
@@ -625,12 +648,17 @@ keep_status decode_impl(keep_ctx* c, const void* final_norm, const void* lm_head
         att_plan.valid = false;
       }
       launch_rmsnorm<T>(Typed<T>::p(x_cur), Typed<T>::p(w.ln1), 1, d.hidden, d.rms_eps, Typed<T>::p(c->hbuf), s);
-      GemmB b;
+      GemmB b{};
       b.n_parts = 3;
       b.ptr[0] = w.wq; b.ptr[1] = w.wk; b.ptr[2] = w.wv;
       b.bias[0] = w.bq; b.bias[1] = w.bk; b.bias[2] = w.bv;
       b.n_rows[0] = d.n_q_heads * d.head_dim;
       b.n_rows[1] = b.n_rows[2] = d.n_kv_heads * d.head_dim;
+      if (!c->w4.empty()) {
+        set_w4(b, 0, c->w4[l].wq);
+        set_w4(b, 1, c->w4[l].wk);
+        set_w4(b, 2, c->w4[l].wv);
+      }
       const int n_qkv = b.n_rows[0] + 2 * b.n_rows[1];
       if (c->mfma)
         launch_gemm_mfma(reinterpret_cast<const bf16_t*>(c->hbuf), 1, d.hidden, b, nullptr, n_qkv, EPI_STORE_F32,
@@ -1153,6 +1181,35 @@ keep_status keep_decode(keep_ctx* c, const void* final_norm, const void* lm_head
     return decode_impl<T>(c, final_norm, lm_head, x_last, k_cache, v_cache, cache_rows, n_ctx, n_new, tokens_out,
                           logits_out, forced_tokens);
   });
+}
+
+keep_status keep_dequantize_int4(const void* codes, const void* scale_zero, int32_t rows, int32_t K, void* out,
+                                 void* stream) {
+  if (!codes || !scale_zero || !out) return fail(nullptr, KEEP_ERR_INVALID_ARG, "codes / scale_zero / out is NULL");
+  if (rows < 1 || K < 128 || K % 128)
+    return fail(nullptr, KEEP_ERR_INVALID_ARG, "rows %d must be positive and K %d a positive multiple of 128", rows, K);
+  launch_dequant_int4(codes, scale_zero, rows, K, out, reinterpret_cast<hipStream_t>(stream));
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(nullptr, KEEP_ERR_HIP, "dequantisation launch failed: %s", hipGetErrorString(e));
+  return KEEP_OK;
+}
+
+keep_status keep_attach_int4(keep_ctx* c, const keep_layer_weights_int4* layers) {
+  if (!c) return KEEP_ERR_INVALID_ARG;
+  if (!layers) {
+    c->w4.clear();
+    return KEEP_OK;
+  }
+  if (!c->mfma) return fail(c, KEEP_ERR_UNSUPPORTED, "the INT4 form is read by the bf16 matrix-core path only");
+  if (c->d.hidden % 128 || c->d.ffn_dim % 128 || (c->d.n_q_heads * c->d.head_dim) % 128)
+    return fail(c, KEEP_ERR_SHAPE, "hidden, ffn_dim and n_q_heads * head_dim must be multiples of the group length 128");
+  for (int l = 0; l < c->d.n_layers; ++l) {
+    const keep_layer_weights_int4& w = layers[l];
+    for (const keep_int4_matrix* m : {&w.wq, &w.wk, &w.wv, &w.wo, &w.wgate, &w.wup, &w.wdown})
+      if (!m->codes || !m->scale_zero) return fail(c, KEEP_ERR_INVALID_ARG, "an INT4 pointer of layer %d is NULL", l);
+  }
+  c->w4.assign(layers, layers + c->d.n_layers);
+  return KEEP_OK;
 }
 
 keep_status keep_precompute_group(keep_ctx* c, const int32_t* token_ids, int32_t n_tokens, void* k_blocks,

@@ -155,9 +155,180 @@ __global__ void __launch_bounds__(256)
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// INT4 weight-only variant (Section 6.1: the 32B model runs with INT4 weight-only quantisation).
+// The weights the model computes with are  w = bf16((q - z) * s)  per group of 128 input features
+// (codes q and zero z of 4 bits, scale s in bf16).  Launches of at most 64 rows are bound by
+// reading the weights, so they read the 4-bit form (a quarter of the bytes) and expand it in
+// registers to exactly those bf16 values; launches with many rows are bound by the matrix cores
+// and use a bf16 copy expanded once by k_dequant_int4.
+//
+// Storage: codes [rows, K/2] bytes, within a run of 8 features byte t holds feature t (low nibble)
+// and feature t + 4 (high nibble); one 32-bit word per (row, group): scale bits | zero << 16.
+// ---------------------------------------------------------------------------------------------
+constexpr int W4_GROUP = 128;
+
+// Eight weights of one code word -> 8 bf16 (4 packed words), in feature order.
+// (q - z) * s has <= 13 significant bits, so fma(q, s, -z*s) is exact and the only rounding is the
+// conversion to bf16 (round to nearest even).
+__device__ __forceinline__ void w4_expand8(uint32_t d, float sc, float nzs, uint32_t out[4]) {
+  const uint32_t lo = d & 0x0F0F0F0Fu, hi = (d >> 4) & 0x0F0F0F0Fu;
+  float f[8];
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    f[t] = __builtin_fmaf((float)((lo >> (8 * t)) & 0xFFu), sc, nzs);
+    f[t + 4] = __builtin_fmaf((float)((hi >> (8 * t)) & 0xFFu), sc, nzs);
+  }
+#pragma unroll
+  for (int t = 0; t < 4; ++t) out[t] = pack_bf16x2(f[2 * t], f[2 * t + 1]);
+}
+
+__device__ __forceinline__ void w4_scale_zero(uint32_t word, float& sc, float& nzs) {
+  sc = __uint_as_float(word << 16);
+  nzs = -(float)((word >> 16) & 0xFu) * sc;  // exact: 4 bits times 8 bits
+}
+
+// out[r, 8 j .. 8 j + 7] for one code word per thread
+__global__ void __launch_bounds__(256)
+    k_dequant_int4(const uint32_t* __restrict__ codes, const uint32_t* __restrict__ scale_zero, long n_words,
+                   int words_per_row, uint4* __restrict__ out) {
+  const long i = (long)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n_words) return;
+  const long r = i / words_per_row;
+  const int j = (int)(i - r * words_per_row);
+  float sc, nzs;
+  w4_scale_zero(scale_zero[r * (words_per_row / (W4_GROUP / 8)) + j / (W4_GROUP / 8)], sc, nzs);
+  uint32_t o[4];
+  w4_expand8(codes[i], sc, nzs, o);
+  out[i] = make_uint4(o[0], o[1], o[2], o[3]);
+}
+
+void launch_dequant_int4(const void* codes, const void* scale_zero, int32_t rows, int32_t K, void* out, hipStream_t s) {
+  const long n_words = (long)rows * (K / 8);
+  if (n_words <= 0) return;
+  hipLaunchKernelGGL(k_dequant_int4, dim3((unsigned)((n_words + 255) / 256)), dim3(256), 0, s,
+                     reinterpret_cast<const uint32_t*>(codes), reinterpret_cast<const uint32_t*>(scale_zero), n_words,
+                     K / 8, reinterpret_cast<uint4*>(out));
+}
+
+struct SkinnyW4 {
+  const uint8_t* codes[3];
+  const uint32_t* sz[3];
+  int32_t begin[4];  // first output column of each part; unused parts never match
+};
+
+// Same work split as k_gemm_skinny, but a wave step covers one quantisation group (128 input features):
+// the half-wave g reads the 32 code bytes of features 64 g .. 64 g + 63 of each of its two weight rows
+// (two 16-byte loads per row) and one scale/zero word per row; code words are requested two steps
+// ahead (three register buffers), activations one step ahead (from L2).
+// (with two row tiles the registers of one workgroup per CU are needed: three code buffers, 16 activation
+// fragments and 64 accumulators)
+template <int MT>
+__global__ void __launch_bounds__(256, MT == 1 ? 2 : 1)
+    k_gemm_skinny_w4(const bf16_t* __restrict__ A, int M, int K, SkinnyW4 B, int n_rows_b, int n_splits,
+                     float* __restrict__ part, int ld) {
+  __shared__ float s_red[4][MT * 32][SK_BN + 1];
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int g = lane >> 5, lq = lane & 31;
+  const int n0 = blockIdx.x * SK_BN;
+  const int z = blockIdx.y;
+  const int steps = K / W4_GROUP;
+  const int s_begin = (int)((long)z * steps / n_splits), s_end = (int)((long)(z + 1) * steps / n_splits);
+
+  const uint8_t* cp[2];
+  const uint32_t* zp[2];
+#pragma unroll
+  for (int ct = 0; ct < 2; ++ct) {
+    const int n = min(n0 + ct * 32 + lq, n_rows_b - 1);
+    int p = 0;
+    if (n >= B.begin[1]) p = 1;
+    if (n >= B.begin[2]) p = 2;
+    const size_t r = (size_t)(n - B.begin[p]);
+    cp[ct] = B.codes[p] + r * (size_t)(K / 2) + 32 * g;
+    zp[ct] = B.sz[p] + r * (size_t)steps;
+  }
+  const bf16_t* ap[MT];
+#pragma unroll
+  for (int rt = 0; rt < MT; ++rt) ap[rt] = A + (size_t)min(rt * 32 + lq, M - 1) * K + 64 * g;
+
+  f32x16 acc[MT][2];
+#pragma unroll
+  for (int rt = 0; rt < MT; ++rt)
+#pragma unroll
+    for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[rt][ct][e] = 0.f;
+
+  uint4 cw[3][2][2];   // code words: [buffer][weight row][half of the 32 bytes]
+  uint32_t zw[3][2];   // scale / zero words
+  bf16x8 a[MT][8];
+#define W4_LOAD(BUF, STEP)                                                                          \
+  {                                                                                                 \
+    _Pragma("unroll") for (int ct = 0; ct < 2; ++ct) {                                              \
+      const uint4* src_ = reinterpret_cast<const uint4*>(cp[ct] + (size_t)(STEP) * (W4_GROUP / 2)); \
+      cw[BUF][ct][0] = src_[0];                                                                     \
+      cw[BUF][ct][1] = src_[1];                                                                     \
+      zw[BUF][ct] = zp[ct][STEP];                                                                   \
+    }                                                                                               \
+  }
+#define W4_COMPUTE(BUF, STEP)                                                                       \
+  {                                                                                                 \
+    _Pragma("unroll") for (int rt = 0; rt < MT; ++rt) _Pragma("unroll") for (int c = 0; c < 8; ++c) \
+        a[rt][c] = *reinterpret_cast<const bf16x8*>(ap[rt] + (size_t)(STEP) * W4_GROUP + 8 * c);    \
+    _Pragma("unroll") for (int ct = 0; ct < 2; ++ct) {                                              \
+      float sc_, nzs_;                                                                              \
+      w4_scale_zero(zw[BUF][ct], sc_, nzs_);                                                        \
+      const uint32_t d_[8] = {cw[BUF][ct][0].x, cw[BUF][ct][0].y, cw[BUF][ct][0].z, cw[BUF][ct][0].w, \
+                              cw[BUF][ct][1].x, cw[BUF][ct][1].y, cw[BUF][ct][1].z, cw[BUF][ct][1].w}; \
+      _Pragma("unroll") for (int c = 0; c < 8; ++c) {                                               \
+        uint32_t o_[4];                                                                             \
+        w4_expand8(d_[c], sc_, nzs_, o_);                                                           \
+        typedef uint32_t u32x4_ __attribute__((ext_vector_type(4)));                                \
+        const u32x4_ ov_ = {o_[0], o_[1], o_[2], o_[3]};                                            \
+        const bf16x8 b_ = __builtin_bit_cast(bf16x8, ov_);                                          \
+        _Pragma("unroll") for (int rt = 0; rt < MT; ++rt) acc[rt][ct] =                             \
+            __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[rt][c], b_, acc[rt][ct], 0, 0, 0);            \
+      }                                                                                             \
+    }                                                                                               \
+  }
+  // this wave's steps: s_begin + wave, + 4, ...
+  const int first = s_begin + wave;
+  const int n_i = first < s_end ? (s_end - first + 3) / 4 : 0;
+  if (n_i > 0) W4_LOAD(0, first)
+  if (n_i > 1) W4_LOAD(1, first + 4)
+  for (int i = 0; i < n_i;) {  // three steps per trip so that the register buffers keep fixed names
+    if (i + 2 < n_i) W4_LOAD(2, first + 4 * (i + 2))
+    W4_COMPUTE(0, first + 4 * i)
+    if (++i >= n_i) break;
+    if (i + 2 < n_i) W4_LOAD(0, first + 4 * (i + 2))
+    W4_COMPUTE(1, first + 4 * i)
+    if (++i >= n_i) break;
+    if (i + 2 < n_i) W4_LOAD(1, first + 4 * (i + 2))
+    W4_COMPUTE(2, first + 4 * i)
+    ++i;
+  }
+#undef W4_LOAD
+#undef W4_COMPUTE
+
+#pragma unroll
+  for (int rt = 0; rt < MT; ++rt)
+#pragma unroll
+    for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) s_red[wave][rt * 32 + 8 * (e >> 2) + 4 * g + (e & 3)][ct * 32 + lq] = acc[rt][ct][e];
+  __syncthreads();
+  float* dst = part + (size_t)z * M * ld;
+  for (int i = tid; i < MT * 32 * SK_BN; i += 256) {
+    const int r = i / SK_BN, cidx = i % SK_BN;
+    const float v = (s_red[0][r][cidx] + s_red[1][r][cidx]) + (s_red[2][r][cidx] + s_red[3][r][cidx]);
+    if (r < M && n0 + cidx < n_rows_b) dst[(size_t)r * ld + n0 + cidx] = v;
+  }
+}
+
 bool gemm_skinny_fits(int32_t M, int32_t K, const GemmB& B, int32_t N, int epilogue) {
   const long rows = epilogue == EPI_SWIGLU_STORE ? 2L * N : N;
   const long ld = (rows + SK_BN - 1) / SK_BN * SK_BN;
+  if (B.has_w4 && K % W4_GROUP) return false;
   return M >= 1 && M <= 64 && K % SK_KSTEP == 0 && K >= SK_KSTEP && rows < (1L << 24) &&
          (size_t)M * (size_t)ld <= SK_MAX_PART_FLOATS && (epilogue != EPI_SWIGLU_STORE || B.n_parts == 1);
 }
@@ -182,7 +353,7 @@ void launch_gemm_skinny(const bf16_t* A, int32_t M, int32_t K, const GemmB& B, c
   const int tiles = (rows + SK_BN - 1) / SK_BN;
   const int ld = tiles * SK_BN;
   const int mt = M <= 32 ? 1 : 2;
-  const int steps = K / SK_KSTEP;
+  const int steps = B.has_w4 ? K / W4_GROUP : K / SK_KSTEP;
   // enough K slices for ~2048 waves (8 per CU), at least 4 steps per workgroup, partials within the workspace
   int splits = (512 + tiles - 1) / tiles;
   splits = std::min(splits, std::max(1, steps / 4));
@@ -190,7 +361,23 @@ void launch_gemm_skinny(const bf16_t* A, int32_t M, int32_t K, const GemmB& B, c
   splits = std::max(splits, 1);
   float* part = reinterpret_cast<float*>(ws);
   const dim3 grid(tiles, splits);
-  if (mt == 1)
+  if (B.has_w4) {
+    SkinnyW4 q;
+    for (int p = 0; p < 3; ++p) {
+      q.codes[p] = reinterpret_cast<const uint8_t*>(B.w4_codes[p]);
+      q.sz[p] = reinterpret_cast<const uint32_t*>(B.w4_scale_zero[p]);
+      q.begin[p] = b.begin[p];
+    }
+    q.begin[3] = b.begin[3];
+    if (epilogue == EPI_SWIGLU_STORE) {  // the up rows are the second part
+      q.codes[1] = reinterpret_cast<const uint8_t*>(B.w4_codes_b2);
+      q.sz[1] = reinterpret_cast<const uint32_t*>(B.w4_scale_zero_b2);
+    }
+    if (mt == 1)
+      hipLaunchKernelGGL(k_gemm_skinny_w4<1>, grid, dim3(256), 0, s, A, M, K, q, rows, splits, part, ld);
+    else
+      hipLaunchKernelGGL(k_gemm_skinny_w4<2>, grid, dim3(256), 0, s, A, M, K, q, rows, splits, part, ld);
+  } else if (mt == 1)
     hipLaunchKernelGGL(k_gemm_skinny<1>, grid, dim3(256), 0, s, A, M, K, b, rows, splits, part, ld);
   else
     hipLaunchKernelGGL(k_gemm_skinny<2>, grid, dim3(256), 0, s, A, M, K, b, rows, splits, part, ld);

@@ -77,6 +77,13 @@ struct GemmB {
   const void* bias[3];  // unused by the GEMM itself
   int32_t n_rows[3];
   int32_t n_parts;
+  // INT4 form of the same parts (codes, scale/zero words) and of the second operand of the SwiGLU
+  // epilogue; read instead of `ptr` by the launches that stream the weights (at most 64 rows)
+  bool has_w4;
+  const void* w4_codes[3];
+  const void* w4_scale_zero[3];
+  const void* w4_codes_b2;
+  const void* w4_scale_zero_b2;
 };
 
 // ---------------------------------------------------------------------------
@@ -134,6 +141,8 @@ void launch_score_finish(const float* rowmass, const int32_t* d_row_start, int32
 size_t gemm_ws_bytes();
 void launch_gemm_mfma(const bf16_t* A, int32_t M, int32_t K, const GemmB& B, const void* B2, int32_t N, int epilogue,
                       const bf16_t* residual, void* C, hipStream_t s, void* skinny_ws = nullptr);
+// bf16 expansion of an INT4 matrix: out[rows, K] = bf16((code - zero) * scale)
+void launch_dequant_int4(const void* codes, const void* scale_zero, int32_t rows, int32_t K, void* out, hipStream_t s);
 size_t gemm_skinny_ws_bytes();
 bool gemm_skinny_fits(int32_t M, int32_t K, const GemmB& B, int32_t N, int epilogue);
 void launch_gemm_skinny(const bf16_t* A, int32_t M, int32_t K, const GemmB& B, const void* B2, int32_t N, int epilogue,

@@ -19,7 +19,7 @@ def _declared_functions():
             continue
         text = open(os.path.join(inc, h)).read()
         text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-        names |= set(re.findall(r"\b(keep_[a-z_]+)\s*\(", text))
+        names |= set(re.findall(r"\b(keep_[a-z0-9_]+)\s*\(", text))
     return sorted(names)
 
 
