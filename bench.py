@@ -50,6 +50,9 @@ def parse():
                          "greedy decode steps over the joined cache")
     ap.add_argument("--memory-update", action="store_true",
                     help="measure the cost of one memory update on the workload's model shape instead of the prefill")
+    ap.add_argument("--int4", action="store_true",
+                    help="with --decode-tokens / --memory-update: INT4 weight-only projections (the launches of at "
+                         "most 64 rows read the 4-bit form; the bf16 weights are its expansion)")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="launch one device copy of this many MiB before the warm-up: the known-size "
                          "kernel that scales rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
@@ -124,7 +127,9 @@ def decode_bench(ctx, prompt, ratios, w, s, n_tokens, budget_mode, a, torch, dt)
     ms_tok = (ms_all - ms_first) / k
     esz = 2 if s.storage == "bf16" else 4
     qd, kvd = s.n_q_heads * s.head_dim, s.n_kv_heads * s.head_dim
-    w_layer = (s.hidden * (qd + 2 * kvd) + qd * s.hidden + 3 * s.hidden * s.ffn_dim) * esz
+    n_w = s.hidden * (qd + 2 * kvd) + qd * s.hidden + 3 * s.hidden * s.ffn_dim
+    # INT4 form: half a byte per weight + one 4-byte scale/zero word per 128 weights
+    w_layer = n_w * esz if not a.int4 else n_w // 2 + n_w // 128 * 4
     head = s.vocab * s.hidden * esz
     cache = 2.0 * (n_tokens + k / 2.0) * kvd * esz
     bytes_tok = s.n_layers * (w_layer + cache) + head
@@ -134,8 +139,9 @@ def decode_bench(ctx, prompt, ratios, w, s, n_tokens, budget_mode, a, torch, dt)
             "bytes_per_token": int(bytes_tok), "hbm": {"bound": "hbm", "achieved": round(bytes_tok / (ms_tok * 1e-3) / 1e9, 1),
                                                        "peak": PEAK_HBM_GBS, "unit": "GB/s",
                                                        "frac": round(bytes_tok / (ms_tok * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)},
-            "first_token_gbs": round(head / (ms_first * 1e-3) / 1e9, 1), "dtype": s.storage, "data": "synthetic",
-            "tokens": toks[:8]}
+            "first_token_gbs": round(head / (ms_first * 1e-3) / 1e9, 1), "dtype": s.storage,
+            "weights": "int4 weight-only (group 128) for the projections, bf16 LM head" if a.int4 else s.storage,
+            "data": "synthetic", "tokens": toks[:8]}
 
 
 def memory_update_cost(ctx, w, torch, steps, warmup):
@@ -283,15 +289,31 @@ def main():
     gate = ProfilerGate()
     gate.pause()                    # set-up (weights, group caches) is not part of the measurement
     t_setup = time.perf_counter()
-    layers = [ks.make_layer_weights(s, l, "cuda") for l in range(s.n_layers)]
+    layers4 = None
+    if a.int4:
+        # weights arrive quantised; the library expands them to the bf16 values the model computes with
+        layers4 = [ks.make_int4_layer_on_device(s, l, "cuda") for l in range(s.n_layers)]
+        layers = []
+        for l in range(s.n_layers):
+            wl = {n: kb.dequantize_int4(*layers4[l][n]) for n in ks.INT4_MATS}
+            wl["ln1"] = torch.ones(s.hidden, dtype=dt, device="cuda")
+            wl["ln2"] = torch.ones(s.hidden, dtype=dt, device="cuda")
+            wl["bq"] = wl["bk"] = wl["bv"] = None
+            layers.append(wl)
+    else:
+        layers = [ks.make_layer_weights(s, l, "cuda") for l in range(s.n_layers)]
     embed = ks.make_embedding(s, "cuda")
     ids = ks.make_token_ids(n_tokens, s.vocab, 0)
     streams = [torch.cuda.Stream() for _ in range(3)]
     torch.cuda.synchronize()
     ctx = KeepContext(s, layers, embed, n_tokens + a.decode_tokens + 1, G, kb.KEEP_KERNELS_AUTO, *streams)
+    if layers4 is not None:
+        ctx.attach_int4(layers4)
     if a.memory_update:
         gate.resume()
-        print(json.dumps(memory_update_cost(ctx, w, torch, a.steps, a.warmup)))
+        res = memory_update_cost(ctx, w, torch, a.steps, a.warmup)
+        res["weights"] = "int4 weight-only (group 128) where a launch has at most 64 rows" if a.int4 else s.storage
+        print(json.dumps(res))
         return
     if a.random_cache:
         kb_all = torch.empty((s.n_layers, w.mem_tokens, s.n_kv_heads, s.head_dim), dtype=dt, device="cuda")

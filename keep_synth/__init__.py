@@ -25,4 +25,5 @@ from .gen import (
     pack_int4_codes,
     make_int4_matrix,
     make_int4_layer,
+    make_int4_layer_on_device,
 )

@@ -176,6 +176,24 @@ def make_int4_layer(s: ModelShape, layer: int, std: float = 0.02) -> Dict[str, D
             for i, name in enumerate(INT4_MATS)}
 
 
+def make_int4_layer_on_device(s: ModelShape, layer: int, device: str = "cuda", std: float = 0.02):
+    """Full-size stand-in drawn on the device (the numpy draws above take minutes at 14B/32B shapes):
+    uniform code bytes, zero point 7 or 8, bf16 scale std / 4.6 * U[0.75, 1.25] (uniform codes have a
+    standard deviation of 4.6).  Returns name -> (codes uint8 [rows, K/2], scale_zero int32 [rows, K/128])."""
+    g = torch.Generator(device=device)
+    g.manual_seed(7000 + layer)
+    shapes = layer_weight_shapes(s)
+    out = {}
+    for name in INT4_MATS:
+        rows, k = shapes[name]
+        codes = torch.randint(0, 256, (rows, k // 2), generator=g, device=device, dtype=torch.uint8)
+        zero = torch.randint(7, 9, (rows, k // INT4_GROUP), generator=g, device=device, dtype=torch.int32)
+        scale = (std / 4.6) * (0.75 + 0.5 * torch.rand((rows, k // INT4_GROUP), generator=g, device=device))
+        bits = scale.to(torch.bfloat16).view(torch.int16).to(torch.int32) & 0xFFFF
+        out[name] = (codes, (bits | (zero << 16)).contiguous())
+    return out
+
+
 # ----------------------------------------------------------------------------
 # random stand-ins for cached K/V blocks and hidden rows (teacher-forced layer tests)
 # ----------------------------------------------------------------------------

@@ -11,7 +11,10 @@
 // lines.  Which K index feeds which MFMA slot is free as long as A and B agree, so the lane's 32
 // K values are simply its four 16-byte chunks in order.  The four waves' partial tiles are added
 // through LDS and written as fp32 partials [S][M][ld]; a second kernel adds the S slices in
-// order (no atomics: reproducible) and applies the epilogue.
+// order (no atomics: reproducible) and applies the epilogue.  (Letting the workgroup that finishes a
+// column tile last do that sum instead, found by a ticket counter, was measured and dropped: the
+// device-wide release each workgroup then needs before it draws its ticket writes back the XCD's L2,
+// which made a one-row launch 3x slower.)
 #include <algorithm>
 
 #include "keep_internal.h"
@@ -31,6 +34,32 @@ constexpr int SK_KSTEP = 64;    // K per wave step
 constexpr size_t SK_MAX_PART_FLOATS = (size_t)64 * 65536;  // capacity of the partials workspace
 
 size_t gemm_skinny_ws_bytes() { return SK_MAX_PART_FLOATS * sizeof(float); }
+
+struct SkinnyEpi {       // what the finishing pass needs
+  int epilogue;          // GemmEpilogue
+  int N;                 // output columns (SwiGLU: gate and up each have N)
+  const bf16_t* residual;
+  void* C;
+};
+
+// One output element from the S slices, summed in slice order.
+__device__ __forceinline__ void skinny_store(const float* __restrict__ part, int n_splits, int ld, int M, int m, int n,
+                                             const SkinnyEpi& e) {
+  float s0 = 0.f, s1 = 0.f;
+  for (int z = 0; z < n_splits; ++z) {
+    const float* p = part + ((size_t)z * M + m) * ld;
+    s0 += p[n];
+    if (e.epilogue == EPI_SWIGLU_STORE) s1 += p[e.N + n];
+  }
+  const size_t idx = (size_t)m * e.N + n;
+  if (e.epilogue == EPI_STORE_F32) {
+    reinterpret_cast<float*>(e.C)[idx] = s0;
+  } else if (e.epilogue == EPI_RESIDUAL_STORE) {
+    reinterpret_cast<bf16_t*>(e.C)[idx].bits = f32_to_bf16_bits(bf16_bits_to_f32(e.residual[idx].bits) + s0);
+  } else {
+    reinterpret_cast<bf16_t*>(e.C)[idx].bits = f32_to_bf16_bits(s0 / (1.0f + __expf(-s0)) * s1);
+  }
+}
 
 template <int MT>
 __global__ void __launch_bounds__(256, 2)
@@ -132,27 +161,12 @@ __global__ void __launch_bounds__(256, 2)
 }
 
 // C = epilogue(sum over the K slices, in slice order)
-template <int EPI>
 __global__ void __launch_bounds__(256)
-    k_skinny_finish(const float* __restrict__ part, int n_splits, int ld, int M, int N,
-                    const bf16_t* __restrict__ residual, void* __restrict__ Cv) {
+    k_skinny_finish(const float* __restrict__ part, int n_splits, int ld, int M, SkinnyEpi e) {
   const int n = blockIdx.x * 256 + threadIdx.x;
   const int m = blockIdx.y;
-  if (n >= N || m >= M) return;
-  float s0 = 0.f, s1 = 0.f;
-  for (int z = 0; z < n_splits; ++z) {
-    const float* p = part + ((size_t)z * M + m) * ld;
-    s0 += p[n];
-    if (EPI == EPI_SWIGLU_STORE) s1 += p[N + n];
-  }
-  const size_t idx = (size_t)m * N + n;
-  if (EPI == EPI_STORE_F32) {
-    reinterpret_cast<float*>(Cv)[idx] = s0;
-  } else if (EPI == EPI_RESIDUAL_STORE) {
-    reinterpret_cast<bf16_t*>(Cv)[idx].bits = f32_to_bf16_bits(bf16_bits_to_f32(residual[idx].bits) + s0);
-  } else {
-    reinterpret_cast<bf16_t*>(Cv)[idx].bits = f32_to_bf16_bits(s0 / (1.0f + __expf(-s0)) * s1);
-  }
+  if (n >= e.N || m >= M) return;
+  skinny_store(part, n_splits, ld, M, m, n, e);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -171,17 +185,19 @@ constexpr int W4_GROUP = 128;
 // Eight weights of one code word -> 8 bf16 (4 packed words), in feature order.
 // (q - z) * s has <= 13 significant bits, so fma(q, s, -z*s) is exact and the only rounding is the
 // conversion to bf16 (round to nearest even).
+// byte N of a word as a float (v_cvt_f32_ubyteN: the shift, the mask and the conversion in one instruction)
+#define W4_UBYTE(N, DST, SRC) asm("v_cvt_f32_ubyte" #N " %0, %1" : "=v"(DST) : "v"(SRC))
 __device__ __forceinline__ void w4_expand8(uint32_t d, float sc, float nzs, uint32_t out[4]) {
-  const uint32_t lo = d & 0x0F0F0F0Fu, hi = (d >> 4) & 0x0F0F0F0Fu;
+  const uint32_t lo = d & 0x0F0F0F0Fu, hi = (d >> 4) & 0x0F0F0F0Fu;  // features 0..3 and 4..7 as bytes
   float f[8];
+  W4_UBYTE(0, f[0], lo); W4_UBYTE(1, f[1], lo); W4_UBYTE(2, f[2], lo); W4_UBYTE(3, f[3], lo);
+  W4_UBYTE(0, f[4], hi); W4_UBYTE(1, f[5], hi); W4_UBYTE(2, f[6], hi); W4_UBYTE(3, f[7], hi);
 #pragma unroll
-  for (int t = 0; t < 4; ++t) {
-    f[t] = __builtin_fmaf((float)((lo >> (8 * t)) & 0xFFu), sc, nzs);
-    f[t + 4] = __builtin_fmaf((float)((hi >> (8 * t)) & 0xFFu), sc, nzs);
-  }
+  for (int t = 0; t < 8; ++t) f[t] = __builtin_fmaf(f[t], sc, nzs);
 #pragma unroll
   for (int t = 0; t < 4; ++t) out[t] = pack_bf16x2(f[2 * t], f[2 * t + 1]);
 }
+#undef W4_UBYTE
 
 __device__ __forceinline__ void w4_scale_zero(uint32_t word, float& sc, float& nzs) {
   sc = __uint_as_float(word << 16);
@@ -219,12 +235,9 @@ struct SkinnyW4 {
 
 // Same work split as k_gemm_skinny, but a wave step covers one quantisation group (128 input features):
 // the half-wave g reads the 32 code bytes of features 64 g .. 64 g + 63 of each of its two weight rows
-// (two 16-byte loads per row) and one scale/zero word per row; code words are requested two steps
-// ahead (three register buffers), activations one step ahead (from L2).
-// (with two row tiles the registers of one workgroup per CU are needed: three code buffers, 16 activation
-// fragments and 64 accumulators)
+// (two 16-byte loads per row) and one scale/zero word per row.
 template <int MT>
-__global__ void __launch_bounds__(256, MT == 1 ? 2 : 1)
+__global__ void __launch_bounds__(256, 2)
     k_gemm_skinny_w4(const bf16_t* __restrict__ A, int M, int K, SkinnyW4 B, int n_rows_b, int n_splits,
                      float* __restrict__ part, int ld) {
   __shared__ float s_red[4][MT * 32][SK_BN + 1];
@@ -259,10 +272,14 @@ __global__ void __launch_bounds__(256, MT == 1 ? 2 : 1)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[rt][ct][e] = 0.f;
 
-  uint4 cw[3][2][2];   // code words: [buffer][weight row][half of the 32 bytes]
-  uint32_t zw[3][2];   // scale / zero words
-  bf16x8 a[MT][8];
-#define W4_LOAD(BUF, STEP)                                                                          \
+  // Code words (the HBM stream) and, with one row tile, the activations are requested one step ahead in
+  // two register buffers; with two row tiles the activations (from L2) are single-buffered and requested
+  // before the next step's codes, so that waiting for them leaves the code loads in flight.
+  constexpr int AB = MT == 1 ? 2 : 1;
+  uint4 cw[2][2][2];   // [buffer][weight row][half of the 32 bytes]
+  uint32_t zw[2][2];   // scale / zero words
+  bf16x8 a[AB][MT][8];
+#define W4_LOAD_B(BUF, STEP)                                                                        \
   {                                                                                                 \
     _Pragma("unroll") for (int ct = 0; ct < 2; ++ct) {                                              \
       const uint4* src_ = reinterpret_cast<const uint4*>(cp[ct] + (size_t)(STEP) * (W4_GROUP / 2)); \
@@ -271,10 +288,13 @@ __global__ void __launch_bounds__(256, MT == 1 ? 2 : 1)
       zw[BUF][ct] = zp[ct][STEP];                                                                   \
     }                                                                                               \
   }
-#define W4_COMPUTE(BUF, STEP)                                                                       \
+#define W4_LOAD_A(BUF, STEP)                                                                        \
   {                                                                                                 \
     _Pragma("unroll") for (int rt = 0; rt < MT; ++rt) _Pragma("unroll") for (int c = 0; c < 8; ++c) \
-        a[rt][c] = *reinterpret_cast<const bf16x8*>(ap[rt] + (size_t)(STEP) * W4_GROUP + 8 * c);    \
+        a[(BUF) % AB][rt][c] = *reinterpret_cast<const bf16x8*>(ap[rt] + (size_t)(STEP) * W4_GROUP + 8 * c); \
+  }
+#define W4_COMPUTE(BUF)                                                                             \
+  {                                                                                                 \
     _Pragma("unroll") for (int ct = 0; ct < 2; ++ct) {                                              \
       float sc_, nzs_;                                                                              \
       w4_scale_zero(zw[BUF][ct], sc_, nzs_);                                                        \
@@ -287,27 +307,38 @@ __global__ void __launch_bounds__(256, MT == 1 ? 2 : 1)
         const u32x4_ ov_ = {o_[0], o_[1], o_[2], o_[3]};                                            \
         const bf16x8 b_ = __builtin_bit_cast(bf16x8, ov_);                                          \
         _Pragma("unroll") for (int rt = 0; rt < MT; ++rt) acc[rt][ct] =                             \
-            __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[rt][c], b_, acc[rt][ct], 0, 0, 0);            \
+            __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[(BUF) % AB][rt][c], b_, acc[rt][ct], 0, 0, 0); \
       }                                                                                             \
     }                                                                                               \
   }
-  // this wave's steps: s_begin + wave, + 4, ...
+  // This wave's steps: s_begin + wave, + 4, ... (n_i of them).  Every request is issued unconditionally
+  // (past the end the last step is requested again and never used): with no branch around the loads the
+  // compiler's wait counts are exact, and a step waits for its own operands only, not for the newer requests.
   const int first = s_begin + wave;
   const int n_i = first < s_end ? (s_end - first + 3) / 4 : 0;
-  if (n_i > 0) W4_LOAD(0, first)
-  if (n_i > 1) W4_LOAD(1, first + 4)
-  for (int i = 0; i < n_i;) {  // three steps per trip so that the register buffers keep fixed names
-    if (i + 2 < n_i) W4_LOAD(2, first + 4 * (i + 2))
-    W4_COMPUTE(0, first + 4 * i)
-    if (++i >= n_i) break;
-    if (i + 2 < n_i) W4_LOAD(0, first + 4 * (i + 2))
-    W4_COMPUTE(1, first + 4 * i)
-    if (++i >= n_i) break;
-    if (i + 2 < n_i) W4_LOAD(1, first + 4 * (i + 2))
-    W4_COMPUTE(2, first + 4 * i)
-    ++i;
+  if (n_i > 0) {
+    const int last = first + 4 * (n_i - 1);
+    int st = first;
+    W4_LOAD_A(0, st)
+    W4_LOAD_B(0, st)
+    for (int i = 0; i < n_i; i += 2) {  // two steps per trip so that the register buffers keep fixed names
+      int nx = min(st + 4, last);
+      if (AB == 2) W4_LOAD_A(1, nx)
+      W4_LOAD_B(1, nx)
+      W4_COMPUTE(0)
+      if (i + 1 >= n_i) break;
+      st = nx;
+      if (AB == 1) W4_LOAD_A(1, st)
+      nx = min(st + 4, last);
+      if (AB == 2) W4_LOAD_A(0, nx)
+      W4_LOAD_B(0, nx)
+      W4_COMPUTE(1)
+      st = nx;
+      if (AB == 1) W4_LOAD_A(0, st)
+    }
   }
-#undef W4_LOAD
+#undef W4_LOAD_A
+#undef W4_LOAD_B
 #undef W4_COMPUTE
 
 #pragma unroll
@@ -361,6 +392,11 @@ void launch_gemm_skinny(const bf16_t* A, int32_t M, int32_t K, const GemmB& B, c
   splits = std::max(splits, 1);
   float* part = reinterpret_cast<float*>(ws);
   const dim3 grid(tiles, splits);
+  SkinnyEpi e;
+  e.epilogue = epilogue;
+  e.N = N;
+  e.residual = residual;
+  e.C = C;
   if (B.has_w4) {
     SkinnyW4 q;
     for (int p = 0; p < 3; ++p) {
@@ -382,12 +418,7 @@ void launch_gemm_skinny(const bf16_t* A, int32_t M, int32_t K, const GemmB& B, c
   else
     hipLaunchKernelGGL(k_gemm_skinny<2>, grid, dim3(256), 0, s, A, M, K, b, rows, splits, part, ld);
   const dim3 fgrid((N + 255) / 256, M);
-  if (epilogue == EPI_STORE_F32)
-    hipLaunchKernelGGL(k_skinny_finish<EPI_STORE_F32>, fgrid, dim3(256), 0, s, part, splits, ld, M, N, residual, C);
-  else if (epilogue == EPI_RESIDUAL_STORE)
-    hipLaunchKernelGGL(k_skinny_finish<EPI_RESIDUAL_STORE>, fgrid, dim3(256), 0, s, part, splits, ld, M, N, residual, C);
-  else
-    hipLaunchKernelGGL(k_skinny_finish<EPI_SWIGLU_STORE>, fgrid, dim3(256), 0, s, part, splits, ld, M, N, residual, C);
+  hipLaunchKernelGGL(k_skinny_finish, fgrid, dim3(256), 0, s, part, splits, ld, M, e);
 }
 
 }  // namespace keep
