@@ -169,3 +169,57 @@ def test_int4_error_paths():
     from paper_2602_23592_amd.binding import LayerWeightsInt4
     arr = (LayerWeightsInt4 * 1)()
     assert ctx.lib.keep_attach_int4(ctx.handle, arr) == KEEP_ERR_INVALID_ARG
+
+
+def test_fullsize_projections_read_the_int4_form():
+    """One layer of the Qwen-14B shape (K = 5120 and 13 824, N up to 27 648): a 48-token unit cached on its own
+    (two row tiles per workgroup) and one decoded token (one row) with the 4-bit form attached, against the
+    oracle on the dequantised weights.  Codes are uniform draws here (the binomial recipe takes minutes at
+    this size on the host)."""
+    full = ks.workload("qwen14b_32k").shape
+    shape = ks.ModelShape(1, full.hidden, full.n_q_heads, full.n_kv_heads, full.head_dim, full.ffn_dim, 1031,
+                          full.rope_theta, full.rms_eps, "bf16")
+    sh = oracle_shape(shape)
+    dev4 = ks.make_int4_layer_on_device(shape, 0, "cuda", std=0.02)
+    wd = {n: dequantize_int4(*dev4[n]) for n in ks.INT4_MATS}
+    wo = {n: io.dequantize(dev4[n][0].cpu().numpy(), dev4[n][1].cpu().numpy().view(np.uint32)) for n in ks.INT4_MATS}
+    for n in ks.INT4_MATS:   # the library's expansion is the oracle's, bit for bit, at full size too
+        assert torch.equal(wd[n].cpu().view(torch.int16), torch.from_numpy(wo[n]).to(torch.bfloat16).view(torch.int16)), n
+    g = torch.Generator().manual_seed(5)
+    for n in ("ln1", "ln2"):
+        t = (1.0 + 0.1 * torch.randn(shape.hidden, generator=g)).to(torch.bfloat16)
+        wd[n], wo[n] = t.cuda(), ks.to_numpy_f64(t)
+    wd["bq"] = wd["bk"] = wd["bv"] = None
+    wo["bq"] = wo["bk"] = wo["bv"] = None
+    emb = torch.randn(shape.vocab, shape.hidden, generator=g).to(torch.bfloat16)
+    fn = torch.ones(shape.hidden, dtype=torch.bfloat16)
+    lm = (0.05 * torch.randn(shape.vocab, shape.hidden, generator=g)).to(torch.bfloat16)
+    n_unit, cap = 48, 52
+    ctx = KeepContext(shape, [wd], emb.cuda(), cap, 1)
+    assert ctx.uses_mfma
+    ctx.attach_int4([dev4])
+    ids = ks.make_token_ids(n_unit, shape.vocab, 9)
+    kc = torch.zeros((1, cap, shape.n_kv_heads, shape.head_dim), dtype=torch.bfloat16, device="cuda")
+    vc = torch.zeros_like(kc)
+    k = torch.empty((1, n_unit, shape.n_kv_heads, shape.head_dim), dtype=torch.bfloat16, device="cuda")
+    v = torch.empty_like(k)
+    ctx.precompute_group(ids, k, v)
+    kb, vb = ko.precompute_group_caches(sh, [wo], ks.to_numpy_f64(emb), ids, [n_unit])
+    assert max_rel(to_np(k[0]), kb[0][0]) < TOL and max_rel(to_np(v[0]), vb[0][0]) < TOL
+    # one decoded token over that unit as the context (K/V of the unit from the oracle, rounded to storage)
+    kc[0, :n_unit] = torch.from_numpy(kb[0][0]).to(torch.bfloat16).cuda()
+    vc[0, :n_unit] = torch.from_numpy(vb[0][0]).to(torch.bfloat16).cuda()
+    x_last = (0.5 * torch.randn(shape.hidden, generator=g)).to(torch.bfloat16)
+    logits = torch.empty((2, shape.vocab), dtype=torch.float32, device="cuda")
+    toks = ctx.decode(fn.cuda(), lm.cuda(), x_last.cuda(), kc, vc, n_unit, 2, logits_out=logits)
+    torch.cuda.synchronize()
+    kr = [np.concatenate([to_np(kc[0, :n_unit]), np.zeros((cap - n_unit,) + kb[0][0].shape[1:])])]
+    vr = [np.concatenate([to_np(vc[0, :n_unit]), np.zeros((cap - n_unit,) + vb[0][0].shape[1:])])]
+    _, rlg = ko.greedy_decode(sh, [wo], ks.to_numpy_f64(emb), ks.to_numpy_f64(fn), ks.to_numpy_f64(lm),
+                              ks.to_numpy_f64(x_last), kr, vr, n_unit, 2, forced_tokens=toks)
+    lg = to_np(logits)
+    for t in range(2):
+        e = max_rel(lg[t], rlg[t])
+        print("full-size int4 decode step", t, "logits %.2e" % e)
+        assert e < TOL
+    assert max_rel(to_np(kc[0, n_unit]), kr[0][n_unit]) < TOL and max_rel(to_np(vc[0, n_unit]), vr[0][n_unit]) < TOL
