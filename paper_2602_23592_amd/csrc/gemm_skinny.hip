@@ -385,11 +385,25 @@ void launch_gemm_skinny(const bf16_t* A, int32_t M, int32_t K, const GemmB& B, c
   const int ld = tiles * SK_BN;
   const int mt = M <= 32 ? 1 : 2;
   const int steps = B.has_w4 ? K / W4_GROUP : K / SK_KSTEP;
-  // enough K slices for ~2048 waves (8 per CU), at least 4 steps per workgroup, partials within the workspace
-  int splits = (512 + tiles - 1) / tiles;
-  splits = std::min(splits, std::max(1, steps / 4));
-  splits = std::min<long>(splits, (long)(SK_MAX_PART_FLOATS / ((size_t)M * ld)));
-  splits = std::max(splits, 1);
+  // K slices: the chip holds 512 workgroups at a time (two per CU), and a count just above a multiple of 512
+  // leaves most of it idle during the last round.  Among the slice counts that keep at least 4 steps per
+  // workgroup and fit the workspace, take the one with the least estimated time, in bytes at the streaming
+  // rate: per round of 512 workgroups their share of the weight bytes plus a fixed cost (a round's start-up
+  // and its reduction through LDS, ~2 us), plus the partials written and read back.
+  int smax = std::max(1, steps / 4);
+  smax = (int)std::min<long>(smax, (long)(SK_MAX_PART_FLOATS / ((size_t)M * ld)));
+  smax = std::max(1, std::min(smax, 64));
+  const double w_bytes = (double)rows * K * (B.has_w4 ? 0.53 : 2.0);
+  int splits = 1;
+  double best = 0.0;
+  for (int sp = 1; sp <= smax; ++sp) {
+    const long wgs = (long)tiles * sp;
+    const double est = (double)((wgs + 511) / 512) * (512.0 * (w_bytes / wgs) + 9.0e6) + 2.0 * M * (double)ld * sp * 4.0;
+    if (sp == 1 || est < best) {
+      best = est;
+      splits = sp;
+    }
+  }
   float* part = reinterpret_cast<float*>(ws);
   const dim3 grid(tiles, splits);
   SkinnyEpi e;
