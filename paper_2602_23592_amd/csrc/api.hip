@@ -92,6 +92,12 @@ struct keep_ctx {
   bool tok_pending = false;          // an upload from h_token_ids may still be in flight
   std::vector<hipEvent_t> ev_chunk; // ring for pre-load flow control
 
+  // work list of the last whole-layer MFMA attention, still in attn_scratch: the next layer reuses it when its
+  // rows sit at the same positions (equal sets; the layers of a pure-reuse prompt)
+  AttnPlan att_plan;
+  std::vector<int32_t> att_plan_row_start, att_plan_set_off;
+  int att_plan_n_mem = -1;
+
   // state left by keep_recompute_layer for keep_score_groups
   int last_layer = -1;
   std::vector<int32_t> last_groups;
@@ -433,12 +439,24 @@ keep_status layer_front(keep_ctx* c, const PromptInfo& pi, int layer, const Laye
     return KEEP_OK;
   }
   if (c->mfma)
+  {
+    const int32_t* set_off = c->stage[layer].set_off;
+    const bool same = c->att_plan.valid && !c->units_mode && c->att_plan_n_mem == pi.n_mem &&
+                      c->att_plan_row_start == plan.row_start && (int)c->att_plan_set_off.size() == plan.m &&
+                      std::equal(set_off, set_off + plan.m, c->att_plan_set_off.begin());
+    if (!same) {
+      c->att_plan.valid = false;
+      c->att_plan_row_start = plan.row_start;
+      c->att_plan_set_off.assign(set_off, set_off + plan.m);
+      c->att_plan_n_mem = pi.n_mem;
+    }
     launch_attn_mfma(reinterpret_cast<const bf16_t*>(c->q), reinterpret_cast<const bf16_t*>(k_cache_l),
-                     reinterpret_cast<const bf16_t*>(v_cache_l), c->d_row_pos, plan.row_start.data(),
-                     c->stage[layer].set_off, plan.m, pi.n_mem, n, pi.N, d.n_q_heads, d.n_kv_heads, d.max_tokens,
-                     c->stage[layer].attn_items, c->attn_scratch, reinterpret_cast<bf16_t*>(c->o), c->lse, s,
-                     c->units_mode ? c->h_row_lo : nullptr, c->units_mode ? c->d_row_lo : nullptr);
-  else
+                     reinterpret_cast<const bf16_t*>(v_cache_l), c->d_row_pos, plan.row_start.data(), set_off, plan.m,
+                     pi.n_mem, n, pi.N, d.n_q_heads, d.n_kv_heads, d.max_tokens, c->stage[layer].attn_items,
+                     c->attn_scratch, reinterpret_cast<bf16_t*>(c->o), c->lse, s, c->units_mode ? c->h_row_lo : nullptr,
+                     c->units_mode ? c->d_row_lo : nullptr, c->units_mode ? nullptr : &c->att_plan);
+    if (c->units_mode) c->att_plan.valid = false;
+  } else
     launch_attn_generic<T>(Typed<T>::p(c->q), Typed<T>::p(k_cache_l), Typed<T>::p(v_cache_l), c->d_row_pos, n,
                            d.n_q_heads, d.n_kv_heads, d.head_dim, Typed<T>::p(c->o), c->lse, s,
                            c->units_mode ? c->d_row_lo : nullptr);
@@ -467,6 +485,7 @@ keep_status attend_blocks(keep_ctx* c, const PromptInfo& pi, int layer, const La
   *rows_out = n;
   *keys_out = keys;
   if (n == 0) return KEEP_OK;
+  c->att_plan.valid = false;  // this launch's work list replaces the one in attn_scratch
   HIP_TRY(c, hipMemcpyAsync(c->d_row_list, c->h_row_list, (size_t)n * 4, hipMemcpyHostToDevice, s));
   if (ev_begin) HIP_TRY(c, hipEventRecord(ev_begin, s));
   launch_attn_mfma(reinterpret_cast<const bf16_t*>(c->q), reinterpret_cast<const bf16_t*>(k_cache_l),
@@ -616,6 +635,7 @@ keep_status decode_impl(keep_ctx* c, const void* final_norm, const void* lm_head
   plan.row_start = {0, 1};
   const void* x = x_last;
   AttnPlan att_plan;
+  c->att_plan.valid = false;  // the decode steps put their own work lists into attn_scratch
   for (int t = 0; t < n_new; ++t) {
     // vocabulary projection of the newest hidden row, greedy choice
     float* lg = logits_out ? logits_out + (size_t)t * d.vocab : c->dec_logits;
