@@ -21,8 +21,10 @@ from .gen import (
     make_random_group_cache,
     make_random_rows,
     INT4_GROUP,
+    INT4_ROWS,
     INT4_MATS,
     pack_int4_codes,
+    pack_int4_scale_zero,
     make_int4_matrix,
     make_int4_layer,
     make_int4_layer_on_device,

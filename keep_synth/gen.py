@@ -141,15 +141,27 @@ INT4_GROUP = 128   # input features that share one scale and one zero point
 INT4_MATS = ("wq", "wk", "wv", "wo", "wgate", "wup", "wdown")
 
 
-def pack_int4_codes(q: np.ndarray) -> np.ndarray:
-    """Storage packing of 4-bit codes [rows, K] -> bytes [rows, K/2].
+INT4_ROWS = 32     # output rows per storage block
 
-    Within each run of 8 consecutive input features, byte t (t < 4) holds feature t in its low
-    nibble and feature t + 4 in its high nibble."""
+
+def pack_int4_codes(q: np.ndarray) -> np.ndarray:
+    """Storage packing of 4-bit codes [rows, K] -> flat bytes [rows * K / 2].
+
+    Blocks of 32 rows x 128 input features, ordered by (row block, feature group); inside a block the 32
+    rows follow each other, 64 bytes each; within each run of 8 consecutive input features of a row, byte t
+    (t < 4) holds feature t in its low nibble and feature t + 4 in its high nibble."""
     rows, k = q.shape
-    assert k % 8 == 0
+    assert rows % INT4_ROWS == 0 and k % INT4_GROUP == 0
     q8 = q.reshape(rows, k // 8, 8).astype(np.uint8)
-    return (q8[:, :, 0:4] | (q8[:, :, 4:8] << np.uint8(4))).reshape(rows, k // 2)
+    by = (q8[:, :, 0:4] | (q8[:, :, 4:8] << np.uint8(4))).reshape(rows // INT4_ROWS, INT4_ROWS, k // INT4_GROUP, 64)
+    return np.ascontiguousarray(by.transpose(0, 2, 1, 3)).reshape(-1)
+
+
+def pack_int4_scale_zero(scale_bits: np.ndarray, zero: np.ndarray) -> np.ndarray:
+    """[rows, K/128] scale patterns and zero points -> flat uint32 words in block order (32 words per block)."""
+    rows, kg = scale_bits.shape
+    w = scale_bits.astype(np.uint32) | (zero.astype(np.uint32) << np.uint32(16))
+    return np.ascontiguousarray(w.reshape(rows // INT4_ROWS, INT4_ROWS, kg).transpose(0, 2, 1)).reshape(-1)
 
 
 def make_int4_matrix(rows: int, k: int, seed: int, std: float = 0.02) -> Dict[str, np.ndarray]:
@@ -157,16 +169,16 @@ def make_int4_matrix(rows: int, k: int, seed: int, std: float = 0.02) -> Dict[st
     that (code - zero) * scale has a standard deviation near `std`.
 
     Returns the raw draws (`q` [rows, K] uint8, `zero` [rows, K/128] uint8, `scale_bits` [rows, K/128]
-    uint16 bf16 patterns) and their storage form: `codes` [rows, K/2] uint8 (pack_int4_codes) and
-    `scale_zero` [rows, K/128] uint32 = scale_bits | zero << 16."""
-    assert k % INT4_GROUP == 0
+    uint16 bf16 patterns) and their storage form: `codes` (pack_int4_codes) and `scale_zero`
+    (pack_int4_scale_zero), plus `rows` and `k`."""
+    assert k % INT4_GROUP == 0 and rows % INT4_ROWS == 0
     rng = np.random.Generator(np.random.PCG64(seed))
     q = rng.binomial(15, 0.5, size=(rows, k)).astype(np.uint8)
     zero = rng.integers(7, 9, size=(rows, k // INT4_GROUP)).astype(np.uint8)
     scale = (std / 1.94) * rng.uniform(0.75, 1.25, size=(rows, k // INT4_GROUP))
     scale_bits = bf16_bits_from_f32(scale.astype(np.float32))
-    scale_zero = scale_bits.astype(np.uint32) | (zero.astype(np.uint32) << np.uint32(16))
-    return {"q": q, "zero": zero, "scale_bits": scale_bits, "codes": pack_int4_codes(q), "scale_zero": scale_zero}
+    return {"q": q, "zero": zero, "scale_bits": scale_bits, "codes": pack_int4_codes(q),
+            "scale_zero": pack_int4_scale_zero(scale_bits, zero), "rows": rows, "k": k}
 
 
 def make_int4_layer(s: ModelShape, layer: int, std: float = 0.02) -> Dict[str, Dict[str, np.ndarray]]:
@@ -179,18 +191,19 @@ def make_int4_layer(s: ModelShape, layer: int, std: float = 0.02) -> Dict[str, D
 def make_int4_layer_on_device(s: ModelShape, layer: int, device: str = "cuda", std: float = 0.02):
     """Full-size stand-in drawn on the device (the numpy draws above take minutes at 14B/32B shapes):
     uniform code bytes, zero point 7 or 8, bf16 scale std / 4.6 * U[0.75, 1.25] (uniform codes have a
-    standard deviation of 4.6).  Returns name -> (codes uint8 [rows, K/2], scale_zero int32 [rows, K/128])."""
+    standard deviation of 4.6); independent draws, so the storage order needs no permutation.
+    Returns name -> (codes uint8 [rows * K / 2], scale_zero int32 [rows * K / 128], rows, K)."""
     g = torch.Generator(device=device)
     g.manual_seed(7000 + layer)
     shapes = layer_weight_shapes(s)
     out = {}
     for name in INT4_MATS:
         rows, k = shapes[name]
-        codes = torch.randint(0, 256, (rows, k // 2), generator=g, device=device, dtype=torch.uint8)
-        zero = torch.randint(7, 9, (rows, k // INT4_GROUP), generator=g, device=device, dtype=torch.int32)
-        scale = (std / 4.6) * (0.75 + 0.5 * torch.rand((rows, k // INT4_GROUP), generator=g, device=device))
+        codes = torch.randint(0, 256, (rows * k // 2,), generator=g, device=device, dtype=torch.uint8)
+        zero = torch.randint(7, 9, (rows * k // INT4_GROUP,), generator=g, device=device, dtype=torch.int32)
+        scale = (std / 4.6) * (0.75 + 0.5 * torch.rand((rows * k // INT4_GROUP,), generator=g, device=device))
         bits = scale.to(torch.bfloat16).view(torch.int16).to(torch.int32) & 0xFFFF
-        out[name] = (codes, (bits | (zero << 16)).contiguous())
+        out[name] = (codes, (bits | (zero << 16)).contiguous(), rows, k)
     return out
 
 

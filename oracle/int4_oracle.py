@@ -9,17 +9,20 @@ never does.  Plain numpy, written from the format's definition:
   * the weight the model computes with is  w = bf16( (q - z) * s ),  rounded to nearest even;
     (q - z) * s has at most 13 significant bits, so the product itself is exact in binary32 and
     the only rounding is the final one to bfloat16;
-  * storage: codes packed two per byte, [out, in/2]: within each run of 8 consecutive input features
-    byte t (t < 4) carries feature t in its low nibble and feature t + 4 in its high nibble;
+  * storage (rows a multiple of 32): codes packed two per byte in blocks of 32 rows x 128 input
+    features, blocks ordered by (row block, feature group), 2048 bytes each; inside a block the 32 rows
+    follow each other, 64 bytes per row; within each run of 8 consecutive input features byte t (t < 4)
+    carries feature t in its low nibble and feature t + 4 in its high nibble;
     scale and zero point share one 32-bit word per (row, group): bits 0..15 the scale's bfloat16
-    pattern, bits 16..19 the zero point, the rest 0.
+    pattern, bits 16..19 the zero point, the rest 0; the words are stored in the same block order,
+    32 words (one per row) per block.
 
 Readings (the paper only names the scheme): group length 128 and asymmetric zero points as in the
 cited scheme's usual configuration; the calibration that chooses codes and scales is outside this
 build (weights arrive quantised).
 
-Pins (tests/test_int4_oracle.py): the unpacking order against a hand-written byte fixture
-(tests/golden/int4_words.json), the rounding against torch's float32 -> bfloat16 conversion, closed
+Pins (tests/test_int4_oracle.py): the nibble order against hand-written bytes and the block
+addressing against hand-computed byte offsets and word indices (tests/golden/int4_words.json), the rounding against torch's float32 -> bfloat16 conversion, closed
 forms (zero point = code -> 0; scale 1, zero 0 -> the code itself), and a matmul with dequantised
 weights against an integer-arithmetic evaluation of sum a * (q - z) per group times the scale.
 """
@@ -28,20 +31,28 @@ import numpy as np
 GROUP = 128
 
 
-def unpack_codes(codes: np.ndarray) -> np.ndarray:
-    """bytes [rows, K/2] -> codes [rows, K] (uint8 in 0..15)."""
-    rows, half = codes.shape
-    b = np.asarray(codes, dtype=np.uint8).reshape(rows, half // 4, 4)
-    q = np.empty((rows, half // 4, 8), dtype=np.uint8)
-    for t in range(4):
-        q[:, :, t] = b[:, :, t] & 0x0F          # feature t of the run of eight
-        q[:, :, t + 4] = b[:, :, t] >> 4        # feature t + 4
-    return q.reshape(rows, half * 2)
+ROWS = 32
 
 
-def split_scale_zero(scale_zero: np.ndarray):
-    """uint32 words -> (scale as float64, exactly the bfloat16 value; zero point as int)."""
-    w = np.asarray(scale_zero, dtype=np.uint32)
+def unpack_codes(codes: np.ndarray, rows: int, k: int) -> np.ndarray:
+    """flat storage bytes -> codes [rows, K] (uint8 in 0..15)."""
+    by = np.asarray(codes, dtype=np.uint8).reshape(rows // ROWS, k // GROUP, ROWS, 64)   # (row block, group, row, byte)
+    q = np.empty((rows, k), dtype=np.uint8)
+    for rb in range(rows // ROWS):
+        for kg in range(k // GROUP):
+            blk = by[rb, kg]                                   # [32 rows, 64 bytes]
+            for run in range(GROUP // 8):
+                for t in range(4):
+                    b = blk[:, 4 * run + t]
+                    q[rb * ROWS:(rb + 1) * ROWS, kg * GROUP + 8 * run + t] = b & 0x0F          # feature t of the run
+                    q[rb * ROWS:(rb + 1) * ROWS, kg * GROUP + 8 * run + t + 4] = b >> 4        # feature t + 4
+    return q
+
+
+def split_scale_zero(scale_zero: np.ndarray, rows: int, k: int):
+    """flat storage words -> (scale [rows, K/128] as float64, exactly the bfloat16 value; zero point as int)."""
+    w = np.asarray(scale_zero, dtype=np.uint32).reshape(rows // ROWS, k // GROUP, ROWS)
+    w = w.transpose(0, 2, 1).reshape(rows, k // GROUP)
     scale = ((w & np.uint32(0xFFFF)) << np.uint32(16)).view(np.float32).astype(np.float64)
     zero = ((w >> np.uint32(16)) & np.uint32(0xF)).astype(np.int64)
     return scale, zero
@@ -59,11 +70,9 @@ def round_to_bf16(x: np.ndarray) -> np.ndarray:
     return (up.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
 
 
-def dequantize(codes: np.ndarray, scale_zero: np.ndarray) -> np.ndarray:
+def dequantize(codes: np.ndarray, scale_zero: np.ndarray, rows: int, k: int) -> np.ndarray:
     """The weights the model computes with, [rows, K] float64 (each value a bfloat16 number)."""
-    q = unpack_codes(codes).astype(np.int64)
-    scale, zero = split_scale_zero(scale_zero)
-    rows, k = q.shape
-    assert scale.shape == (rows, k // GROUP)
+    q = unpack_codes(codes, rows, k).astype(np.int64)
+    scale, zero = split_scale_zero(scale_zero, rows, k)
     diff = q.reshape(rows, k // GROUP, GROUP) - zero[:, :, None]
     return round_to_bf16(diff.astype(np.float64) * scale[:, :, None]).reshape(rows, k)
