@@ -295,7 +295,7 @@ def main():
         layers4 = [ks.make_int4_layer_on_device(s, l, "cuda") for l in range(s.n_layers)]
         layers = []
         for l in range(s.n_layers):
-            wl = {n: kb.dequantize_int4(*layers4[l][n]) for n in ks.INT4_MATS}
+            wl = {n: kb.dequantize_int4(*layers4[l][n]) for n in ks.INT4_MATS}   # (codes, words, rows, K)
             wl["ln1"] = torch.ones(s.hidden, dtype=dt, device="cuda")
             wl["ln2"] = torch.ones(s.hidden, dtype=dt, device="cuda")
             wl["bq"] = wl["bk"] = wl["bv"] = None

@@ -255,11 +255,16 @@ keep_status keep_decode(keep_ctx* ctx, const void* final_norm, const void* lm_he
                         int32_t* tokens_out, float* logits_out, const int32_t* forced_tokens);
 
 /* ---- INT4 weight-only matrices (Section 6.1: the 32B model is run with INT4 weight-only quantisation) ----
- * Format of one matrix W[rows, K] (K a multiple of 128), all DEVICE memory, caller-owned:
- *   codes       [rows, K/2] bytes: 4-bit codes q in 0..15; within each run of 8 consecutive input
+ * Format of one matrix W[rows, K] (rows a multiple of 32, K a multiple of 128), all DEVICE memory, caller-owned:
+ *   codes       rows * K / 2 bytes: 4-bit codes q in 0..15, stored in blocks of 32 rows x 128 input features.
+ *               Block (row / 32, feature / 128) starts at byte ((row / 32) * (K / 128) + feature / 128) * 2048;
+ *               inside it row r % 32 takes bytes 64 (r % 32) .. + 63; within each run of 8 consecutive input
  *               features, byte t (t < 4) holds feature t in its low nibble and feature t + 4 in its high one;
- *   scale_zero  [rows, K/128] uint32: bits 0..15 the bfloat16 pattern of the group's scale s, bits 16..19
- *               its zero point z, other bits 0.
+ *   scale_zero  rows * K / 128 uint32, one per (row, group of 128 features), in the same block order, 32 words
+ *               per block: word ((row / 32) * (K / 128) + group) * 32 + row % 32; bits 0..15 the bfloat16
+ *               pattern of the group's scale s, bits 16..19 its zero point z, other bits 0.
+ *   (A request for 32 bytes of each of 32 consecutive rows is then one contiguous 2 KB block instead of 32
+ *   pieces K/2 bytes apart.)
  * The weight the model computes with is  w = bf16((q - z) * s), rounded to nearest even: the 4-bit form is
  * a compact storage of exactly those bfloat16 values.  The calibration that chooses q, z, s is not part of
  * this library (weights arrive quantised). */
@@ -276,7 +281,7 @@ typedef struct {
 /* out[rows, K] (DEVICE, bfloat16) = the weights of an INT4 matrix.  With these as the keep_layer_weights
  * of keep_init, the launches that are bound by the matrix cores (many rows) run on the expanded copy.
  *   stream: hipStream_t or NULL (default stream); the call does not wait for the kernel.
- * Errors: INVALID_ARG (NULL, rows < 1, K not a positive multiple of 128), HIP.  Needs no context:
+ * Errors: INVALID_ARG (NULL, rows not a positive multiple of 32, K not a positive multiple of 128), HIP.  Needs no context:
  * the message of a failure is at keep_last_error(NULL). */
 keep_status keep_dequantize_int4(const void* codes, const void* scale_zero, int32_t rows, int32_t K, void* out,
                                  void* stream);
@@ -289,7 +294,7 @@ keep_status keep_dequantize_int4(const void* codes, const void* scale_zero, int3
  *   layers: HOST array [n_layers] of DEVICE pointers, borrowed until keep_destroy; NULL detaches.
  *   The LM head of keep_decode stays bfloat16.
  * Errors: INVALID_ARG (a NULL pointer inside), UNSUPPORTED (context not on the bf16 MFMA path),
- * SHAPE (hidden or ffn_dim not a multiple of 128). */
+ * SHAPE (hidden, ffn_dim or n_q_heads * head_dim not a multiple of 128, n_kv_heads * head_dim not of 64). */
 keep_status keep_attach_int4(keep_ctx* ctx, const keep_layer_weights_int4* layers);
 
 #ifdef __cplusplus

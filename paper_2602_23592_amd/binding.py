@@ -216,13 +216,14 @@ class KeepPrompt:
         return sum(self.group_len[g] for g in groups) + self.instr_len
 
 
-def dequantize_int4(codes: torch.Tensor, scale_zero: torch.Tensor, stream=None) -> torch.Tensor:
-    """keep_dequantize_int4: codes [rows, K/2] uint8, scale_zero [rows, K/128] int32/uint32 words (device) ->
-    the bfloat16 weights [rows, K] (new device tensor; the allocation is the only thing done here)."""
+def dequantize_int4(codes: torch.Tensor, scale_zero: torch.Tensor, rows: int, k: int, stream=None) -> torch.Tensor:
+    """keep_dequantize_int4: codes (uint8, rows * K / 2) and scale_zero (32-bit words, rows * K / 128) in the
+    library's block order, on the device -> the bfloat16 weights [rows, K] (new device tensor; the allocation is
+    the only thing done here)."""
     lib = load_library()
-    assert codes.is_cuda and codes.is_contiguous() and codes.dtype == torch.uint8
+    assert codes.is_cuda and codes.is_contiguous() and codes.dtype == torch.uint8 and codes.numel() == rows * k // 2
     assert scale_zero.is_cuda and scale_zero.is_contiguous() and scale_zero.element_size() == 4
-    rows, k = codes.shape[0], codes.shape[1] * 2
+    assert scale_zero.numel() == rows * k // 128
     out = torch.empty((rows, k), dtype=torch.bfloat16, device=codes.device)
     st = lib.keep_dequantize_int4(codes.data_ptr(), scale_zero.data_ptr(), rows, k, out.data_ptr(),
                                   _stream_handle(stream if stream is not None else torch.cuda.current_stream()))
@@ -281,7 +282,7 @@ class KeepContext:
         arr = (LayerWeightsInt4 * self.shape.n_layers)()
         for l, w in enumerate(layers4):
             for n in _W4_NAMES:
-                codes, sz = w[n]
+                codes, sz = w[n][0], w[n][1]
                 assert codes.is_cuda and codes.is_contiguous() and sz.is_cuda and sz.is_contiguous(), n
                 getattr(arr[l], n).codes = codes.data_ptr()
                 getattr(arr[l], n).scale_zero = sz.data_ptr()

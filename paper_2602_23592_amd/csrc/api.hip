@@ -1206,8 +1206,8 @@ keep_status keep_decode(keep_ctx* c, const void* final_norm, const void* lm_head
 keep_status keep_dequantize_int4(const void* codes, const void* scale_zero, int32_t rows, int32_t K, void* out,
                                  void* stream) {
   if (!codes || !scale_zero || !out) return fail(nullptr, KEEP_ERR_INVALID_ARG, "codes / scale_zero / out is NULL");
-  if (rows < 1 || K < 128 || K % 128)
-    return fail(nullptr, KEEP_ERR_INVALID_ARG, "rows %d must be positive and K %d a positive multiple of 128", rows, K);
+  if (rows < 32 || rows % 32 || K < 128 || K % 128)
+    return fail(nullptr, KEEP_ERR_INVALID_ARG, "rows %d must be a positive multiple of 32 and K %d of 128", rows, K);
   launch_dequant_int4(codes, scale_zero, rows, K, out, reinterpret_cast<hipStream_t>(stream));
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(nullptr, KEEP_ERR_HIP, "dequantisation launch failed: %s", hipGetErrorString(e));
@@ -1221,8 +1221,10 @@ keep_status keep_attach_int4(keep_ctx* c, const keep_layer_weights_int4* layers)
     return KEEP_OK;
   }
   if (!c->mfma) return fail(c, KEEP_ERR_UNSUPPORTED, "the INT4 form is read by the bf16 matrix-core path only");
-  if (c->d.hidden % 128 || c->d.ffn_dim % 128 || (c->d.n_q_heads * c->d.head_dim) % 128)
-    return fail(c, KEEP_ERR_SHAPE, "hidden, ffn_dim and n_q_heads * head_dim must be multiples of the group length 128");
+  if (c->d.hidden % 128 || c->d.ffn_dim % 128 || (c->d.n_q_heads * c->d.head_dim) % 128 ||
+      (c->d.n_kv_heads * c->d.head_dim) % 64)
+    return fail(c, KEEP_ERR_SHAPE, "hidden, ffn_dim and n_q_heads * head_dim must be multiples of the group length 128, "
+                                    "n_kv_heads * head_dim of 64");
   for (int l = 0; l < c->d.n_layers; ++l) {
     const keep_layer_weights_int4& w = layers[l];
     for (const keep_int4_matrix* m : {&w.wq, &w.wk, &w.wv, &w.wo, &w.wgate, &w.wup, &w.wdown})

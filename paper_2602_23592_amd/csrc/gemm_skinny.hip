@@ -177,10 +177,15 @@ __global__ void __launch_bounds__(256)
 // registers to exactly those bf16 values; launches with many rows are bound by the matrix cores
 // and use a bf16 copy expanded once by k_dequant_int4.
 //
-// Storage: codes [rows, K/2] bytes, within a run of 8 features byte t holds feature t (low nibble)
-// and feature t + 4 (high nibble); one 32-bit word per (row, group): scale bits | zero << 16.
+// Storage (rows a multiple of 32): codes in blocks of 32 rows x 128 features, ordered by (row block, feature
+// group), 2048 bytes each; inside a block 64 bytes per row; within a run of 8 features byte t holds feature t
+// (low nibble) and feature t + 4 (high nibble).  One 32-bit word per (row, group): scale bits | zero << 16,
+// in the same block order, 32 words per block.  A wave step of the GEMM below reads one such block per row
+// tile: one contiguous 2 KB request for the codes, one 128-byte request for the words.
 // ---------------------------------------------------------------------------------------------
 constexpr int W4_GROUP = 128;
+constexpr int W4_ROWS = 32;                          // rows per storage block
+constexpr int W4_BLOCK_BYTES = W4_ROWS * W4_GROUP / 2;  // 2048
 
 // Eight weights of one code word -> 8 bf16 (4 packed words), in feature order.
 // (q - z) * s has <= 13 significant bits, so fma(q, s, -z*s) is exact and the only rounding is the
@@ -204,19 +209,23 @@ __device__ __forceinline__ void w4_scale_zero(uint32_t word, float& sc, float& n
   nzs = -(float)((word >> 16) & 0xFu) * sc;  // exact: 4 bits times 8 bits
 }
 
-// out[r, 8 j .. 8 j + 7] for one code word per thread
+// one code word (8 features of one row) per thread, in storage order
 __global__ void __launch_bounds__(256)
     k_dequant_int4(const uint32_t* __restrict__ codes, const uint32_t* __restrict__ scale_zero, long n_words,
-                   int words_per_row, uint4* __restrict__ out) {
+                   int groups, int K, uint4* __restrict__ out) {
   const long i = (long)blockIdx.x * 256 + threadIdx.x;
   if (i >= n_words) return;
-  const long r = i / words_per_row;
-  const int j = (int)(i - r * words_per_row);
+  const long block = i / (W4_BLOCK_BYTES / 4);                 // (row block, group)
+  const int within = (int)(i - block * (W4_BLOCK_BYTES / 4));  // word inside the block: row * 16 + run of 8
+  const int r = within >> 4, run = within & 15;
+  const long rb = block / groups;
+  const int kg = (int)(block - rb * groups);
   float sc, nzs;
-  w4_scale_zero(scale_zero[r * (words_per_row / (W4_GROUP / 8)) + j / (W4_GROUP / 8)], sc, nzs);
+  w4_scale_zero(scale_zero[block * W4_ROWS + r], sc, nzs);
   uint32_t o[4];
   w4_expand8(codes[i], sc, nzs, o);
-  out[i] = make_uint4(o[0], o[1], o[2], o[3]);
+  const size_t row = (size_t)rb * W4_ROWS + r;
+  out[(row * K + (size_t)kg * W4_GROUP + 8 * run) / 8] = make_uint4(o[0], o[1], o[2], o[3]);
 }
 
 void launch_dequant_int4(const void* codes, const void* scale_zero, int32_t rows, int32_t K, void* out, hipStream_t s) {
@@ -224,7 +233,7 @@ void launch_dequant_int4(const void* codes, const void* scale_zero, int32_t rows
   if (n_words <= 0) return;
   hipLaunchKernelGGL(k_dequant_int4, dim3((unsigned)((n_words + 255) / 256)), dim3(256), 0, s,
                      reinterpret_cast<const uint32_t*>(codes), reinterpret_cast<const uint32_t*>(scale_zero), n_words,
-                     K / 8, reinterpret_cast<uint4*>(out));
+                     K / W4_GROUP, K, reinterpret_cast<uint4*>(out));
 }
 
 struct SkinnyW4 {
@@ -235,7 +244,7 @@ struct SkinnyW4 {
 
 // Same work split as k_gemm_skinny, but a wave step covers one quantisation group (128 input features):
 // the half-wave g reads the 32 code bytes of features 64 g .. 64 g + 63 of each of its two weight rows
-// (two 16-byte loads per row) and one scale/zero word per row.
+// (two 16-byte loads per row) and one scale/zero word per row; a row tile's 32 rows are one storage block.
 template <int MT>
 __global__ void __launch_bounds__(256, 2)
     k_gemm_skinny_w4(const bf16_t* __restrict__ A, int M, int K, SkinnyW4 B, int n_rows_b, int n_splits,
@@ -256,9 +265,11 @@ __global__ void __launch_bounds__(256, 2)
     int p = 0;
     if (n >= B.begin[1]) p = 1;
     if (n >= B.begin[2]) p = 2;
+    // row r of the part: block row r / 32, row r % 32 inside the block; step s of the wave is block (r / 32, s)
     const size_t r = (size_t)(n - B.begin[p]);
-    cp[ct] = B.codes[p] + r * (size_t)(K / 2) + 32 * g;
-    zp[ct] = B.sz[p] + r * (size_t)steps;
+    const size_t blk0 = (r / W4_ROWS) * (size_t)steps;
+    cp[ct] = B.codes[p] + blk0 * W4_BLOCK_BYTES + (r % W4_ROWS) * (W4_GROUP / 2) + 32 * g;
+    zp[ct] = B.sz[p] + blk0 * W4_ROWS + (r % W4_ROWS);
   }
   const bf16_t* ap[MT];
 #pragma unroll
@@ -282,10 +293,10 @@ __global__ void __launch_bounds__(256, 2)
 #define W4_LOAD_B(BUF, STEP)                                                                        \
   {                                                                                                 \
     _Pragma("unroll") for (int ct = 0; ct < 2; ++ct) {                                              \
-      const uint4* src_ = reinterpret_cast<const uint4*>(cp[ct] + (size_t)(STEP) * (W4_GROUP / 2)); \
+      const uint4* src_ = reinterpret_cast<const uint4*>(cp[ct] + (size_t)(STEP) * W4_BLOCK_BYTES); \
       cw[BUF][ct][0] = src_[0];                                                                     \
       cw[BUF][ct][1] = src_[1];                                                                     \
-      zw[BUF][ct] = zp[ct][STEP];                                                                   \
+      zw[BUF][ct] = zp[ct][(size_t)(STEP) * W4_ROWS];                                               \
     }                                                                                               \
   }
 #define W4_LOAD_A(BUF, STEP)                                                                        \
@@ -359,7 +370,12 @@ __global__ void __launch_bounds__(256, 2)
 bool gemm_skinny_fits(int32_t M, int32_t K, const GemmB& B, int32_t N, int epilogue) {
   const long rows = epilogue == EPI_SWIGLU_STORE ? 2L * N : N;
   const long ld = (rows + SK_BN - 1) / SK_BN * SK_BN;
-  if (B.has_w4 && K % W4_GROUP) return false;
+  if (B.has_w4) {  // whole groups along K; every part a whole number of column tiles (two storage blocks)
+    if (K % W4_GROUP) return false;
+    for (int p = 0; p < B.n_parts; ++p)
+      if (B.n_rows[p] % SK_BN) return false;
+    if (epilogue == EPI_SWIGLU_STORE && N % SK_BN) return false;
+  }
   return M >= 1 && M <= 64 && K % SK_KSTEP == 0 && K >= SK_KSTEP && rows < (1L << 24) &&
          (size_t)M * (size_t)ld <= SK_MAX_PART_FLOATS && (epilogue != EPI_SWIGLU_STORE || B.n_parts == 1);
 }

@@ -20,7 +20,9 @@ SHAPE = ks.ModelShape(2, 512, 8, 2, 128, 1024, 1031, 1.0e6, 1e-6, "bf16")
 
 
 def _dev(m):
-    return (torch.from_numpy(m["codes"]).cuda(), torch.from_numpy(m["scale_zero"].view(np.int32)).cuda())
+    """storage arrays of a keep_synth INT4 matrix on the device, with its shape: (codes, words, rows, K)"""
+    return (torch.from_numpy(m["codes"]).cuda(), torch.from_numpy(m["scale_zero"].view(np.int32)).cuda(),
+            m["rows"], m["k"])
 
 
 class Int4Problem:
@@ -34,7 +36,8 @@ class Int4Problem:
             raw = ks.make_int4_layer(shape, l, std=std)
             dev4 = {n: _dev(raw[n]) for n in ks.INT4_MATS}
             wd = {n: dequantize_int4(*dev4[n]) for n in ks.INT4_MATS}            # the library's own expansion
-            wo = {n: io.dequantize(raw[n]["codes"], raw[n]["scale_zero"]) for n in ks.INT4_MATS}
+            wo = {n: io.dequantize(raw[n]["codes"], raw[n]["scale_zero"], raw[n]["rows"], raw[n]["k"])
+                  for n in ks.INT4_MATS}
             for n, width in (("ln1", shape.hidden), ("ln2", shape.hidden), ("bq", shape.q_dim), ("bk", shape.kv_dim),
                              ("bv", shape.kv_dim)):
                 t = torch.randn(width, generator=g)
@@ -54,12 +57,12 @@ class Int4Problem:
         return ctx
 
 
-@pytest.mark.parametrize("rows,k", [(3, 128), (200, 384), (512, 13824)])
+@pytest.mark.parametrize("rows,k", [(32, 128), (224, 384), (512, 13824)])
 def test_expansion_is_bit_exact(rows, k):
     m = ks.make_int4_matrix(rows, k, seed=rows + k, std=0.02)
     got = dequantize_int4(*_dev(m))
     torch.cuda.synchronize()
-    want = torch.from_numpy(io.dequantize(m["codes"], m["scale_zero"])).to(torch.bfloat16)     # exact: bf16 values
+    want = torch.from_numpy(io.dequantize(m["codes"], m["scale_zero"], rows, k)).to(torch.bfloat16)   # exact: bf16 values
     assert torch.equal(got.cpu().view(torch.int16), want.view(torch.int16))
 
 
@@ -70,10 +73,9 @@ def test_expansion_covers_every_code_zero_pair_and_awkward_scales():
     zero = np.repeat(np.arange(16, dtype=np.uint8), 4).reshape(rows, 1)
     scales = np.array([0.0131, 1.0 + 127.0 / 128, 3.3e-5, 7.77], dtype=np.float32)
     bits = np.tile(ks.bf16_bits_from_f32(scales), 16).reshape(rows, 1)
-    sz = bits.astype(np.uint32) | (zero.astype(np.uint32) << 16)
-    codes = ks.pack_int4_codes(q)
-    got = dequantize_int4(torch.from_numpy(codes).cuda(), torch.from_numpy(sz.view(np.int32)).cuda())
-    want = torch.from_numpy(io.dequantize(codes, sz)).to(torch.bfloat16)
+    codes, sz = ks.pack_int4_codes(q), ks.pack_int4_scale_zero(bits, zero)
+    got = dequantize_int4(torch.from_numpy(codes).cuda(), torch.from_numpy(sz.view(np.int32)).cuda(), rows, k)
+    want = torch.from_numpy(io.dequantize(codes, sz, rows, k)).to(torch.bfloat16)
     assert torch.equal(got.cpu().view(torch.int16), want.view(torch.int16))
 
 
@@ -148,12 +150,13 @@ def test_short_prompt_unit_caching_and_decode_read_the_int4_form():
 
 def test_int4_error_paths():
     lib = load_library()
-    m = ks.make_int4_matrix(4, 128, seed=1)
-    codes, sz = _dev(m)
-    out = torch.empty((4, 128), dtype=torch.bfloat16, device="cuda")
-    assert lib.keep_dequantize_int4(codes.data_ptr(), sz.data_ptr(), 4, 100, out.data_ptr(), None) == KEEP_ERR_INVALID_ARG
-    assert lib.keep_dequantize_int4(None, sz.data_ptr(), 4, 128, out.data_ptr(), None) == KEEP_ERR_INVALID_ARG
+    m = ks.make_int4_matrix(32, 128, seed=1)
+    codes, sz, _, _ = _dev(m)
+    out = torch.empty((32, 128), dtype=torch.bfloat16, device="cuda")
+    assert lib.keep_dequantize_int4(codes.data_ptr(), sz.data_ptr(), 32, 100, out.data_ptr(), None) == KEEP_ERR_INVALID_ARG
+    assert lib.keep_dequantize_int4(None, sz.data_ptr(), 32, 128, out.data_ptr(), None) == KEEP_ERR_INVALID_ARG
     assert lib.keep_dequantize_int4(codes.data_ptr(), sz.data_ptr(), 0, 128, out.data_ptr(), None) == KEEP_ERR_INVALID_ARG
+    assert lib.keep_dequantize_int4(codes.data_ptr(), sz.data_ptr(), 33, 128, out.data_ptr(), None) == KEEP_ERR_INVALID_ARG
     assert b"128" in lib.keep_last_error(None)
     # a context on the generic fp32 path has no INT4 launches
     f32 = ks.ModelShape(1, 128, 2, 1, 64, 256, 50, 1.0e6, 1e-6, "f32")
@@ -182,7 +185,8 @@ def test_fullsize_projections_read_the_int4_form():
     sh = oracle_shape(shape)
     dev4 = ks.make_int4_layer_on_device(shape, 0, "cuda", std=0.02)
     wd = {n: dequantize_int4(*dev4[n]) for n in ks.INT4_MATS}
-    wo = {n: io.dequantize(dev4[n][0].cpu().numpy(), dev4[n][1].cpu().numpy().view(np.uint32)) for n in ks.INT4_MATS}
+    wo = {n: io.dequantize(dev4[n][0].cpu().numpy(), dev4[n][1].cpu().numpy().view(np.uint32), dev4[n][2], dev4[n][3])
+          for n in ks.INT4_MATS}
     for n in ks.INT4_MATS:   # the library's expansion is the oracle's, bit for bit, at full size too
         assert torch.equal(wd[n].cpu().view(torch.int16), torch.from_numpy(wo[n]).to(torch.bfloat16).view(torch.int16)), n
     g = torch.Generator().manual_seed(5)
