@@ -157,6 +157,7 @@ size_t attn_mfma_scratch_bytes(int32_t max_rows, int32_t n_q_heads, int32_t n_kv
 struct AttnPlan {
   bool valid = false;
   int n_items = 0, n_splits = 0;
+  bool wide_combine = false;  // some tile is cut into 16 or more chunks: merge with the chunks spread over lanes
 };
 void launch_attn_mfma(const bf16_t* q, const bf16_t* k_cache, const bf16_t* v_cache, const int32_t* d_row_pos,
                       const int32_t* h_row_start, const int32_t* h_set_off, int32_t m, int32_t instr_off,
