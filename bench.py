@@ -25,7 +25,7 @@ PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 
 
 # (2.0 x FETCH_SIZE + 1.0 x WRITE_SIZE) of the gate/up GEMM launches (and their fix-up launches) of two steps / 96
-GATE_UP_TRAFFIC_BYTES_PER_LAUNCH = int(((76944310 + 1520936) * 2.0 + (11157280 + 192864)) * 1024 / 96)
+GATE_UP_TRAFFIC_BYTES_PER_LAUNCH = int(((76520876 + 1520935) * 2.0 + (11157280 + 192864)) * 1024 / 96)
 
 
 def parse():
