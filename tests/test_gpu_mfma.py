@@ -160,3 +160,36 @@ def test_many_candidates_with_host_resident_caches_in_every_load_mode():
     for l in range(3):
         assert max_rel(to_np(outs[0][1][l]), ref["k_hat"][l]) < TOL and max_rel(to_np(outs[0][2][l]), ref["v_hat"][l]) < TOL
     assert max_rel(to_np(outs[0][3]), ref["x_final"]) < TOL
+
+
+def test_attention_work_list_reuse_survives_other_launches():
+    """Layers with equal sets share one attention work list on the device.  Decoding and a prompt of another
+    layout in between put their own lists into the same scratch: a repeated prefill must still give the caches,
+    rows and sets of a fresh context, bit for bit."""
+    shape = _shape(4, 512, 8, 2, 1024)
+    pa = Problem(shape, [40, 24, 64, 33], 9, seed=21, std=0.05, bias=True, random_cache=True)
+    pb = Problem(shape, [17, 80, 12], 21, seed=22, std=0.05, bias=True, random_cache=True)
+    ratios = [1.0, 0.5, 0.5, 0.5]                       # layers 1..3 recompute the same two memories
+
+    def run(ctx, p, cap):
+        kc = torch.zeros((4, cap, shape.n_kv_heads, shape.head_dim), dtype=torch.bfloat16, device="cuda")
+        vc = torch.zeros_like(kc)
+        xf = torch.empty((p.instr_len, shape.hidden), dtype=torch.bfloat16, device="cuda")
+        sets, _ = ctx.prefill(p.prompt(), ratios, 2, kc, vc, xf, cache_rows=cap)
+        torch.cuda.synchronize()
+        return sets, kc, vc, xf
+
+    cap = max(pa.n_tokens, pb.n_tokens) + 4
+    fresh = run(pa.context(max_tokens=cap, max_groups=4), pa, cap)
+    assert fresh[0][1] == fresh[0][2] == fresh[0][3] and len(fresh[0][1]) == 2
+    ctx = pa.context(max_tokens=cap, max_groups=4)      # same weights (seeded by shape), used for everything below
+    first = run(ctx, pa, cap)
+    g = torch.Generator().manual_seed(3)
+    fn = torch.ones(shape.hidden, dtype=torch.bfloat16, device="cuda")
+    lm = (0.05 * torch.randn(shape.vocab, shape.hidden, generator=g)).to(torch.bfloat16).cuda()
+    ctx.decode(fn, lm, first[3][-1], first[1].clone(), first[2].clone(), pa.n_tokens, 3)
+    run(ctx, pb, cap)
+    again = run(ctx, pa, cap)
+    for got in (first, again):
+        assert got[0] == fresh[0]
+        assert torch.equal(got[1], fresh[1]) and torch.equal(got[2], fresh[2]) and torch.equal(got[3], fresh[3])
