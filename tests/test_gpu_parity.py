@@ -136,6 +136,29 @@ def test_selection_bit_exact_against_oracle():
     assert n_checked == 360
 
 
+def test_selection_bit_exact_with_many_candidates():
+    """The selector with hundreds to thousands of candidates: row totals over several row blocks and ragged
+    column tiles, several candidates per thread, token-budget walks over long orders."""
+    shape = SHAPES["f32_small"]
+    pb = Problem(shape, [4] * 8, 2, seed=2, random_cache=True)
+    ctx = pb.context(max_groups=1600)
+    rng = np.random.default_rng(19)
+    for m in (257, 300, 1100, 1500):
+        G = m + 7
+        glen = [int(v) for v in rng.integers(1, 50, size=G)]
+        groups = sorted(rng.choice(G, size=m, replace=False).tolist())
+        S = np.tril(rng.random((m + 1, m)), -1).astype(np.float32)
+        S[m] = rng.random(m).astype(np.float32)
+        if m == 300:
+            S = (np.round(S * 8) / 8).astype(np.float32)      # many ties
+        for mode in (0, 1):
+            for hops, ratio in ((1, 0.1), (3, 0.07), (4, 0.3)):
+                want, runs = ko.select_multihop(S, groups, glen, ratio, hops, mode)
+                got, got_runs = ctx.select_groups(S, groups, glen, ratio, hops, mode)
+                assert got == want, (m, mode, hops)
+                assert got_runs == runs
+
+
 def test_prefill_multi_layer_sets_and_token_budget():
     shape = ks.ModelShape(4, 64, 4, 2, 16, 96, 97, 1.0e4, 1e-6, "f32")
     glen, lq = [9, 14, 3, 22, 8, 17, 5, 12], 6
