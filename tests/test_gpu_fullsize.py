@@ -1,5 +1,6 @@
-"""Parity at the benchmark's full size (Qwen-14B-shaped layer, 33 024-token prompt), in the launch
-configuration bench.py times: one selective layer teacher-forced on seeded inputs, checked against
+"""Parity at the full size of every benchmark workload (the Qwen-14B-shaped 33 024-token prompt that bench.py
+times by default, and the 7B / 32B / 64k-token shapes), in the launch configuration bench.py uses: one
+selective layer teacher-forced on seeded inputs, checked against
 the CPU oracle on the whole refreshed K/V cache, on sampled output rows, and on sampled rows of the
 score matrix.  Inputs are seeded draws (keep_synth); nothing the oracle reads comes from the GPU."""
 import numpy as np
@@ -14,9 +15,11 @@ pytestmark = pytest.mark.gpu
 TOL = 2e-2
 
 
-def test_fullsize_selective_layer_sampled():
+@pytest.mark.parametrize("workload", ["qwen14b_32k", "qwen7b_16k", "qwen32b_32k_host", "qwen14b_64k_stress"])
+def test_fullsize_selective_layer_sampled(workload):
     from paper_2602_23592_amd import KeepContext, KeepPrompt
-    w = ks.workload("qwen14b_32k")
+    from paper_2602_23592_amd.binding import KEEP_BUDGET_TOKENS, KEEP_BUDGET_GROUP_COUNT
+    w = ks.workload(workload)
     s = w.shape
     one = ks.ModelShape(1, s.hidden, s.n_q_heads, s.n_kv_heads, s.head_dim, s.ffn_dim, s.vocab, s.rope_theta,
                         s.rms_eps, s.storage)
@@ -27,12 +30,16 @@ def test_fullsize_selective_layer_sampled():
     # seeded set that fills the layer-1 token budget of the benchmark schedule
     ratios = ks.ratio_schedule(w.ratio, s.n_layers, w.schedule)
     rng = np.random.Generator(np.random.PCG64(5))
-    left, groups = ko.budget_tokens(float(ratios[1]), w.mem_tokens), []
-    for g in rng.permutation(G):
-        if glist[g] <= left:
-            groups.append(int(g))
-            left -= glist[g]
-    groups.sort()
+    tokens_mode = w.budget == "tokens"
+    if tokens_mode:
+        left, groups = ko.budget_tokens(float(ratios[1]), w.mem_tokens), []
+        for g in rng.permutation(G):
+            if glist[g] <= left:
+                groups.append(int(g))
+                left -= glist[g]
+        groups.sort()
+    else:
+        groups = sorted(int(g) for g in rng.choice(G, size=ko.budget_count(float(ratios[1]), G, G), replace=False))
     m = len(groups)
     # inputs: one layer of weights (with biases), random group caches, random hidden rows
     lw_t = ks.make_layer_weights(one, 0, "cpu", bias=True, norm_jitter=0.1)
@@ -54,7 +61,8 @@ def test_fullsize_selective_layer_sampled():
     vc = torch.zeros_like(kc)
     x_out = torch.empty((n_rows, s.hidden), dtype=torch.bfloat16, device=dev)
     ctx.recompute_layer(pr, 0, groups, x_t.to(dev), x_out, kc, vc)
-    nxt, runs, S = ctx.score_groups(pr, 0, groups, float(ratios[2]), w.hops, 1)
+    mode = KEEP_BUDGET_TOKENS if tokens_mode else KEEP_BUDGET_GROUP_COUNT
+    nxt, runs, S = ctx.score_groups(pr, 0, groups, float(ratios[2]), w.hops, mode)
     torch.cuda.synchronize()
     # ---- oracle (float64): K/V refresh of every row; attention/FFN and score rows for sampled blocks
     sh = ko.Shape(1, s.hidden, s.n_q_heads, s.n_kv_heads, s.head_dim, s.ffn_dim, 8, s.rope_theta, s.rms_eps, s.storage)
@@ -63,8 +71,10 @@ def test_fullsize_selective_layer_sampled():
     vb = [ks.to_numpy_f64(t) for t in vb_t]
     kh, vh = ko.realign_concat(sh, kb, vb, glist, lq)
     x_np = ks.to_numpy_f64(x_t)
-    small = [i for i, g in enumerate(groups) if glist[g] <= 64]
-    blocks = sorted({small[0], small[len(small) // 2], small[-1]})           # three 64-token memories
+    # three of the shorter memories (first, middle, last of those no longer than the median) as score samples
+    med = int(np.median([glist[g] for g in groups]))
+    small = [i for i, g in enumerate(groups) if glist[g] <= med]
+    blocks = sorted({small[0], small[len(small) // 2], small[-1]})
     xo_ref, lse_ref, S_ref = ko.selective_layer(sh, lw, x_np, groups, glist, lq, kh, vh, score_blocks=blocks + [m])
     # whole cache
     ek, ev = max_rel(to_np(kc), kh), max_rel(to_np(vc), vh)
@@ -73,11 +83,12 @@ def test_fullsize_selective_layer_sampled():
     rows = np.concatenate([np.arange(starts[b], starts[b + 1]) for b in blocks] + [np.arange(starts[m], starts[m] + lq)])
     ex = max_rel(to_np(x_out[torch.from_numpy(rows).to(dev)]), xo_ref)
     es = np.nanmax(np.abs(S[blocks + [m]] - S_ref[blocks + [m]])) / np.nanmax(S_ref[blocks + [m]])
-    print("full size: rows %d groups %d  K %.2e V %.2e X(sampled %d rows) %.2e S(sampled %d rows) %.2e"
-          % (n_rows, m, ek, ev, len(rows), ex, len(blocks) + 1, es))
+    print("full size %s: rows %d groups %d  K %.2e V %.2e X(sampled %d rows) %.2e S(sampled %d rows) %.2e"
+          % (workload, n_rows, m, ek, ev, len(rows), ex, len(blocks) + 1, es))
     assert ek < TOL and ev < TOL and ex < TOL and es < TOL
     # the device's selection is the oracle's selection applied to the device's scores
-    want, want_runs = ko.select_multihop(S, groups, glist, float(ratios[2]), w.hops, ko.BUDGET_TOKENS)
+    want, want_runs = ko.select_multihop(S, groups, glist, float(ratios[2]), w.hops,
+                                         ko.BUDGET_TOKENS if tokens_mode else ko.BUDGET_GROUP_COUNT)
     assert nxt == want and runs == want_runs
 
 
