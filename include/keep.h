@@ -162,6 +162,34 @@ int32_t keep_uses_mfma(const keep_ctx* ctx);
 /* Device bytes a context for this description allocates (0 if desc is invalid). */
 uint64_t keep_workspace_bytes(const keep_model_desc* desc);
 
+/* Options of a context (keep_set_option).
+ * KEEP_OPT_PROPAGATION_SOURCES: which rows of the normalised score matrix the importance propagation of
+ *   Section 4.2 averages from the second selection on.
+ *   KEEP_SOURCES_QUERY_AND_SET (default): the query's row and the rows of the current relevant set (the
+ *     query keeps anchoring the importance, so first-hop memories are not evicted by their neighbours);
+ *   KEEP_SOURCES_SET_ONLY: the rows of the current relevant set alone, which is the section's propagation
+ *     step taken word for word (the query's row only initialises the importance). */
+typedef enum { KEEP_OPT_PROPAGATION_SOURCES = 0 } keep_option;
+typedef enum { KEEP_SOURCES_QUERY_AND_SET = 0, KEEP_SOURCES_SET_ONLY = 1 } keep_propagation_sources;
+
+/* Sets an option for every later keep_score_groups / keep_select_groups / keep_prefill on this context.
+ * Errors: INVALID_ARG (NULL context, unknown option or value). */
+keep_status keep_set_option(keep_ctx* ctx, int32_t option, int32_t value);
+
+/* What keep_read_layer_state copies out: the state keep_recompute_layer leaves in the workspace. */
+typedef enum {
+  KEEP_STATE_ATTN_OUT = 0, /* attention output of the recomputed rows, [n_rows, n_q_heads * head_dim], storage dtype */
+  KEEP_STATE_LSE = 1       /* log-sum-exp of each row's scaled scores, [n_rows, n_q_heads], float */
+} keep_layer_state;
+
+/* Copies a piece of the state that the last keep_recompute_layer left in the workspace (Section 5: the
+ * attention of a layer is what its importance evaluation reads) to HOST memory, for inspection and tests.
+ * Waits for the compute stream.  dst: HOST, capacity `bytes`, which must equal the size given above for
+ * the rows of that call.
+ * Errors: STATE (no keep_recompute_layer since the last call that overwrote the workspace),
+ * INVALID_ARG (NULL, unknown `what`, wrong size), HIP. */
+keep_status keep_read_layer_state(keep_ctx* ctx, int32_t what, void* dst, uint64_t bytes);
+
 /* `prefill_layer` (Section 5): one layer of selective recomputation.
  *   groups[n_sel]: HOST, ascending: the relevant set R of this layer.
  *   x_in:  DEVICE [n_rows, hidden] hidden rows of the recomputed tokens in prompt

@@ -243,7 +243,7 @@ def rows_of(groups: Sequence[int], group_len: Sequence[int], instr_len: int) -> 
 def selective_layer(sh: Shape, w: Dict[str, np.ndarray], x: np.ndarray, groups: Sequence[int],
                     group_len: Sequence[int], instr_len: int, k_hat: np.ndarray, v_hat: np.ndarray,
                     want_scores: bool = True, only_rows: Optional[np.ndarray] = None,
-                    score_blocks: Optional[Sequence[int]] = None):
+                    score_blocks: Optional[Sequence[int]] = None, probe: Optional[dict] = None):
     """Recompute the KV of the memories in `groups` (and of the instruction) over the
     joined cache of this layer.
 
@@ -263,6 +263,10 @@ def selective_layer(sh: Shape, w: Dict[str, np.ndarray], x: np.ndarray, groups: 
     those blocks and S comes back with only those rows filled (NaN elsewhere);
     x_out and lse hold those blocks' rows in order.  For sampled checks at sizes
     where the full matrix is too slow.
+
+    probe: optional dict that receives intermediate values for tests: "attn_out"
+    [rows, n_q_heads, head_dim], the attention output of the evaluated rows before
+    the output projection.
     """
     groups = sorted(int(g) for g in groups)
     assert instr_len >= 1 and min(group_len) >= 1      # a query is needed; blocks are non-empty
@@ -321,6 +325,8 @@ def selective_layer(sh: Shape, w: Dict[str, np.ndarray], x: np.ndarray, groups: 
             by_key = np.add.reduceat(p, key_starts, axis=1)          # [n_l, G+1]
             mass += np.add.reduceat(by_key, row_starts, axis=0)      # [m+1, G+1]
 
+    if probe is not None:
+        probe["attn_out"] = o
     x_out = output_and_ffn(sh, w, x_res, o)
     scores = None
     if want_scores and score_blocks is None:

@@ -23,7 +23,12 @@ KEEP_LOAD_SERIAL, KEEP_LOAD_NEXT_LAYER, KEEP_LOAD_LAYER_BALANCED = 0, 1, 2
 KEEP_KERNELS_AUTO, KEEP_KERNELS_GENERIC = 0, 1
 KEEP_REPORT_MAX_LAYERS = 128
 
+KEEP_OPT_PROPAGATION_SOURCES = 0
+KEEP_SOURCES_QUERY_AND_SET, KEEP_SOURCES_SET_ONLY = 0, 1
+KEEP_STATE_ATTN_OUT, KEEP_STATE_LSE = 0, 1
+
 EXPORTED = ("keep_init", "keep_destroy", "keep_last_error", "keep_uses_mfma", "keep_workspace_bytes", "keep_recompute_layer",
+            "keep_set_option", "keep_read_layer_state",
             "keep_score_groups", "keep_select_groups", "keep_prefill",
             "keep_prefill_padded", "keep_decode", "keep_precompute_group", "keep_precompute_groups",
             "keep_dequantize_int4", "keep_attach_int4",
@@ -115,6 +120,10 @@ def load_library() -> C.CDLL:
     lib.keep_uses_mfma.argtypes = [vp]
     lib.keep_workspace_bytes.restype = C.c_uint64
     lib.keep_workspace_bytes.argtypes = [C.POINTER(ModelDesc)]
+    lib.keep_set_option.restype = i32
+    lib.keep_set_option.argtypes = [vp, i32, i32]
+    lib.keep_read_layer_state.restype = i32
+    lib.keep_read_layer_state.argtypes = [vp, i32, vp, C.c_uint64]
     lib.keep_recompute_layer.restype = i32
     lib.keep_recompute_layer.argtypes = [vp, C.POINTER(Prompt), i32, pi32, i32, vp, vp, vp, vp]
     lib.keep_score_groups.restype = i32
@@ -298,6 +307,24 @@ class KeepContext:
             raise KeepError(st, self.lib.keep_last_error(self.handle).decode())
 
     # -- the C entry points ---------------------------------------------------
+    def set_option(self, option: int, value: int):
+        self._check(self.lib.keep_set_option(self.handle, option, value))
+
+    def read_layer_state(self, what: int, n_rows: int) -> np.ndarray:
+        """keep_read_layer_state: attention output [n_rows, Hq, dh] (float32 view of the stored values) or
+        log-sum-exp [n_rows, Hq] of the last keep_recompute_layer, on the host."""
+        s = self.shape
+        if what == KEEP_STATE_LSE:
+            out = np.empty((n_rows, s.n_q_heads), dtype=np.float32)
+        elif self.dtype == KEEP_BF16:
+            out = np.empty((n_rows, s.n_q_heads, s.head_dim), dtype=np.uint16)
+        else:
+            out = np.empty((n_rows, s.n_q_heads, s.head_dim), dtype=np.float32)
+        self._check(self.lib.keep_read_layer_state(self.handle, what, out.ctypes.data_as(C.c_void_p), out.nbytes))
+        if out.dtype == np.uint16:      # bfloat16 bit patterns -> the float32 values they stand for
+            out = (out.astype(np.uint32) << np.uint32(16)).view(np.float32)
+        return out
+
     def recompute_layer(self, prompt: KeepPrompt, layer: int, groups: Sequence[int], x_in: Optional[torch.Tensor],
                         x_out: torch.Tensor, k_cache_l: torch.Tensor, v_cache_l: torch.Tensor):
         g, gp = _i32_array(groups if len(groups) else [0])

@@ -79,6 +79,9 @@ struct keep_ctx {
   hipEvent_t ev_part[16] = {};      // begin / end pairs of such launches (timing)
   int32_t* h_row_lo = nullptr;      // pinned [max_tokens]: first visible key per row (batched unit caching)
   int32_t* d_row_lo = nullptr;
+  hipEvent_t ev_rowlist = nullptr;  // the last upload from h_row_list has been read by the device
+  bool rowlist_pending = false;
+  bool set_only = false;            // KEEP_OPT_PROPAGATION_SOURCES = KEEP_SOURCES_SET_ONLY
   bool ev_light = false;            // record only the events around the gate/up GEMM (keep_report.events_in = 1)
   bool units_mode = false;          // rows attend only from their unit's first row on
   int32_t* h_dec = nullptr;         // pinned [4 * KEEP_DECODE_MAX_TOKENS]: positions, fed tokens, results
@@ -466,8 +469,8 @@ keep_status layer_front(keep_ctx* c, const PromptInfo& pi, int layer, const Laye
 }
 
 // Attention of the rows of the flagged blocks only (blocks 0..m-1 the layer's memories, m the instruction),
-// on the compute stream; MFMA family.  The caller has made sure that no earlier upload from h_row_list is
-// still pending.  rows_out / keys_out: how many rows were attended and how many keys they see in all.
+// on the compute stream; MFMA family.  No earlier upload from h_row_list that is
+// still pending is overwritten (it waits for that upload's event).  rows_out / keys_out: how many rows were attended and how many keys they see in all.
 keep_status attend_blocks(keep_ctx* c, const PromptInfo& pi, int layer, const LayerPlan& plan, const uint8_t* flags,
                           void* k_cache_l, void* v_cache_l, hipEvent_t ev_begin, hipEvent_t ev_end, int* rows_out,
                           uint64_t* keys_out) {
@@ -475,6 +478,11 @@ keep_status attend_blocks(keep_ctx* c, const PromptInfo& pi, int layer, const La
   hipStream_t s = c->s_comp;
   int n = 0;
   uint64_t keys = 0;
+  // the pinned list is about to be rewritten: the previous upload from it must have been read
+  if (c->rowlist_pending) {
+    HIP_TRY(c, hipEventSynchronize(c->ev_rowlist));
+    c->rowlist_pending = false;
+  }
   for (int a = 0; a <= plan.m; ++a)
     if (flags[a]) {
       const int64_t first = a < plan.m ? c->stage[layer].set_off[a] : pi.n_mem;  // position of the block's first row
@@ -487,6 +495,8 @@ keep_status attend_blocks(keep_ctx* c, const PromptInfo& pi, int layer, const La
   if (n == 0) return KEEP_OK;
   c->att_plan.valid = false;  // this launch's work list replaces the one in attn_scratch
   HIP_TRY(c, hipMemcpyAsync(c->d_row_list, c->h_row_list, (size_t)n * 4, hipMemcpyHostToDevice, s));
+  HIP_TRY(c, hipEventRecord(c->ev_rowlist, s));
+  c->rowlist_pending = true;
   if (ev_begin) HIP_TRY(c, hipEventRecord(ev_begin, s));
   launch_attn_mfma(reinterpret_cast<const bf16_t*>(c->q), reinterpret_cast<const bf16_t*>(k_cache_l),
                    reinterpret_cast<const bf16_t*>(v_cache_l), c->d_row_pos, plan.row_start.data(),
@@ -588,7 +598,8 @@ SelectKind classify_budget(const PromptInfo& pi, const keep_prompt* p, const int
 }
 
 keep_status enqueue_select(keep_ctx* c, int m, int k_count, int tok_budget, int mode, int hops, hipStream_t s) {
-  launch_select(c->S, m, c->d_cand_len, k_count, tok_budget, mode, hops, c->sel_work, c->sel_iwork, c->sel_out, s);
+  launch_select(c->S, m, c->d_cand_len, k_count, tok_budget, mode, hops, c->sel_work, c->sel_iwork, c->sel_out, s,
+                c->set_only);
   HIP_TRY(c, hipGetLastError());
   HIP_TRY(c, hipMemcpyAsync(c->h_sel_out, c->sel_out, (size_t)(m + 2) * 4, hipMemcpyDeviceToHost, s));
   return KEEP_OK;
@@ -760,7 +771,7 @@ keep_status keep_destroy(keep_ctx* c) {
   if (c->h_token_ids) (void)hipHostFree(c->h_token_ids);
   for (hipEvent_t e : c->ev) (void)hipEventDestroy(e);
   for (hipEvent_t e : c->ev_chunk) (void)hipEventDestroy(e);
-  for (hipEvent_t e : {c->ev_attn, c->ev_eval, c->ev_load, c->ev_comp, c->ev_tok})
+  for (hipEvent_t e : {c->ev_attn, c->ev_eval, c->ev_load, c->ev_comp, c->ev_tok, c->ev_rowlist})
     if (e) (void)hipEventDestroy(e);
   delete c;
   return KEEP_OK;
@@ -901,6 +912,7 @@ keep_status keep_init(const keep_model_desc* desc, const keep_layer_weights* lay
     HIP_TRY(c, hipEventCreateWithFlags(&c->ev_load, hipEventDisableTiming));
     HIP_TRY(c, hipEventCreateWithFlags(&c->ev_comp, hipEventDisableTiming));
     HIP_TRY(c, hipEventCreateWithFlags(&c->ev_tok, hipEventDisableTiming));
+    HIP_TRY(c, hipEventCreateWithFlags(&c->ev_rowlist, hipEventDisableTiming));
     c->ev_chunk.resize(64);
     for (hipEvent_t& e : c->ev_chunk) HIP_TRY(c, hipEventCreateWithFlags(&e, hipEventDisableTiming));
     return KEEP_OK;
@@ -1097,6 +1109,41 @@ keep_status keep_score_groups(keep_ctx* c, const keep_prompt* p, int32_t layer, 
     *hops_run = c->h_sel_out[1];
     for (int i = 0; i < *n_next; ++i) next_groups[i] = groups[c->h_sel_out[2 + i]];
   }
+  return KEEP_OK;
+}
+
+keep_status keep_set_option(keep_ctx* c, int32_t option, int32_t value) {
+  if (!c) return KEEP_ERR_INVALID_ARG;
+  if (option == KEEP_OPT_PROPAGATION_SOURCES) {
+    if (value != KEEP_SOURCES_QUERY_AND_SET && value != KEEP_SOURCES_SET_ONLY)
+      return fail(c, KEEP_ERR_INVALID_ARG, "unknown value %d for KEEP_OPT_PROPAGATION_SOURCES", value);
+    c->set_only = value == KEEP_SOURCES_SET_ONLY;
+    return KEEP_OK;
+  }
+  return fail(c, KEEP_ERR_INVALID_ARG, "unknown option %d", option);
+}
+
+keep_status keep_read_layer_state(keep_ctx* c, int32_t what, void* dst, uint64_t bytes) {
+  if (!c) return KEEP_ERR_INVALID_ARG;
+  if (!dst) return fail(c, KEEP_ERR_INVALID_ARG, "dst is NULL");
+  if (c->last_layer < 0)
+    return fail(c, KEEP_ERR_STATE, "keep_read_layer_state needs a keep_recompute_layer whose state is still in the workspace");
+  const void* src = nullptr;
+  uint64_t want = 0;
+  if (what == KEEP_STATE_ATTN_OUT) {
+    src = c->o;
+    want = (uint64_t)c->last_n_rows * c->d.n_q_heads * c->d.head_dim * c->esz;
+  } else if (what == KEEP_STATE_LSE) {
+    src = c->lse;
+    want = (uint64_t)c->last_n_rows * c->d.n_q_heads * sizeof(float);
+  } else {
+    return fail(c, KEEP_ERR_INVALID_ARG, "unknown layer state %d", what);
+  }
+  if (bytes != want)
+    return fail(c, KEEP_ERR_INVALID_ARG, "state %d of the last layer holds %llu bytes, the buffer %llu", what,
+                (unsigned long long)want, (unsigned long long)bytes);
+  HIP_TRY(c, hipStreamSynchronize(c->s_comp));
+  HIP_TRY(c, hipMemcpy(dst, src, (size_t)bytes, hipMemcpyDeviceToHost));
   return KEEP_OK;
 }
 

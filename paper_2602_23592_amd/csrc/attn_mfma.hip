@@ -413,12 +413,8 @@ static void launch_attn_planned(const bf16_t* q, const bf16_t* k_cache, const bf
   float* part_o = reinterpret_cast<float*>(base + off);
   float* part_ml = part_o + (size_t)ATT_MAX_SLOTS * PART_FLOATS;
   const size_t sh = (size_t)2 * ATT_BUF * sizeof(uint16_t);
-  static bool attr_set = false;
-  if (!attr_set) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_attn_mfma), hipFuncAttributeMaxDynamicSharedMemorySize,
-                              (int)sh);
-    attr_set = true;
-  }
+  static std::atomic<uint64_t> attr_done{0};
+  set_max_dyn_smem_once(attr_done, reinterpret_cast<const void*>(k_attn_mfma), (int)sh);
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)DH);
   hipLaunchKernelGGL(k_attn_mfma, dim3(n_items * n_kv_heads), dim3(256), sh, s, q, k_cache, v_cache, d_row_pos, d_row_lo,
                      d_row_list, n_rows, n_total, n_q_heads, n_kv_heads, d_items, scale_log2e, o, lse, part_o, part_ml);

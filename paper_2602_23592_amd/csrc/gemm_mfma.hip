@@ -377,12 +377,8 @@ static void launch_cfg(const bf16_t* A, int M, int K, const MfmaB& b, const bf16
 #define GO(E)                                                                                              \
   do {                                                                                                     \
     auto kern = k_gemm_mfma<BM, BN, WM, WN, E, GBK, NST>;                                                  \
-    static bool attr_set = false;                                                                          \
-    if (!attr_set) {                                                                                       \
-      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, \
-                                (int)sh);                                                                  \
-      attr_set = true;                                                                                     \
-    }                                                                                                      \
+    static std::atomic<uint64_t> attr_done{0};                                                             \
+    set_max_dyn_smem_once(attr_done, reinterpret_cast<const void*>(kern), (int)sh);                        \
     hipLaunchKernelGGL(kern, grid, block, sh, s, A, M, K, b, B2, N, residual, C, tiles_m, tiles_n, full, split, part); \
     if (split > 1)                                                                                         \
       hipLaunchKernelGGL((k_gemm_fixup<BM, BN, WM, WN, E>), dim3(8 * rem, BM * BN / 1024), dim3(256), 0, s, part, M, N, \

@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "keep.h"
 
 namespace keep {
@@ -51,6 +53,17 @@ __device__ inline float ldf(const float* p) { return *p; }
 __device__ inline float ldf(const bf16_t* p) { return bf16_bits_to_f32(p->bits); }
 __device__ inline void stf(float* p, float v) { *p = v; }
 __device__ inline void stf(bf16_t* p, float v) { p->bits = f32_to_bf16_bits(v); }
+
+// Raises a kernel's dynamic shared-memory limit once per device (bit d of `done` = done on device d);
+// safe when several host threads launch at the same time: a second call with the same value is harmless.
+inline void set_max_dyn_smem_once(std::atomic<uint64_t>& done, const void* fn, int bytes) {
+  int dev = 0;
+  (void)hipGetDevice(&dev);
+  const uint64_t bit = 1ull << (dev & 63);
+  if (done.load(std::memory_order_acquire) & bit) return;
+  (void)hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  done.fetch_or(bit, std::memory_order_release);
+}
 
 // ---------------------------------------------------------------------------
 // per-layer row bookkeeping that lives on the device
@@ -183,6 +196,11 @@ void launch_score_mfma(const bf16_t* q, const bf16_t* k_compact, const float* ls
 // multi-hop selection on the device; d_out: [0] = n_next, [1] = hops_run, [2..] = slots kept (ascending)
 void launch_select(const float* S, int32_t m, const int32_t* d_cand_len, int32_t k_count, int32_t token_budget,
                    int32_t mode, int32_t hops, float* d_work /*[(m+1)*m + 2m]*/, int32_t* d_iwork /*[4m]*/,
-                   int32_t* d_out /*[m+2]*/, hipStream_t s);
+                   int32_t* d_out /*[m+2]*/, hipStream_t s, bool set_only = false,
+                   const int32_t* d_cand_total = nullptr, const int32_t* d_id_map = nullptr);
+// d_cand_total (device scalar or NULL): sum of d_cand_len; when given, the kernel itself settles budgets that
+// keep all or none of the candidates (hops_run 0).  d_id_map (device [m] or NULL): ids written instead of slots.
+// set_only: the propagation averages the normalised rows of the relevant set alone (the query's row
+// only initialises the importance); default: the query stays a source at every hop.
 
 }  // namespace keep

@@ -57,8 +57,8 @@ __device__ void take(float* imp, int m, const int32_t* len, int k_count, int tok
 // (0 where the row is empty); it is formed where it is used, only the row totals are kept.
 __global__ void __launch_bounds__(SEL_THREADS)
     k_select(const float* __restrict__ S, int m, const int32_t* __restrict__ cand_len, int k_count, int token_budget,
-             int mode, int hops, int tile_rows, float* __restrict__ work, int32_t* __restrict__ iwork,
-             int32_t* __restrict__ out) {
+             int mode, int hops, int set_only, int tile_rows, float* __restrict__ work, int32_t* __restrict__ iwork,
+             int32_t* __restrict__ out, const int32_t* __restrict__ cand_total, const int32_t* __restrict__ id_map) {
   extern __shared__ float sel_smem[];
   float* tot = sel_smem;                                   // [m + 1] row totals
   float* imp = tot + (m + 1);                              // [m]
@@ -69,6 +69,22 @@ __global__ void __launch_bounds__(SEL_THREADS)
   __shared__ int s_same, s_cnt;
   (void)work;
   (void)iwork;
+  // Callers that could not classify the budget on the host pass the candidates' token total: a budget that
+  // takes every candidate or none is settled here without a selection (0 selections run), as the host does
+  // for the other callers.
+  if (cand_total) {
+    const bool all = m > 0 && (mode == KEEP_BUDGET_GROUP_COUNT ? k_count >= m : token_budget >= *cand_total);
+    const bool none = m == 0 || (mode == KEEP_BUDGET_GROUP_COUNT ? k_count == 0 : token_budget <= 0);
+    if (all || none) {
+      const int n = all ? m : 0;
+      for (int a = threadIdx.x; a < n; a += SEL_THREADS) out[2 + a] = id_map ? id_map[a] : a;
+      if (threadIdx.x == 0) {
+        out[0] = n;
+        out[1] = 0;
+      }
+      return;
+    }
+  }
 
   if (tile_rows > 0) {
     // Row totals, each still summed one element after the other in ascending order, but read through LDS:
@@ -116,15 +132,18 @@ __global__ void __launch_bounds__(SEL_THREADS)
       if (c) atomicAdd(&s_cnt, c);
     }
     __syncthreads();
-    const float denom = (float)(1 + s_cnt);
+    // sources of the propagation: the query and the relevant set, or (set_only: the section's wording taken
+    // literally) the relevant set alone; an empty source set leaves the importance at zero
+    const int n_src = (set_only ? 0 : 1) + s_cnt;
+    const float denom = (float)n_src;
     for (int b = threadIdx.x; b < m; b += SEL_THREADS) {
-      float acc = tq > 0.f ? S[(size_t)m * m + b] / tq : 0.f;
+      float acc = (!set_only && tq > 0.f) ? S[(size_t)m * m + b] / tq : 0.f;
       for (int a = 0; a < m; ++a)
         if (rel[a]) {
           const float ta = tot[a];
           acc = acc + (ta > 0.f ? S[(size_t)a * m + b] / ta : 0.f);
         }
-      imp[b] = acc / denom;
+      imp[b] = n_src > 0 ? acc / denom : acc;
     }
     __syncthreads();
     take(imp, m, len, k_count, token_budget, mode, order, rel2);
@@ -146,14 +165,15 @@ __global__ void __launch_bounds__(SEL_THREADS)
   if (threadIdx.x == 0) {
     int n = 0;
     for (int a = 0; a < m; ++a)
-      if (rel[a]) out[2 + n++] = a;
+      if (rel[a]) out[2 + n++] = id_map ? id_map[a] : a;
     out[0] = n;
     out[1] = runs;
   }
 }
 
 void launch_select(const float* S, int32_t m, const int32_t* d_cand_len, int32_t k_count, int32_t token_budget,
-                   int32_t mode, int32_t hops, float* d_work, int32_t* d_iwork, int32_t* d_out, hipStream_t s) {
+                   int32_t mode, int32_t hops, float* d_work, int32_t* d_iwork, int32_t* d_out, hipStream_t s,
+                   bool set_only, const int32_t* d_cand_total, const int32_t* d_id_map) {
   size_t sh = ((size_t)(m + 1) + m) * sizeof(float) + (size_t)4 * m * sizeof(int32_t);  // <= 160 KB: m <= 6000
   // room for the staging tile of the row totals (256 rows x 33 floats) unless the arrays leave none
   int tile_rows = 0;
@@ -161,14 +181,10 @@ void launch_select(const float* S, int32_t m, const int32_t* d_cand_len, int32_t
     tile_rows = 256;
     sh += (size_t)256 * 33 * sizeof(float);
   }
-  static bool attr_set = false;
-  if (!attr_set) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_select), hipFuncAttributeMaxDynamicSharedMemorySize,
-                              160 * 1024 - 256);
-    attr_set = true;
-  }
+  static std::atomic<uint64_t> attr_done{0};
+  set_max_dyn_smem_once(attr_done, reinterpret_cast<const void*>(k_select), 160 * 1024 - 256);
   hipLaunchKernelGGL(k_select, dim3(1), dim3(SEL_THREADS), sh, s, S, m, d_cand_len, k_count, token_budget, mode, hops,
-                     tile_rows, d_work, d_iwork, d_out);
+                     set_only ? 1 : 0, tile_rows, d_work, d_iwork, d_out, d_cand_total, d_id_map);
 }
 
 }  // namespace keep

@@ -19,6 +19,35 @@ def max_rel(a: np.ndarray, b: np.ndarray) -> float:
     return float(np.abs(a - b).max() / (den if den > 0 else 1.0))
 
 
+def update_err(x_out: np.ndarray, x_in: np.ndarray, ref_out: np.ndarray, storage: str):
+    """Error of the layer's UPDATE (x_out - x_in: output projection of the attention plus FFN), relative to the
+    largest reference update, and the share of that error the output format itself accounts for.
+
+    The residual stream is several times larger than what a layer adds to it, so max|a-b| / max|b| over x_out
+    would let an attention error of tens of percent through; the update has no such cushion.  x_out is stored
+    in `storage`: writing it costs up to half an ulp of the largest output, 2^-9 max|x_out| in bf16
+    (2^-25 in fp32), which the returned allowance expresses in units of the largest update.
+    Returns (error, allowance): assert error < tol + allowance."""
+    x_out, x_in, ref_out = (np.asarray(v, dtype=np.float64) for v in (x_out, x_in, ref_out))
+    d_ref = ref_out - x_in
+    den = max(np.abs(d_ref).max(), 1e-300)
+    err = float(np.abs((x_out - x_in) - d_ref).max() / den)
+    half_ulp = 2.0 ** -9 if storage == "bf16" else 2.0 ** -25
+    return err, float(half_ulp * np.abs(ref_out).max() / den)
+
+
+def layer_state_err(ctx, n_rows: int, probe: dict, lse_ref: np.ndarray, rows=None):
+    """The attention output and the log-sum-exp that keep_recompute_layer left in the workspace against the
+    oracle's (probe["attn_out"], lse_ref), each relative to its own largest value; `rows` restricts the
+    device side to the rows the oracle evaluated.  Returns (attention error, log-sum-exp error)."""
+    from paper_2602_23592_amd.binding import KEEP_STATE_ATTN_OUT, KEEP_STATE_LSE
+    o = ctx.read_layer_state(KEEP_STATE_ATTN_OUT, n_rows).astype(np.float64)
+    lse = ctx.read_layer_state(KEEP_STATE_LSE, n_rows).astype(np.float64)
+    if rows is not None:
+        o, lse = o[rows], lse[rows]
+    return max_rel(o, probe["attn_out"]), max_rel(lse, lse_ref)
+
+
 def to_np(t: torch.Tensor) -> np.ndarray:
     return t.detach().to("cpu", torch.float64).numpy()
 

@@ -9,7 +9,7 @@ import torch
 
 import keep_synth as ks
 from oracle import keep_oracle as ko
-from gpu_util import max_rel, to_np
+from gpu_util import max_rel, to_np, update_err, layer_state_err
 
 pytestmark = pytest.mark.gpu
 TOL = 2e-2
@@ -61,6 +61,9 @@ def test_fullsize_selective_layer_sampled(workload):
     vc = torch.zeros_like(kc)
     x_out = torch.empty((n_rows, s.hidden), dtype=torch.bfloat16, device=dev)
     ctx.recompute_layer(pr, 0, groups, x_t.to(dev), x_out, kc, vc)
+    from paper_2602_23592_amd.binding import KEEP_STATE_ATTN_OUT, KEEP_STATE_LSE
+    o_dev = ctx.read_layer_state(KEEP_STATE_ATTN_OUT, n_rows)
+    lse_dev = ctx.read_layer_state(KEEP_STATE_LSE, n_rows)
     mode = KEEP_BUDGET_TOKENS if tokens_mode else KEEP_BUDGET_GROUP_COUNT
     nxt, runs, S = ctx.score_groups(pr, 0, groups, float(ratios[2]), w.hops, mode)
     torch.cuda.synchronize()
@@ -75,17 +78,27 @@ def test_fullsize_selective_layer_sampled(workload):
     med = int(np.median([glist[g] for g in groups]))
     small = [i for i, g in enumerate(groups) if glist[g] <= med]
     blocks = sorted({small[0], small[len(small) // 2], small[-1]})
-    xo_ref, lse_ref, S_ref = ko.selective_layer(sh, lw, x_np, groups, glist, lq, kh, vh, score_blocks=blocks + [m])
+    probe = {}
+    xo_ref, lse_ref, S_ref = ko.selective_layer(sh, lw, x_np, groups, glist, lq, kh, vh, score_blocks=blocks + [m],
+                                                probe=probe)
     # whole cache
     ek, ev = max_rel(to_np(kc), kh), max_rel(to_np(vc), vh)
     # sampled output rows: the rows of the sampled blocks and of the instruction
     starts = np.concatenate([[0], np.cumsum([glist[g] for g in groups])])
     rows = np.concatenate([np.arange(starts[b], starts[b + 1]) for b in blocks] + [np.arange(starts[m], starts[m] + lq)])
-    ex = max_rel(to_np(x_out[torch.from_numpy(rows).to(dev)]), xo_ref)
+    xo_dev = to_np(x_out[torch.from_numpy(rows).to(dev)])
+    ex = max_rel(xo_dev, xo_ref)
     es = np.nanmax(np.abs(S[blocks + [m]] - S_ref[blocks + [m]])) / np.nanmax(S_ref[blocks + [m]])
-    print("full size %s: rows %d groups %d  K %.2e V %.2e X(sampled %d rows) %.2e S(sampled %d rows) %.2e"
-          % (workload, n_rows, m, ek, ev, len(rows), ex, len(blocks) + 1, es))
+    # on their own scale: the attention output and log-sum-exp of the sampled rows, and the layer's update
+    # (output minus input) of those rows, where the residual stream does not hide an attention error
+    eo = max_rel(o_dev[rows].astype(np.float64), probe["attn_out"])
+    el = max_rel(lse_dev[rows].astype(np.float64), lse_ref)
+    ed, allow = update_err(xo_dev, x_np[rows], xo_ref, "bf16")
+    print("full size %s: rows %d groups %d  K %.2e V %.2e X(sampled %d rows) %.2e S(sampled %d rows) %.2e  "
+          "attention %.2e lse %.2e update %.2e (format %.1e)"
+          % (workload, n_rows, m, ek, ev, len(rows), ex, len(blocks) + 1, es, eo, el, ed, allow))
     assert ek < TOL and ev < TOL and ex < TOL and es < TOL
+    assert eo < TOL and el < TOL and ed < TOL + allow
     # the device's selection is the oracle's selection applied to the device's scores
     want, want_runs = ko.select_multihop(S, groups, glist, float(ratios[2]), w.hops,
                                          ko.BUDGET_TOKENS if tokens_mode else ko.BUDGET_GROUP_COUNT)
@@ -173,3 +186,143 @@ def test_fullsize_prefill_layer0_selection_equals_full_matrix_selection():
     want, want_runs = ko.select_multihop(S, list(range(G)), glist, ratio1, w.hops, ko.BUDGET_TOKENS)
     assert nxt == want and runs == want_runs
     assert rep.ffn_rows[0] == sum(glist[g] for g in nxt) + lq       # evaluation went first: FFN on the survivors only
+
+
+# ---------------------------------------------------------------------------------------------------------
+# The first two layers of the benchmark workload through keep_prefill, as bench.py launches it
+# ---------------------------------------------------------------------------------------------------------
+_TWO_LAYER_RUN = {}
+
+
+def _two_layer_run():
+    """Layers 0 and 1 of qwen14b_32k through keep_prefill in bench.py's configuration: three streams, token
+    budget, 3 hops, 272 candidates (scores hop by hop, attention on demand, evaluation before the FFN, FFN on
+    the survivors).  Weights and token ids are the seeded draws of the benchmark; the group caches are seeded
+    random blocks (the oracle must not read anything the device produced).  Run once per process."""
+    if _TWO_LAYER_RUN:
+        return _TWO_LAYER_RUN
+    from paper_2602_23592_amd import KeepContext, KeepPrompt
+    from paper_2602_23592_amd.binding import KEEP_BUDGET_TOKENS
+    w = ks.workload("qwen14b_32k")
+    s = w.shape
+    two = ks.ModelShape(2, s.hidden, s.n_q_heads, s.n_kv_heads, s.head_dim, s.ffn_dim, 4099, s.rope_theta,
+                        s.rms_eps, s.storage)
+    glen, kinds = ks.group_lengths(w)
+    glist = [int(v) for v in glen]
+    G, lq = len(glist), w.instr_len
+    n_tokens = w.mem_tokens + lq
+    dev = "cuda"
+    layers_t = [ks.make_layer_weights(two, l, "cpu") for l in range(2)]
+    embed_t = ks.make_embedding(two, "cpu")
+    ids = ks.make_token_ids(n_tokens, two.vocab, 0)
+    caches = [ks.make_random_group_cache(two, glist, l, seed=7) for l in range(2)]
+    streams = [torch.cuda.Stream() for _ in range(3)]
+    ctx = KeepContext(two, [{k: (None if v is None else v.to(dev)) for k, v in lw.items()} for lw in layers_t],
+                      embed_t.to(dev), n_tokens, G, 0, *streams)
+    assert ctx.uses_mfma
+    kb_d = [[t.to(dev) for t in caches[l][0]] for l in range(2)]
+    vb_d = [[t.to(dev) for t in caches[l][1]] for l in range(2)]
+    pr = KeepPrompt(glist, lq, ids, kb_d, vb_d, 2, group_kind=kinds)
+    ratio1 = float(ks.ratio_schedule(w.ratio, s.n_layers, w.schedule)[1])
+    kc = torch.full((2, n_tokens, s.n_kv_heads, s.head_dim), float("nan"), dtype=torch.bfloat16, device=dev)
+    vc = kc.clone()
+    xf = torch.empty((lq, s.hidden), dtype=torch.bfloat16, device=dev)
+    torch.cuda.synchronize()
+    sets, rep = ctx.prefill(pr, [1.0, ratio1], w.hops, kc, vc, xf, KEEP_BUDGET_TOKENS, want_report=True)
+    torch.cuda.synchronize()
+    # the configuration under test really ran
+    assert rep.attn_rows[0] < rep.rows[0] == n_tokens and rep.ffn_rows[0] == rep.rows[1] < n_tokens // 2
+    _TWO_LAYER_RUN.update(dict(w=w, two=two, glist=glist, lq=lq, n_tokens=n_tokens, layers_t=layers_t, embed_t=embed_t,
+                               ids=ids, caches=caches, ratio1=ratio1, sets=sets, hops_run=rep.hops_run[0],
+                               kc=kc.cpu(), vc=vc.cpu(), xf=xf.cpu()))
+    ctx.close()
+    return _TWO_LAYER_RUN
+
+
+def _oracle_inputs(r, dtype):
+    two = r["two"]
+    sh = ko.Shape(2, two.hidden, two.n_q_heads, two.n_kv_heads, two.head_dim, two.ffn_dim, two.vocab, two.rope_theta,
+                  two.rms_eps, two.storage)
+    lws = [{k: (None if v is None else v.to(torch.float64 if dtype == np.float64 else torch.float32).numpy())
+            for k, v in lw.items()} for lw in r["layers_t"]]
+    embed = r["embed_t"].to(torch.float64).numpy().astype(dtype)
+    return sh, lws, embed
+
+
+def test_fullsize_first_two_layers_against_the_oracle():
+    """What the benchmark's layer 0 leaves behind, against the oracle teacher-forced to the device's sets: the
+    whole K/V cache of layer 0 (every row refreshed), the whole K/V cache of layer 1 (survivors refreshed from
+    layer 0's output rows, the rest re-aligned) and the final instruction rows.  An error in the hop-by-hop
+    attention, the survivor gather or the survivors-only FFN would show in layer 1."""
+    r = _two_layer_run()
+    glist, lq, sets = r["glist"], r["lq"], r["sets"]
+    G = len(glist)
+    assert sets[0] == list(range(G)) and 0 < len(sets[1]) < G
+    sh, lws, embed = _oracle_inputs(r, np.float64)
+    off = ko.group_offsets(glist)
+    # layer 0: K/V of all rows; attention, projection and FFN only for the rows that survive
+    kb0 = [ks.to_numpy_f64(t) for t in r["caches"][0][0]]
+    vb0 = [ks.to_numpy_f64(t) for t in r["caches"][0][1]]
+    kh0, vh0 = ko.realign_concat(sh, kb0, vb0, glist, lq)
+    x0 = embed[np.asarray(r["ids"])]
+    keep_rows = ko.rows_of(sets[1], glist, lq)              # at layer 0 the compact row index is the position
+    x1, _, _ = ko.selective_layer(sh, lws[0], x0, sets[0], glist, lq, kh0, vh0, want_scores=False, only_rows=keep_rows)
+    ek0, ev0 = max_rel(to_np(r["kc"][0]), kh0), max_rel(to_np(r["vc"][0]), vh0)
+    # layer 1: survivors refreshed over the joined cache; only the instruction rows are needed afterwards
+    kb1 = [ks.to_numpy_f64(t) for t in r["caches"][1][0]]
+    vb1 = [ks.to_numpy_f64(t) for t in r["caches"][1][1]]
+    kh1, vh1 = ko.realign_concat(sh, kb1, vb1, glist, lq)
+    n1 = len(keep_rows)
+    xf_ref, _, _ = ko.selective_layer(sh, lws[1], x1, sets[1], glist, lq, kh1, vh1, want_scores=False,
+                                      only_rows=np.arange(n1 - lq, n1))
+    ek1, ev1 = max_rel(to_np(r["kc"][1]), kh1), max_rel(to_np(r["vc"][1]), vh1)
+    # refreshed rows of layer 1 on their own scale (the re-aligned random blocks dominate the whole-cache norm)
+    ek1r = max_rel(to_np(r["kc"][1])[keep_rows], kh1[keep_rows])
+    ev1r = max_rel(to_np(r["vc"][1])[keep_rows], vh1[keep_rows])
+    ex = max_rel(to_np(r["xf"]), xf_ref)
+    ed, allow = update_err(to_np(r["xf"]), x1[n1 - lq:], xf_ref, "bf16")
+    print("two layers at full size: set sizes %s  layer 0 K %.2e V %.2e | layer 1 K %.2e V %.2e, refreshed rows K %.2e "
+          "V %.2e | x_final %.2e, its layer-1 update %.2e (format %.1e)"
+          % ([len(x) for x in sets], ek0, ev0, ek1, ev1, ek1r, ev1r, ex, ed, allow))
+    assert not torch.isnan(r["kc"]).any() and not torch.isnan(r["vc"]).any()
+    assert max(ek0, ev0, ek1, ev1, ek1r, ev1r, ex) < TOL and ed < TOL + allow
+
+
+def test_fullsize_layer0_selection_overlap_with_the_free_running_oracle():
+    """The device's bf16 decision for layer 1 (272 candidates, token budget, 3 hops) against the oracle deciding
+    on its own scores: the oracle forms the rows of S that its own propagation reads (the query's, then those of
+    each selection's memories), nothing is taken from the device.  Reports the share of the oracle's recomputed
+    tokens that the device recomputes too, and asserts the benchmark spec's bound."""
+    r = _two_layer_run()
+    glist, lq, w = r["glist"], r["lq"], r["w"]
+    G = len(glist)
+    sh, lws, embed = _oracle_inputs(r, np.float32)            # binary32 oracle: the selection arithmetic is binary32
+    kb0 = [t.float().numpy() for t in r["caches"][0][0]]
+    vb0 = [t.float().numpy() for t in r["caches"][0][1]]
+    x0 = embed[np.asarray(r["ids"])]
+    groups = list(range(G))
+    S = np.zeros((G + 1, G), dtype=np.float32)
+    known = set()
+
+    def fill(blocks):
+        kh0, vh0 = ko.realign_concat(sh, kb0, vb0, glist, lq, dtype=np.float32)
+        _, _, Sb = ko.selective_layer(sh, lws[0], x0, groups, glist, lq, kh0, vh0, score_blocks=sorted(blocks))
+        for b in blocks:
+            S[b] = Sb[b]
+            known.add(b)
+
+    fill([G])                                                  # the query's row
+    sel, runs = None, 0
+    for h in range(1, w.hops + 1):
+        sel, runs = ko.select_multihop(S, groups, glist, r["ratio1"], h, ko.BUDGET_TOKENS)
+        if runs < h:
+            break                                              # converged before the hop limit
+        missing = [b for b in sel if b not in known]
+        if h < w.hops and missing:
+            fill(missing)                                      # the next selection reads these rows
+    tok = lambda gs: sum(glist[g] for g in gs)
+    dev = r["sets"][1]
+    share = tok(set(dev) & set(sel)) / max(1, tok(sel))
+    print("layer 0 -> 1 at full size: device set %s (%d tokens, %d selections) | free-running oracle %s (%d tokens, "
+          "%d selections) | token overlap %.4f" % (dev, tok(dev), r["hops_run"], sel, tok(sel), runs, share))
+    assert share >= 0.99

@@ -7,7 +7,7 @@ import torch
 
 import keep_synth as ks
 from oracle import keep_oracle as ko
-from gpu_util import Problem, max_rel, to_np
+from gpu_util import Problem, max_rel, to_np, update_err, layer_state_err
 
 pytestmark = pytest.mark.gpu
 
@@ -69,15 +69,21 @@ def test_layer_teacher_forced(shape_name, layout):
         x_t = ks.make_random_rows(n_rows, shape.hidden, shape.storage, seed=11 + layer)
         x_np = ks.to_numpy_f64(x_t)
         kh, vh = pb.oracle_joined_cache(layer)
-        xo_ref, lse_ref, S_ref = ko.selective_layer(pb.sh, pb.layers[layer], x_np, groups, glen, lq, kh, vh)
+        probe = {}
+        xo_ref, lse_ref, S_ref = ko.selective_layer(pb.sh, pb.layers[layer], x_np, groups, glen, lq, kh, vh, probe=probe)
         kc, vc = pb.empty_cache(1)
         x_out = torch.empty_like(x_t, device="cuda")
         ctx.recompute_layer(pr, layer, groups, x_t.cuda(), x_out, kc[0], vc[0])
+        eo, el = layer_state_err(ctx, n_rows, probe, lse_ref)
         nxt, runs, S = ctx.score_groups(pr, layer, groups, 0.5, 2)
         torch.cuda.synchronize()
         assert max_rel(to_np(kc[0]), kh) < tol, (layer, groups)
         assert max_rel(to_np(vc[0]), vh) < tol
         assert max_rel(to_np(x_out), xo_ref) < tol
+        # the attention output and its log-sum-exp on their own scale, and the layer's update without the
+        # residual stream's cushion
+        ed, allow = update_err(to_np(x_out), x_np, xo_ref, shape.storage)
+        assert eo < tol and el < tol and ed < tol + allow, (layer, groups, eo, el, ed, allow)
         if len(groups):
             assert np.abs(S - S_ref).max() <= tol * max(S_ref.max(), 1e-30), (S, S_ref)
             # the device selection is the oracle's selection applied to the device's own scores
@@ -134,6 +140,46 @@ def test_selection_bit_exact_against_oracle():
                 assert got_runs == runs
                 n_checked += 1
     assert n_checked == 360
+
+
+def test_selection_literal_propagation_bit_exact_against_oracle():
+    """KEEP_SOURCES_SET_ONLY: the propagation averages the rows of the relevant set alone (the section's wording
+    taken literally).  Same bit-exact bar against the oracle's drop_query variant; the option is per context and
+    can be switched back."""
+    from paper_2602_23592_amd import binding as kbind
+    shape = SHAPES["f32_small"]
+    pb = Problem(shape, [4] * 40, 2, seed=2, random_cache=True)
+    ctx = pb.context(max_groups=400)
+    rng = np.random.default_rng(29)
+    differs = 0
+    for trial in range(40):
+        G = int(rng.integers(2, 41)) if trial < 36 else int(rng.integers(260, 400))
+        glen = [int(v) for v in rng.integers(1, 50, size=G)]
+        m = int(rng.integers(1, G + 1))
+        groups = sorted(rng.choice(G, size=m, replace=False).tolist())
+        S = np.tril(rng.random((m + 1, m)), -1).astype(np.float32)
+        S[m] = rng.random(m).astype(np.float32)
+        if trial % 4 == 0:
+            S = (np.round(S * 4) / 4).astype(np.float32)
+        if trial % 7 == 0:
+            S[m] = 0.0                          # empty first set: the literal variant has no source at all
+        for mode in (0, 1):
+            for hops in (2, 5):
+                ratio = float(np.float32(rng.random()))
+                ctx.set_option(kbind.KEEP_OPT_PROPAGATION_SOURCES, kbind.KEEP_SOURCES_SET_ONLY)
+                want, runs = ko.select_multihop(S, groups, glen, ratio, hops, mode, drop_query=True)
+                got, got_runs = ctx.select_groups(S, groups, glen, ratio, hops, mode)
+                assert got == want and got_runs == runs, (trial, mode, hops, ratio)
+                ctx.set_option(kbind.KEEP_OPT_PROPAGATION_SOURCES, kbind.KEEP_SOURCES_QUERY_AND_SET)
+                want2, runs2 = ko.select_multihop(S, groups, glen, ratio, hops, mode)
+                got2, got_runs2 = ctx.select_groups(S, groups, glen, ratio, hops, mode)
+                assert got2 == want2 and got_runs2 == runs2
+                differs += want != want2
+    assert differs > 0          # the two readings do select differently on some of these matrices
+    with pytest.raises(kbind.KeepError):
+        ctx.set_option(kbind.KEEP_OPT_PROPAGATION_SOURCES, 7)
+    with pytest.raises(kbind.KeepError):
+        ctx.set_option(99, 0)
 
 
 def test_selection_bit_exact_with_many_candidates():
