@@ -232,6 +232,30 @@ keep_status keep_select_groups(keep_ctx* ctx, const float* S, const int32_t* gro
                                const int32_t* group_len, int32_t n_groups_total, float ratio_next, int32_t hops,
                                int32_t budget_mode, int32_t* next_groups, int32_t* n_next, int32_t* hops_run);
 
+#define KEEP_STATIC_MAX_CANDIDATES 4096
+/* keep_select_groups for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  It needs no context: the scratch that the selection uses
+ * beyond its inputs and outputs (the candidates' lengths and their token total) lives in a device array built
+ * into the library (16.25 KiB, held by every GPU the library runs on until the process ends), and the call
+ * makes no allocation, on the device or through any library.  Inputs and outputs are DEVICE memory:
+ *   S:         DEVICE [(n_sel + 1) * n_sel], last row the query (as keep_select_groups, but on the device).
+ *   groups:    DEVICE [n_sel], strictly ascending group ids below n_groups_total (not checked; ids are clamped
+ *              into range when the lengths are looked up).
+ *   group_len: DEVICE [n_groups_total] lengths of all the prompt's groups; mem_tokens: their sum (the token
+ *              budget is a share of it).
+ *   propagation_sources: keep_propagation_sources (there is no context to hold the option).
+ *   result:    DEVICE [n_sel + 2]: result[0] = n_next, result[1] = selections run (0 where the budget keeps all
+ *              or none of the candidates), result[2 .. 2 + n_next) = the kept group ids, ascending.
+ *   stream:    hipStream_t or NULL; the kernels are enqueued on it and the call does not wait for them.
+ * Every call on one GPU shares that GPU's scratch array: calls that overlap on one GPU (two streams, two
+ * threads) race; calls on one stream are ordered and need nothing cleared in between.
+ * Errors (text at keep_last_error(NULL)): INVALID_ARG (NULL pointer, unknown mode, ratio outside [0, 1],
+ * hops < 1, n_sel outside [0, n_groups_total], mem_tokens < n_groups_total), WORKSPACE (n_sel above
+ * KEEP_STATIC_MAX_CANDIDATES), HIP. */
+keep_status keep_select_groups_static(const float* S, const int32_t* groups, int32_t n_sel, const int32_t* group_len,
+                                      int32_t n_groups_total, int32_t mem_tokens, float ratio_next, int32_t hops,
+                                      int32_t budget_mode, int32_t propagation_sources, int32_t* result, void* stream);
+
 /* Whole selective prefill (Section 4.2 + 4.3 + 5): for l = 0..n_layers-1 recompute
  * the relevant set of layer l, evaluate importance beside the FFN, load what layer
  * l+1 needs.  Evaluation runs beside the output projection and FFN (Section 4.2), except where the

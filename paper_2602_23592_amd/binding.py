@@ -28,7 +28,7 @@ KEEP_SOURCES_QUERY_AND_SET, KEEP_SOURCES_SET_ONLY = 0, 1
 KEEP_STATE_ATTN_OUT, KEEP_STATE_LSE = 0, 1
 
 EXPORTED = ("keep_init", "keep_destroy", "keep_last_error", "keep_uses_mfma", "keep_workspace_bytes", "keep_recompute_layer",
-            "keep_set_option", "keep_read_layer_state",
+            "keep_set_option", "keep_read_layer_state", "keep_select_groups_static",
             "keep_score_groups", "keep_select_groups", "keep_prefill",
             "keep_prefill_padded", "keep_decode", "keep_precompute_group", "keep_precompute_groups",
             "keep_dequantize_int4", "keep_attach_int4",
@@ -130,6 +130,8 @@ def load_library() -> C.CDLL:
     lib.keep_score_groups.argtypes = [vp, C.POINTER(Prompt), i32, pi32, i32, f32, i32, i32, C.POINTER(f32), pi32, pi32, pi32]
     lib.keep_select_groups.restype = i32
     lib.keep_select_groups.argtypes = [vp, C.POINTER(f32), pi32, i32, pi32, i32, f32, i32, i32, pi32, pi32, pi32]
+    lib.keep_select_groups_static.restype = i32
+    lib.keep_select_groups_static.argtypes = [vp, vp, i32, vp, i32, i32, f32, i32, i32, i32, vp, vp]
     lib.keep_prefill.restype = i32
     lib.keep_prefill.argtypes = [vp, C.POINTER(Prompt), C.POINTER(f32), i32, i32, i32, vp, vp, vp, pi32, pi32,
                                  C.POINTER(Report)]
@@ -239,6 +241,24 @@ def dequantize_int4(codes: torch.Tensor, scale_zero: torch.Tensor, rows: int, k:
     if st != KEEP_OK:
         raise KeepError(st, lib.keep_last_error(None).decode())
     return out
+
+
+def select_groups_static(S: torch.Tensor, groups: torch.Tensor, group_len: torch.Tensor, mem_tokens: int,
+                         ratio_next: float, hops: int, budget_mode: int, propagation_sources: int,
+                         result: torch.Tensor, stream=None):
+    """keep_select_groups_static: every tensor is caller-allocated device memory (S float32 [(m+1), m], groups
+    int32 [m], group_len int32 [G], result int32 [m + 2]); nothing is allocated here or in the library."""
+    lib = load_library()
+    m = int(groups.numel())
+    for t, dt in ((S, torch.float32), (groups, torch.int32), (group_len, torch.int32), (result, torch.int32)):
+        assert t.is_cuda and t.is_contiguous() and t.dtype == dt
+    assert S.numel() == (m + 1) * m and result.numel() >= m + 2
+    st = lib.keep_select_groups_static(S.data_ptr(), groups.data_ptr(), m, group_len.data_ptr(), int(group_len.numel()),
+                                       int(mem_tokens), float(ratio_next), hops, budget_mode, propagation_sources,
+                                       result.data_ptr(),
+                                       _stream_handle(stream if stream is not None else torch.cuda.current_stream()))
+    if st != KEEP_OK:
+        raise KeepError(st, lib.keep_last_error(None).decode())
 
 
 class KeepContext:

@@ -112,6 +112,15 @@ struct keep_ctx {
 
 namespace {
 
+}  // namespace
+
+namespace keep {
+// message behind keep_last_error(NULL), for entry points that have no context
+void set_init_error(const char* text) { g_init_error = text; }
+}  // namespace keep
+
+namespace {
+
 keep_status fail(keep_ctx* c, keep_status st, const char* fmt, ...) {
   char buf[512];
   va_list ap;
