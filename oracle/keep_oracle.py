@@ -32,7 +32,9 @@ relative-position property; first-group and layer-0 invariances; attention-mass
 conservation; harmonic closed form under uniform attention; brute-force top-k
 and token-budget walks; hand-built propagation chains; decoding one token over
 a cache == the last row of a dense prefill of the longer sequence; logits vs an
-independent PyTorch-CPU expression; argmax tie rule.
+independent PyTorch-CPU expression; argmax tie rule; token-granularity variant:
+ratio 1 == dense prefill, whole memories forced == the memory-granularity path,
+zero deviation at layer 0 and for the first memory, top-k by brute force.
 Parity unpinned: whether the selected memories are the ones a trained model
 needs (task success rate) -- that needs the paper's datasets and weights.
 """
@@ -511,6 +513,116 @@ def keep_prefill(sh: Shape, layers, embed: np.ndarray, token_ids: np.ndarray, gr
         cur, pos = nxt, pos_next
     return {"k_hat": k_hat, "v_hat": v_hat, "x_final": x[len(x) - instr_len:], "sets": sets,
             "scores": scores, "hops_run": hops_run}
+
+
+# ----------------------------------------------------------------------------
+# token-granularity recomputation (the comparison scheme of Section 3 and of
+# Section 4.2, "System advantage"): tokens, not memories, are the units.  The
+# tokens to recompute are chosen by how far their recomputed K/V state lies from
+# the cached one, every cached block is loaded in full, and the recomputed
+# tokens' K/V are written over the loaded rows in place.
+# ----------------------------------------------------------------------------
+def token_budget_count(ratio: float, mem_tokens: int, n_candidates: int) -> int:
+    """Number of memory tokens to keep: ratio of the prompt's memory tokens, rounded up."""
+    k = int(np.ceil(float(np.float32(ratio)) * mem_tokens - BUDGET_EPS))
+    return max(0, min(n_candidates, k))
+
+
+def token_deviation(k_new: np.ndarray, v_new: np.ndarray, k_old: np.ndarray, v_old: np.ndarray) -> np.ndarray:
+    """Per token, the squared distance between its recomputed K/V state and its cached
+    one (both as they sit in the cache format, keys at the same global position):
+    sum over KV heads and head dimensions of (k_new - k_old)^2 + (v_new - v_old)^2.
+    Reading: Section 3 speaks of the discrepancy between the full-attention KV state
+    and the cached KV state without fixing a norm; the squared Euclidean one is taken.
+    Inputs [n, n_kv_heads, head_dim]; returns [n]."""
+    dk = (k_new - k_old).reshape(k_new.shape[0], -1)
+    dv = (v_new - v_old).reshape(v_new.shape[0], -1)
+    return (dk * dk).sum(axis=1) + (dv * dv).sum(axis=1)
+
+
+def select_tokens(deviation: np.ndarray, k: int) -> List[int]:
+    """Indices of the k candidates with the largest deviation (compared as binary32
+    values, because they decide integers), the lower index first among equal values;
+    returned ascending."""
+    d32 = np.asarray(deviation, dtype=np.float32)
+    order = sorted(range(len(d32)), key=lambda i: (-float(d32[i]), i))
+    return sorted(order[:max(0, k)])
+
+
+def recompute_token_rows(sh: Shape, w: Dict[str, np.ndarray], x: np.ndarray, pos: np.ndarray,
+                         k_hat: np.ndarray, v_hat: np.ndarray):
+    """One layer for the token rows at global positions `pos` (ascending; x[n, hidden] holds
+    their hidden rows): project, measure the deviation from the cache rows they replace,
+    overwrite those rows in place, attend over the whole cache causally, output projection
+    and FFN.  Returns (x_out [n, hidden], deviation [n])."""
+    q, k, v = project_qkv(sh, w, x, pos)
+    k = round_to_storage(k, sh.storage)
+    v = round_to_storage(v, sh.storage)
+    dev = token_deviation(k, v, k_hat[pos], v_hat[pos])
+    k_hat[pos] = k
+    v_hat[pos] = v
+    n_total = k_hat.shape[0]
+    rep = sh.n_q_heads // sh.n_kv_heads
+    visible = np.arange(n_total)[None, :] <= pos[:, None]
+    o = np.empty_like(q)
+    for h in range(sh.n_q_heads):
+        s = (q[:, h, :] @ k_hat[:, h // rep, :].T) / np.sqrt(float(sh.head_dim))
+        s = np.where(visible, s, -np.inf)
+        e = np.exp(s - s.max(axis=1, keepdims=True))
+        o[:, h, :] = (e / e.sum(axis=1, keepdims=True)) @ v_hat[:, h // rep, :]
+    return output_and_ffn(sh, w, x, o), dev
+
+
+def keep_prefill_tokens(sh: Shape, layers, embed: np.ndarray, token_ids: np.ndarray, group_len: Sequence[int],
+                        instr_len: int, k_blocks, v_blocks, ratios: Sequence[float],
+                        forced_rows: Optional[Sequence[Sequence[int]]] = None, dtype=np.float64):
+    """Token-granularity selective prefill of the joined prompt.
+
+    Layer l recomputes the memory tokens of T_l and every instruction token; T_0 is every
+    memory token (ratios[0] = 1) or none (0).  T_{l+1} = the ceil(ratios[l+1] * N_mem)
+    tokens of T_l whose K/V at layer l deviate most from the cache (ties: lower position),
+    so the sets are nested as in the memory-granularity method.
+    Reading: the deviation of layer l decides layer l+1; at layer 0 it is zero up to rounding
+    (K/V of the first layer depend on the token alone), so a schedule that means anything
+    keeps ratios[1] = 1 and starts selecting from layer 1's deviation.
+    forced_rows[l]: positions of the memory tokens recomputed at layer l (teacher forcing).
+
+    Returns dict with k_hat[l], v_hat[l], x_final [instr_len, hidden], rows[l] (sorted memory
+    positions recomputed at l), deviation[l] (aligned with rows[l])."""
+    n_mem = int(np.sum(group_len))
+    assert ratios[0] in (0.0, 1.0)
+    k_hat, v_hat = [], []
+    for l in range(sh.n_layers):
+        kh, vh = realign_concat(sh, k_blocks[l], v_blocks[l], group_len, instr_len, dtype)
+        k_hat.append(kh)
+        v_hat.append(vh)
+    instr_pos = np.arange(n_mem, n_mem + instr_len, dtype=np.int64)
+    cur = np.arange(n_mem, dtype=np.int64) if ratios[0] == 1.0 else np.zeros(0, dtype=np.int64)
+    if forced_rows is not None:
+        cur = np.asarray(sorted(forced_rows[0]), dtype=np.int64)
+    pos = np.concatenate([cur, instr_pos])
+    x = embed[np.asarray(token_ids)[pos]].astype(dtype)
+    rows, deviations = [], []
+    for l in range(sh.n_layers):
+        rows.append([int(p) for p in cur])
+        x, dev = recompute_token_rows(sh, layers[l], x, pos, k_hat[l], v_hat[l])
+        deviations.append(dev[:len(cur)])
+        if l + 1 == sh.n_layers:
+            break
+        if forced_rows is not None:
+            nxt = np.asarray(sorted(forced_rows[l + 1]), dtype=np.int64)
+            assert set(nxt.tolist()) <= set(cur.tolist()), "token sets must be nested"
+            keep = np.searchsorted(cur, nxt)
+        else:
+            keep = np.asarray(select_tokens(dev[:len(cur)], token_budget_count(ratios[l + 1], n_mem, len(cur))),
+                              dtype=np.int64)
+            nxt = cur[keep]
+        # hidden rows of the tokens that leave the set are discarded
+        x = np.concatenate([x[keep], x[len(cur):]])
+        cur = nxt
+        pos = np.concatenate([cur, instr_pos])
+    return {"k_hat": k_hat, "v_hat": v_hat, "x_final": x[len(x) - instr_len:], "rows": rows,
+            "deviation": deviations}
 
 
 # ----------------------------------------------------------------------------

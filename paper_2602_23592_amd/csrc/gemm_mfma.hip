@@ -170,6 +170,21 @@ __global__ void __launch_bounds__(WM* WN * 64)
   __builtin_amdgcn_s_waitcnt(vmcnt_imm((NST - 1) * LD));  // slice 0 has landed in LDS
   __syncthreads();
 
+  // A wave whose rows all lie past M (the last, partly filled row of tiles) has nothing to multiply: it keeps
+  // doing its share of the staging and takes part in every barrier, but issues no operand reads and no MFMAs,
+  // which leaves the SIMD's matrix pipe (and its power) to the wave it shares the SIMD with.
+  if (m0 + wm * TM >= M) {
+    int st_ = 0;
+    for (int kt = kt_begin; kt < KT; ++kt) {
+      __builtin_amdgcn_s_waitcnt(vmcnt_imm((NST - 2) * LD));
+      __syncthreads();
+      GEMM_STAGE(min(kt + NST, KT - 1), st_)
+      st_ = st_ + 1 == NST ? 0 : st_ + 1;
+    }
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    return;
+  }
+
   const int a_row0 = wm * TM + (lane & 31);
   const int b_row0 = wn * TN + (lane & 31);
   const int kg = lane >> 5;
@@ -422,7 +437,10 @@ void launch_gemm_mfma(const bf16_t* A, int32_t M, int32_t K, const GemmB& B, con
   // multiples of 256.  A last, partly filled round of workgroups is cut along K in either case.
   const long tiles256 = (long)((M + 255) / 256) * (rows / 256);
   if (aligned256 && rows % 256 == 0 && tiles256 * (K / 64) >= 10000)
-    launch_cfg<256, 256, 4, 2, 64, 2>(A, M, K, b, b2, N, epilogue, residual, C, s, skinny_ws);
+#ifndef GEMM_BIG_CFG
+#define GEMM_BIG_CFG 256, 256, 4, 2, 64, 2
+#endif
+    launch_cfg<GEMM_BIG_CFG>(A, M, K, b, b2, N, epilogue, residual, C, s, skinny_ws);
   else if (rows % 128 == 0)
     launch_cfg<128, 128, 2, 2, 64, 2>(A, M, K, b, b2, N, epilogue, residual, C, s, skinny_ws);
   else
