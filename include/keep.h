@@ -278,6 +278,32 @@ keep_status keep_prefill(keep_ctx* ctx, const keep_prompt* prompt, const float* 
                          int32_t budget_mode, int32_t load_mode, void* k_cache, void* v_cache, void* x_final,
                          int32_t* sel_groups, int32_t* sel_counts, keep_report* report);
 
+/* The token-granularity scheme that Section 3 and Section 4.2 ("System advantage") set the method against, on the
+ * same kernels: single tokens, not memories, are recomputed.  Every cached block of every layer is loaded and
+ * re-aligned (the whole cache is joined), the recomputed tokens' K/V are written over their rows in place, and
+ * the memory tokens of layer l+1 are the ceil(ratios[l+1] * N_mem) tokens of layer l whose recomputed K/V state
+ * lies furthest from the cached one: deviation = sum over KV heads and dimensions of (k_new - k_cached)^2 +
+ * (v_new - v_cached)^2 on the values as stored, summed in binary32 in a fixed order; ties: the lower position.
+ * Instruction tokens are recomputed at every layer.  The deviation of a layer is known after its K/V
+ * projection, so the attention, the output projection and the FFN of a layer run for the tokens that stay.
+ * (At layer 0 the deviation is zero up to rounding: K/V of the first layer depend on the token alone.  A
+ * schedule that means anything keeps ratios[1] = 1 and starts selecting from layer 1.)
+ *   ratios, k_cache, v_cache, x_final, report: as keep_prefill.  load_mode: SERIAL loads layer l+1 after layer
+ *           l's compute, the other two modes load it beside layer l (the whole of it, whatever is selected).
+ *   sel_rows: HOST [n_layers * N_mem] or NULL; row l holds the ascending positions of the memory tokens
+ *           recomputed at layer l.  sel_counts: HOST [n_layers] or NULL.
+ *   deviation_out: HOST [n_layers * N_mem] or NULL; row l holds the deviation of the tokens of sel_rows row l
+ *           (costs one device-to-host copy and a wait per layer).
+ * Errors: INVALID_ARG (schedule), WORKSPACE, SHAPE, HIP. */
+keep_status keep_prefill_tokens(keep_ctx* ctx, const keep_prompt* prompt, const float* ratios, int32_t load_mode,
+                                void* k_cache, void* v_cache, void* x_final, int32_t* sel_rows, int32_t* sel_counts,
+                                float* deviation_out, keep_report* report);
+
+/* The token selection alone on caller-supplied deviations: deviation HOST [n], kept HOST [k] receives the
+ * ascending indices of the k largest (ties: lower index).  Errors: INVALID_ARG (k outside [0, n], NULL),
+ * WORKSPACE (n above max_tokens), HIP. */
+keep_status keep_select_tokens(keep_ctx* ctx, const float* deviation, int32_t n, int32_t k, int32_t* kept);
+
 /* keep_prefill into caches with room for decoded tokens: as keep_prefill, but layer l of k_cache / v_cache
  * starts at row l * cache_rows (cache_rows >= N); rows N..cache_rows-1 of every layer are left untouched.
  * Errors: as keep_prefill, INVALID_ARG if cache_rows < N. */

@@ -28,7 +28,8 @@ KEEP_SOURCES_QUERY_AND_SET, KEEP_SOURCES_SET_ONLY = 0, 1
 KEEP_STATE_ATTN_OUT, KEEP_STATE_LSE = 0, 1
 
 EXPORTED = ("keep_init", "keep_destroy", "keep_last_error", "keep_uses_mfma", "keep_workspace_bytes", "keep_recompute_layer",
-            "keep_set_option", "keep_read_layer_state", "keep_select_groups_static",
+            "keep_set_option", "keep_read_layer_state", "keep_select_groups_static", "keep_prefill_tokens",
+            "keep_select_tokens",
             "keep_score_groups", "keep_select_groups", "keep_prefill",
             "keep_prefill_padded", "keep_decode", "keep_precompute_group", "keep_precompute_groups",
             "keep_dequantize_int4", "keep_attach_int4",
@@ -132,6 +133,11 @@ def load_library() -> C.CDLL:
     lib.keep_select_groups.argtypes = [vp, C.POINTER(f32), pi32, i32, pi32, i32, f32, i32, i32, pi32, pi32, pi32]
     lib.keep_select_groups_static.restype = i32
     lib.keep_select_groups_static.argtypes = [vp, vp, i32, vp, i32, i32, f32, i32, i32, i32, vp, vp]
+    lib.keep_prefill_tokens.restype = i32
+    lib.keep_prefill_tokens.argtypes = [vp, C.POINTER(Prompt), C.POINTER(f32), i32, vp, vp, vp, pi32, pi32,
+                                        C.POINTER(f32), C.POINTER(Report)]
+    lib.keep_select_tokens.restype = i32
+    lib.keep_select_tokens.argtypes = [vp, C.POINTER(f32), i32, i32, pi32]
     lib.keep_prefill.restype = i32
     lib.keep_prefill.argtypes = [vp, C.POINTER(Prompt), C.POINTER(f32), i32, i32, i32, vp, vp, vp, pi32, pi32,
                                  C.POINTER(Report)]
@@ -405,6 +411,33 @@ class KeepContext:
                 C.byref(rep) if want_report else None))
         sets = [[int(v) for v in sel[l * G:l * G + cnt[l]]] for l in range(L)]
         return sets, rep
+
+    def prefill_tokens(self, prompt: KeepPrompt, ratios: Sequence[float], k_cache: torch.Tensor, v_cache: torch.Tensor,
+                       x_final: torch.Tensor, load_mode: int = KEEP_LOAD_LAYER_BALANCED, want_deviation: bool = False,
+                       want_report: bool = False):
+        """keep_prefill_tokens.  Returns (rows per layer, deviations per layer or None, report or None)."""
+        L, nm = self.shape.n_layers, prompt.n_mem
+        r = np.ascontiguousarray(np.asarray(ratios, dtype=np.float32))
+        sel = np.zeros(max(1, L * nm), dtype=np.int32)
+        cnt = np.zeros(L, dtype=np.int32)
+        dev = np.zeros(max(1, L * nm), dtype=np.float32) if want_deviation else None
+        rep = Report() if want_report else None
+        self._check(self.lib.keep_prefill_tokens(
+            self.handle, C.byref(prompt.c), r.ctypes.data_as(C.POINTER(C.c_float)), load_mode, k_cache.data_ptr(),
+            v_cache.data_ptr(), x_final.data_ptr(), sel.ctypes.data_as(C.POINTER(C.c_int32)),
+            cnt.ctypes.data_as(C.POINTER(C.c_int32)),
+            dev.ctypes.data_as(C.POINTER(C.c_float)) if want_deviation else None,
+            C.byref(rep) if want_report else None))
+        rows = [[int(v) for v in sel[l * nm:l * nm + cnt[l]]] for l in range(L)]
+        devs = [dev[l * nm:l * nm + cnt[l]].copy() for l in range(L)] if want_deviation else None
+        return rows, devs, rep
+
+    def select_tokens(self, deviation: np.ndarray, k: int) -> List[int]:
+        d = np.ascontiguousarray(deviation, dtype=np.float32)
+        out = np.zeros(max(1, k), dtype=np.int32)
+        self._check(self.lib.keep_select_tokens(self.handle, d.ctypes.data_as(C.POINTER(C.c_float)), len(d), k,
+                                                out.ctypes.data_as(C.POINTER(C.c_int32))))
+        return [int(v) for v in out[:k]]
 
     def precompute_groups(self, unit_len: Sequence[int], token_ids: Sequence[int], k_blocks: torch.Tensor,
                           v_blocks: torch.Tensor, want_report: bool = False):

@@ -79,6 +79,10 @@ struct keep_ctx {
   hipEvent_t ev_part[16] = {};      // begin / end pairs of such launches (timing)
   int32_t* h_row_lo = nullptr;      // pinned [max_tokens]: first visible key per row (batched unit caching)
   int32_t* d_row_lo = nullptr;
+  float* d_dev = nullptr;           // [max_tokens] per-row K/V deviation (token-granularity selection)
+  int32_t *d_tok_flags = nullptr, *d_tok_list = nullptr;  // [max_tokens] each
+  int32_t* h_tok_list = nullptr;    // pinned [max_tokens]
+  float* h_dev = nullptr;           // pinned [max_tokens]
   hipEvent_t ev_rowlist = nullptr;  // the last upload from h_row_list has been read by the device
   bool rowlist_pending = false;
   bool set_only = false;            // KEEP_OPT_PROPAGATION_SOURCES = KEEP_SOURCES_SET_ONLY
@@ -250,6 +254,7 @@ uint64_t workspace_bytes(const keep_model_desc* d) {
   t += align256(4 * z.G * sizeof(int32_t)) + align256((z.G + 2) * sizeof(int32_t));
   t += align256(4 * KEEP_DECODE_MAX_TOKENS * 4) + align256((size_t)d->vocab * sizeof(float));  // decode
   t += 2 * align256(z.M * sizeof(int32_t));                            // row_lo, row_list
+  t += 3 * align256(z.M * sizeof(int32_t));                            // token deviation, flags, kept list
   return t;
 }
 
@@ -742,6 +747,10 @@ namespace {
 keep_status prefill_impl(keep_ctx* c, const keep_prompt* p, const float* ratios, int32_t hops, int32_t budget_mode,
                          int32_t load_mode, void* k_cache, void* v_cache, int32_t cache_rows, void* x_final,
                          int32_t* sel_groups, int32_t* sel_counts, keep_report* report);
+template <typename T>
+keep_status prefill_tokens_impl(keep_ctx* c, const keep_prompt* p, const float* ratios, int32_t load_mode, void* k_cache,
+                                void* v_cache, void* x_final, int32_t* sel_rows, int32_t* sel_counts,
+                                float* deviation_out, keep_report* report);
 }  // namespace
 
 extern "C" {
@@ -774,6 +783,8 @@ keep_status keep_destroy(keep_ctx* c) {
   if (c->h_dec) (void)hipHostFree(c->h_dec);
   if (c->h_row_lo) (void)hipHostFree(c->h_row_lo);
   if (c->h_row_list) (void)hipHostFree(c->h_row_list);
+  if (c->h_tok_list) (void)hipHostFree(c->h_tok_list);
+  if (c->h_dev) (void)hipHostFree(c->h_dev);
   for (hipEvent_t e : c->ev_part)
     if (e) (void)hipEventDestroy(e);
   if (c->h_S) (void)hipHostFree(c->h_S);
@@ -909,6 +920,11 @@ keep_status keep_init(const keep_model_desc* desc, const keep_layer_weights* lay
     TRY_INIT(mk());
   }
   TRY_INIT(dev_alloc(c, &c->d_row_lo, z.M * 4));
+  TRY_INIT(dev_alloc(c, &c->d_dev, z.M * 4));
+  TRY_INIT(dev_alloc(c, &c->d_tok_flags, z.M * 4));
+  TRY_INIT(dev_alloc(c, &c->d_tok_list, z.M * 4));
+  TRY_INIT(pin_alloc(c, &c->h_tok_list, z.M * 4));
+  TRY_INIT(pin_alloc(c, &c->h_dev, z.M * 4));
   TRY_INIT(dev_alloc(c, &c->d_dec, 4 * KEEP_DECODE_MAX_TOKENS * 4));
   TRY_INIT(dev_alloc(c, &c->dec_logits, (size_t)desc->vocab * sizeof(float)));
   TRY_INIT(pin_alloc(c, &c->h_S, (z.G + 1) * z.G * sizeof(float)));
@@ -1231,6 +1247,36 @@ keep_status keep_prefill_padded(keep_ctx* c, const keep_prompt* p, const float* 
   if (cache_rows < 1) return fail(c, KEEP_ERR_INVALID_ARG, "cache_rows must be positive");
   return prefill_impl(c, p, ratios, hops, budget_mode, load_mode, k_cache, v_cache, cache_rows, x_final, sel_groups,
                       sel_counts, report);
+}
+
+keep_status keep_prefill_tokens(keep_ctx* c, const keep_prompt* p, const float* ratios, int32_t load_mode, void* k_cache,
+                                void* v_cache, void* x_final, int32_t* sel_rows, int32_t* sel_counts,
+                                float* deviation_out, keep_report* report) {
+  if (!c) return KEEP_ERR_INVALID_ARG;
+  if (!x_final) return fail(c, KEEP_ERR_INVALID_ARG, "x_final is NULL");
+  return by_dtype(c, [&](auto* tag) {
+    using T = std::remove_pointer_t<decltype(tag)>;
+    return prefill_tokens_impl<T>(c, p, ratios, load_mode, k_cache, v_cache, x_final, sel_rows, sel_counts,
+                                  deviation_out, report);
+  });
+}
+
+keep_status keep_select_tokens(keep_ctx* c, const float* deviation, int32_t n, int32_t k, int32_t* kept) {
+  if (!c) return KEEP_ERR_INVALID_ARG;
+  if (n < 0 || k < 0 || k > n) return fail(c, KEEP_ERR_INVALID_ARG, "need 0 <= k <= n");
+  if (n > c->d.max_tokens) return fail(c, KEEP_ERR_WORKSPACE, "n %d above max_tokens %d", n, c->d.max_tokens);
+  if ((n > 0 && !deviation) || (k > 0 && !kept)) return fail(c, KEEP_ERR_INVALID_ARG, "deviation / kept is NULL");
+  if (k == 0) return KEEP_OK;
+  hipStream_t s = c->s_comp;
+  HIP_TRY(c, hipStreamSynchronize(s));  // the pinned staging buffers are free
+  memcpy(c->h_dev, deviation, (size_t)n * sizeof(float));
+  HIP_TRY(c, hipMemcpyAsync(c->d_dev, c->h_dev, (size_t)n * sizeof(float), hipMemcpyHostToDevice, s));
+  launch_select_tokens(c->d_dev, n, k, 0, c->d_tok_flags, c->d_tok_list, s);
+  HIP_TRY(c, hipGetLastError());
+  HIP_TRY(c, hipMemcpyAsync(c->h_tok_list, c->d_tok_list, (size_t)k * 4, hipMemcpyDeviceToHost, s));
+  HIP_TRY(c, hipStreamSynchronize(s));
+  memcpy(kept, c->h_tok_list, (size_t)k * 4);
+  return KEEP_OK;
 }
 
 keep_status keep_decode(keep_ctx* c, const void* final_norm, const void* lm_head, const void* x_last, void* k_cache,
@@ -1747,6 +1793,240 @@ keep_status prefill_impl(keep_ctx* c, const keep_prompt* p, const float* ratios,
       (void)hipEventElapsedTime(&report->ms_norm2[l], e[6], e[7]);
       (void)hipEventElapsedTime(&report->ms_down[l], e[8], e[9]);
       if (report->hops_run[l] > 0) (void)hipEventElapsedTime(&report->ms_score[l], e[10], e[11]);
+    }
+  }
+  return KEEP_OK;
+}
+
+// Token-granularity prefill (the comparison scheme of Section 3 and Section 4.2, "System advantage"): the rows of
+// a layer are single tokens; every cached block is loaded and re-aligned, the recomputed tokens' K/V are written
+// over their rows in place, and the tokens of the next layer are the ones whose K/V moved furthest.  The
+// deviation is known right after the K/V projection, so the selection runs before the attention and the
+// attention, output projection and FFN are computed for the surviving tokens only (the others' hidden rows
+// would be discarded).
+template <typename T>
+keep_status prefill_tokens_impl(keep_ctx* c, const keep_prompt* p, const float* ratios, int32_t load_mode, void* k_cache,
+                                void* v_cache, void* x_final, int32_t* sel_rows, int32_t* sel_counts,
+                                float* deviation_out, keep_report* report) {
+  const auto t_begin = std::chrono::steady_clock::now();
+  const keep_model_desc& d = c->d;
+  const int L = d.n_layers;
+  if (!ratios || !k_cache || !v_cache) return fail(c, KEEP_ERR_INVALID_ARG, "ratios / k_cache / v_cache is NULL");
+  if (load_mode < KEEP_LOAD_SERIAL || load_mode > KEEP_LOAD_LAYER_BALANCED)
+    return fail(c, KEEP_ERR_INVALID_ARG, "unknown load_mode");
+  if (ratios[0] != 0.f && ratios[0] != 1.f)
+    return fail(c, KEEP_ERR_INVALID_ARG, "ratios[0] must be 1 (recompute every token at the first layer) or 0");
+  for (int l = 1; l < L; ++l) {
+    if (!(ratios[l] >= 0.f && ratios[l] <= 1.f)) return fail(c, KEEP_ERR_INVALID_ARG, "ratios[%d] outside [0, 1]", l);
+    if (ratios[l] > ratios[l - 1])
+      return fail(c, KEEP_ERR_INVALID_ARG, "ratios must not increase (ratios[%d] > ratios[%d])", l, l - 1);
+  }
+  PromptInfo pi;
+  keep_status st = check_prompt(c, p, &pi, true);
+  if (st != KEEP_OK) return st;
+  c->last_layer = -1;
+  c->att_plan.valid = false;
+  const bool host_kv = p->kv_location == KEEP_KV_PINNED_HOST;
+  const size_t row_bytes = (size_t)d.n_kv_heads * d.head_dim * c->esz;
+  const size_t layer_bytes = (size_t)pi.N * row_bytes;
+  const int qd = d.n_q_heads * d.head_dim;
+  hipStream_t s = c->s_comp;
+  c->ev_light = false;
+  if (report) {
+    memset(report, 0, sizeof *report);
+    report->n_layers = L;
+    report->used_mfma = c->mfma ? 1 : 0;
+  }
+  Loader ld{c, p, &pi, (char*)k_cache, (char*)v_cache, row_bytes, layer_bytes};
+  if (host_kv) {
+    ld.loaded.assign((size_t)L * pi.G, 0);
+    ld.chunk_bytes.assign(c->ev_chunk.size(), 0);
+  }
+  st = upload_tokens(c, p, pi);
+  if (st != KEEP_OK) return st;
+  const std::vector<int32_t> nothing;
+  std::vector<int32_t> cur, nxt;  // positions of the memory tokens recomputed at this layer / the next
+  if (ratios[0] == 1.f)
+    for (int t = 0; t < pi.n_mem; ++t) cur.push_back(t);
+  void* x_cur = c->xa;
+  void* x_nxt = c->xb;
+  bool from_embed = true;
+  int n_out = 0;
+  LayerPlan plan;
+  auto upload_positions = [&](const std::vector<int32_t>& mem_pos) -> keep_status {
+    if (c->rowlist_pending) {
+      HIP_TRY(c, hipEventSynchronize(c->ev_rowlist));
+      c->rowlist_pending = false;
+    }
+    const int nm = (int)mem_pos.size();
+    if (nm) memcpy(c->h_row_list, mem_pos.data(), (size_t)nm * 4);
+    for (int j = 0; j < pi.Lq; ++j) c->h_row_list[nm + j] = pi.n_mem + j;
+    HIP_TRY(c, hipMemcpyAsync(c->d_row_pos, c->h_row_list, (size_t)(nm + pi.Lq) * 4, hipMemcpyHostToDevice, s));
+    HIP_TRY(c, hipEventRecord(c->ev_rowlist, s));
+    c->rowlist_pending = true;
+    return KEEP_OK;
+  };
+  auto attend_rows = [&](const void* q_rows, int n_rows, void* kl, void* vl) -> keep_status {
+    if (c->mfma)
+      launch_attn_mfma(reinterpret_cast<const bf16_t*>(q_rows), reinterpret_cast<const bf16_t*>(kl),
+                       reinterpret_cast<const bf16_t*>(vl), c->d_row_pos, nullptr, nullptr, 0, pi.n_mem, n_rows, pi.N,
+                       d.n_q_heads, d.n_kv_heads, d.max_tokens, c->stage[0].attn_items, c->attn_scratch,
+                       reinterpret_cast<bf16_t*>(c->o), c->lse, s, nullptr, nullptr, nullptr, nullptr, nullptr, 0,
+                       c->h_row_list);
+    else
+      launch_attn_generic<T>(Typed<T>::p(q_rows), Typed<T>::p(kl), Typed<T>::p(vl), c->d_row_pos, n_rows, d.n_q_heads,
+                             d.n_kv_heads, d.head_dim, Typed<T>::p(c->o), c->lse, s);
+    HIP_TRY(c, hipGetLastError());
+    return KEEP_OK;
+  };
+
+  if (host_kv) {  // the whole cache of layer 0
+    st = ld.copy_outside(0, nothing);
+    if (st != KEEP_OK) return st;
+    HIP_TRY(c, hipEventRecord(c->ev_load, c->s_copy));
+    HIP_TRY(c, hipStreamWaitEvent(s, c->ev_load, 0));
+    if (report) report->bytes_loaded[0] = ld.bytes_total;
+  }
+  for (int l = 0; l < L; ++l) {
+    hipEvent_t* evs = report ? &c->ev[(size_t)l * EV_PER_LAYER] : nullptr;
+    char* kl = (char*)k_cache + (size_t)l * layer_bytes;
+    char* vl = (char*)v_cache + (size_t)l * layer_bytes;
+    const keep_layer_weights& w = c->w[l];
+    const int n_mem_rows = (int)cur.size();
+    const int n = n_mem_rows + pi.Lq;
+    if (sel_counts) sel_counts[l] = n_mem_rows;
+    if (sel_rows && n_mem_rows) memcpy(sel_rows + (size_t)l * pi.n_mem, cur.data(), (size_t)n_mem_rows * 4);
+    // the next layer's blocks are all needed whatever is selected: their load runs beside this layer
+    const uint64_t bytes_before = ld.bytes_total;
+    if (host_kv && l + 1 < L && load_mode != KEEP_LOAD_SERIAL) {
+      st = ld.copy_outside(l + 1, nothing);
+      if (st != KEEP_OK) return st;
+      HIP_TRY(c, hipEventRecord(c->ev_load, c->s_copy));
+    }
+    // every group is re-aligned (the whole cache is joined, then tokens are overwritten in place)
+    st = stage_layer(c, p, pi, l, nullptr, 0, kl, vl, host_kv, &plan);
+    if (st != KEEP_OK) return st;
+    // (the work list of the attention goes through staging slot 0: wait for its previous user)
+    if (l > 0 && c->stage[0].used) HIP_TRY(c, hipEventSynchronize(c->stage[0].done));
+    st = upload_positions(cur);
+    if (st != KEEP_OK) return st;
+    if (evs) HIP_TRY(c, hipEventRecord(evs[0], s));
+    launch_realign<T>(c->d_segs, plan.n_segs, plan.n_realign_rows, d.n_kv_heads, d.head_dim, c->rope_cos, c->rope_sin,
+                      Typed<T>::p(kl), Typed<T>::p(vl), s);
+    if (evs) HIP_TRY(c, hipEventRecord(evs[1], s));
+    if (from_embed)
+      launch_embed_gather<T>(Typed<T>::p(c->embed), c->d_token_ids, c->d_row_pos, n, d.hidden, Typed<T>::p(x_cur), s);
+    launch_rmsnorm<T>(Typed<T>::p(x_cur), Typed<T>::p(w.ln1), n, d.hidden, d.rms_eps, Typed<T>::p(c->hbuf), s);
+    if (evs) HIP_TRY(c, hipEventRecord(evs[2], s));
+    GemmB b{};
+    b.n_parts = 3;
+    b.ptr[0] = w.wq; b.ptr[1] = w.wk; b.ptr[2] = w.wv;
+    b.n_rows[0] = qd;
+    b.n_rows[1] = b.n_rows[2] = d.n_kv_heads * d.head_dim;
+    if (!c->w4.empty()) {
+      set_w4(b, 0, c->w4[l].wq);
+      set_w4(b, 1, c->w4[l].wk);
+      set_w4(b, 2, c->w4[l].wv);
+    }
+    const int n_qkv = qd + 2 * b.n_rows[1];
+    if (c->mfma)
+      launch_gemm_mfma(reinterpret_cast<const bf16_t*>(c->hbuf), n, d.hidden, b, nullptr, n_qkv, EPI_STORE_F32, nullptr,
+                       c->qkv_raw, s, c->skinny_ws);
+    else
+      launch_gemm_generic<T>(Typed<T>::p(c->hbuf), n, d.hidden, b, nullptr, n_qkv, EPI_STORE_F32, nullptr, c->qkv_raw, s);
+    if (evs) HIP_TRY(c, hipEventRecord(evs[3], s));
+    const int k_next = l + 1 < L ? std::max(0, std::min(n_mem_rows, (int)ceil((double)ratios[l + 1] * pi.n_mem - BUDGET_EPS)))
+                                 : n_mem_rows;
+    const bool shrink = l + 1 < L && k_next < n_mem_rows;
+    const bool want_dev = (shrink || deviation_out) && n_mem_rows > 0;
+    launch_rope_scatter<T>(c->qkv_raw, Typed<T>::p(w.bq), Typed<T>::p(w.bk), Typed<T>::p(w.bv), c->d_row_pos, n,
+                           d.n_q_heads, d.n_kv_heads, d.head_dim, c->rope_cos, c->rope_sin, Typed<T>::p(c->q),
+                           Typed<T>::p(c->kc), Typed<T>::p(kl), Typed<T>::p(vl), s, nullptr, want_dev ? c->d_dev : nullptr);
+    HIP_TRY(c, hipGetLastError());
+    if (evs) {
+      HIP_TRY(c, hipEventRecord(evs[4], s));
+      HIP_TRY(c, hipEventRecord(evs[10], s));
+    }
+    if (deviation_out && n_mem_rows) {
+      HIP_TRY(c, hipMemcpyAsync(c->h_dev, c->d_dev, (size_t)n_mem_rows * 4, hipMemcpyDeviceToHost, s));
+      HIP_TRY(c, hipStreamSynchronize(s));
+      memcpy(deviation_out + (size_t)l * pi.n_mem, c->h_dev, (size_t)n_mem_rows * 4);
+    }
+    int n_back = n;
+    if (shrink) {
+      // kept rows (ascending compact indices) followed by the instruction rows
+      launch_select_tokens(c->d_dev, n_mem_rows, k_next, pi.Lq, c->d_tok_flags, c->d_tok_list, s);
+      HIP_TRY(c, hipGetLastError());
+      if (k_next) HIP_TRY(c, hipMemcpyAsync(c->h_tok_list, c->d_tok_list, (size_t)k_next * 4, hipMemcpyDeviceToHost, s));
+      n_back = k_next + pi.Lq;
+      // q rows into the projection's fp32 buffer (free once RoPE has read it), hidden rows into the other row buffer
+      launch_rows_gather_list<T>(Typed<T>::p(c->q), c->d_tok_list, n_back, qd, Typed<T>::p(c->qkv_raw), s);
+      launch_rows_gather_list<T>(Typed<T>::p(x_cur), c->d_tok_list, n_back, d.hidden, Typed<T>::p(x_nxt), s);
+      HIP_TRY(c, hipGetLastError());
+      HIP_TRY(c, hipStreamSynchronize(s));  // the host needs the kept rows to plan the attention and the next layer
+      nxt.resize(k_next);
+      for (int i = 0; i < k_next; ++i) nxt[i] = cur[c->h_tok_list[i]];
+      st = upload_positions(nxt);
+      if (st != KEEP_OK) return st;
+    }
+    if (evs) HIP_TRY(c, hipEventRecord(evs[11], s));
+    st = attend_rows(shrink ? (const void*)c->qkv_raw : (const void*)c->q, n_back, kl, vl);
+    if (st != KEEP_OK) return st;
+    if (evs) HIP_TRY(c, hipEventRecord(evs[5], s));
+    HIP_TRY(c, hipEventRecord(c->stage[0].done, s));
+    c->stage[0].used = true;
+    if (shrink) {
+      st = layer_back<T>(c, l, n_back, c->o, x_nxt, x_cur, evs);  // output lands in x_cur, in the next layer's layout
+      cur.swap(nxt);
+    } else {
+      st = layer_back<T>(c, l, n_back, c->o, x_cur, x_nxt, evs);
+      std::swap(x_cur, x_nxt);
+    }
+    if (st != KEEP_OK) return st;
+    Staging& sg = c->stage[l];
+    HIP_TRY(c, hipEventRecord(sg.done, s));
+    sg.used = true;
+    from_embed = false;
+    n_out = n_back;
+    if (report) {
+      report->rows[l] = n;
+      report->set_size[l] = n_mem_rows;
+      report->realign_rows[l] = plan.n_realign_rows;
+      report->attn_rows[l] = n_back;
+      report->ffn_rows[l] = n_back;
+    }
+    if (host_kv && l + 1 < L) {
+      if (load_mode == KEEP_LOAD_SERIAL) {  // load strictly after this layer's compute
+        HIP_TRY(c, hipEventRecord(c->ev_comp, s));
+        HIP_TRY(c, hipStreamWaitEvent(c->s_copy, c->ev_comp, 0));
+        st = ld.copy_outside(l + 1, nothing);
+        if (st != KEEP_OK) return st;
+        HIP_TRY(c, hipEventRecord(c->ev_load, c->s_copy));
+      }
+      HIP_TRY(c, hipStreamWaitEvent(s, c->ev_load, 0));
+      if (report) report->bytes_loaded[l + 1] = ld.bytes_total - bytes_before;
+    }
+  }
+  {
+    const char* src = (const char*)x_cur + (size_t)(n_out - pi.Lq) * d.hidden * c->esz;
+    HIP_TRY(c, hipMemcpyAsync(x_final, src, (size_t)pi.Lq * d.hidden * c->esz, hipMemcpyDeviceToDevice, s));
+  }
+  HIP_TRY(c, hipStreamSynchronize(c->s_copy));
+  HIP_TRY(c, hipStreamSynchronize(s));
+  if (report) {
+    report->ms_total = std::chrono::duration<float, std::milli>(std::chrono::steady_clock::now() - t_begin).count();
+    for (int l = 0; l < L; ++l) {
+      hipEvent_t* e = &c->ev[(size_t)l * EV_PER_LAYER];
+      (void)hipEventElapsedTime(&report->ms_realign[l], e[0], e[1]);
+      (void)hipEventElapsedTime(&report->ms_prep[l], e[1], e[2]);
+      (void)hipEventElapsedTime(&report->ms_qkv_gemm[l], e[2], e[3]);
+      (void)hipEventElapsedTime(&report->ms_rope[l], e[3], e[4]);
+      (void)hipEventElapsedTime(&report->ms_score[l], e[10], e[11]);
+      (void)hipEventElapsedTime(&report->ms_attn[l], e[11], e[5]);
+      (void)hipEventElapsedTime(&report->ms_oproj[l], e[12], e[6]);
+      (void)hipEventElapsedTime(&report->ms_norm2[l], e[6], e[7]);
+      (void)hipEventElapsedTime(&report->ms_gateup[l], e[7], e[8]);
+      (void)hipEventElapsedTime(&report->ms_down[l], e[8], e[9]);
     }
   }
   return KEEP_OK;

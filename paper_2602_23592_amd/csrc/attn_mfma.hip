@@ -433,7 +433,7 @@ void launch_attn_mfma(const bf16_t* q, const bf16_t* k_cache, const bf16_t* v_ca
                       int32_t n_rows, int32_t n_total, int32_t n_q_heads, int32_t n_kv_heads, int32_t max_rows,
                       int32_t* h_stage, void* d_scratch, bf16_t* o, float* lse, hipStream_t s,
                       const int32_t* h_row_lo, const int32_t* d_row_lo, AttnPlan* plan, const int32_t* h_row_list,
-                      const int32_t* d_row_list, int32_t n_list) {
+                      const int32_t* d_row_list, int32_t n_list, const int32_t* h_row_pos) {
   // With a row list only the listed rows (ascending ids into q / o / lse / row_pos) are attended; n_rows then
   // stands for the length of the list everywhere below.
   const int32_t n_all_rows = n_rows;
@@ -451,6 +451,7 @@ void launch_attn_mfma(const bf16_t* q, const bf16_t* k_cache, const bf16_t* v_ca
   // key tiles each query tile needs: up to the position of its last row
   auto pos_of_row = [&](int r) {
     if (h_row_list) r = h_row_list[r];
+    if (h_row_pos) return h_row_pos[r];  // the caller has the positions as a plain list (token rows)
     int lo = 0, hi = m;  // blocks 0..m
     while (lo < hi) {
       const int mid = (lo + hi + 1) >> 1;

@@ -125,7 +125,18 @@ template <typename T>
 void launch_rope_scatter(const float* qkv_raw /*[n_rows, q_dim + 2 kv_dim]*/, const T* bq, const T* bk, const T* bv,
                          const int32_t* d_row_pos, int32_t n_rows, int32_t n_q_heads, int32_t n_kv_heads,
                          int32_t head_dim, const float* rope_cos, const float* rope_sin, T* q, T* k_compact,
-                         T* k_cache, T* v_cache, hipStream_t s, const int32_t* d_row_lo = nullptr);
+                         T* k_cache, T* v_cache, hipStream_t s, const int32_t* d_row_lo = nullptr,
+                         float* d_deviation = nullptr);
+// d_deviation [n_rows] or NULL: per row, the squared distance between the refreshed K/V (as stored) and the
+// cache rows they overwrite, summed in a fixed order (token-granularity selection).
+template <typename T>
+void launch_rows_gather_list(const T* x_src, const int32_t* d_idx, int32_t n_rows_dst, int32_t width, T* x_dst,
+                             hipStream_t s);
+// Token-granularity selection: the k of the n candidates with the largest deviation (ties: lower index), as an
+// ascending list in d_list[0..k), followed by the n_tail indices n, n+1, ... (the instruction rows);
+// d_flags: [n] scratch.
+void launch_select_tokens(const float* d_deviation, int32_t n, int32_t k, int32_t n_tail, int32_t* d_flags,
+                          int32_t* d_list, hipStream_t s);
 
 // out[0] = index of the largest of logits[0..n), the lowest index among equal values
 void launch_argmax(const float* logits, int32_t n, int32_t* out, hipStream_t s);
@@ -177,7 +188,10 @@ void launch_attn_mfma(const bf16_t* q, const bf16_t* k_cache, const bf16_t* v_ca
                       int32_t n_rows, int32_t n_total, int32_t n_q_heads, int32_t n_kv_heads, int32_t max_rows,
                       int32_t* h_stage, void* d_scratch, bf16_t* o, float* lse, hipStream_t s,
                       const int32_t* h_row_lo = nullptr, const int32_t* d_row_lo = nullptr, AttnPlan* plan = nullptr,
-                      const int32_t* h_row_list = nullptr, const int32_t* d_row_list = nullptr, int32_t n_list = 0);
+                      const int32_t* h_row_list = nullptr, const int32_t* d_row_list = nullptr, int32_t n_list = 0,
+                      const int32_t* h_row_pos = nullptr);
+// h_row_pos: HOST [n_rows] positions of the rows (ascending), used for planning instead of the block layout
+// (h_row_start / h_set_off / m / instr_off are then ignored).
 // h_row_list / d_row_list (host and device copies) of n_list ascending row ids: attend only these rows.
 // h_row_lo / d_row_lo (host and device copies, both or neither): first key each row may see (default 0);
 // used where several units are cached in one pass, each attending to itself only.

@@ -269,13 +269,36 @@ __device__ inline void store4<bf16_t>(bf16_t* p, const float* f) {
   *reinterpret_cast<uint2*>(p) = u;
 }
 
+// sum over 4 elements of (value as it will sit in the cache - value in the cache now)^2
+template <typename T>
+__device__ inline float sq_dist4(const T* old, const float* f);
+template <>
+__device__ inline float sq_dist4<float>(const float* old, const float* f) {
+  const float4 o = *reinterpret_cast<const float4*>(old);
+  const float d0 = f[0] - o.x, d1 = f[1] - o.y, d2 = f[2] - o.z, d3 = f[3] - o.w;
+  return d0 * d0 + d1 * d1 + d2 * d2 + d3 * d3;
+}
+template <>
+__device__ inline float sq_dist4<bf16_t>(const bf16_t* old, const float* f) {
+  const uint2 o = *reinterpret_cast<const uint2*>(old);
+  const uint32_t n0 = pack_bf16x2(f[0], f[1]), n1 = pack_bf16x2(f[2], f[3]);  // the stored (rounded) new values
+  const float d0 = __uint_as_float(n0 << 16) - __uint_as_float(o.x << 16);
+  const float d1 = __uint_as_float(n0 & 0xffff0000u) - __uint_as_float(o.x & 0xffff0000u);
+  const float d2 = __uint_as_float(n1 << 16) - __uint_as_float(o.y << 16);
+  const float d3 = __uint_as_float(n1 & 0xffff0000u) - __uint_as_float(o.y & 0xffff0000u);
+  return d0 * d0 + d1 * d1 + d2 * d2 + d3 * d3;
+}
+
 template <typename T>
 __global__ void __launch_bounds__(256)
     k_rope_scatter(const float* __restrict__ qkv_raw, const T* __restrict__ bq, const T* __restrict__ bk,
                    const T* __restrict__ bv, const int32_t* __restrict__ row_pos, const int32_t* __restrict__ row_lo,
                    int n_q_heads, int n_kv_heads, int head_dim, const float* __restrict__ rope_cos,
                    const float* __restrict__ rope_sin,
-                   T* __restrict__ q, T* __restrict__ k_compact, T* __restrict__ k_cache, T* __restrict__ v_cache) {
+                   T* __restrict__ q, T* __restrict__ k_compact, T* __restrict__ k_cache, T* __restrict__ v_cache,
+                   float* __restrict__ dev_out) {
+  __shared__ float s_red[4];
+  float dev = 0.f;  // squared distance of this thread's refreshed K/V elements from the cache rows they replace
   const int r = blockIdx.x;
   const int pos = row_pos[r];
   const int half = head_dim / 2;
@@ -321,6 +344,7 @@ __global__ void __launch_bounds__(256)
         const int hk = h - n_q_heads;
         T* d1 = k_compact + (size_t)r * kv_dim + hk * head_dim;
         T* d2 = k_cache + (size_t)pos * kv_dim + hk * head_dim;
+        if (dev_out) dev += sq_dist4<T>(d2 + c, olo) + sq_dist4<T>(d2 + half + c, ohi);
         store4<T>(d1 + c, olo);
         store4<T>(d1 + half + c, ohi);
         store4<T>(d2 + c, olo);
@@ -334,8 +358,13 @@ __global__ void __launch_bounds__(256)
 #pragma unroll
         for (int e = 0; e < 4; ++e) f[e] += ldf(bv + c + e);
       }
+      if (dev_out) dev += sq_dist4<T>(v_cache + (size_t)pos * kv_dim + c, f);
       store4<T>(v_cache + (size_t)pos * kv_dim + c, f);
     }
+  }
+  if (dev_out) {  // (uniform branch: every thread of the block takes part in the sum)
+    const float tot = block_sum_256(dev, s_red);
+    if (threadIdx.x == 0) dev_out[r] = tot;
   }
 }
 
@@ -344,10 +373,28 @@ void launch_rope_scatter(const float* qkv_raw, const T* bq, const T* bk, const T
                          int32_t n_rows, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
                          const float* rope_cos, const float* rope_sin, T* q, T* k_compact, T* k_cache, T* v_cache,
                          hipStream_t s,
-                         const int32_t* d_row_lo) {
+                         const int32_t* d_row_lo, float* d_deviation) {
   if (n_rows <= 0) return;
   hipLaunchKernelGGL(k_rope_scatter<T>, dim3(n_rows), dim3(256), 0, s, qkv_raw, bq, bk, bv, d_row_pos, d_row_lo,
-                     n_q_heads, n_kv_heads, head_dim, rope_cos, rope_sin, q, k_compact, k_cache, v_cache);
+                     n_q_heads, n_kv_heads, head_dim, rope_cos, rope_sin, q, k_compact, k_cache, v_cache, d_deviation);
+}
+
+// x_dst[r] = x_src[idx[r]] for r < n_rows_dst (rows of `width` elements, a multiple of the 16-byte vector)
+template <typename T>
+__global__ void k_rows_gather_list(const T* __restrict__ x_src, const int32_t* __restrict__ idx, int width,
+                                   T* __restrict__ x_dst) {
+  const int r = blockIdx.x;
+  const uint4* src = reinterpret_cast<const uint4*>(x_src + (size_t)idx[r] * width);
+  uint4* dst = reinterpret_cast<uint4*>(x_dst + (size_t)r * width);
+  const int nv = width / Vec<T>::N;
+  for (int i = threadIdx.x; i < nv; i += blockDim.x) dst[i] = src[i];
+}
+
+template <typename T>
+void launch_rows_gather_list(const T* x_src, const int32_t* d_idx, int32_t n_rows_dst, int32_t width, T* x_dst,
+                             hipStream_t s) {
+  if (n_rows_dst <= 0) return;
+  hipLaunchKernelGGL(k_rows_gather_list<T>, dim3(n_rows_dst), dim3(256), 0, s, x_src, d_idx, width, x_dst);
 }
 
 // Greedy choice over one row of logits: the largest value, the lowest index among equal ones.
@@ -398,7 +445,8 @@ void launch_argmax(const float* logits, int32_t n, int32_t* out, hipStream_t s) 
   template void launch_rmsnorm<T>(const T*, const T*, int32_t, int32_t, float, T*, hipStream_t);                     \
   template void launch_rope_scatter<T>(const float*, const T*, const T*, const T*, const int32_t*, int32_t, int32_t, \
                                        int32_t, int32_t, const float*, const float*, T*, T*, T*, T*, hipStream_t,   \
-                                       const int32_t*);
+                                       const int32_t*, float*);                                                      \
+  template void launch_rows_gather_list<T>(const T*, const int32_t*, int32_t, int32_t, T*, hipStream_t);
 INST(float)
 INST(bf16_t)
 #undef INST
