@@ -174,12 +174,14 @@ def test_int4_error_paths():
     assert ctx.lib.keep_attach_int4(ctx.handle, arr) == KEEP_ERR_INVALID_ARG
 
 
-def test_fullsize_projections_read_the_int4_form():
-    """One layer of the Qwen-14B shape (K = 5120 and 13 824, N up to 27 648): a 48-token unit cached on its own
+@pytest.mark.parametrize("workload", ["qwen14b_32k", "qwen32b_32k_host"])
+def test_fullsize_projections_read_the_int4_form(workload):
+    """One layer of the Qwen-14B shape (K = 5120 and 13 824, N up to 27 648) and of the Qwen-32B shape, the one the
+    paper runs with INT4 weights (Section 6.1; FFN 27 648: K up to 27 648, N up to 55 296): a 48-token unit cached on its own
     (two row tiles per workgroup) and one decoded token (one row) with the 4-bit form attached, against the
     oracle on the dequantised weights.  Codes are uniform draws here (the binomial recipe takes minutes at
     this size on the host)."""
-    full = ks.workload("qwen14b_32k").shape
+    full = ks.workload(workload).shape
     shape = ks.ModelShape(1, full.hidden, full.n_q_heads, full.n_kv_heads, full.head_dim, full.ffn_dim, 1031,
                           full.rope_theta, full.rms_eps, "bf16")
     sh = oracle_shape(shape)
