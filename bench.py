@@ -24,8 +24,31 @@ PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 
 
-# (2.0 x FETCH_SIZE + 1.0 x WRITE_SIZE) of the gate/up GEMM launches (and their fix-up launches) of two steps / 96
-GATE_UP_TRAFFIC_BYTES_PER_LAUNCH = int(((76520876 + 1520935) * 2.0 + (11157280 + 192864)) * 1024 / 96)
+TRAFFIC_JSON = os.path.join(ROOT, "profiles", "keep_prefill_qwen14b_32k_gate_up_traffic.json")
+TRAFFIC_SOURCES = ("paper_2602_23592_amd/csrc/gemm_mfma.hip",)
+
+
+def sources_sha16(paths=TRAFFIC_SOURCES):
+    """Hash of the sources of the roofline kernel: a stored counter figure holds only for the kernel it was measured on."""
+    import hashlib
+    h = hashlib.sha256()
+    for rel in paths:
+        with open(os.path.join(ROOT, rel), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def stored_traffic():
+    """L2-miss bytes per gate/up launch from the two rocprofv3 --pmc runs summarised under profiles/ (written by
+    bench_profile_summary.py), or None when the kernel's source has changed since they were made."""
+    try:
+        with open(TRAFFIC_JSON) as f:
+            t = json.load(f)
+    except (OSError, ValueError):
+        return None, "no stored counter run"
+    if t.get("sources_sha16") != sources_sha16():
+        return None, "stored counter run is for another build of the kernel (%s)" % t.get("sources_sha16")
+    return int(t["bytes_per_launch"]), "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, %s" % t.get("measured_at", "")
 
 
 def parse():
@@ -53,6 +76,12 @@ def parse():
     ap.add_argument("--int4", action="store_true",
                     help="with --decode-tokens / --memory-update: INT4 weight-only projections (the launches of at "
                          "most 64 rows read the 4-bit form; the bf16 weights are its expansion)")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the extra keys of the default run (the count-budget reading of the same prompt, the "
+                         "other workloads, the loading modes and the token-granularity pair on the host-resident one)")
+    ap.add_argument("--granularity", default="groups", help="groups (the method) or tokens (the comparison scheme)")
+    ap.add_argument("--sweep", action="store_true",
+                    help="instead of one line: recompute ratio 5/10/20/30 %% x hops 1-4 on the workload, one JSON line each")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="launch one device copy of this many MiB before the warm-up: the known-size "
                          "kernel that scales rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
@@ -257,6 +286,230 @@ def cpu_baseline(w, glen, rows_per_layer, n_tokens):
             "seconds": times[0] + times[1], "extrapolated": True}
 
 
+class Case:
+    """One workload set up on the GPU: weights, context, prompt with its group caches, output buffers."""
+
+    def __init__(self, name, a, torch, ks, kb, ratio=None, sparse_rows=0, layers=None, int4=False, random_cache=False,
+                 extra_tokens=0):
+        import dataclasses
+        from paper_2602_23592_amd import KeepContext, KeepPrompt
+        t0 = time.perf_counter()
+        w = ks.workload(name)
+        if ratio is not None:
+            w = dataclasses.replace(w, ratio=ratio)
+        if sparse_rows > 0:
+            w = dataclasses.replace(w, instr_len=sparse_rows, ratio=0.0)
+        self.w, self.s = w, w.shape
+        s = w.shape
+        self.torch, self.kb = torch, kb
+        self.dt = torch.bfloat16 if s.storage == "bf16" else torch.float32
+        self.glen, self.kinds = ks.group_lengths(w)
+        self.G, self.lq = len(self.glen), w.instr_len
+        self.n_tokens = w.mem_tokens + self.lq
+        self.layers4 = None
+        if layers is not None:
+            self.layers = layers
+        elif int4:
+            # weights arrive quantised; the library expands them to the bf16 values the model computes with
+            self.layers4 = [ks.make_int4_layer_on_device(s, l, "cuda") for l in range(s.n_layers)]
+            self.layers = []
+            for l in range(s.n_layers):
+                wl = {n: kb.dequantize_int4(*self.layers4[l][n]) for n in ks.INT4_MATS}   # (codes, words, rows, K)
+                wl["ln1"] = torch.ones(s.hidden, dtype=self.dt, device="cuda")
+                wl["ln2"] = torch.ones(s.hidden, dtype=self.dt, device="cuda")
+                wl["bq"] = wl["bk"] = wl["bv"] = None
+                self.layers.append(wl)
+        else:
+            self.layers = [ks.make_layer_weights(s, l, "cuda") for l in range(s.n_layers)]
+        self.embed = ks.make_embedding(s, "cuda")
+        self.ids = ks.make_token_ids(self.n_tokens, s.vocab, 0)
+        self.streams = [torch.cuda.Stream() for _ in range(3)]
+        torch.cuda.synchronize()
+        self.ctx = KeepContext(s, self.layers, self.embed, self.n_tokens + extra_tokens, self.G, kb.KEEP_KERNELS_AUTO,
+                               *self.streams)
+        if self.layers4 is not None:
+            self.ctx.attach_int4(self.layers4)
+        self.prompt = None
+        self.random_cache = random_cache
+        self.setup_s = time.perf_counter() - t0
+
+    def make_prompt(self):
+        """Group caches (outside every timed region) and the prompt that points at them."""
+        from paper_2602_23592_amd import KeepPrompt
+        torch, kb, w, s = self.torch, self.kb, self.w, self.s
+        t0 = time.perf_counter()
+        if self.random_cache:
+            kb_all = torch.empty((s.n_layers, w.mem_tokens, s.n_kv_heads, s.head_dim), dtype=self.dt, device="cuda")
+            vb_all = torch.empty_like(kb_all)
+            gen = torch.Generator(device="cuda")
+            gen.manual_seed(7)
+            for l in range(s.n_layers):
+                kb_all[l] = torch.randn(kb_all[l].shape, generator=gen, device="cuda").to(self.dt)
+                vb_all[l] = torch.randn(vb_all[l].shape, generator=gen, device="cuda").to(self.dt)
+        else:
+            kb_all, vb_all = precompute_group_caches(self.ctx, w, self.glen, self.ids, torch)
+        off = np.concatenate([[0], np.cumsum(self.glen)]).astype(np.int64)
+        self.host = w.kv_location == "pinned_host"
+        if self.host:
+            kb_src = torch.empty(kb_all.shape, dtype=self.dt, pin_memory=True)
+            vb_src = torch.empty(vb_all.shape, dtype=self.dt, pin_memory=True)
+            kb_src.copy_(kb_all)
+            vb_src.copy_(vb_all)
+            del kb_all, vb_all
+        else:
+            kb_src, vb_src = kb_all, vb_all
+        self.k_blocks = [[kb_src[l, off[g]:off[g + 1]] for g in range(self.G)] for l in range(s.n_layers)]
+        self.v_blocks = [[vb_src[l, off[g]:off[g + 1]] for g in range(self.G)] for l in range(s.n_layers)]
+        self.prompt = KeepPrompt(self.glen, self.lq, self.ids, self.k_blocks, self.v_blocks, s.n_layers,
+                                 kb.KEEP_KV_PINNED_HOST if self.host else kb.KEEP_KV_DEVICE, self.kinds)
+        self.k_cache = torch.empty((s.n_layers, self.n_tokens, s.n_kv_heads, s.head_dim), dtype=self.dt, device="cuda")
+        self.v_cache = torch.empty_like(self.k_cache)
+        self.x_final = torch.empty((self.lq, s.hidden), dtype=self.dt, device="cuda")
+        torch.cuda.synchronize()
+        self.setup_s += time.perf_counter() - t0
+
+    def close(self):
+        self.ctx.close()
+        for n in ("k_blocks", "v_blocks", "prompt", "k_cache", "v_cache", "layers", "layers4", "embed", "ctx"):
+            setattr(self, n, None)
+        import gc
+        gc.collect()
+        self.torch.cuda.empty_cache()
+
+
+def time_steps(fn, steps, warmup, torch):
+    """Warm-up, then `steps` calls timed one by one between device synchronisations (host clock).
+    Returns (list of ms, results of the calls)."""
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    ms, res = [], []
+    for _ in range(steps):
+        t0 = time.perf_counter()
+        res.append(fn())
+        torch.cuda.synchronize()
+        ms.append((time.perf_counter() - t0) * 1e3)
+    return ms, res
+
+
+def stats(ms):
+    return {"ms_median": round(float(np.median(ms)), 3), "ms_min": round(float(np.min(ms)), 3),
+            "ms_mean": round(float(np.mean(ms)), 3)}
+
+
+def check_outputs(case, runs):
+    """Sanity of what the timed steps produced: finite final rows and caches of the last step, nested sets,
+    the same sets at every step (the run is deterministic)."""
+    torch = case.torch
+    assert bool(torch.isfinite(case.x_final.float()).all()), "non-finite value in x_final"
+    assert bool(torch.isfinite(case.k_cache[-1].float()).all()) and bool(torch.isfinite(case.v_cache[-1].float()).all())
+    sets0 = runs[0][0]
+    for sets, _ in runs:
+        assert sets == sets0, "the selected sets differ between steps"
+    for a, b in zip(sets0, sets0[1:]):
+        assert set(b) <= set(a), "sets are not nested"
+    return True
+
+
+def token_schedule(ks, w, L, sched):
+    """Ratio schedule of the token-granularity scheme: as the workload's, with the first selection made from layer
+    1's deviation (layer 0's is zero), so layers 0 and 1 recompute every token."""
+    r = ks.ratio_schedule(w.ratio, L, sched)
+    if L > 2:
+        r[1] = 1.0
+    return r
+
+
+def extras(a, torch, ks, kb, main_case, main_ratios, sched):
+    """Extra keys of the default line: the paper-literal count budget on the same prompt, the other workloads, and on
+    the host-resident one the three loading modes and the token-granularity comparison (bytes loaded, TTFT)."""
+    out = {}
+    steps, warm = 3, 1
+    c = main_case
+    ms, runs = time_steps(lambda: c.ctx.prefill(c.prompt, main_ratios, c.w.hops, c.k_cache, c.v_cache, c.x_final,
+                                                kb.KEEP_BUDGET_GROUP_COUNT, a.load_mode, want_report=True,
+                                                gate_up_events_only=True), steps, warm, torch)
+    rep = runs[-1][1]
+    L = c.s.n_layers
+    out["count_budget_reading"] = dict(stats(ms), tokens_per_s=round(c.n_tokens / (np.median(ms) * 1e-3), 1),
+                                       rows_per_layer_mean=round(float(np.mean([rep.rows[l] for l in range(1, L)])), 1),
+                                       set_sizes=[len(x) for x in runs[-1][0]],
+                                       note="ratio %.2f counted in memories (ceil(r G) of the %d memories), the section's "
+                                            "wording; the 16 long static groups fit such a budget" % (c.w.ratio, c.G))
+    layers14 = c.layers
+    c.ctx.close()
+    for n in ("k_blocks", "v_blocks", "prompt", "k_cache", "v_cache"):
+        setattr(c, n, None)
+    torch.cuda.empty_cache()
+    others = {}
+    for name in ("qwen14b_64k_stress", "qwen7b_16k", "qwen32b_32k_host"):
+        same_shape = ks.workload(name).shape == c.s
+        oc = Case(name, a, torch, ks, kb, layers=layers14 if same_shape else None)
+        if not same_shape:
+            layers14 = None
+            c.layers = None
+            torch.cuda.empty_cache()
+        oc.make_prompt()
+        w = oc.w
+        ratios = ks.ratio_schedule(w.ratio, w.shape.n_layers, w.schedule)
+        mode = kb.KEEP_BUDGET_TOKENS if w.budget == "tokens" else kb.KEEP_BUDGET_GROUP_COUNT
+        entry = {"tokens": oc.n_tokens, "groups": oc.G, "layers": w.shape.n_layers, "ratio": w.ratio, "hops": w.hops,
+                 "kv": w.kv_location}
+        modes = (("layer_balanced", 2),) if not oc.host else (("serial", 0), ("next_layer", 1), ("layer_balanced", 2))
+        for mname, lm in modes:
+            ms, runs = time_steps(lambda: oc.ctx.prefill(oc.prompt, ratios, w.hops, oc.k_cache, oc.v_cache, oc.x_final,
+                                                         mode, lm, want_report=True, gate_up_events_only=True),
+                                  steps, warm, torch)
+            check_outputs(oc, runs)
+            rep = runs[-1][1]
+            e = dict(stats(ms), tokens_per_s=round(oc.n_tokens / (np.median(ms) * 1e-3), 1))
+            if oc.host:
+                e["bytes_loaded"] = int(sum(rep.bytes_loaded[l] for l in range(w.shape.n_layers)))
+            entry[mname] = e
+        if oc.host:
+            # the comparison the section draws: token granularity loads every block and updates in place
+            tr = token_schedule(ks, w, w.shape.n_layers, w.schedule)
+            ms, runs = time_steps(lambda: oc.ctx.prefill_tokens(oc.prompt, tr, oc.k_cache, oc.v_cache, oc.x_final,
+                                                                load_mode=2, want_report=True), steps, warm, torch)
+            rep = runs[-1][2]
+            entry["token_granularity"] = dict(
+                stats(ms), tokens_per_s=round(oc.n_tokens / (np.median(ms) * 1e-3), 1),
+                bytes_loaded=int(sum(rep.bytes_loaded[l] for l in range(w.shape.n_layers))),
+                rows_per_layer_mean=round(float(np.mean([rep.rows[l] for l in range(2, w.shape.n_layers)])), 1),
+                note="same prompt and mean ratio; tokens chosen by K/V deviation from layer 1 on, every block of every "
+                     "layer loaded, recomputed rows written in place")
+        others[name] = entry
+        oc.close()
+    out["other_workloads"] = others
+    return out
+
+
+def sweep(a, torch, ks, kb):
+    """BASELINE's stress sweep: recompute ratio 5/10/20/30 % x hops 1-4 on one prompt (default: the 65 536-token,
+    1 024-memory one).  One JSON line per point."""
+    c = Case(a.workload, a, torch, ks, kb)
+    c.make_prompt()
+    w, s, L = c.w, c.s, c.s.n_layers
+    mode = kb.KEEP_BUDGET_TOKENS if (a.budget or w.budget) == "tokens" else kb.KEEP_BUDGET_GROUP_COUNT
+    for ratio in (0.05, 0.10, 0.20, 0.30):
+        ratios = ks.ratio_schedule(ratio, L, a.schedule or w.schedule)
+        for hops in (1, 2, 3, 4):
+            ms, runs = time_steps(lambda: c.ctx.prefill(c.prompt, ratios, hops, c.k_cache, c.v_cache, c.x_final, mode,
+                                                        a.load_mode, want_report=True), a.steps, 1, torch)
+            check_outputs(c, runs)
+            rep = runs[-1][1]
+            tot = lambda n: round(float(sum(getattr(rep, n)[l] for l in range(L))), 2)
+            print(json.dumps(dict(stats(ms), workload=w.name, ratio=ratio, hops=hops,
+                                  tokens_per_s=round(c.n_tokens / (np.median(ms) * 1e-3), 1),
+                                  rows_per_layer_mean=round(float(np.mean([rep.rows[l] for l in range(1, L)])), 1),
+                                  hops_run_layer0=int(rep.hops_run[0]), set_size_layer1=int(rep.set_size[1]),
+                                  ms_gemms=round(tot("ms_qkv_gemm") + tot("ms_oproj") + tot("ms_gateup") + tot("ms_down"), 2),
+                                  ms_attention=tot("ms_attn"), ms_score_select=tot("ms_score"),
+                                  ms_realign=tot("ms_realign"), note="per-kernel sums from the fully instrumented steps "
+                                  "(HIP events around every kernel add about 2 ms per step)")), flush=True)
+    c.close()
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -265,88 +518,48 @@ def main():
         sys.exit(2)
     import torch
     import keep_synth as ks
-    from paper_2602_23592_amd import KeepContext, KeepPrompt
+    from paper_2602_23592_amd import KeepPrompt
     from paper_2602_23592_amd import binding as kb
 
     if not torch.cuda.is_available():
         print("bench.py needs a GPU (no CPU fallback exists)", file=sys.stderr)
         sys.exit(3)
-    w = ks.workload(a.workload)
-    if a.ratio is not None:
-        import dataclasses
-        w = dataclasses.replace(w, ratio=a.ratio)
-    if a.sparse_rows > 0:
-        import dataclasses
-        w = dataclasses.replace(w, instr_len=a.sparse_rows, ratio=0.0)
-    s = w.shape
+    gate = ProfilerGate()
+    gate.pause()                    # set-up (weights, group caches) is not part of the measurement
+    if a.sweep:
+        if a.workload == "qwen14b_32k":
+            a.workload = "qwen14b_64k_stress"
+        gate.resume()
+        sweep(a, torch, ks, kb)
+        return
+    case = Case(a.workload, a, torch, ks, kb, ratio=a.ratio, sparse_rows=a.sparse_rows, int4=a.int4,
+                random_cache=a.random_cache, extra_tokens=a.decode_tokens + 1)
+    w, s, ctx = case.w, case.s, case.ctx
     sched = a.schedule or w.schedule
     budget = a.budget or w.budget
     budget_mode = kb.KEEP_BUDGET_TOKENS if budget == "tokens" else kb.KEEP_BUDGET_GROUP_COUNT
-    glen, kinds = ks.group_lengths(w)
-    G, lq = len(glen), w.instr_len
-    n_tokens = w.mem_tokens + lq
-    dt = torch.bfloat16 if s.storage == "bf16" else torch.float32
-    gate = ProfilerGate()
-    gate.pause()                    # set-up (weights, group caches) is not part of the measurement
-    t_setup = time.perf_counter()
-    layers4 = None
-    if a.int4:
-        # weights arrive quantised; the library expands them to the bf16 values the model computes with
-        layers4 = [ks.make_int4_layer_on_device(s, l, "cuda") for l in range(s.n_layers)]
-        layers = []
-        for l in range(s.n_layers):
-            wl = {n: kb.dequantize_int4(*layers4[l][n]) for n in ks.INT4_MATS}   # (codes, words, rows, K)
-            wl["ln1"] = torch.ones(s.hidden, dtype=dt, device="cuda")
-            wl["ln2"] = torch.ones(s.hidden, dtype=dt, device="cuda")
-            wl["bq"] = wl["bk"] = wl["bv"] = None
-            layers.append(wl)
-    else:
-        layers = [ks.make_layer_weights(s, l, "cuda") for l in range(s.n_layers)]
-    embed = ks.make_embedding(s, "cuda")
-    ids = ks.make_token_ids(n_tokens, s.vocab, 0)
-    streams = [torch.cuda.Stream() for _ in range(3)]
-    torch.cuda.synchronize()
-    ctx = KeepContext(s, layers, embed, n_tokens + a.decode_tokens + 1, G, kb.KEEP_KERNELS_AUTO, *streams)
-    if layers4 is not None:
-        ctx.attach_int4(layers4)
+    glen, kinds, G, lq, n_tokens, dt, ids = case.glen, case.kinds, case.G, case.lq, case.n_tokens, case.dt, case.ids
     if a.memory_update:
         gate.resume()
         res = memory_update_cost(ctx, w, torch, a.steps, a.warmup)
         res["weights"] = "int4 weight-only (group 128) where a launch has at most 64 rows" if a.int4 else s.storage
         print(json.dumps(res))
         return
-    if a.random_cache:
-        kb_all = torch.empty((s.n_layers, w.mem_tokens, s.n_kv_heads, s.head_dim), dtype=dt, device="cuda")
-        vb_all = torch.empty_like(kb_all)
-        gen = torch.Generator(device="cuda")
-        gen.manual_seed(7)
-        for l in range(s.n_layers):
-            kb_all[l] = torch.randn(kb_all[l].shape, generator=gen, device="cuda").to(dt)
-            vb_all[l] = torch.randn(vb_all[l].shape, generator=gen, device="cuda").to(dt)
-    else:
-        kb_all, vb_all = precompute_group_caches(ctx, w, glen, ids, torch)
-    off = np.concatenate([[0], np.cumsum(glen)]).astype(np.int64)
-    host = w.kv_location == "pinned_host"
-    if host:
-        kb_src = kb_all.cpu().pin_memory()
-        vb_src = vb_all.cpu().pin_memory()
-        del kb_all, vb_all
-    else:
-        kb_src, vb_src = kb_all, vb_all
-    k_blocks = [[kb_src[l, off[g]:off[g + 1]] for g in range(G)] for l in range(s.n_layers)]
-    v_blocks = [[vb_src[l, off[g]:off[g + 1]] for g in range(G)] for l in range(s.n_layers)]
-    prompt = KeepPrompt(glen, lq, ids, k_blocks, v_blocks, s.n_layers,
-                        kb.KEEP_KV_PINNED_HOST if host else kb.KEEP_KV_DEVICE, kinds)
-    ratios = ks.ratio_schedule(w.ratio, s.n_layers, sched)
+    case.make_prompt()
+    prompt, host = case.prompt, case.host
+    k_blocks, v_blocks = case.k_blocks, case.v_blocks
+    k_cache, v_cache, x_final = case.k_cache, case.v_cache, case.x_final
+    tokens_mode = a.granularity == "tokens"
+    ratios = token_schedule(ks, w, s.n_layers, sched) if tokens_mode else ks.ratio_schedule(w.ratio, s.n_layers, sched)
     if a.sparse_rows > 0:
         ratios[:] = 0.0
-    k_cache = torch.empty((s.n_layers, n_tokens, s.n_kv_heads, s.head_dim), dtype=dt, device="cuda")
-    v_cache = torch.empty_like(k_cache)
-    x_final = torch.empty((lq, s.hidden), dtype=dt, device="cuda")
-    torch.cuda.synchronize()
-    t_setup = time.perf_counter() - t_setup
+    t_setup = case.setup_s
 
     def step(report, light=False):
+        if tokens_mode:
+            rows_t, _, rep_t = ctx.prefill_tokens(prompt, ratios, k_cache, v_cache, x_final, load_mode=a.load_mode,
+                                                  want_report=report)
+            return rows_t, rep_t
         return ctx.prefill(prompt, ratios, w.hops, k_cache, v_cache, x_final, budget_mode,
                            a.load_mode, want_report=report, gate_up_events_only=light)
 
@@ -366,17 +579,22 @@ def main():
     for _ in range(a.warmup):
         step(False)
     torch.cuda.synchronize()
-    # Timed region: HIP events only around the roofline kernel (the gate/up GEMM); a report with events around
-    # every kernel costs about 2 ms per step.  One more step with the full report follows, outside the timed
-    # region, for the per-kernel table.
-    light_reports = []
+    # Timed region: EXACTLY a.steps steps between two device synchronisations.  HIP events only around the roofline
+    # kernel (the gate/up GEMM); a report with events around every kernel costs about 2 ms per step.  Each step is
+    # also timed on its own (median / min); one more step with the full report follows, outside the timed region,
+    # for the per-kernel table.
+    light_reports, step_ms, runs = [], [], []
     t0 = time.perf_counter()
     for _ in range(a.steps):
-        sets, rep = step(True, light=True)
+        t1 = time.perf_counter()
+        sets, rep = step(True, light=True)       # keep_prefill returns when its streams have drained
+        step_ms.append((time.perf_counter() - t1) * 1e3)
         light_reports.append(rep)
+        runs.append((sets, rep))
     torch.cuda.synchronize()
     dt_s = time.perf_counter() - t0
     ms_per_step = dt_s * 1e3 / max(1, a.steps)
+    outputs_ok = check_outputs(case, runs)
     sets, full_rep = step(True)
     torch.cuda.synchronize()
     reports = [full_rep]
@@ -410,7 +628,8 @@ def main():
     add("gemm_down", mean_ms("ms_down"), 2.0 * ffn_rows * s.hidden * s.ffn_dim, "TFLOP/s", PEAK_BF16_TFLOPS)
     add("gemm_qkv", mean_ms("ms_qkv_gemm"), 2.0 * rows * s.hidden * (qd + 2 * kvd), "TFLOP/s", PEAK_BF16_TFLOPS)
     add("gemm_out_proj", mean_ms("ms_oproj"), 2.0 * ffn_rows * qd * s.hidden, "TFLOP/s", PEAK_BF16_TFLOPS)
-    add("sparse_row_attention", mean_ms("ms_attn"), 4.0 * s.head_dim * s.n_q_heads * vis, "TFLOP/s", PEAK_BF16_TFLOPS)
+    if not tokens_mode:
+        add("sparse_row_attention", mean_ms("ms_attn"), 4.0 * s.head_dim * s.n_q_heads * vis, "TFLOP/s", PEAK_BF16_TFLOPS)
     add("realign_concat", mean_ms("ms_realign"), 4.0 * re_rows * kvd * esz, "GB/s", PEAK_HBM_GBS)
     add("rope_scatter", mean_ms("ms_rope"), rows * ((qd + 2 * kvd) * 4.0 + (qd + 3 * kvd) * esz), "GB/s", PEAK_HBM_GBS)
     # score pass: Q.K^T of every recomputed row against the recomputed memory keys at or before it
@@ -419,40 +638,45 @@ def main():
     ms_sc = mean_ms("ms_score")
     mem = np.maximum(rows - lq, 0.0)
     pairs = np.where(ms_sc > 0, mem * (mem + 1) / 2 + lq * mem, 0.0)
-    add("score_select", ms_sc, 2.0 * s.head_dim * s.n_q_heads * pairs, "TFLOP/s", PEAK_BF16_TFLOPS)
+    if not tokens_mode:
+        add("score_select", ms_sc, 2.0 * s.head_dim * s.n_q_heads * pairs, "TFLOP/s", PEAK_BF16_TFLOPS)
     # attention in bytes too: one pass over the visible K and V per (row tile, KV head) is the algorithmic
     # minimum only when rows share tiles; report the cache-size figure (K_hat + V_hat of the layer, once)
     att_ms = float(np.sum(mean_ms("ms_attn")))
-    kern["sparse_row_attention"]["cache_gbs"] = round(L * 2.0 * n_tokens * kvd * esz / (att_ms * 1e-3) / 1e9, 1) if att_ms else 0
+    if not tokens_mode:
+        kern["sparse_row_attention"]["cache_gbs"] = round(L * 2.0 * n_tokens * kvd * esz / (att_ms * 1e-3) / 1e9, 1) if att_ms else 0
 
-    # the roofline kernel from the timed steps themselves
+    # the roofline kernel from the timed steps themselves (the token-granularity run carries full reports)
     gu_ms = float(np.sum(np.mean([[r.ms_gateup[l] for l in range(L)] for r in light_reports], axis=0)))
     gu_work = float(np.sum(2.0 * ffn_rows * s.hidden * 2 * s.ffn_dim))
     gu = {"ms_per_step": round(gu_ms, 3), "achieved": round(gu_work / (gu_ms * 1e-3) / 1e12, 2),
           "frac": round(gu_work / (gu_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4)}
     kern["gemm_gate_up_swiglu"]["timed_region"] = gu
     n_launch = L
-    # L2-miss bytes per launch from the two rocprofv3 counter runs summarised in
-    # profiles/keep_prefill_qwen14b_32k_hbm_traffic.md; they hold for that workload at its default settings only
+    # L2-miss bytes per launch: measured by rocprofv3 counter runs of this same command and stored under profiles/;
+    # valid for the default workload and settings, and only while the kernel's source is the one that was measured
     default_run = (a.workload == "qwen14b_32k" and a.schedule is None and a.ratio is None and a.budget is None
-                   and not a.random_cache and a.sparse_rows == 0)
-    traffic = GATE_UP_TRAFFIC_BYTES_PER_LAUNCH if default_run else None
+                   and not a.random_cache and a.sparse_rows == 0 and not tokens_mode)
+    traffic, traffic_src = stored_traffic() if default_run else (None, "not the workload of the stored counter run")
     roofline = {"kernel": "k_gemm_mfma<256,256,...,SWIGLU> + k_gemm_fixup (gate/up projection with fused SiLU*mul; "
                           "256x256 tiles, the last partly filled round cut along K)",
                 "bound": "mfma", "achieved": gu["achieved"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": gu["frac"], "traffic": traffic,
+                "frac": gu["frac"], "traffic": traffic, "traffic_source": traffic_src,
                 "avg_launch_ms": round(gu["ms_per_step"] / n_launch, 4), "launches_per_step": n_launch}
 
     out = {
         "metric": "prefill tokens/s with KV reuse (TTFT in ms_per_step; sparse-attn HBM GB/s in sparse_attn_hbm)",
         "value": round(n_tokens / (ms_per_step * 1e-3), 1), "unit": "tokens/s",
         "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": round(ms_per_step, 3),
-        "ttft_ms": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "ttft_ms": round(ms_per_step, 3), "ttft_ms_median": round(float(np.median(step_ms)), 3),
+        "ttft_ms_min": round(float(np.min(step_ms)), 3), "outputs_checked": outputs_ok,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": s.storage, "data": "synthetic",
         "config": {"workload": "%s: %d layers, hidden %d, %d Q / %d KV heads, head_dim %d, FFN %d; %d tokens = %d "
-                               "memory groups (%d tokens) + %d-token instruction; ratio %.2f of the %s (%s), %d hops; KV %s"
+                               "memory groups (%d tokens) + %d-token instruction; ratio %.2f of the %s (%s), %d hops; KV %s%s"
                                % (w.name, L, s.hidden, s.n_q_heads, s.n_kv_heads, s.head_dim, s.ffn_dim, n_tokens, G,
-                                  w.mem_tokens, lq, w.ratio, budget, sched, w.hops, w.kv_location),
+                                  w.mem_tokens, lq, w.ratio, budget, sched, w.hops, w.kv_location,
+                                  "; TOKEN granularity (comparison scheme)" if tokens_mode else ""),
                    "rows_per_layer_mean": round(float(np.mean(rows[1:])) if L > 1 else float(rows[0]), 1),
                    "attn_rows_layer0": attn_rows[0], "rows_layer0": int(rows[0]), "ffn_rows_layer0": int(ffn_rows[0]), "set_sizes": [len(x) for x in sets],
                    "group_caches": "random draws" if a.random_cache else "library dense prefill of each group alone",
@@ -460,7 +684,9 @@ def main():
         "roofline": roofline,
         "kernels": kern,
     }
-    if a.sparse_rows == 0 and not host:
+    if host:
+        out["bytes_loaded"] = int(sum(full_rep.bytes_loaded[l] for l in range(L)))
+    if a.sparse_rows == 0 and not host and not tokens_mode:
         # the third figure of the metric: cache bytes per second of the sparse-row attention where it is bound by
         # reading the cache once (pure reuse, a 16-row instruction behind the same memories; outside the timed region)
         lq_s = 16
@@ -490,9 +716,12 @@ def main():
             per_layer[name] = [round(float(v), 4) for v in mean_ms(name)]
         with open(a.layers_json, "w") as f:
             json.dump(per_layer, f)
+    if default_run and not a.no_extras:
+        out.update(extras(a, torch, ks, kb, case, ratios, sched))
+    else:
+        ctx.close()
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, glen, rows, n_tokens)
-    ctx.close()
     print(json.dumps(out), flush=True)
 
 

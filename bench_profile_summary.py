@@ -1,0 +1,136 @@
+"""Turns the output of a rocprofv3 run of bench.py into the short summaries kept under profiles/.
+
+    python bench_profile_summary.py stats   <rocprofv3 output dir> <bench stdout log> <out.md> "<command>"
+    python bench_profile_summary.py traffic <FETCH_SIZE output dir> <WRITE_SIZE output dir> <out.md> <out.json> "<command>"
+    python bench_profile_summary.py counters <output dir> [<output dir> ...] <out.md> "<command>" [kernel name part]
+
+`stats` lists the per-kernel rows of a `--kernel-trace --stats` run beside bench.py's own line.  `traffic` sums
+FETCH_SIZE / WRITE_SIZE per kernel, scales them by what the same counters read for the known-size calibration
+copy, and writes the gate/up GEMM's bytes per launch (with a hash of the kernel's source) to the JSON that
+bench.py reads for `roofline.traffic`.  `counters` sums any other --pmc counters per kernel.
+"""
+import collections
+import csv
+import glob
+import json
+import os
+import sys
+import time
+
+
+def _short(name):
+    name = name.replace("void keep::", "").replace("keep::", "")
+    return name[:name.index("(")] if "(" in name else name
+
+
+def _counter_rows(d):
+    f = glob.glob(os.path.join(d, "**", "*counter_collection.csv"), recursive=True)
+    if not f:
+        raise SystemExit("no counter_collection.csv under " + d)
+    return list(csv.DictReader(open(f[0])))
+
+
+def _per_kernel(rows):
+    """counter -> kernel -> [calls, total, max] (one row per dispatch and counter)."""
+    out = collections.defaultdict(lambda: collections.defaultdict(lambda: [0, 0.0, 0.0]))
+    for r in rows:
+        e = out[r["Counter_Name"]][_short(r["Kernel_Name"])]
+        v = float(r["Counter_Value"])
+        e[0] += 1
+        e[1] += v
+        e[2] = max(e[2], v)
+    return out
+
+
+def stats(argv):
+    d, benchlog, out, cmd = argv
+    f = glob.glob(os.path.join(d, "**", "*kernel_stats.csv"), recursive=True)
+    rows = list(csv.DictReader(open(f[0])))
+    bench = json.loads([l for l in open(benchlog) if l.startswith("{")][-1])
+    with open(out, "w") as o:
+        o.write("# rocprofv3 kernel stats: keep_prefill, %s (one MI355X)\n\n" % bench["config"]["workload"].split(":")[0])
+        o.write("Command (from /tmp with TMPDIR=/tmp on the GPU box):\n\n    %s\n\n" % cmd)
+        o.write("bench.py pauses the profiler during set-up (roctxProfilerPause/Resume, honoured with --marker-trace), so "
+                "the rows cover the warm-up, the timed steps and the one fully instrumented step.\n\n")
+        o.write("| kernel | calls | total ms | avg us | % | min us | max us |\n|---|---|---|---|---|---|---|\n")
+        for r in rows:
+            if float(r["Percentage"]) < 0.01:
+                continue
+            o.write("| `%s` | %s | %.2f | %.1f | %s | %.1f | %.1f |\n" % (
+                _short(r["Name"])[:70], r["Calls"], int(r["TotalDurationNs"]) / 1e6, float(r["AverageNs"]) / 1e3,
+                r["Percentage"], int(r["MinNs"]) / 1e3, int(r["MaxNs"]) / 1e3))
+        n_calls = sum(int(r["Calls"]) for r in rows)
+        o.write("\nKernel launches in all: %d.\n" % n_calls)
+        o.write("\nbench.py line of the same run (HIP-event timings on the compute stream):\n\n")
+        o.write("    TTFT %.1f ms (median %.1f, min %.1f), %.0f tokens/s; roofline kernel: avg launch %.4f ms, %.1f TFLOP/s = %.3f of 2500\n" % (
+            bench["ms_per_step"], bench.get("ttft_ms_median", 0), bench.get("ttft_ms_min", 0), bench["value"],
+            bench["roofline"]["avg_launch_ms"], bench["roofline"]["achieved"], bench["roofline"]["frac"]))
+        for k, v in bench["kernels"].items():
+            o.write("    %-24s %8.2f ms/step  %9.2f %s  (%.3f of peak)\n" % (k, v["ms_per_step"], v["achieved"], v["unit"], v["frac"]))
+
+
+def traffic(argv):
+    d_fetch, d_write, out_md, out_json, cmd = argv
+    sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
+    import bench
+    pk = {"FETCH_SIZE": _per_kernel(_counter_rows(d_fetch))["FETCH_SIZE"],
+          "WRITE_SIZE": _per_kernel(_counter_rows(d_write))["WRITE_SIZE"]}
+    # calibration: the largest device-to-device copy of the run moved a known number of bytes
+    calib = {}
+    for c in pk:
+        copies = [v for k, v in pk[c].items() if "copyBuffer" in k]
+        calib[c] = max(v[2] for v in copies) if copies else 0.0
+    copy_kib = None
+    for part in cmd.split():
+        if part.isdigit():
+            copy_kib = int(part) * 1024
+    f_scale = copy_kib / calib["FETCH_SIZE"] if calib["FETCH_SIZE"] else 0.0
+    w_scale = copy_kib / calib["WRITE_SIZE"] if calib["WRITE_SIZE"] else 0.0
+    gu = lambda c: sum(v[1] for k, v in pk[c].items() if k.startswith("k_gemm_mfma<256, 256, 4, 2, 2") or k.startswith("k_gemm_fixup<256, 256, 4, 2, 2"))
+    launches = sum(v[0] for k, v in pk["FETCH_SIZE"].items() if k.startswith("k_gemm_mfma<256, 256, 4, 2, 2"))
+    bytes_per_launch = (gu("FETCH_SIZE") * f_scale + gu("WRITE_SIZE") * w_scale) * 1024.0 / max(1, launches)
+    with open(out_json, "w") as o:
+        json.dump({"bytes_per_launch": int(bytes_per_launch), "launches": launches, "fetch_scale": round(f_scale, 4),
+                   "write_scale": round(w_scale, 4), "sources_sha16": bench.sources_sha16(),
+                   "measured_at": time.strftime("%Y-%m-%d"), "command": cmd}, o, indent=1)
+        o.write("\n")
+    with open(out_md, "w") as o:
+        o.write("# rocprofv3 counters FETCH_SIZE / WRITE_SIZE: keep_prefill, workload qwen14b_32k (one MI355X)\n\n")
+        o.write("Commands (each from /tmp with TMPDIR=/tmp on the GPU box, one counter per run):\n\n    %s\n    %s\n\n"
+                % (cmd.replace("COUNTER", "FETCH_SIZE"), cmd.replace("COUNTER", "WRITE_SIZE")))
+        o.write("Calibration (same runs): the %d KiB device-to-device copy reads %.0f KiB by FETCH_SIZE and writes %.0f KiB "
+                "by WRITE_SIZE, so true bytes = %.2f x FETCH_SIZE and %.2f x WRITE_SIZE.  The counters sit between L2 and "
+                "the fabric: they count L2 misses, whether the Infinity Cache or HBM serves them.\n\n"
+                % (copy_kib, calib["FETCH_SIZE"], calib["WRITE_SIZE"], f_scale, w_scale))
+        o.write("Gate/up GEMM (k_gemm_mfma<256,256,4,2,SWIGLU> + its fix-up): %d launches, %.3f GB per launch (scaled).\n\n"
+                % (launches, bytes_per_launch / 1e9))
+        o.write("```\n")
+        for c in ("FETCH_SIZE", "WRITE_SIZE"):
+            o.write(c + " (KiB as counted)\n")
+            for k, v in sorted(pk[c].items(), key=lambda kv: -kv[1][1])[:16]:
+                o.write("  %-64s calls %5d  total %12.0f  max %10.0f\n" % (k[:64], v[0], v[1], v[2]))
+        o.write("```\n")
+
+
+def counters(argv):
+    *dirs, out_md, cmd = argv[:-1] if len(argv) > 2 and not os.path.isdir(argv[-1]) and not argv[-1].endswith(".md") and " " not in argv[-1] else argv
+    part = argv[-1] if len(argv) > 2 and " " not in argv[-1] and not argv[-1].endswith(".md") and not os.path.isdir(argv[-1]) else ""
+    with open(out_md, "w") as o:
+        o.write("# rocprofv3 --pmc counters per kernel (one MI355X)\n\nCommand (from /tmp with TMPDIR=/tmp on the GPU box; "
+                "one run per counter set):\n\n    %s\n\nValues are sums over all dispatches of the kernel in the run "
+                "(and over the chip's counter instances).\n\n" % cmd)
+        for d in dirs:
+            pk = _per_kernel(_counter_rows(d))
+            kernels = sorted({k for c in pk.values() for k in c})
+            for k in kernels:
+                if part and part not in k:
+                    continue
+                o.write("`%s`\n\n" % k[:90])
+                for c in sorted(pk):
+                    if k in pk[c]:
+                        o.write("    %-34s calls %5d  total %.6g\n" % (c, pk[c][k][0], pk[c][k][1]))
+                o.write("\n")
+
+
+if __name__ == "__main__":
+    {"stats": stats, "traffic": traffic, "counters": counters}[sys.argv[1]](sys.argv[2:])
