@@ -631,7 +631,10 @@ def main():
     if not tokens_mode:
         add("sparse_row_attention", mean_ms("ms_attn"), 4.0 * s.head_dim * s.n_q_heads * vis, "TFLOP/s", PEAK_BF16_TFLOPS)
     add("realign_concat", mean_ms("ms_realign"), 4.0 * re_rows * kvd * esz, "GB/s", PEAK_HBM_GBS)
-    add("rope_scatter", mean_ms("ms_rope"), rows * ((qd + 2 * kvd) * 4.0 + (qd + 3 * kvd) * esz), "GB/s", PEAK_HBM_GBS)
+    if float(np.sum(mean_ms("ms_rope"))) > 0.02 * L:
+        add("rope_scatter", mean_ms("ms_rope"), rows * ((qd + 2 * kvd) * 4.0 + (qd + 3 * kvd) * esz), "GB/s", PEAK_HBM_GBS)
+    else:   # bias, RoPE and the K/V scatter ran as the QKV projection's epilogue: no kernel of their own
+        kern["rope_scatter"] = {"ms_per_step": 0.0, "fused_into": "gemm_qkv"}
     # score pass: Q.K^T of every recomputed row against the recomputed memory keys at or before it
     # (the same compact list), then the reductions and the selector; layers whose budget keeps all
     # or none of the candidates run no pass

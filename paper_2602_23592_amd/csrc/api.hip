@@ -439,17 +439,39 @@ keep_status layer_front(keep_ctx* c, const PromptInfo& pi, int layer, const Laye
     set_w4(b, 2, c->w4[layer].wv);
   }
   const int n_qkv = b.n_rows[0] + 2 * b.n_rows[1];
-  if (c->mfma)
-    launch_gemm_mfma(reinterpret_cast<const bf16_t*>(c->hbuf), n, d.hidden, b, nullptr, n_qkv, EPI_STORE_F32, nullptr,
-                     c->qkv_raw, s, c->skinny_ws);
-  else
-    launch_gemm_generic<T>(Typed<T>::p(c->hbuf), n, d.hidden, b, nullptr, n_qkv, EPI_STORE_F32, nullptr, c->qkv_raw, s);
-  if (evs && !c->ev_light) HIP_TRY(c, hipEventRecord(evs[3], s));
-  launch_rope_scatter<T>(c->qkv_raw, Typed<T>::p(w.bq), Typed<T>::p(w.bk), Typed<T>::p(w.bv), c->d_row_pos, n,
-                         d.n_q_heads, d.n_kv_heads, d.head_dim, c->rope_cos, c->rope_sin, Typed<T>::p(c->q),
-                         Typed<T>::p(c->kc), Typed<T>::p(k_cache_l), Typed<T>::p(v_cache_l), s,
-                         c->units_mode ? c->d_row_lo : nullptr);
-  if (evs && !c->ev_light) HIP_TRY(c, hipEventRecord(evs[4], s));
+  if (c->mfma && gemm_mfma_fuses_qkv(n, d.hidden, b, n_qkv, c->skinny_ws != nullptr)) {
+    // bias, RoPE, the compact q / k rows and the scatter of K and V into the cache are the projection's epilogue
+    QkvEpilogue qe{};
+    qe.row_pos = c->d_row_pos;
+    qe.row_lo = c->units_mode ? c->d_row_lo : nullptr;
+    qe.rope_cos = c->rope_cos;
+    qe.rope_sin = c->rope_sin;
+    qe.bias[0] = w.bq; qe.bias[1] = w.bk; qe.bias[2] = w.bv;
+    qe.q = c->q;
+    qe.k_compact = c->kc;
+    qe.k_cache = k_cache_l;
+    qe.v_cache = v_cache_l;
+    qe.q_dim = b.n_rows[0];
+    qe.kv_dim = b.n_rows[1];
+    launch_gemm_mfma(reinterpret_cast<const bf16_t*>(c->hbuf), n, d.hidden, b, nullptr, n_qkv, EPI_QKV_ROPE, nullptr,
+                     nullptr, s, c->skinny_ws, &qe);
+    if (evs && !c->ev_light) {
+      HIP_TRY(c, hipEventRecord(evs[3], s));
+      HIP_TRY(c, hipEventRecord(evs[4], s));
+    }
+  } else {
+    if (c->mfma)
+      launch_gemm_mfma(reinterpret_cast<const bf16_t*>(c->hbuf), n, d.hidden, b, nullptr, n_qkv, EPI_STORE_F32, nullptr,
+                       c->qkv_raw, s, c->skinny_ws);
+    else
+      launch_gemm_generic<T>(Typed<T>::p(c->hbuf), n, d.hidden, b, nullptr, n_qkv, EPI_STORE_F32, nullptr, c->qkv_raw, s);
+    if (evs && !c->ev_light) HIP_TRY(c, hipEventRecord(evs[3], s));
+    launch_rope_scatter<T>(c->qkv_raw, Typed<T>::p(w.bq), Typed<T>::p(w.bk), Typed<T>::p(w.bv), c->d_row_pos, n,
+                           d.n_q_heads, d.n_kv_heads, d.head_dim, c->rope_cos, c->rope_sin, Typed<T>::p(c->q),
+                           Typed<T>::p(c->kc), Typed<T>::p(k_cache_l), Typed<T>::p(v_cache_l), s,
+                           c->units_mode ? c->d_row_lo : nullptr);
+    if (evs && !c->ev_light) HIP_TRY(c, hipEventRecord(evs[4], s));
+  }
   if (skip_attention) {  // the caller attends the rows as they turn out to be needed
     if (evs && !c->ev_light) HIP_TRY(c, hipEventRecord(evs[5], s));
     HIP_TRY(c, hipGetLastError());

@@ -56,7 +56,7 @@ template <int BM, int BN, int WM, int WN, int EPI, int GBK, int NST>
 __global__ void __launch_bounds__(WM* WN * 64)
     k_gemm_mfma(const bf16_t* __restrict__ A, int M, int K, MfmaB B, const bf16_t* __restrict__ B2, int N,
                 const bf16_t* __restrict__ residual, void* __restrict__ Cv, int tiles_m, int tiles_n,
-                int full_per_xcd, int split_s, float* __restrict__ part) {
+                int full_per_xcd, int split_s, float* __restrict__ part, QkvEpilogue qe) {
   constexpr int T = WM * WN * 64;
   constexpr int TM = BM / WM, TN = BN / WN;
   constexpr int MI = TM / 32, NI = TN / 32;
@@ -151,6 +151,36 @@ __global__ void __launch_bounds__(WM* WN * 64)
         __builtin_amdgcn_global_load_lds((gptr_t)(b_src[i] + (size_t)(slice) * GBK), (lptr_t)(sb_ + i * RPI * GBK), 16, 0, 0); \
   }
 
+  // Fused QKV epilogue: once the K loop is over the operand tiles in LDS are dead, and the cos / sin rows of the
+  // tile's BM rows (64 + 64 floats each, picked by the row's rotation position) are staged there, with the
+  // rows' cache positions behind them, so that the epilogue's loads are LDS reads that no global store can
+  // delay.  Wave w stages rows 32 w .. 32 w + 31; a load instruction fills two rows (lanes 0-15 / 32-47 the cos
+  // chunks, lanes 16-31 / 48-63 the sin chunks).  Tiles that hold only value columns need no table.
+#define QKV_STAGE_TABLES                                                                                          \
+  {                                                                                                               \
+    __syncthreads();                                                                                              \
+    float* tab_ = reinterpret_cast<float*>(smem);                                                                 \
+    int32_t* spos_ = reinterpret_cast<int32_t*>(smem) + BM * 128;                                                 \
+    const int r_ = wave * (BM / NW) + (lane & 31);                                                                \
+    const int gmr_ = min(m0 + r_, M - 1);                                                                         \
+    const int p_ = qe.row_pos[gmr_];                                                                              \
+    const int rp_ = p_ - (qe.row_lo ? qe.row_lo[gmr_] : 0);                                                       \
+    if (lane < 32) {                                                                                              \
+      spos_[r_] = p_;                                                                                             \
+      spos_[BM + r_] = rp_;                                                                                       \
+    }                                                                                                             \
+    if (n0 < qe.q_dim + qe.kv_dim) {                                                                              \
+      _Pragma("unroll") for (int i_ = 0; i_ < 16; ++i_) {                                                         \
+        const int rp2_ = __shfl(rp_, 2 * i_ + (lane >> 5), 64);                                                   \
+        const int ch_ = lane & 31;                                                                                \
+        const float* src_ = (ch_ < 16 ? qe.rope_cos : qe.rope_sin) + (size_t)rp2_ * 64 + (ch_ & 15) * 4;          \
+        __builtin_amdgcn_global_load_lds((gptr_t)src_, (lptr_t)(tab_ + (wave * (BM / NW) + 2 * i_) * 128), 16, 0, 0); \
+      }                                                                                                           \
+    }                                                                                                             \
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));                                                                     \
+    __syncthreads();                                                                                              \
+  }
+
   f32x16 acc[MI][NI];
 #pragma unroll
   for (int i = 0; i < MI; ++i)
@@ -182,6 +212,9 @@ __global__ void __launch_bounds__(WM* WN * 64)
       st_ = st_ + 1 == NST ? 0 : st_ + 1;
     }
     __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    if constexpr (EPI == EPI_QKV_ROPE) {
+      if (pieces == 1) QKV_STAGE_TABLES  // (its two barriers are the workgroup's: every wave takes part)
+    }
     return;
   }
 
@@ -250,7 +283,6 @@ __global__ void __launch_bounds__(WM* WN * 64)
     }
     stage = next_stage;
   }
-#undef GEMM_STAGE
   __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));  // no LDS write of this workgroup may outlive it
 
   // ---- epilogue.  acc[i][j][e]: row = i*32 + 8*(e/4) + 4*(lane/32) + e%4, col = j*32 + lane%32
@@ -267,6 +299,65 @@ __global__ void __launch_bounds__(WM* WN * 64)
 #pragma unroll
         for (int j = 0; j < NI; ++j) pt[(size_t)r * BN + wn * TN + j * 32 + col_l] = acc[i][j][e];
       }
+    return;
+  }
+  if constexpr (EPI == EPI_QKV_ROPE) {
+    // The wave's TN = 128 columns are one head: query head, key head or value head by where they start.
+    // RoPE pairs column c with c + 64: accumulator tiles j and j + 2, same lane, same register.
+    static_assert(EPI != EPI_QKV_ROPE || (TN == 128 && NI == 4 && BM / NW == 32),
+                  "the fused QKV epilogue needs one head per wave and 32 staged rows per wave");
+    QKV_STAGE_TABLES
+    const float* tab = reinterpret_cast<const float*>(smem);
+    const int32_t* spos = reinterpret_cast<const int32_t*>(smem) + BM * 128;
+    const int col0 = n0 + wn * TN;
+    const int kind = col0 < qe.q_dim ? 0 : (col0 < qe.q_dim + qe.kv_dim ? 1 : 2);
+    const int hcol = kind == 0 ? col0 : (kind == 1 ? col0 - qe.q_dim : col0 - qe.q_dim - qe.kv_dim);  // column inside q / k / v
+    const bf16_t* bias = reinterpret_cast<const bf16_t*>(qe.bias[kind]);
+    float bl[2] = {0.f, 0.f}, bh[2] = {0.f, 0.f};
+    if (bias) {
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        bl[j] = bf16_bits_to_f32(bias[hcol + j * 32 + col_l].bits);
+        bh[j] = bf16_bits_to_f32(bias[hcol + 64 + j * 32 + col_l].bits);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < MI; ++i) {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int rt = wm * TM + i * 32 + 8 * (e >> 2) + row_l + (e & 3);  // row inside the tile
+        const int gm = m0 + rt;
+        if (gm >= M) continue;
+        const int pos = spos[rt];
+        if (kind == 2) {
+          bf16_t* dst = reinterpret_cast<bf16_t*>(qe.v_cache) + (size_t)pos * qe.kv_dim + hcol;
+#pragma unroll
+          for (int j = 0; j < 2; ++j) {
+            dst[j * 32 + col_l].bits = f32_to_bf16_bits(acc[i][j][e] + bl[j]);
+            dst[64 + j * 32 + col_l].bits = f32_to_bf16_bits(acc[i][j + 2][e] + bh[j]);
+          }
+        } else {
+          const float* cs = tab + rt * 128;
+          const float* sn = cs + 64;
+          bf16_t* d1 = kind == 0 ? reinterpret_cast<bf16_t*>(qe.q) + (size_t)gm * qe.q_dim + hcol
+                                 : reinterpret_cast<bf16_t*>(qe.k_compact) + (size_t)gm * qe.kv_dim + hcol;
+          bf16_t* d2 = reinterpret_cast<bf16_t*>(qe.k_cache) + (size_t)pos * qe.kv_dim + hcol;
+#pragma unroll
+          for (int j = 0; j < 2; ++j) {
+            const int c = j * 32 + col_l;
+            const float lo = acc[i][j][e] + bl[j], hi = acc[i][j + 2][e] + bh[j];
+            const float cc = cs[c], ss = sn[c];
+            const uint16_t olo = f32_to_bf16_bits(lo * cc - hi * ss), ohi = f32_to_bf16_bits(hi * cc + lo * ss);
+            d1[c].bits = olo;
+            d1[64 + c].bits = ohi;
+            if (kind == 1) {
+              d2[c].bits = olo;
+              d2[64 + c].bits = ohi;
+            }
+          }
+        }
+      }
+    }
     return;
   }
 #pragma unroll
@@ -300,6 +391,9 @@ __global__ void __launch_bounds__(WM* WN * 64)
     }
   }
 }
+
+#undef GEMM_STAGE
+#undef QKV_STAGE_TABLES
 
 // Epilogue of the tiles that were cut along K: partial slices added in slice order (reproducible).
 template <int BM, int BN, int WM, int WN, int EPI>
@@ -361,19 +455,99 @@ __global__ void __launch_bounds__(256)
   }
 }
 
+// The same for the fused QKV epilogue: a thread owns 4 consecutive columns c.. of the low half of a head and their
+// partners c + 64.. (RoPE pairs), of one row.
+template <int BM, int BN>
+__global__ void __launch_bounds__(256)
+    k_gemm_fixup_qkv(const float* __restrict__ part, int M, int tiles_m, int tiles_n, int full_per_xcd, int split_s,
+                     QkvEpilogue qe) {
+  const int n_tiles = tiles_m * tiles_n;
+  const int per_xcd = (n_tiles + 7) >> 3;
+  const int rem_per_xcd = per_xcd - full_per_xcd;
+  const int xcd = blockIdx.x / rem_per_xcd, ri = blockIdx.x % rem_per_xcd;
+  const int t = xcd * per_xcd + full_per_xcd + ri;
+  if (t >= n_tiles) return;
+  int tile_m, tile_n;
+  gemm_tile_of<BM>(t, tiles_m, tiles_n, tile_m, tile_n);
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
+  const float* pt = part + (size_t)blockIdx.x * split_s * (BM * BN);
+  constexpr int HEADS = BN / 128;               // heads per tile
+  constexpr int ITEMS = BM * HEADS * 16;        // (row, head, group of 4 low columns)
+  const int it = blockIdx.y * 256 + threadIdx.x;
+  if (it >= ITEMS) return;
+  const int r = it / (HEADS * 16), hh = (it / 16) % HEADS, c = (it % 16) * 4;
+  const int gm = m0 + r;
+  if (gm >= M) return;
+  const float* p = pt + (size_t)r * BN + hh * 128 + c;
+  float4 lo = make_float4(0.f, 0.f, 0.f, 0.f), hi = lo;
+#pragma unroll 4
+  for (int z = 0; z < split_s; ++z) {
+    const float4 a = *reinterpret_cast<const float4*>(p + (size_t)z * (BM * BN));
+    const float4 b = *reinterpret_cast<const float4*>(p + (size_t)z * (BM * BN) + 64);
+    lo.x += a.x; lo.y += a.y; lo.z += a.z; lo.w += a.w;
+    hi.x += b.x; hi.y += b.y; hi.z += b.z; hi.w += b.w;
+  }
+  float l4[4] = {lo.x, lo.y, lo.z, lo.w}, h4[4] = {hi.x, hi.y, hi.z, hi.w};
+  const int col0 = n0 + hh * 128;
+  const int kind = col0 < qe.q_dim ? 0 : (col0 < qe.q_dim + qe.kv_dim ? 1 : 2);
+  const int hcol = kind == 0 ? col0 : (kind == 1 ? col0 - qe.q_dim : col0 - qe.q_dim - qe.kv_dim);
+  const bf16_t* bias = reinterpret_cast<const bf16_t*>(qe.bias[kind]);
+  if (bias) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      l4[e] += bf16_bits_to_f32(bias[hcol + c + e].bits);
+      h4[e] += bf16_bits_to_f32(bias[hcol + 64 + c + e].bits);
+    }
+  }
+  const int pos = qe.row_pos[gm];
+  uint2 olo, ohi;
+  if (kind == 2) {
+    olo.x = pack_bf16x2(l4[0], l4[1]); olo.y = pack_bf16x2(l4[2], l4[3]);
+    ohi.x = pack_bf16x2(h4[0], h4[1]); ohi.y = pack_bf16x2(h4[2], h4[3]);
+    bf16_t* dst = reinterpret_cast<bf16_t*>(qe.v_cache) + (size_t)pos * qe.kv_dim + hcol;
+    *reinterpret_cast<uint2*>(dst + c) = olo;
+    *reinterpret_cast<uint2*>(dst + 64 + c) = ohi;
+    return;
+  }
+  const int rpos = pos - (qe.row_lo ? qe.row_lo[gm] : 0);
+  const float4 cs = *reinterpret_cast<const float4*>(qe.rope_cos + (size_t)rpos * 64 + c);
+  const float4 sn = *reinterpret_cast<const float4*>(qe.rope_sin + (size_t)rpos * 64 + c);
+  const float c4[4] = {cs.x, cs.y, cs.z, cs.w}, s4[4] = {sn.x, sn.y, sn.z, sn.w};
+  float ol[4], oh[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    ol[e] = l4[e] * c4[e] - h4[e] * s4[e];
+    oh[e] = h4[e] * c4[e] + l4[e] * s4[e];
+  }
+  olo.x = pack_bf16x2(ol[0], ol[1]); olo.y = pack_bf16x2(ol[2], ol[3]);
+  ohi.x = pack_bf16x2(oh[0], oh[1]); ohi.y = pack_bf16x2(oh[2], oh[3]);
+  bf16_t* d1 = kind == 0 ? reinterpret_cast<bf16_t*>(qe.q) + (size_t)gm * qe.q_dim + hcol
+                         : reinterpret_cast<bf16_t*>(qe.k_compact) + (size_t)gm * qe.kv_dim + hcol;
+  *reinterpret_cast<uint2*>(d1 + c) = olo;
+  *reinterpret_cast<uint2*>(d1 + 64 + c) = ohi;
+  if (kind == 1) {
+    bf16_t* d2 = reinterpret_cast<bf16_t*>(qe.k_cache) + (size_t)pos * qe.kv_dim + hcol;
+    *reinterpret_cast<uint2*>(d2 + c) = olo;
+    *reinterpret_cast<uint2*>(d2 + 64 + c) = ohi;
+  }
+}
+
 constexpr size_t GEMM_SPLIT_WS_BYTES = (size_t)256 * 256 * 256 * sizeof(float);  // 256 partial tiles of 256 x 256
 
 template <int BM, int BN, int WM, int WN, int GBK, int NST>
 static void launch_cfg(const bf16_t* A, int M, int K, const MfmaB& b, const bf16_t* B2, int N, int epilogue,
-                       const bf16_t* residual, void* C, hipStream_t s, void* ws) {
-  const size_t sh = (size_t)NST * (BM + BN) * GBK * sizeof(uint16_t);
+                       const bf16_t* residual, void* C, hipStream_t s, void* ws, const QkvEpilogue& qe) {
+  // operand stages; the fused QKV epilogue re-uses them for BM rows of cos / sin (512 B each) and needs 2 BM
+  // ints more for the rows' positions
+  const size_t sh_ops = (size_t)NST * (BM + BN) * GBK * sizeof(uint16_t);
+  const size_t sh = epilogue == EPI_QKV_ROPE ? std::max(sh_ops, (size_t)BM * 512) + (size_t)BM * 8 : sh_ops;
   const dim3 block(WM * WN * 64);
   const int n_tile_rows = epilogue == EPI_SWIGLU_STORE ? 2 * N : N;  // B-tile rows to cover
   const int tiles_n = n_tile_rows / BN, tiles_m = (M + BM - 1) / BM;
   const int per_xcd = (tiles_m * tiles_n + 7) / 8;
   // Workgroups resident per XCD (32 CUs): one per CU for the 256 x 256 tile (128 KB of LDS), two otherwise.
   // What would be a last, partly filled round is cut along K so that it fills the XCD once.
-  const int slots = sh > 80 * 1024 ? 32 : 64;
+  const int slots = sh_ops > 80 * 1024 ? 32 : 64;
   int full = per_xcd, split = 1;
   if (ws && BM >= 128) {
     const int f = per_xcd / slots * slots, rem = per_xcd - f;
@@ -394,8 +568,8 @@ static void launch_cfg(const bf16_t* A, int M, int K, const MfmaB& b, const bf16
     auto kern = k_gemm_mfma<BM, BN, WM, WN, E, GBK, NST>;                                                  \
     static std::atomic<uint64_t> attr_done{0};                                                             \
     set_max_dyn_smem_once(attr_done, reinterpret_cast<const void*>(kern), (int)sh);                        \
-    hipLaunchKernelGGL(kern, grid, block, sh, s, A, M, K, b, B2, N, residual, C, tiles_m, tiles_n, full, split, part); \
-    if (split > 1)                                                                                         \
+    hipLaunchKernelGGL(kern, grid, block, sh, s, A, M, K, b, B2, N, residual, C, tiles_m, tiles_n, full, split, part, qe); \
+    if (split > 1 && E != EPI_QKV_ROPE)                                                                    \
       hipLaunchKernelGGL((k_gemm_fixup<BM, BN, WM, WN, E>), dim3(8 * rem, BM * BN / 1024), dim3(256), 0, s, part, M, N, \
                          residual, C, tiles_m, tiles_n, full, split);                                      \
   } while (0)
@@ -403,48 +577,64 @@ static void launch_cfg(const bf16_t* A, int M, int K, const MfmaB& b, const bf16
     GO(EPI_STORE_F32);
   else if (epilogue == EPI_RESIDUAL_STORE)
     GO(EPI_RESIDUAL_STORE);
-  else
+  else if (epilogue == EPI_SWIGLU_STORE)
     GO(EPI_SWIGLU_STORE);
+  else if constexpr (BN / WN == 128) {  // one head per wave
+    GO(EPI_QKV_ROPE);
+    if (split > 1)
+      hipLaunchKernelGGL((k_gemm_fixup_qkv<BM, BN>), dim3(8 * rem, (BM * (BN / 128) * 16 + 255) / 256), dim3(256), 0, s,
+                         part, M, tiles_m, tiles_n, full, split, qe);
+  }
 #undef GO
 }
 
 size_t gemm_ws_bytes() { return std::max(GEMM_SPLIT_WS_BYTES, gemm_skinny_ws_bytes()); }
 
+// 256x256 tiles (8 waves, 64x128 each) unless the launch is so small that their start-up cost shows
+// (fewer than ~10000 tile K-slices in all); 128x128 tiles then, and where the row counts are not
+// multiples of 256.  A last, partly filled round of workgroups is cut along K in either case.
+static bool big_tiles(int32_t M, int32_t K, const GemmB& B, int32_t rows) {
+  int acc = 0;
+  for (int p = 0; p < B.n_parts; ++p) {
+    acc += B.n_rows[p];
+    if (acc % 256) return false;
+  }
+  const long tiles256 = (long)((M + 255) / 256) * (rows / 256);
+  return rows % 256 == 0 && tiles256 * (K / 64) >= 10000;
+}
+
+bool gemm_mfma_fuses_qkv(int32_t M, int32_t K, const GemmB& B, int32_t N, bool have_ws) {
+  if (M <= 0 || N <= 0 || B.n_parts != 3) return false;
+  if (have_ws && gemm_skinny_fits(M, K, B, N, EPI_STORE_F32)) return false;
+  // every part a whole number of 128-column heads, so that a wave's columns never straddle q / k / v
+  return big_tiles(M, K, B, N) && B.n_rows[0] % 128 == 0 && B.n_rows[1] % 128 == 0 && B.n_rows[2] % 128 == 0;
+}
+
 void launch_gemm_mfma(const bf16_t* A, int32_t M, int32_t K, const GemmB& B, const void* B2, int32_t N, int epilogue,
-                      const bf16_t* residual, void* C, hipStream_t s, void* skinny_ws) {
+                      const bf16_t* residual, void* C, hipStream_t s, void* skinny_ws, const QkvEpilogue* qkv) {
   if (M <= 0 || N <= 0) return;
-  if (skinny_ws && gemm_skinny_fits(M, K, B, N, epilogue)) {
+  if (epilogue != EPI_QKV_ROPE && skinny_ws && gemm_skinny_fits(M, K, B, N, epilogue)) {
     launch_gemm_skinny(A, M, K, B, B2, N, epilogue, residual, C, skinny_ws, s);
     return;
   }
   MfmaB b;
   b.n_parts = B.n_parts;
   int acc = 0;
-  bool aligned256 = true;
   for (int p = 0; p < 3; ++p) {
     b.ptr[p] = p < B.n_parts ? reinterpret_cast<const bf16_t*>(B.ptr[p]) : nullptr;
     b.begin[p] = acc;
-    if (p < B.n_parts) {
-      acc += B.n_rows[p];
-      if (acc % 256) aligned256 = false;
-    }
+    if (p < B.n_parts) acc += B.n_rows[p];
   }
   b.begin[3] = acc;
   const bf16_t* b2 = reinterpret_cast<const bf16_t*>(B2);
   const int rows = epilogue == EPI_SWIGLU_STORE ? 2 * N : N;
-  // 256x256 tiles (8 waves, 64x128 each) unless the launch is so small that their start-up cost shows
-  // (fewer than ~10000 tile K-slices in all); 128x128 tiles then, and where the row counts are not
-  // multiples of 256.  A last, partly filled round of workgroups is cut along K in either case.
-  const long tiles256 = (long)((M + 255) / 256) * (rows / 256);
-  if (aligned256 && rows % 256 == 0 && tiles256 * (K / 64) >= 10000)
-#ifndef GEMM_BIG_CFG
-#define GEMM_BIG_CFG 256, 256, 4, 2, 64, 2
-#endif
-    launch_cfg<GEMM_BIG_CFG>(A, M, K, b, b2, N, epilogue, residual, C, s, skinny_ws);
+  const QkvEpilogue qe = qkv ? *qkv : QkvEpilogue{};
+  if (big_tiles(M, K, B, rows))
+    launch_cfg<256, 256, 4, 2, 64, 2>(A, M, K, b, b2, N, epilogue, residual, C, s, skinny_ws, qe);
   else if (rows % 128 == 0)
-    launch_cfg<128, 128, 2, 2, 64, 2>(A, M, K, b, b2, N, epilogue, residual, C, s, skinny_ws);
+    launch_cfg<128, 128, 2, 2, 64, 2>(A, M, K, b, b2, N, epilogue, residual, C, s, skinny_ws, qe);
   else
-    launch_cfg<64, 64, 1, 1, 64, 2>(A, M, K, b, b2, N, epilogue, residual, C, s, skinny_ws);
+    launch_cfg<64, 64, 1, 1, 64, 2>(A, M, K, b, b2, N, epilogue, residual, C, s, skinny_ws, qe);
 }
 
 }  // namespace keep

@@ -82,6 +82,22 @@ enum GemmEpilogue {
   EPI_STORE_F32 = 0,      // C (fp32) = acc
   EPI_RESIDUAL_STORE = 1, // C (T) = residual (T) + acc
   EPI_SWIGLU_STORE = 2,   // C (T) = silu(acc_gate) * acc_up   (B = gate rows, B2 = up rows)
+  EPI_QKV_ROPE = 3,       // fused QKV projection: bias, RoPE at the row's position, q / compact k written, K and V
+                          // scattered into the cache rows (matrix-core path, 256 x 256 tiles, head_dim 128)
+};
+
+// Where the fused QKV epilogue reads positions and writes its results (device pointers).
+struct QkvEpilogue {
+  const int32_t* row_pos;  // [M] cache row (global position) of each projected row
+  const int32_t* row_lo;   // [M] or NULL: first row of the unit a row belongs to (rotation at pos - row_lo)
+  const float* rope_cos;   // [positions, 64]
+  const float* rope_sin;
+  const void* bias[3];     // q, k, v biases or NULL
+  void* q;                 // [M, q_dim]
+  void* k_compact;         // [M, kv_dim]
+  void* k_cache;           // [N, kv_dim]
+  void* v_cache;
+  int32_t q_dim, kv_dim;
 };
 
 // One B operand made of up to three row blocks stacked along N (Wq | Wk | Wv).
@@ -164,7 +180,12 @@ void launch_score_finish(const float* rowmass, const int32_t* d_row_start, int32
 // most 64 rows, and of the tiles that are cut along K to fill the last round of workgroups.  NULL: neither.
 size_t gemm_ws_bytes();
 void launch_gemm_mfma(const bf16_t* A, int32_t M, int32_t K, const GemmB& B, const void* B2, int32_t N, int epilogue,
-                      const bf16_t* residual, void* C, hipStream_t s, void* skinny_ws = nullptr);
+                      const bf16_t* residual, void* C, hipStream_t s, void* skinny_ws = nullptr,
+                      const QkvEpilogue* qkv = nullptr);
+// true where launch_gemm_mfma would run this QKV projection on 256 x 256 tiles, the configuration that has the
+// fused epilogue (EPI_QKV_ROPE; a wave's 128 columns are one head); elsewhere the caller projects to fp32
+// (EPI_STORE_F32) and runs the RoPE/scatter kernel.
+bool gemm_mfma_fuses_qkv(int32_t M, int32_t K, const GemmB& B, int32_t N, bool have_ws);
 // bf16 expansion of an INT4 matrix: out[rows, K] = bf16((code - zero) * scale)
 void launch_dequant_int4(const void* codes, const void* scale_zero, int32_t rows, int32_t K, void* out, hipStream_t s);
 size_t gemm_skinny_ws_bytes();

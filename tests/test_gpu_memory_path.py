@@ -148,3 +148,31 @@ def test_units_cached_in_one_pass_match_each_unit_alone(shape, tol):
     k1, v1 = unit_cache(ctx, shape, tokens[:40])
     kr, vr, _ = ko.dense_prefill(pb.sh, pb.layers, pb.embed, np.asarray(tokens[:40]))
     assert max_rel(to_np(k1[-1]), kr[-1]) < tol and max_rel(to_np(v1[-1]), vr[-1]) < tol
+
+
+def test_fused_projection_epilogue_with_unit_local_positions():
+    """Enough rows for the 256 x 256 GEMM tiles, whose QKV projection carries bias, RoPE and the K/V scatter in its
+    epilogue (with tiles of the last round cut along K, which take the separate fix-up kernel): several units
+    cached in one pass, so that the rotation uses the unit-local position (cache row minus the unit's first row),
+    two layers, biases on; every unit's blocks against the oracle's dense prefill of that unit alone."""
+    shape = ks.ModelShape(2, 2048, 16, 4, 128, 2048, 311, 1.0e6, 1e-6, "bf16")
+    pb = Problem(shape, [1], 1, seed=5, std=0.03, bias=True)
+    lens = [700, 1024, 513, 64, 900, 1100, 300, 777, 1000, 652]          # 7030 rows: 28 row tiles x 12 column tiles
+    total = sum(lens)
+    ctx = pb.context(max_tokens=total, max_groups=4)
+    assert ctx.uses_mfma
+    rng = np.random.default_rng(17)
+    tokens = [int(t) for t in rng.integers(0, shape.vocab, size=total)]
+    k = torch.full((shape.n_layers, total, shape.n_kv_heads, shape.head_dim), float("nan"), dtype=torch.bfloat16, device="cuda")
+    v = k.clone()
+    ctx.precompute_groups(lens, tokens, k, v)
+    torch.cuda.synchronize()
+    assert not torch.isnan(k).any() and not torch.isnan(v).any()
+    off = 0
+    for n in lens:
+        kr, vr, _ = ko.dense_prefill(pb.sh, pb.layers, pb.embed, np.asarray(tokens[off:off + n]))
+        for l in range(shape.n_layers):
+            ek = max_rel(to_np(k[l, off:off + n]), kr[l])
+            ev = max_rel(to_np(v[l, off:off + n]), vr[l])
+            assert ek < 2e-2 and ev < 2e-2, (n, l, ek, ev)
+        off += n
