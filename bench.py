@@ -467,6 +467,17 @@ def extras(a, torch, ks, kb, main_case, main_ratios, sched):
                 e["bytes_loaded"] = int(sum(rep.bytes_loaded[l] for l in range(w.shape.n_layers)))
             entry[mname] = e
         if oc.host:
+            # where loading, not compute, is the longer leg (half the recompute ratio): the loading modes again
+            import dataclasses
+            low = ks.ratio_schedule(w.ratio / 2, w.shape.n_layers, w.schedule)
+            entry["ratio_%.2f" % (w.ratio / 2)] = {}
+            for mname, lm in (("next_layer", 1), ("layer_balanced", 2)):
+                ms, runs = time_steps(lambda: oc.ctx.prefill(oc.prompt, low, w.hops, oc.k_cache, oc.v_cache, oc.x_final,
+                                                             mode, lm, want_report=True, gate_up_events_only=True),
+                                      steps, warm, torch)
+                rep = runs[-1][1]
+                entry["ratio_%.2f" % (w.ratio / 2)][mname] = dict(
+                    stats(ms), bytes_loaded=int(sum(rep.bytes_loaded[l] for l in range(w.shape.n_layers))))
             # the comparison the section draws: token granularity loads every block and updates in place
             tr = token_schedule(ks, w, w.shape.n_layers, w.schedule)
             ms, runs = time_steps(lambda: oc.ctx.prefill_tokens(oc.prompt, tr, oc.k_cache, oc.v_cache, oc.x_final,

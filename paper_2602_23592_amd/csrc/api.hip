@@ -1417,408 +1417,502 @@ keep_status keep_precompute_groups(keep_ctx* c, int32_t n_units, const int32_t* 
 
 namespace {
 
-// x_final may be NULL (the hidden rows are not wanted).  cache_rows: rows per layer of the caches, 0 = N.
-keep_status prefill_impl(keep_ctx* c, const keep_prompt* p, const float* ratios, int32_t hops, int32_t budget_mode,
-                         int32_t load_mode, void* k_cache, void* v_cache, int32_t cache_rows, void* x_final,
-                         int32_t* sel_groups, int32_t* sel_counts, keep_report* report) {
-  const auto t_begin = std::chrono::steady_clock::now();
-  const keep_model_desc& d = c->d;
-  const int L = d.n_layers;
-  if (!ratios || !k_cache || !v_cache)
-    return fail(c, KEEP_ERR_INVALID_ARG, "ratios / k_cache / v_cache is NULL");
-  if (budget_mode != KEEP_BUDGET_GROUP_COUNT && budget_mode != KEEP_BUDGET_TOKENS)
-    return fail(c, KEEP_ERR_INVALID_ARG, "unknown budget_mode");
-  if (load_mode < KEEP_LOAD_SERIAL || load_mode > KEEP_LOAD_LAYER_BALANCED)
-    return fail(c, KEEP_ERR_INVALID_ARG, "unknown load_mode");
-  if (hops < 1) return fail(c, KEEP_ERR_INVALID_ARG, "hops must be at least 1");
-  if (ratios[0] != 0.f && ratios[0] != 1.f)
-    return fail(c, KEEP_ERR_INVALID_ARG, "ratios[0] must be 1 (recompute all memories at the first layer) or 0");
-  for (int l = 1; l < L; ++l) {
-    if (!(ratios[l] >= 0.f && ratios[l] <= 1.f)) return fail(c, KEEP_ERR_INVALID_ARG, "ratios[%d] outside [0, 1]", l);
-    if (ratios[l] > ratios[l - 1])
-      return fail(c, KEEP_ERR_INVALID_ARG, "ratios must not increase (ratios[%d] > ratios[%d])", l, l - 1);
-  }
+// ---------------------------------------------------------------------------
+// keep_prefill: the per-layer pipeline (Section 5: compute / evaluate / load)
+// ---------------------------------------------------------------------------
+// How one layer is ordered.  Decided in one place, plan_order(), from the next layer's budget alone.
+struct LayerOrder {
+  SelectKind kind = SEL_NONE;  // SEL_DEVICE: the next set needs scores and the selector; otherwise it is all or none
+  int k_count = 0, tok = 0;    // the next layer's budget in memories and in tokens
+  // Output projection + FFN normally run beside the evaluation (Section 4.2).  When the budget says that at most
+  // half of this layer's rows survive into the next set, evaluation goes first and they run on the surviving rows
+  // only: the hidden rows of dropped memories are discarded anyway (Section 4.3).
+  bool eval_first = false;
+  // With many candidates only a few rows of S are ever read: the query's, and those of the memories that enter a
+  // relevant set during the hops (Section 4.2: propagation averages the rows of the current relevant set).  They
+  // are formed hop by hop, as the sets become known; the selector re-runs hops 1..h each time, so the result is
+  // that of one run.  (Worth it only where the budget keeps at most half of the candidates' rows: otherwise
+  // nearly every row is read anyway and the hop-by-hop round trips are pure overhead.)
+  bool lazy_scores = false;
+  // Where both hold, the attention itself is needed only for the rows whose scores are read and for the rows
+  // that survive: it runs for the instruction first and for each hop's new memories after that.
+  bool lazy_attn = false;
+};
+
+struct PrefillRun {
+  keep_ctx* c;
+  const keep_prompt* p;
+  const float* ratios;
+  int hops, budget_mode, load_mode;
+  char *k_cache, *v_cache;
+  void* x_final;
+  int32_t *sel_groups, *sel_counts;
+  keep_report* report;
+
   PromptInfo pi;
-  keep_status st = check_prompt(c, p, &pi, true);
-  if (st != KEEP_OK) return st;
-  c->last_layer = -1;
-  const bool host_kv = p->kv_location == KEEP_KV_PINNED_HOST;
-  const size_t row_bytes = (size_t)d.n_kv_heads * d.head_dim * c->esz;
-  if (cache_rows != 0 && cache_rows < pi.N)
-    return fail(c, KEEP_ERR_INVALID_ARG, "cache_rows %d below the prompt's %d tokens", cache_rows, pi.N);
-  const size_t layer_bytes = (size_t)(cache_rows ? cache_rows : pi.N) * row_bytes;
-  c->ev_light = false;
-  if (report) {
-    c->ev_light = report->events_in == KEEP_REPORT_EVENTS_GATE_UP;
-    const int32_t events_in = report->events_in;
-    memset(report, 0, sizeof *report);
-    report->events_in = events_in;
-    report->n_layers = L;
-    report->used_mfma = c->mfma ? 1 : 0;
-  }
-
-  Loader ld{c, p, &pi, (char*)k_cache, (char*)v_cache, row_bytes, layer_bytes};
-  if (host_kv) {
-    ld.loaded.assign((size_t)L * pi.G, 0);
-    ld.chunk_bytes.assign(c->ev_chunk.size(), 0);
-  }
-
-  st = upload_tokens(c, p, pi);
-  if (st != KEEP_OK) return st;
-
-  std::vector<int32_t> cur;
-  if (ratios[0] == 1.f)
-    for (int g = 0; g < pi.G; ++g) cur.push_back(g);
-  std::vector<int32_t> nxt;
-  void* x_cur = c->xa;   // hidden rows of the current layer (compact)
-  void* x_nxt = c->xb;
+  int L = 0;
+  bool host_kv = false;
+  size_t row_bytes = 0, layer_bytes = 0;
+  Loader ld{};
+  std::vector<int32_t> cur, nxt;  // the relevant set of this layer / of the next
+  void *x_cur = nullptr, *x_nxt = nullptr;  // hidden rows of the current layer (compact) / the other row buffer
   bool x_from_embed = true;
   LayerPlan plan;
-  int preload_layer = 2, preload_group = 0;  // cursor of the layer-balanced pre-loader
-  bool lazy = false;                          // this layer's scores are formed hop by hop
-  std::vector<float> part_attn_ms((size_t)L, 0.f);  // attention launches on parts of a layer
-  std::vector<uint8_t> want, have;
+  std::vector<float> part_attn_ms;  // attention launches on parts of a layer
+  std::vector<uint8_t> want, have;  // source blocks of S wanted now / formed so far (block m = the instruction)
 
-  if (host_kv) {  // what layer 0 needs must be there before it starts
-    st = ld.copy_outside(0, cur);
+  // state of the layer in hand
+  int l = 0;
+  hipEvent_t* evs = nullptr;
+  char *kl = nullptr, *vl = nullptr;
+  LayerOrder ord;
+  int part_launches = 0;  // attention launches on parts of the layer (timed with c->ev_part)
+  long attn_rows = 0;
+  uint64_t attn_keys = 0;
+
+  bool timed() const { return evs && !c->ev_light; }
+
+  LayerOrder plan_order() const {
+    LayerOrder o;
+    if (l + 1 == L) return o;
+    const int m = (int)cur.size();
+    o.kind = classify_budget(pi, p, cur.data(), m, ratios[l + 1], budget_mode, &o.k_count, &o.tok);
+    if (o.kind != SEL_DEVICE) return o;
+    const long mem_rows = plan.n_rows - pi.Lq;
+    const long keep_rows = budget_mode == KEEP_BUDGET_TOKENS ? std::min<long>(o.tok, mem_rows)
+                                                             : mem_rows * o.k_count / std::max(1, m);
+    o.eval_first = (keep_rows + pi.Lq) * 2 <= plan.n_rows;
+    o.lazy_scores = c->mfma && m >= LAZY_MIN_CANDIDATES && hops > 1 && keep_rows * 2 <= mem_rows;
+    o.lazy_attn = o.lazy_scores && o.eval_first;
+    return o;
+  }
+
+  // ---- compute stream: everything up to attention (up to RoPE/scatter where the attention runs on demand)
+  keep_status front() {
+    const void* x_in = x_from_embed ? nullptr : x_cur;
+    return by_dtype(c, [&](auto* tag) {
+      using T = std::remove_pointer_t<decltype(tag)>;
+      return layer_front<T>(c, pi, l, plan, x_in, kl, vl, evs, ord.lazy_attn);
+    });
+  }
+
+  // attention of the rows of the flagged blocks (on-demand layers)
+  keep_status attend(const uint8_t* flags) {
+    int n_att = 0;
+    uint64_t n_keys = 0;
+    const int slot = std::min(part_launches, 7);
+    keep_status st = attend_blocks(c, pi, l, plan, flags, kl, vl, timed() ? c->ev_part[2 * slot] : nullptr,
+                                   timed() ? c->ev_part[2 * slot + 1] : nullptr, &n_att, &n_keys);
+    if (st != KEEP_OK) return st;
+    if (n_att > 0) {
+      attn_rows += n_att;
+      attn_keys += n_keys;
+      if (part_launches < 8) ++part_launches;
+    }
+    return KEEP_OK;
+  }
+
+  keep_status scores(const uint8_t* h_want) {
+    return by_dtype(c, [&](auto* tag) {
+      using T = std::remove_pointer_t<decltype(tag)>;
+      return score_matrix<T>(c, l, plan, c->s_eval, h_want);
+    });
+  }
+
+  // the eval stream follows the compute stream's attention (second dependency of Section 5's pipeline)
+  keep_status eval_after_attention() {
+    HIP_TRY(c, hipEventRecord(c->ev_attn, c->s_comp));
+    HIP_TRY(c, hipStreamWaitEvent(c->s_eval, c->ev_attn, 0));
+    return KEEP_OK;
+  }
+
+  // ---- eval stream: first score pass + selector (all hops, or the first selection where rows come on demand)
+  keep_status start_evaluation() {
+    const int m = (int)cur.size();
+    keep_status st;
+    if (ord.lazy_scores) {
+      want.assign((size_t)m + 1, 0);
+      have.assign((size_t)m + 1, 0);
+      want[m] = have[m] = 1;
+    }
+    if (ord.lazy_attn) {
+      attn_rows = 0;
+      attn_keys = 0;
+      st = attend(want.data());  // the instruction's rows
+      if (st != KEEP_OK) return st;
+    }
+    st = eval_after_attention();
+    if (st != KEEP_OK) return st;
+    if (timed()) HIP_TRY(c, hipEventRecord(evs[10], c->s_eval));
+    if (ord.lazy_scores) HIP_TRY(c, hipMemsetAsync(c->S, 0, (size_t)(m + 1) * m * sizeof(float), c->s_eval));
+    st = scores(ord.lazy_scores ? want.data() : nullptr);
+    if (st != KEEP_OK) return st;
+    st = enqueue_select(c, m, ord.k_count, ord.tok, budget_mode, ord.lazy_scores ? 1 : hops, c->s_eval);
+    if (st != KEEP_OK) return st;
+    if (timed()) HIP_TRY(c, hipEventRecord(evs[11], c->s_eval));
+    HIP_TRY(c, hipEventRecord(c->ev_eval, c->s_eval));
+    return KEEP_OK;
+  }
+
+  // ---- compute stream: output projection + FFN on n_rows rows
+  keep_status back(int n_rows, const void* o_rows, const void* x_in, void* x_out) {
+    keep_status st = by_dtype(c, [&](auto* tag) {
+      using T = std::remove_pointer_t<decltype(tag)>;
+      return layer_back<T>(c, l, n_rows, o_rows, x_in, x_out, evs);
+    });
+    if (st != KEEP_OK) return st;
+    if (report) report->ffn_rows[l] = n_rows;
+    Staging& sg = c->stage[l];
+    HIP_TRY(c, hipEventRecord(sg.done, c->s_comp));
+    sg.used = true;
+    return KEEP_OK;
+  }
+
+  // Layer-balanced loading (Section 4.3): while the host waits for the selection the loader is idle, and the
+  // memories outside the current set can never come back, so their blocks of later layers are pre-loaded,
+  // layer by layer, with a bounded number of bytes in flight so that the copies the next layer is waiting
+  // for never queue behind a long run of pre-loads.
+  keep_status preload_while_waiting() {
+    int preload_layer = l + 2, preload_group = 0;
+    while (hipEventQuery(c->ev_eval) == hipErrorNotReady) {
+      ld.retire();
+      if (preload_layer >= L || ld.inflight >= PRELOAD_INFLIGHT_CAP) continue;
+      bool issued = false;
+      while (preload_layer < L && !issued) {
+        while (preload_group < pi.G && std::binary_search(cur.begin(), cur.end(), preload_group)) ++preload_group;
+        if (preload_group >= pi.G) {
+          ++preload_layer;
+          preload_group = 0;
+          continue;
+        }
+        // the run of groups outside the set that starts at the cursor (at most 8 of them per chunk)
+        int run_end = preload_group + 1;
+        while (run_end < pi.G && run_end < preload_group + 8 && !std::binary_search(cur.begin(), cur.end(), run_end))
+          ++run_end;
+        bool any = false;
+        for (int gg = preload_group; gg < run_end; ++gg) any |= !ld.loaded[(size_t)preload_layer * pi.G + gg];
+        if (any) {
+          keep_status st = ld.copy_run(preload_layer, preload_group, run_end);
+          if (st != KEEP_OK) return st;
+          issued = true;
+        }
+        preload_group = run_end;
+      }
+    }
+    return KEEP_OK;
+  }
+
+  // flags of the selector's current set that have no score row (and no attention) yet; marks them as had
+  bool flag_new_members() {
+    bool any = false;
+    std::fill(want.begin(), want.end(), 0);
+    for (int i = 0; i < c->h_sel_out[0]; ++i) {
+      const int a = c->h_sel_out[2 + i];
+      if (!have[a]) want[a] = have[a] = 1, any = true;
+    }
+    return any;
+  }
+
+  // ---- host: wait for the selection (it sizes the next layer's launches); on-demand layers go round by round
+  keep_status await_selection() {
+    const int m = (int)cur.size();
+    keep_status st;
+    if (host_kv && load_mode == KEEP_LOAD_LAYER_BALANCED) {
+      st = preload_while_waiting();
+      if (st != KEEP_OK) return st;
+    }
+    HIP_TRY(c, hipEventSynchronize(c->ev_eval));
+    if (ord.lazy_scores) {
+      std::vector<int32_t> prev_set;
+      for (int h = 1; h < hops; ++h) {
+        // the set repeated: converged (the selector would stop here as well)
+        std::vector<int32_t> this_set(c->h_sel_out + 2, c->h_sel_out + 2 + c->h_sel_out[0]);
+        if (c->h_sel_out[1] < h || (h > 1 && this_set == prev_set)) break;
+        prev_set.swap(this_set);
+        // rows of the memories selected at hop h that are not there yet
+        if (flag_new_members()) {
+          if (ord.lazy_attn) {  // their attention first: the scores need its log-sum-exp
+            st = attend(want.data());
+            if (st != KEEP_OK) return st;
+            st = eval_after_attention();
+            if (st != KEEP_OK) return st;
+          }
+          st = scores(want.data());
+          if (st != KEEP_OK) return st;
+        }
+        st = enqueue_select(c, m, ord.k_count, ord.tok, budget_mode, h + 1, c->s_eval);
+        if (st != KEEP_OK) return st;
+        if (timed()) HIP_TRY(c, hipEventRecord(evs[11], c->s_eval));
+        HIP_TRY(c, hipStreamSynchronize(c->s_eval));
+      }
+    }
+    nxt.clear();
+    const int nn = c->h_sel_out[0];
+    for (int i = 0; i < nn; ++i) nxt.push_back(cur[c->h_sel_out[2 + i]]);
+    if (report) report->hops_run[l] = c->h_sel_out[1];
+    if (ord.lazy_attn) {
+      // members of the final set that no hop has needed yet: their outputs are needed now
+      if (flag_new_members()) {
+        st = attend(want.data());
+        if (st != KEEP_OK) return st;
+      }
+      if (report) {
+        report->attn_rows[l] = (int32_t)attn_rows;
+        report->attn_keys[l] = attn_keys;
+      }
+      if (timed() && part_launches > 0) {  // the events are reused by later layers: read them now
+        HIP_TRY(c, hipEventSynchronize(c->ev_part[2 * (part_launches - 1) + 1]));
+        for (int i = 0; i < part_launches; ++i) {
+          float ms = 0.f;
+          (void)hipEventElapsedTime(&ms, c->ev_part[2 * i], c->ev_part[2 * i + 1]);
+          part_attn_ms[l] += ms;
+        }
+      }
+    }
+    return KEEP_OK;
+  }
+
+  // ---- copy stream: the groups that just left the set complete layer l+1 (first dependency of the pipeline)
+  keep_status finish_loading(uint64_t bytes_before) {
+    if (load_mode == KEEP_LOAD_SERIAL) {  // load strictly after this layer's compute
+      HIP_TRY(c, hipEventRecord(c->ev_comp, c->s_comp));
+      HIP_TRY(c, hipStreamWaitEvent(c->s_copy, c->ev_comp, 0));
+    }
+    keep_status st = ld.copy_outside(l + 1, nxt);
     if (st != KEEP_OK) return st;
     HIP_TRY(c, hipEventRecord(c->ev_load, c->s_copy));
     HIP_TRY(c, hipStreamWaitEvent(c->s_comp, c->ev_load, 0));
-    if (report) report->bytes_loaded[0] = ld.bytes_total;
+    if (report) report->bytes_loaded[l + 1] = ld.bytes_total - bytes_before;
+    return KEEP_OK;
   }
 
-  for (int l = 0; l < L; ++l) {
-    hipEvent_t* evs = report ? &c->ev[(size_t)l * EV_PER_LAYER] : nullptr;
-    char* kl = (char*)k_cache + (size_t)l * layer_bytes;
-    char* vl = (char*)v_cache + (size_t)l * layer_bytes;
+  // ---- hidden rows of the next set; where evaluation went first this is also where this layer's output
+  // projection + FFN run (on the survivors)
+  keep_status next_rows() {
+    const keep_model_desc& d = c->d;
+    const int m = (int)cur.size();
+    keep_status st;
+    if (nxt.size() == cur.size()) {  // same rows: this layer's output is the next layer's input
+      if (ord.eval_first) {
+        st = back(plan.n_rows, c->o, x_cur, x_nxt);
+        if (st != KEEP_OK) return st;
+      }
+      std::swap(x_cur, x_nxt);
+      return KEEP_OK;
+    }
+    // compact start of each kept block in the current layout and in the next one
+    Staging& sg = c->stage[l];
+    std::vector<int32_t> dst_start(nxt.size() + 2);
+    int acc = 0;
+    size_t ci = 0;
+    for (size_t i = 0; i < nxt.size(); ++i) {
+      while (cur[ci] != nxt[i]) ++ci;
+      sg.gather_src[i] = plan.row_start[ci];
+      dst_start[i] = acc;
+      acc += p->group_len[nxt[i]];
+    }
+    sg.gather_src[nxt.size()] = plan.row_start[m];
+    dst_start[nxt.size()] = acc;
+    acc += pi.Lq;
+    dst_start[nxt.size() + 1] = acc;
+    // (the destination starts are the next layer's row_start; nothing still reads the old one)
+    memcpy(sg.gather_dst, dst_start.data(), dst_start.size() * 4);
+    HIP_TRY(c, hipMemcpyAsync(c->d_gather_src, sg.gather_src, (nxt.size() + 1) * 4, hipMemcpyHostToDevice, c->s_comp));
+    HIP_TRY(c, hipMemcpyAsync(c->d_row_start, sg.gather_dst, dst_start.size() * 4, hipMemcpyHostToDevice, c->s_comp));
+    const int n_blocks = (int)nxt.size() + 1;
+    if (!ord.eval_first) {
+      void* x_out_buf = x_nxt;  // this layer's output
+      void* x_dst = x_cur;      // this layer's input buffer is free once the layer is done
+      st = by_dtype(c, [&](auto* tag) {
+        using T = std::remove_pointer_t<decltype(tag)>;
+        launch_rows_gather<T>(Typed<T>::p(x_out_buf), c->d_gather_src, c->d_row_start, n_blocks, acc, d.hidden,
+                              Typed<T>::p(x_dst), c->s_comp);
+        return KEEP_OK;
+      });
+      HIP_TRY(c, hipGetLastError());
+      HIP_TRY(c, hipEventRecord(sg.done, c->s_comp));
+      x_cur = x_dst;
+      return KEEP_OK;
+    }
+    // survivors first: gather their attention rows (into the q buffer, free now that the scores are done) and
+    // their input rows, then output projection + FFN on them alone
+    const int qd = d.n_q_heads * d.head_dim;
+    st = by_dtype(c, [&](auto* tag) {
+      using T = std::remove_pointer_t<decltype(tag)>;
+      launch_rows_gather<T>(Typed<T>::p(c->o), c->d_gather_src, c->d_row_start, n_blocks, acc, qd, Typed<T>::p(c->q),
+                            c->s_comp);
+      launch_rows_gather<T>(Typed<T>::p(x_cur), c->d_gather_src, c->d_row_start, n_blocks, acc, d.hidden,
+                            Typed<T>::p(x_nxt), c->s_comp);
+      return KEEP_OK;
+    });
+    HIP_TRY(c, hipGetLastError());
+    return back(acc, c->q, x_nxt, x_cur);  // output lands in x_cur, already in the next layout
+  }
+
+  void read_event_times() {
+    for (int ll = 0; ll < L; ++ll) {
+      hipEvent_t* e = &c->ev[(size_t)ll * EV_PER_LAYER];
+      (void)hipEventElapsedTime(&report->ms_gateup[ll], e[7], e[8]);
+      if (c->ev_light) continue;
+      (void)hipEventElapsedTime(&report->ms_realign[ll], e[0], e[1]);
+      (void)hipEventElapsedTime(&report->ms_prep[ll], e[1], e[2]);
+      (void)hipEventElapsedTime(&report->ms_qkv_gemm[ll], e[2], e[3]);
+      (void)hipEventElapsedTime(&report->ms_rope[ll], e[3], e[4]);
+      (void)hipEventElapsedTime(&report->ms_attn[ll], e[4], e[5]);
+      report->ms_attn[ll] += part_attn_ms[ll];
+      (void)hipEventElapsedTime(&report->ms_oproj[ll], e[12], e[6]);
+      (void)hipEventElapsedTime(&report->ms_norm2[ll], e[6], e[7]);
+      (void)hipEventElapsedTime(&report->ms_down[ll], e[8], e[9]);
+      if (report->hops_run[ll] > 0) (void)hipEventElapsedTime(&report->ms_score[ll], e[10], e[11]);
+    }
+  }
+
+  keep_status one_layer() {
+    evs = report ? &c->ev[(size_t)l * EV_PER_LAYER] : nullptr;
+    kl = k_cache + (size_t)l * layer_bytes;
+    vl = v_cache + (size_t)l * layer_bytes;
     const int m = (int)cur.size();
     if (sel_counts) sel_counts[l] = m;
     if (sel_groups)
       for (int i = 0; i < m; ++i) sel_groups[(size_t)l * pi.G + i] = cur[i];
-    st = stage_layer(c, p, pi, l, cur.data(), m, kl, vl, host_kv, &plan);
+    keep_status st = stage_layer(c, p, pi, l, cur.data(), m, kl, vl, host_kv, &plan);
     if (st != KEEP_OK) return st;
     if (report) {
       report->rows[l] = plan.n_rows;
       report->set_size[l] = m;
       report->realign_rows[l] = plan.n_realign_rows;
     }
-    const bool last = l + 1 == L;
-    lazy = false;
-    const void* x_in = x_from_embed ? nullptr : x_cur;
-    // ---- what the budget of the next layer implies for this one
-    int k_count = 0, tok = 0;
-    SelectKind kind = SEL_NONE;
-    // Output projection + FFN normally run beside the evaluation (Section 4.2).  When the budget says that at
-    // most half of this layer's rows survive into the next set, evaluation goes first and they run on the
-    // surviving rows only: the hidden rows of dropped memories are discarded anyway (Section 4.3).
-    bool eval_first = false;
-    // With many candidates only a few rows of S are ever read: the query's, and those of the memories that
-    // enter a relevant set during the hops (Section 4.2: propagation averages the rows of the current
-    // relevant set).  They are computed hop by hop, as the sets become known; the other rows are never
-    // formed.  The selector re-runs hops 1..h each time, so the result is that of one run.  (Worth it only
-    // where the budget keeps at most half of the candidates' rows: otherwise nearly every row is read anyway
-    // and the hop-by-hop round trips are pure overhead.)
-    // Where both hold, the attention itself is needed only for the rows whose scores are read and for the
-    // rows that survive: it is run for the instruction first and for each hop's new memories after that.
-    bool lazy_attn = false;
-    if (!last) {
-      kind = classify_budget(pi, p, cur.data(), m, ratios[l + 1], budget_mode, &k_count, &tok);
-      if (kind == SEL_DEVICE) {
-        const long mem_rows = plan.n_rows - pi.Lq;
-        const long keep_rows = budget_mode == KEEP_BUDGET_TOKENS ? std::min<long>(tok, mem_rows)
-                                                                 : mem_rows * k_count / std::max(1, m);
-        eval_first = (keep_rows + pi.Lq) * 2 <= plan.n_rows;
-        lazy = c->mfma && m >= LAZY_MIN_CANDIDATES && hops > 1 && keep_rows * 2 <= mem_rows;
-        lazy_attn = lazy && eval_first;
-      }
-    }
-    int part_launches = 0;  // attention launches on parts of the layer (timed with c->ev_part)
-    long attn_rows = plan.n_rows;
-    uint64_t attn_keys = (uint64_t)((int64_t)pi.Lq * (2 * (int64_t)pi.n_mem + pi.Lq + 1) / 2);
+    ord = plan_order();
+    part_launches = 0;
+    attn_rows = plan.n_rows;
+    attn_keys = (uint64_t)((int64_t)pi.Lq * (2 * (int64_t)pi.n_mem + pi.Lq + 1) / 2);
     for (int i = 0; i < m; ++i) {
       const int64_t first = pi.off[cur[i]], len = p->group_len[cur[i]];
       attn_keys += (uint64_t)(len * (2 * first + len + 1) / 2);
     }
-    // ---- compute stream: everything up to attention
-    st = by_dtype(c, [&](auto* tag) {
-      using T = std::remove_pointer_t<decltype(tag)>;
-      return layer_front<T>(c, pi, l, plan, x_in, kl, vl, evs, lazy_attn);
-    });
+    st = front();
     if (st != KEEP_OK) return st;
-    auto attend = [&](const uint8_t* flags) -> keep_status {
-      int n_att = 0;
-      uint64_t n_keys = 0;
-      const int slot = std::min(part_launches, 7);
-      keep_status s2 = attend_blocks(c, pi, l, plan, flags, kl, vl, (evs && !c->ev_light) ? c->ev_part[2 * slot] : nullptr,
-                                     (evs && !c->ev_light) ? c->ev_part[2 * slot + 1] : nullptr, &n_att, &n_keys);
-      if (s2 != KEEP_OK) return s2;
-      if (n_att > 0) {
-        attn_rows += n_att;
-        attn_keys += n_keys;
-        if (part_launches < 8) ++part_launches;
-      }
-      return KEEP_OK;
-    };
-    // ---- eval stream: scores + selection
-    if (kind == SEL_DEVICE) {
-      if (lazy) {
-        want.assign((size_t)m + 1, 0);
-        have.assign((size_t)m + 1, 0);
-        want[m] = have[m] = 1;
-      }
-      if (lazy_attn) {
-        attn_rows = 0;
-        attn_keys = 0;
-        st = attend(want.data());  // the instruction's rows
-        if (st != KEEP_OK) return st;
-      }
-      HIP_TRY(c, hipEventRecord(c->ev_attn, c->s_comp));
-      HIP_TRY(c, hipStreamWaitEvent(c->s_eval, c->ev_attn, 0));
-      if (evs && !c->ev_light) HIP_TRY(c, hipEventRecord(evs[10], c->s_eval));
-      if (lazy) HIP_TRY(c, hipMemsetAsync(c->S, 0, (size_t)(m + 1) * m * sizeof(float), c->s_eval));
-      st = by_dtype(c, [&](auto* tag) {
-        using T = std::remove_pointer_t<decltype(tag)>;
-        return score_matrix<T>(c, l, plan, c->s_eval, lazy ? want.data() : nullptr);
-      });
-      if (st != KEEP_OK) return st;
-      st = enqueue_select(c, m, k_count, tok, budget_mode, lazy ? 1 : hops, c->s_eval);
-      if (st != KEEP_OK) return st;
-      if (evs && !c->ev_light) HIP_TRY(c, hipEventRecord(evs[11], c->s_eval));
-      HIP_TRY(c, hipEventRecord(c->ev_eval, c->s_eval));
-    }
-    auto finish_layer = [&](int n_rows_back, const void* o_rows, const void* x_in_back, void* x_out_back) {
-      keep_status s2 = by_dtype(c, [&](auto* tag) {
-        using T = std::remove_pointer_t<decltype(tag)>;
-        return layer_back<T>(c, l, n_rows_back, o_rows, x_in_back, x_out_back, evs);
-      });
-      if (s2 != KEEP_OK) return s2;
-      if (report) report->ffn_rows[l] = n_rows_back;
-      Staging& sg = c->stage[l];
-      HIP_TRY(c, hipEventRecord(sg.done, c->s_comp));
-      sg.used = true;
-      return KEEP_OK;
-    };
-    if (!eval_first) {
-      st = finish_layer(plan.n_rows, c->o, x_cur, x_nxt);
+    if (ord.kind == SEL_DEVICE) {
+      st = start_evaluation();
       if (st != KEEP_OK) return st;
     }
-    if (report && !lazy_attn) {
+    if (!ord.eval_first) {  // output projection + FFN beside the evaluation
+      st = back(plan.n_rows, c->o, x_cur, x_nxt);
+      if (st != KEEP_OK) return st;
+    }
+    if (report && !ord.lazy_attn) {
       report->attn_rows[l] = (int32_t)attn_rows;
       report->attn_keys[l] = attn_keys;
     }
-    if (last) break;
+    if (l + 1 == L) return KEEP_OK;
 
-    // ---- loading for the layers ahead, while this layer computes
+    // loading for the layers ahead, while this layer computes: groups outside the current set can never come
+    // back, so their blocks of layer l+1 are needed for sure
     const uint64_t bytes_before = ld.bytes_total;
     if (host_kv && load_mode != KEEP_LOAD_SERIAL) {
-      // groups outside the current set can never come back: their blocks of layer l+1 are needed for sure
       st = ld.copy_outside(l + 1, cur);
       if (st != KEEP_OK) return st;
     }
-    // ---- wait for the selection (host needs the set to size the next layer's launches)
-    if (kind == SEL_DEVICE) {
-      if (host_kv && load_mode == KEEP_LOAD_LAYER_BALANCED) {
-        // idle loader: pre-load later layers for the groups that are out for good
-        preload_layer = l + 2;
-        preload_group = 0;
-        while (hipEventQuery(c->ev_eval) == hipErrorNotReady) {
-          ld.retire();
-          if (preload_layer >= L || ld.inflight >= PRELOAD_INFLIGHT_CAP) continue;
-          // next group outside `cur` at the cursor
-          bool issued = false;
-          while (preload_layer < L && !issued) {
-            while (preload_group < pi.G && std::binary_search(cur.begin(), cur.end(), preload_group)) ++preload_group;
-            if (preload_group >= pi.G) {
-              ++preload_layer;
-              preload_group = 0;
-              continue;
-            }
-            // the run of groups outside the set that starts at the cursor (at most 8 of them per chunk)
-            int run_end = preload_group + 1;
-            while (run_end < pi.G && run_end < preload_group + 8 &&
-                   !std::binary_search(cur.begin(), cur.end(), run_end))
-              ++run_end;
-            bool any = false;
-            for (int gg = preload_group; gg < run_end; ++gg) any |= !ld.loaded[(size_t)preload_layer * pi.G + gg];
-            if (any) {
-              st = ld.copy_run(preload_layer, preload_group, run_end);
-              if (st != KEEP_OK) return st;
-              issued = true;
-            }
-            preload_group = run_end;
-          }
-        }
-      }
-      HIP_TRY(c, hipEventSynchronize(c->ev_eval));
-      if (lazy) {
-        std::vector<int32_t> prev_set;
-        for (int h = 1; h < hops; ++h) {
-          // the set repeated: converged (the selector would stop here as well)
-          std::vector<int32_t> this_set(c->h_sel_out + 2, c->h_sel_out + 2 + c->h_sel_out[0]);
-          if (c->h_sel_out[1] < h || (h > 1 && this_set == prev_set)) break;
-          prev_set.swap(this_set);
-          // rows of the memories selected at hop h that are not there yet
-          bool any = false;
-          std::fill(want.begin(), want.end(), 0);
-          for (int i = 0; i < c->h_sel_out[0]; ++i) {
-            const int a = c->h_sel_out[2 + i];
-            if (!have[a]) want[a] = have[a] = 1, any = true;
-          }
-          if (any) {
-            if (lazy_attn) {  // their attention first: the scores need its log-sum-exp
-              st = attend(want.data());
-              if (st != KEEP_OK) return st;
-              HIP_TRY(c, hipEventRecord(c->ev_attn, c->s_comp));
-              HIP_TRY(c, hipStreamWaitEvent(c->s_eval, c->ev_attn, 0));
-            }
-            st = by_dtype(c, [&](auto* tag) {
-              using T = std::remove_pointer_t<decltype(tag)>;
-              return score_matrix<T>(c, l, plan, c->s_eval, want.data());
-            });
-            if (st != KEEP_OK) return st;
-          }
-          st = enqueue_select(c, m, k_count, tok, budget_mode, h + 1, c->s_eval);
-          if (st != KEEP_OK) return st;
-          if (evs && !c->ev_light) HIP_TRY(c, hipEventRecord(evs[11], c->s_eval));
-          HIP_TRY(c, hipStreamSynchronize(c->s_eval));
-        }
-      }
-      nxt.clear();
-      const int nn = c->h_sel_out[0];
-      for (int i = 0; i < nn; ++i) nxt.push_back(cur[c->h_sel_out[2 + i]]);
-      if (report) report->hops_run[l] = c->h_sel_out[1];
-      if (lazy_attn) {  // members of the final set that no hop has needed yet: their outputs are needed now
-        bool any = false;
-        std::fill(want.begin(), want.end(), 0);
-        for (int i = 0; i < nn; ++i) {
-          const int a = c->h_sel_out[2 + i];
-          if (!have[a]) want[a] = have[a] = 1, any = true;
-        }
-        if (any) {
-          st = attend(want.data());
-          if (st != KEEP_OK) return st;
-        }
-        if (report) {
-          report->attn_rows[l] = (int32_t)attn_rows;
-          report->attn_keys[l] = attn_keys;
-        }
-        if (report && !c->ev_light && part_launches > 0) {  // the events are reused by later layers: read them now
-          HIP_TRY(c, hipEventSynchronize(c->ev_part[2 * (part_launches - 1) + 1]));
-          for (int i = 0; i < part_launches; ++i) {
-            float ms = 0.f;
-            (void)hipEventElapsedTime(&ms, c->ev_part[2 * i], c->ev_part[2 * i + 1]);
-            part_attn_ms[l] += ms;
-          }
-        }
-      }
-    } else if (kind == SEL_ALL) {
+    if (ord.kind == SEL_DEVICE) {
+      st = await_selection();
+      if (st != KEEP_OK) return st;
+    } else if (ord.kind == SEL_ALL) {
       nxt = cur;
     } else {
       nxt.clear();
     }
-    // ---- finish loading layer l+1: the groups that just left the set
     if (host_kv) {
-      if (load_mode == KEEP_LOAD_SERIAL) {
-        // load strictly after this layer's compute
-        HIP_TRY(c, hipEventRecord(c->ev_comp, c->s_comp));
-        HIP_TRY(c, hipStreamWaitEvent(c->s_copy, c->ev_comp, 0));
-      }
-      st = ld.copy_outside(l + 1, nxt);
+      st = finish_loading(bytes_before);
+      if (st != KEEP_OK) return st;
+    }
+    st = next_rows();
+    if (st != KEEP_OK) return st;
+    x_from_embed = false;
+    cur.swap(nxt);
+    return KEEP_OK;
+  }
+
+  keep_status run(int32_t cache_rows) {
+    const auto t_begin = std::chrono::steady_clock::now();
+    const keep_model_desc& d = c->d;
+    L = d.n_layers;
+    if (!ratios || !k_cache || !v_cache) return fail(c, KEEP_ERR_INVALID_ARG, "ratios / k_cache / v_cache is NULL");
+    if (budget_mode != KEEP_BUDGET_GROUP_COUNT && budget_mode != KEEP_BUDGET_TOKENS)
+      return fail(c, KEEP_ERR_INVALID_ARG, "unknown budget_mode");
+    if (load_mode < KEEP_LOAD_SERIAL || load_mode > KEEP_LOAD_LAYER_BALANCED)
+      return fail(c, KEEP_ERR_INVALID_ARG, "unknown load_mode");
+    if (hops < 1) return fail(c, KEEP_ERR_INVALID_ARG, "hops must be at least 1");
+    if (ratios[0] != 0.f && ratios[0] != 1.f)
+      return fail(c, KEEP_ERR_INVALID_ARG, "ratios[0] must be 1 (recompute all memories at the first layer) or 0");
+    for (int i = 1; i < L; ++i) {
+      if (!(ratios[i] >= 0.f && ratios[i] <= 1.f)) return fail(c, KEEP_ERR_INVALID_ARG, "ratios[%d] outside [0, 1]", i);
+      if (ratios[i] > ratios[i - 1])
+        return fail(c, KEEP_ERR_INVALID_ARG, "ratios must not increase (ratios[%d] > ratios[%d])", i, i - 1);
+    }
+    keep_status st = check_prompt(c, p, &pi, true);
+    if (st != KEEP_OK) return st;
+    c->last_layer = -1;
+    host_kv = p->kv_location == KEEP_KV_PINNED_HOST;
+    row_bytes = (size_t)d.n_kv_heads * d.head_dim * c->esz;
+    if (cache_rows != 0 && cache_rows < pi.N)
+      return fail(c, KEEP_ERR_INVALID_ARG, "cache_rows %d below the prompt's %d tokens", cache_rows, pi.N);
+    layer_bytes = (size_t)(cache_rows ? cache_rows : pi.N) * row_bytes;
+    c->ev_light = false;
+    if (report) {
+      c->ev_light = report->events_in == KEEP_REPORT_EVENTS_GATE_UP;
+      const int32_t events_in = report->events_in;
+      memset(report, 0, sizeof *report);
+      report->events_in = events_in;
+      report->n_layers = L;
+      report->used_mfma = c->mfma ? 1 : 0;
+    }
+    ld = Loader{c, p, &pi, k_cache, v_cache, row_bytes, layer_bytes};
+    if (host_kv) {
+      ld.loaded.assign((size_t)L * pi.G, 0);
+      ld.chunk_bytes.assign(c->ev_chunk.size(), 0);
+    }
+    st = upload_tokens(c, p, pi);
+    if (st != KEEP_OK) return st;
+    if (ratios[0] == 1.f)
+      for (int g = 0; g < pi.G; ++g) cur.push_back(g);
+    x_cur = c->xa;
+    x_nxt = c->xb;
+    part_attn_ms.assign((size_t)L, 0.f);
+    if (host_kv) {  // what layer 0 needs must be there before it starts
+      st = ld.copy_outside(0, cur);
       if (st != KEEP_OK) return st;
       HIP_TRY(c, hipEventRecord(c->ev_load, c->s_copy));
       HIP_TRY(c, hipStreamWaitEvent(c->s_comp, c->ev_load, 0));
-      if (report) report->bytes_loaded[l + 1] = ld.bytes_total - bytes_before;
+      if (report) report->bytes_loaded[0] = ld.bytes_total;
     }
-    // ---- hidden rows of the next set
-    if (!eval_first && nxt.size() == cur.size()) {
-      std::swap(x_cur, x_nxt);  // same rows: this layer's output is the next layer's input
-      x_from_embed = false;
-    } else if (eval_first && nxt.size() == cur.size()) {
-      st = finish_layer(plan.n_rows, c->o, x_cur, x_nxt);
+    for (l = 0; l < L; ++l) {
+      st = one_layer();
       if (st != KEEP_OK) return st;
-      std::swap(x_cur, x_nxt);
-      x_from_embed = false;
-    } else {
-      // compact start of each kept block in the current layout and in the next one
-      Staging& sg = c->stage[l];
-      std::vector<int32_t> dst_start(nxt.size() + 2);
-      int acc = 0;
-      size_t ci = 0;
-      for (size_t i = 0; i < nxt.size(); ++i) {
-        while (cur[ci] != nxt[i]) ++ci;
-        sg.gather_src[i] = plan.row_start[ci];
-        dst_start[i] = acc;
-        acc += p->group_len[nxt[i]];
-      }
-      sg.gather_src[nxt.size()] = plan.row_start[m];
-      dst_start[nxt.size()] = acc;
-      acc += pi.Lq;
-      dst_start[nxt.size() + 1] = acc;
-      // (the destination starts are the next layer's row_start; nothing still reads the old one)
-      memcpy(sg.gather_dst, dst_start.data(), dst_start.size() * 4);
-      HIP_TRY(c, hipMemcpyAsync(c->d_gather_src, sg.gather_src, (nxt.size() + 1) * 4, hipMemcpyHostToDevice, c->s_comp));
-      HIP_TRY(c, hipMemcpyAsync(c->d_row_start, sg.gather_dst, dst_start.size() * 4, hipMemcpyHostToDevice, c->s_comp));
-      const int n_blocks = (int)nxt.size() + 1;
-      if (!eval_first) {
-        void* x_out_buf = x_nxt;  // this layer's output
-        void* x_dst = x_cur;      // this layer's input buffer is free once the layer is done
-        st = by_dtype(c, [&](auto* tag) {
-          using T = std::remove_pointer_t<decltype(tag)>;
-          launch_rows_gather<T>(Typed<T>::p(x_out_buf), c->d_gather_src, c->d_row_start, n_blocks, acc, d.hidden,
-                                Typed<T>::p(x_dst), c->s_comp);
-          return KEEP_OK;
-        });
-        HIP_TRY(c, hipGetLastError());
-        HIP_TRY(c, hipEventRecord(sg.done, c->s_comp));
-        x_cur = x_dst;
-      } else {
-        // survivors first: gather their attention rows (into the q buffer, free now that the scores are
-        // done) and their input rows, then output projection + FFN on them alone
-        const int qd = d.n_q_heads * d.head_dim;
-        st = by_dtype(c, [&](auto* tag) {
-          using T = std::remove_pointer_t<decltype(tag)>;
-          launch_rows_gather<T>(Typed<T>::p(c->o), c->d_gather_src, c->d_row_start, n_blocks, acc, qd,
-                                Typed<T>::p(c->q), c->s_comp);
-          launch_rows_gather<T>(Typed<T>::p(x_cur), c->d_gather_src, c->d_row_start, n_blocks, acc, d.hidden,
-                                Typed<T>::p(x_nxt), c->s_comp);
-          return KEEP_OK;
-        });
-        HIP_TRY(c, hipGetLastError());
-        st = finish_layer(acc, c->q, x_nxt, x_cur);  // output lands in x_cur, already in the next layout
-        if (st != KEEP_OK) return st;
-      }
-      x_from_embed = false;
     }
-    cur.swap(nxt);
-  }
-  // final hidden rows of the instruction
-  if (x_final) {
-    const char* src = (const char*)x_nxt + (size_t)(plan.n_rows - pi.Lq) * d.hidden * c->esz;
-    HIP_TRY(c, hipMemcpyAsync(x_final, src, (size_t)pi.Lq * d.hidden * c->esz, hipMemcpyDeviceToDevice, c->s_comp));
-  }
-  HIP_TRY(c, hipStreamSynchronize(c->s_copy));
-  HIP_TRY(c, hipStreamSynchronize(c->s_eval));
-  HIP_TRY(c, hipStreamSynchronize(c->s_comp));
-  if (report) {
-    report->ms_total = std::chrono::duration<float, std::milli>(std::chrono::steady_clock::now() - t_begin).count();
-    for (int l = 0; l < L; ++l) {
-      hipEvent_t* e = &c->ev[(size_t)l * EV_PER_LAYER];
-      (void)hipEventElapsedTime(&report->ms_gateup[l], e[7], e[8]);
-      if (c->ev_light) continue;
-      (void)hipEventElapsedTime(&report->ms_realign[l], e[0], e[1]);
-      (void)hipEventElapsedTime(&report->ms_prep[l], e[1], e[2]);
-      (void)hipEventElapsedTime(&report->ms_qkv_gemm[l], e[2], e[3]);
-      (void)hipEventElapsedTime(&report->ms_rope[l], e[3], e[4]);
-      (void)hipEventElapsedTime(&report->ms_attn[l], e[4], e[5]);
-      report->ms_attn[l] += part_attn_ms[l];
-      (void)hipEventElapsedTime(&report->ms_oproj[l], e[12], e[6]);
-      (void)hipEventElapsedTime(&report->ms_norm2[l], e[6], e[7]);
-      (void)hipEventElapsedTime(&report->ms_down[l], e[8], e[9]);
-      if (report->hops_run[l] > 0) (void)hipEventElapsedTime(&report->ms_score[l], e[10], e[11]);
+    if (x_final) {  // final hidden rows of the instruction
+      const char* src = (const char*)x_nxt + (size_t)(plan.n_rows - pi.Lq) * d.hidden * c->esz;
+      HIP_TRY(c, hipMemcpyAsync(x_final, src, (size_t)pi.Lq * d.hidden * c->esz, hipMemcpyDeviceToDevice, c->s_comp));
     }
+    HIP_TRY(c, hipStreamSynchronize(c->s_copy));
+    HIP_TRY(c, hipStreamSynchronize(c->s_eval));
+    HIP_TRY(c, hipStreamSynchronize(c->s_comp));
+    if (report) {
+      report->ms_total = std::chrono::duration<float, std::milli>(std::chrono::steady_clock::now() - t_begin).count();
+      read_event_times();
+    }
+    return KEEP_OK;
   }
-  return KEEP_OK;
+};
+
+// x_final may be NULL (the hidden rows are not wanted).  cache_rows: rows per layer of the caches, 0 = N.
+keep_status prefill_impl(keep_ctx* c, const keep_prompt* p, const float* ratios, int32_t hops, int32_t budget_mode,
+                         int32_t load_mode, void* k_cache, void* v_cache, int32_t cache_rows, void* x_final,
+                         int32_t* sel_groups, int32_t* sel_counts, keep_report* report) {
+  PrefillRun run{c, p, ratios, hops, budget_mode, load_mode, (char*)k_cache, (char*)v_cache, x_final, sel_groups,
+                 sel_counts, report};
+  return run.run(cache_rows);
 }
+
 
 // Token-granularity prefill (the comparison scheme of Section 3 and Section 4.2, "System advantage"): the rows of
 // a layer are single tokens; every cached block is loaded and re-aligned, the recomputed tokens' K/V are written
