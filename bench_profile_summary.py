@@ -2,7 +2,7 @@
 
     python bench_profile_summary.py stats   <rocprofv3 output dir> <bench stdout log> <out.md> "<command>"
     python bench_profile_summary.py traffic <FETCH_SIZE output dir> <WRITE_SIZE output dir> <out.md> <out.json> "<command>"
-    python bench_profile_summary.py counters <output dir> [<output dir> ...] <out.md> "<command>" [kernel name part]
+    python bench_profile_summary.py counters <out.md> "<command>" <kernel name parts, comma separated, or -> <output dir> ...
 
 `stats` lists the per-kernel rows of a `--kernel-trace --stats` run beside bench.py's own line.  `traffic` sums
 FETCH_SIZE / WRITE_SIZE per kernel, scales them by what the same counters read for the known-size calibration
@@ -23,11 +23,23 @@ def _short(name):
     return name[:name.index("(")] if "(" in name else name
 
 
-def _counter_rows(d):
+def _counter_rows(d, after_calibration=True):
+    """Rows of the counter CSV.  With after_calibration, only the dispatches that follow bench.py's calibration copy
+    (--calib-copy-mib: the longest-running device-to-device copy), i.e. without the set-up launches (weights,
+    group caches), but including that copy itself; the profiler cannot be paused in a --pmc run."""
     f = glob.glob(os.path.join(d, "**", "*counter_collection.csv"), recursive=True)
     if not f:
         raise SystemExit("no counter_collection.csv under " + d)
-    return list(csv.DictReader(open(f[0])))
+    rows = list(csv.DictReader(open(f[0])))
+    if after_calibration:
+        copies = [r for r in rows if "copyBuffer" in r["Kernel_Name"]]
+        if copies:
+            dur = lambda r: int(r["End_Timestamp"]) - int(r["Start_Timestamp"])
+            mark = max(copies, key=dur)
+            if dur(mark) >= 50000:      # ns: a copy of hundreds of MiB, not a table upload
+                first = int(mark["Dispatch_Id"])
+                rows = [r for r in rows if int(r["Dispatch_Id"]) >= first]
+    return rows
 
 
 def _per_kernel(rows):
@@ -66,7 +78,10 @@ def stats(argv):
             bench["ms_per_step"], bench.get("ttft_ms_median", 0), bench.get("ttft_ms_min", 0), bench["value"],
             bench["roofline"]["avg_launch_ms"], bench["roofline"]["achieved"], bench["roofline"]["frac"]))
         for k, v in bench["kernels"].items():
-            o.write("    %-24s %8.2f ms/step  %9.2f %s  (%.3f of peak)\n" % (k, v["ms_per_step"], v["achieved"], v["unit"], v["frac"]))
+            if "achieved" in v:
+                o.write("    %-24s %8.2f ms/step  %9.2f %s  (%.3f of peak)\n" % (k, v["ms_per_step"], v["achieved"], v["unit"], v["frac"]))
+            else:
+                o.write("    %-24s %s\n" % (k, json.dumps(v)))
 
 
 def traffic(argv):
@@ -113,23 +128,35 @@ def traffic(argv):
 
 
 def counters(argv):
-    *dirs, out_md, cmd = argv[:-1] if len(argv) > 2 and not os.path.isdir(argv[-1]) and not argv[-1].endswith(".md") and " " not in argv[-1] else argv
-    part = argv[-1] if len(argv) > 2 and " " not in argv[-1] and not argv[-1].endswith(".md") and not os.path.isdir(argv[-1]) else ""
+    out_md, cmd, part = argv[0], argv[1], argv[2]
+    dirs = argv[3:]
+    want = [w for w in part.split(",") if w and w != "-"]
     with open(out_md, "w") as o:
         o.write("# rocprofv3 --pmc counters per kernel (one MI355X)\n\nCommand (from /tmp with TMPDIR=/tmp on the GPU box; "
-                "one run per counter set):\n\n    %s\n\nValues are sums over all dispatches of the kernel in the run "
-                "(and over the chip's counter instances).\n\n" % cmd)
+                "one run per counter set, COUNTERS = the names listed under each kernel):\n\n    %s\n\nValues are sums over all "
+                "dispatches of the kernel in the run and over the chip's counter instances (SQ counters: all CUs).\n\n" % cmd)
+        merged = collections.defaultdict(dict)
         for d in dirs:
             pk = _per_kernel(_counter_rows(d))
-            kernels = sorted({k for c in pk.values() for k in c})
-            for k in kernels:
-                if part and part not in k:
-                    continue
-                o.write("`%s`\n\n" % k[:90])
-                for c in sorted(pk):
-                    if k in pk[c]:
-                        o.write("    %-34s calls %5d  total %.6g\n" % (c, pk[c][k][0], pk[c][k][1]))
-                o.write("\n")
+            for c, per in pk.items():
+                for k, v in per.items():
+                    merged[k][c] = v
+        for k in sorted(merged, key=lambda k: -max(v[1] for v in merged[k].values())):
+            if want and not any(w in k for w in want):
+                continue
+            o.write("`%s`\n\n" % k[:100])
+            for c in sorted(merged[k]):
+                o.write("    %-34s calls %5d  total %.6g\n" % (c, merged[k][c][0], merged[k][c][1]))
+            cs = merged[k]
+            if "SQ_VALU_MFMA_BUSY_CYCLES" in cs and "SQ_BUSY_CU_CYCLES" in cs and cs["SQ_BUSY_CU_CYCLES"][1] > 0:
+                # MFMA busy cycles are counted per SIMD (4 per CU), CU busy cycles per CU
+                o.write("    -> matrix pipe busy %.3f of the cycles its CUs were busy\n"
+                        % (cs["SQ_VALU_MFMA_BUSY_CYCLES"][1] / (4.0 * cs["SQ_BUSY_CU_CYCLES"][1])))
+            if "SQ_WAIT_ANY" in cs and "SQ_WAVE_CYCLES" in cs and cs["SQ_WAVE_CYCLES"][1] > 0:
+                o.write("    -> waves waiting %.3f of their cycles (LDS: %.3f)\n"
+                        % (cs["SQ_WAIT_ANY"][1] / cs["SQ_WAVE_CYCLES"][1],
+                           cs.get("SQ_WAIT_INST_LDS", [0, 0.0])[1] / cs["SQ_WAVE_CYCLES"][1]))
+            o.write("\n")
 
 
 if __name__ == "__main__":

@@ -1431,7 +1431,7 @@ struct LayerOrder {
   // With many candidates only a few rows of S are ever read: the query's, and those of the memories that enter a
   // relevant set during the hops (Section 4.2: propagation averages the rows of the current relevant set).  They
   // are formed hop by hop, as the sets become known; the selector re-runs hops 1..h each time, so the result is
-  // that of one run.  (Worth it only where the budget keeps at most half of the candidates' rows: otherwise
+  // that of one run (with a single selection only the query's row is ever formed).  (Worth it only where the budget keeps at most half of the candidates' rows: otherwise
   // nearly every row is read anyway and the hop-by-hop round trips are pure overhead.)
   bool lazy_scores = false;
   // Where both hold, the attention itself is needed only for the rows whose scores are read and for the rows
@@ -1482,7 +1482,7 @@ struct PrefillRun {
     const long keep_rows = budget_mode == KEEP_BUDGET_TOKENS ? std::min<long>(o.tok, mem_rows)
                                                              : mem_rows * o.k_count / std::max(1, m);
     o.eval_first = (keep_rows + pi.Lq) * 2 <= plan.n_rows;
-    o.lazy_scores = c->mfma && m >= LAZY_MIN_CANDIDATES && hops > 1 && keep_rows * 2 <= mem_rows;
+    o.lazy_scores = c->mfma && m >= LAZY_MIN_CANDIDATES && keep_rows * 2 <= mem_rows;
     o.lazy_attn = o.lazy_scores && o.eval_first;
     return o;
   }

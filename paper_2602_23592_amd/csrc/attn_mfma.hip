@@ -103,8 +103,10 @@ __global__ void __launch_bounds__(256, 2)
 
   // ---- LDS tiles: per buffer K [64 keys][256 B] then V [64 keys][256 B], no padding; 16-byte chunks are
   // XOR-swizzled so that operand reads are bank-conflict free: K chunk c of row r sits at c ^ (r % 16)
-  // (16 consecutive rows x one 16-byte chunk = all 64 banks), V chunk c of row r at c ^ (2 (r % 8))
-  // (the 4 rows x 32 bytes of one transpose read fall on disjoint banks).
+  // (16 consecutive rows x one 16-byte chunk = all 64 banks), V chunk c of row r at c ^ (4 (r % 4))
+  // (a transpose read is served half a wave at a time: its 4 rows x 4 chunks then sit in 16 different chunks,
+  // all 64 banks once; with a row term that moves rows by fewer than 4 chunks two rows share banks and every
+  // V read takes twice as long, which the bank-conflict counter showed as a third of all LDS cycles).
   // Global -> LDS goes through global_load_lds_dwordx4 (lane l's 16 bytes land at base + 16 l, so one
   // instruction fills 4 rows); the swizzle is applied to the global address each lane fetches.
   typedef const void __attribute__((address_space(1))) * gptr_t;
@@ -120,7 +122,7 @@ __global__ void __launch_bounds__(256, 2)
       const size_t g_ = ((size_t)key_ * n_kv_heads + hk) * DH;                                                  \
       uint16_t* l_ = smem + (BUFI) * ATT_BUF + (wave * 16 + 4 * i) * DH;                                        \
       __builtin_amdgcn_global_load_lds((gptr_t)(k_cache + g_ + ((ld_pc ^ (row_ & 15)) << 3)), (lptr_t)l_, 16, 0, 0); \
-      __builtin_amdgcn_global_load_lds((gptr_t)(v_cache + g_ + ((ld_pc ^ ((row_ & 7) << 1)) << 3)),             \
+      __builtin_amdgcn_global_load_lds((gptr_t)(v_cache + g_ + ((ld_pc ^ ((row_ & 3) << 2)) << 3)),             \
                                        (lptr_t)(l_ + KT_KEYS * DH), 16, 0, 0);                                  \
     }                                                                                                           \
   }
@@ -133,7 +135,7 @@ __global__ void __launch_bounds__(256, 2)
     const int vr = 4 * g + ((lane & 15) >> 2);
     const int cl = 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);
 #pragma unroll
-    for (int nt = 0; nt < 4; ++nt) voff[nt] = vr * DH + (((4 * nt + cl) ^ ((vr & 7) << 1)) << 3) + 4 * (lane & 1);
+    for (int nt = 0; nt < 4; ++nt) voff[nt] = vr * DH + (((4 * nt + cl) ^ ((vr & 3) << 2)) << 3) + 4 * (lane & 1);
   }
 
   ATT_STAGE(kt0, 0)

@@ -116,7 +116,7 @@ def test_prefill_with_many_candidates_selects_like_the_full_score_matrix():
     pb = Problem(shape, glen, lq, seed=9, std=0.05, bias=True)
     ctx, pr = pb.context(), pb.prompt()
     G = len(glen)
-    for hops, ratio in ((3, 0.15), (4, 0.3), (2, 0.05)):
+    for hops, ratio in ((3, 0.15), (4, 0.3), (2, 0.05), (1, 0.2)):
         ratios = [1.0, ratio]
         kc, vc = pb.empty_cache()
         xf = torch.empty((lq, shape.hidden), dtype=torch.bfloat16, device="cuda")
