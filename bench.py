@@ -75,7 +75,7 @@ def parse():
                     help="measure the cost of one memory update on the workload's model shape instead of the prefill")
     ap.add_argument("--int4", action="store_true",
                     help="with --decode-tokens / --memory-update: INT4 weight-only projections (the launches of at "
-                         "most 64 rows read the 4-bit form; the bf16 weights are its expansion)")
+                         "most 48 rows read the 4-bit form; the bf16 weights are its expansion)")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the extra keys of the default run (the count-budget reading of the same prompt, the "
                          "other workloads, the loading modes and the token-granularity pair on the host-resident one)")
@@ -200,11 +200,20 @@ def memory_update_cost(ctx, w, torch, steps, warmup):
     def whole_group():
         ctx.precompute_group(toks, kg, vg)
 
+    def unit_of(n):
+        ku = torch.empty((s.n_layers, n, s.n_kv_heads, s.head_dim), dtype=dt, device="cuda")
+        vu = torch.empty_like(ku)
+        return lambda: ctx.precompute_group(toks[:n], ku, vu)
+
     out = {}
-    for name, fn, ntok in (("dynamic_segment_update", one_segment, seg),
-                           ("static_to_dynamic_one_by_one", every_segment, seg * nseg),
-                           ("static_to_dynamic", every_segment_one_pass, seg * nseg),
-                           ("dynamic_to_static", whole_group, seg * nseg)):
+    cases = [("dynamic_segment_update", one_segment, seg),
+             ("static_to_dynamic_one_by_one", every_segment, seg * nseg),
+             ("static_to_dynamic", every_segment_one_pass, seg * nseg),
+             ("dynamic_to_static", whole_group, seg * nseg)]
+    # one unit of n tokens: launches of a few rows stream the weights (at most 16 rows of bf16 weights, at most
+    # 48 of the 4-bit form if it is attached), longer ones run on the matrix-core kernels with the bf16 weights
+    cases += [("unit_%d_tokens" % n, unit_of(n), n) for n in (16, 32, 33, 48, 64, 65, 96, 128, 256, 512)]
+    for name, fn, ntok in cases:
         for _ in range(warmup):
             fn()
         torch.cuda.synchronize()
@@ -553,7 +562,7 @@ def main():
     if a.memory_update:
         gate.resume()
         res = memory_update_cost(ctx, w, torch, a.steps, a.warmup)
-        res["weights"] = "int4 weight-only (group 128) where a launch has at most 64 rows" if a.int4 else s.storage
+        res["weights"] = "int4 weight-only (group 128) where a launch has at most 48 rows" if a.int4 else s.storage
         print(json.dumps(res))
         return
     case.make_prompt()

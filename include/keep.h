@@ -366,7 +366,7 @@ keep_status keep_dequantize_int4(const void* codes, const void* scale_zero, int3
 
 /* Registers the INT4 form of every layer's projections with a context whose keep_layer_weights are their
  * bfloat16 expansion (keep_dequantize_int4).  From then on the launches that are bound by reading the
- * weights (at most 64 rows: keep_decode, keep_precompute_group of a short segment, prompts of a few rows)
+ * weights (at most 48 rows: keep_decode, keep_precompute_group of a short segment, prompts of a few rows)
  * read the 4-bit form, a quarter of the bytes, and expand it in registers to the same bfloat16 values, so
  * results differ from the bfloat16 launches only by the order of the fp32 accumulation.
  *   layers: HOST array [n_layers] of DEVICE pointers, borrowed until keep_destroy; NULL detaches.

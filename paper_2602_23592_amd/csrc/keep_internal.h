@@ -107,7 +107,7 @@ struct GemmB {
   int32_t n_rows[3];
   int32_t n_parts;
   // INT4 form of the same parts (codes, scale/zero words) and of the second operand of the SwiGLU
-  // epilogue; read instead of `ptr` by the launches that stream the weights (at most 64 rows)
+  // epilogue; read instead of `ptr` by the launches that stream the weights (at most 48 rows)
   bool has_w4;
   const void* w4_codes[3];
   const void* w4_scale_zero[3];
@@ -177,7 +177,7 @@ void launch_score_finish(const float* rowmass, const int32_t* d_row_start, int32
 
 // MFMA (bf16, head_dim 128) kernels
 // skinny_ws: device scratch of gemm_ws_bytes(): partials of the weight-streaming kernel for launches of at
-// most 64 rows, and of the tiles that are cut along K to fill the last round of workgroups.  NULL: neither.
+// most 48 rows, and of the tiles that are cut along K to fill the last round of workgroups.  NULL: neither.
 size_t gemm_ws_bytes();
 void launch_gemm_mfma(const bf16_t* A, int32_t M, int32_t K, const GemmB& B, const void* B2, int32_t N, int epilogue,
                       const bf16_t* residual, void* C, hipStream_t s, void* skinny_ws = nullptr,
