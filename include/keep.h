@@ -123,9 +123,11 @@ typedef struct {
   int32_t hops_run[KEEP_REPORT_MAX_LAYERS];    /* selections run after each layer */
   int32_t realign_rows[KEEP_REPORT_MAX_LAYERS];/* cache rows re-aligned (groups outside the set) */
   int32_t ffn_rows[KEEP_REPORT_MAX_LAYERS];    /* rows the output projection + FFN ran on: rows[l], or the
-                                                  next layer's rows when evaluation went first (see keep_prefill) */
+                                                  next layer's rows when evaluation went first (see keep_prefill);
+                                                  at the last layer the instruction's rows */
   int32_t attn_rows[KEEP_REPORT_MAX_LAYERS];   /* rows the attention ran on: rows[l], or fewer where only the rows
-                                                  whose scores or outputs are read were attended (see keep_prefill) */
+                                                  whose scores or outputs are read were attended (see keep_prefill:
+                                                  layers that score on demand, and the last layer) */
   uint64_t attn_keys[KEEP_REPORT_MAX_LAYERS];  /* keys those rows see in all: sum of (position + 1) */
   float ms_realign[KEEP_REPORT_MAX_LAYERS];    /* re-align + concatenate kernel */
   float ms_prep[KEEP_REPORT_MAX_LAYERS];       /* row table, gather, first RMSNorm */
@@ -264,7 +266,9 @@ keep_status keep_select_groups_static(const float* S, const int32_t* groups, int
  * same result because the hidden rows of dropped memories are discarded (Section 4.3).  At such a layer, when
  * there are also 64 or more candidates, the score matrix is formed hop by hop for the rows the propagation
  * reads (the query's, then those of each hop's relevant set), and the attention runs only for those rows and
- * for the rows that survive: neither the scores nor the outputs of the other rows are ever read.
+ * for the rows that survive: neither the scores nor the outputs of the other rows are ever read.  The same
+ * holds for the last layer, whose memory rows feed nothing: K and V of its set are refreshed, attention,
+ * output projection and FFN run for the instruction's rows.
  *   ratios: HOST [n_layers]; ratios[0] is 1 (recompute every memory at the first
  *           layer, Section 4.2) or 0 (pure reuse); ratios[1..] non-increasing (a memory
  *           dropped once is never recomputed, Section 4.3).

@@ -1656,20 +1656,57 @@ struct PrefillRun {
         st = attend(want.data());
         if (st != KEEP_OK) return st;
       }
-      if (report) {
-        report->attn_rows[l] = (int32_t)attn_rows;
-        report->attn_keys[l] = attn_keys;
-      }
-      if (timed() && part_launches > 0) {  // the events are reused by later layers: read them now
-        HIP_TRY(c, hipEventSynchronize(c->ev_part[2 * (part_launches - 1) + 1]));
-        for (int i = 0; i < part_launches; ++i) {
-          float ms = 0.f;
-          (void)hipEventElapsedTime(&ms, c->ev_part[2 * i], c->ev_part[2 * i + 1]);
-          part_attn_ms[l] += ms;
-        }
+      st = note_part_attention();
+      if (st != KEEP_OK) return st;
+    }
+    return KEEP_OK;
+  }
+
+  // rows and keys of the layer's attention launches on parts of its rows, and their time
+  keep_status note_part_attention() {
+    if (report) {
+      report->attn_rows[l] = (int32_t)attn_rows;
+      report->attn_keys[l] = attn_keys;
+    }
+    if (timed() && part_launches > 0) {  // the events are reused by later layers: read them now
+      HIP_TRY(c, hipEventSynchronize(c->ev_part[2 * (part_launches - 1) + 1]));
+      for (int i = 0; i < part_launches; ++i) {
+        float ms = 0.f;
+        (void)hipEventElapsedTime(&ms, c->ev_part[2 * i], c->ev_part[2 * i + 1]);
+        part_attn_ms[l] += ms;
       }
     }
     return KEEP_OK;
+  }
+
+  // The last layer.  Behind it only the instruction's hidden rows are read (Section 5: the prefill hands the
+  // decoder the updated cache and the instruction's state), and none at all where the caller wants the caches
+  // alone (a memory unit cached on its own).  K/V of the whole set are refreshed as in every layer; attention,
+  // output projection and FFN run for the instruction's rows only, which are the tail of the compact layout.
+  keep_status last_layer_tail() {
+    const keep_model_desc& d = c->d;
+    const int m = (int)cur.size();
+    const bool rows_wanted = x_final != nullptr;
+    ord.lazy_attn = c->mfma || !rows_wanted;  // front() stops before the attention
+    keep_status st = front();
+    if (st != KEEP_OK) return st;
+    attn_rows = ord.lazy_attn ? 0 : plan.n_rows;
+    if (ord.lazy_attn) attn_keys = 0;
+    if (rows_wanted && c->mfma) {
+      want.assign((size_t)m + 1, 0);
+      want[m] = 1;
+      st = attend(want.data());
+      if (st != KEEP_OK) return st;
+    }
+    st = note_part_attention();
+    if (st != KEEP_OK) return st;
+    if (!rows_wanted) {
+      if (report) report->ffn_rows[l] = 0;
+      return KEEP_OK;
+    }
+    const size_t first = (size_t)(plan.n_rows - pi.Lq);
+    const size_t o_off = first * d.n_q_heads * d.head_dim * c->esz, x_off = first * d.hidden * c->esz;
+    return back(pi.Lq, (const char*)c->o + o_off, (const char*)x_cur + x_off, (char*)x_nxt + x_off);
   }
 
   // ---- copy stream: the groups that just left the set complete layer l+1 (first dependency of the pipeline)
@@ -1790,6 +1827,7 @@ struct PrefillRun {
       const int64_t first = pi.off[cur[i]], len = p->group_len[cur[i]];
       attn_keys += (uint64_t)(len * (2 * first + len + 1) / 2);
     }
+    if (l + 1 == L && (plan.n_rows > pi.Lq || !x_final)) return last_layer_tail();
     st = front();
     if (st != KEEP_OK) return st;
     if (ord.kind == SEL_DEVICE) {

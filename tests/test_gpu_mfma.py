@@ -247,6 +247,8 @@ def test_pipeline_on_three_streams_mfma_hop_by_hop(set_only):
                 # layers 0 and 1: scores hop by hop, attention on demand, FFN on the survivors only
                 assert rep.attn_rows[0] < rep.rows[0] and rep.attn_rows[1] < rep.rows[1], list(rep.attn_rows[:4])
                 assert rep.ffn_rows[0] == rep.rows[1] and rep.ffn_rows[1] == rep.rows[2]
+                # last layer: K/V of its set refreshed, everything after that for the instruction's rows only
+                assert rep.rows[3] > lq and rep.attn_rows[3] == lq and rep.ffn_rows[3] == lq
         ctx.close()
     for o in outs[1:]:
         assert o[0] == outs[0][0]

@@ -37,6 +37,9 @@ def test_tiny_prefill_fp32_end_to_end():
         assert max_rel(to_np(vc[l]), ref["v_hat"][l]) < TOL["f32"]
     assert max_rel(to_np(xf), ref["x_final"]) < TOL["f32"]
     assert not torch.isnan(kc).any() and not torch.isnan(vc).any()
+    # behind the last layer only the instruction's rows are read: its output projection and FFN ran on those
+    last = w.shape.n_layers - 1
+    assert rep.rows[last] > pb.instr_len and rep.ffn_rows[last] == pb.instr_len
 
 
 SHAPES = {
