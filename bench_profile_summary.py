@@ -160,4 +160,8 @@ def counters(argv):
 
 
 if __name__ == "__main__":
-    {"stats": stats, "traffic": traffic, "counters": counters}[sys.argv[1]](sys.argv[2:])
+    modes = {"stats": stats, "traffic": traffic, "counters": counters}
+    if len(sys.argv) < 2 or sys.argv[1] not in modes:
+        print(__doc__)
+        sys.exit(0 if len(sys.argv) > 1 and sys.argv[1] in ("-h", "--help") else 2)
+    modes[sys.argv[1]](sys.argv[2:])

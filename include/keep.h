@@ -57,7 +57,7 @@ typedef enum {
 typedef enum { KEEP_F32 = 0, KEEP_BF16 = 1 } keep_dtype;
 typedef enum { KEEP_KV_DEVICE = 0, KEEP_KV_PINNED_HOST = 1 } keep_kv_location;
 
-/* How a ratio becomes a budget (Section 4.2, "a ratio of top r_i memories"):
+/* How a ratio becomes a budget (Section 4.2: each layer keeps the top share r_i of the memories):
  * a number of memories, ceil(ratio * n_groups - 1e-3), or a number of tokens,
  * floor(ratio * N_mem + 1e-3), filled by walking the importance order. */
 typedef enum { KEEP_BUDGET_GROUP_COUNT = 0, KEEP_BUDGET_TOKENS = 1 } keep_budget_mode;
@@ -318,7 +318,7 @@ keep_status keep_prefill_padded(keep_ctx* ctx, const keep_prompt* prompt, const 
 
 #define KEEP_DECODE_MAX_TOKENS 64
 /* First token and short greedy decoding over the joined cache (Section 1: after the long prompt the
- * planner emits a short action; Section 5: prefill_layer leaves "the updated KV cache for decoding").
+ * planner emits a short action; Section 5: the decoder continues on the cache that prefill_layer updated).
  * Token 0 = argmax over the vocabulary of lm_head . RMSNorm(x_last); token t > 0 comes from running
  * token t-1 at position n_ctx + t - 1 through every layer: its K/V are written to row n_ctx + t - 1 of
  * the caches and it attends to rows 0 .. n_ctx + t - 1.  Equal logits: the lowest token id.

@@ -370,7 +370,7 @@ def scores_from_mass(mass: np.ndarray, groups: Sequence[int], group_len: Sequenc
 # ----------------------------------------------------------------------------
 def budget_count(ratio: float, n_groups_total: int, n_candidates: int) -> int:
     """Number of memories to keep: ratio of the prompt's memories, rounded up
-    (reading: "a ratio of top r_i memories" counts memories of the whole prompt)."""
+    (reading: the share r_i of Section 4.2 is a share of the memories of the whole prompt)."""
     k = int(np.ceil(float(np.float32(ratio)) * n_groups_total - BUDGET_EPS))
     return max(0, min(n_candidates, k))
 
@@ -405,7 +405,7 @@ def select_multihop(S: np.ndarray, groups: Sequence[int], group_len: Sequence[in
     must reach the same ones from the same S.
 
     Steps (Section 4.2): row-normalise S over the candidate targets (reading of the
-    "normalized cross-attention score" of Fig. 6: each source spreads one unit);
+    normalised scores that Fig. 6 shows: each source spreads one unit);
     initial importance = the query's row; relevant set = top of the importance order
     within the budget; new importance = average of the normalised rows of the query
     and of the relevant memories (reading: the query stays a source; `drop_query`
@@ -628,7 +628,7 @@ def keep_prefill_tokens(sh: Shape, layers, embed: np.ndarray, token_ids: np.ndar
 # ----------------------------------------------------------------------------
 # first token and short greedy decoding over the joined cache
 # (Section 1: the planner emits a short action after the long prompt;
-#  Section 5: `prefill_layer` leaves "the updated KV cache for decoding")
+#  Section 5: the decoder continues on the cache that `prefill_layer` updated)
 # ----------------------------------------------------------------------------
 def lm_logits(sh: Shape, final_norm: np.ndarray, lm_head: np.ndarray, x: np.ndarray) -> np.ndarray:
     """Final RMSNorm and vocabulary projection of hidden rows x [n, hidden] -> [n, vocab]."""
