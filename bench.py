@@ -523,6 +523,9 @@ def sweep(a, torch, ks, kb):
                                   tokens_per_s=round(c.n_tokens / (np.median(ms) * 1e-3), 1),
                                   rows_per_layer_mean=round(float(np.mean([rep.rows[l] for l in range(1, L)])), 1),
                                   hops_run_layer0=int(rep.hops_run[0]), set_size_layer1=int(rep.set_size[1]),
+                                  attn_rows_layer0=int(rep.attn_rows[0]),
+                                  keys_per_attended_row=round(float(sum(rep.attn_keys[l] for l in range(L))) /
+                                                              max(1.0, float(sum(rep.attn_rows[l] for l in range(L)))), 1),
                                   ms_gemms=round(tot("ms_qkv_gemm") + tot("ms_oproj") + tot("ms_gateup") + tot("ms_down"), 2),
                                   ms_attention=tot("ms_attn"), ms_score_select=tot("ms_score"),
                                   ms_realign=tot("ms_realign"), note="per-kernel sums from the fully instrumented steps "
