@@ -119,6 +119,12 @@ def traffic(argv):
                 % (copy_kib, calib["FETCH_SIZE"], calib["WRITE_SIZE"], f_scale, w_scale))
         o.write("Gate/up GEMM (k_gemm_mfma<256,256,4,2,SWIGLU> + its fix-up): %d launches, %.3f GB per launch (scaled).\n\n"
                 % (launches, bytes_per_launch / 1e9))
+        att = [pk[c].get("k_attn_mfma", (0, 0.0, 0.0)) for c in ("FETCH_SIZE", "WRITE_SIZE")]
+        if att[0][0]:
+            o.write("Attention (k_attn_mfma, %d launches: the step's 48 plus the on-demand launches of layer 0 and the launches "
+                    "of the row-sparse diagnostic): %.1f MB fetched and %.1f MB written per launch on average (scaled); K and V "
+                    "of one layer are 135 MB.\n\n"
+                    % (att[0][0], att[0][1] * f_scale * 1024.0 / att[0][0] / 1e6, att[1][1] * w_scale * 1024.0 / att[0][0] / 1e6))
         o.write("```\n")
         for c in ("FETCH_SIZE", "WRITE_SIZE"):
             o.write(c + " (KiB as counted)\n")
