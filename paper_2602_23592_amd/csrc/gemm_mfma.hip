@@ -1,17 +1,21 @@
 // bf16 GEMM on the gfx950 matrix cores:  C[M,N] = A[M,K] . W[N,K]^T  (fp32 accumulate)
 //
-// Both operands are K-contiguous, which is the layout v_mfma_f32_32x32x16_bf16 wants:
-// lane l supplies 8 consecutive k of row (l % 32), k-block (l / 32).  A workgroup owns a
+// Both operands are K-contiguous, which is the layout v_mfma_f32_16x16x32_bf16 wants:
+// lane l supplies 8 consecutive k of row (l % 16), k-block (l / 16).  (Of the two bf16 shapes this one
+// sustains the higher rate under the chip's power limit: a register-only loop on random operands runs at
+// 2.03 PFLOP/s against 1.78 PFLOP/s for 32x32x16, and the whole kernel gains 4 %; operand bytes read from
+// LDS per flop are the same for both.)  A workgroup owns a
 // BM x BN tile of C; K is walked in 64-deep slices staged through LDS (two buffers, one
 // barrier per slice, next slice streamed global -> LDS by global_load_lds_dwordx4 while the
-// current one is multiplied; operand fragments of k-step ks+1 are read while step ks multiplies).  LDS
+// current one is multiplied; operand fragments of the next step are read while a step multiplies).  LDS
 // rows are 128 B; their 16-byte chunks are XOR-swizzled by the row index so that the
 // 16-byte operand reads of consecutive rows spread over all banks.  Workgroups are mapped
 // to tiles XCD by XCD so that the tiles resident on one XCD share slices through its L2.
 //
-// Epilogues: plain fp32 store (QKV), residual add (output and down projections), and
+// Epilogues: plain fp32 store, residual add (output and down projections),
 // SwiGLU: the B tile interleaves rows of W_gate and W_up so that one lane holds
-// gate[m, n] and up[m, n] in matching accumulator registers.
+// gate[m, n] and up[m, n] in matching accumulator registers, and the fused QKV epilogue (bias, RoPE,
+// compact q / k rows, scatter of K and V into the cache).
 #include <algorithm>
 
 #include "keep_internal.h"
@@ -19,7 +23,7 @@
 namespace keep {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;  // 16-byte register vector (native, so arrays of it stay in VGPRs)
 
 struct MfmaB {
@@ -59,7 +63,8 @@ __global__ void __launch_bounds__(WM* WN * 64)
                 int full_per_xcd, int split_s, float* __restrict__ part, QkvEpilogue qe) {
   constexpr int T = WM * WN * 64;
   constexpr int TM = BM / WM, TN = BN / WN;
-  constexpr int MI = TM / 32, NI = TN / 32;
+  constexpr int MI = TM / 16, NI = TN / 16;  // 16x16 accumulator tiles per wave
+  static_assert(NI % 4 == 0, "a wave's columns are walked in groups of four 16-column tiles");
   static_assert(EPI != EPI_SWIGLU_STORE || (NI % 2 == 0), "SwiGLU needs an even number of N tiles per wave");
 
   extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
@@ -100,7 +105,7 @@ __global__ void __launch_bounds__(WM* WN * 64)
   constexpr int CPR = GBK / 8;      // 16-byte chunks per tile row
   constexpr int RPL = 128 / GBK;    // tile rows per 256-byte LDS bank line
   constexpr int RPI = 64 / CPR;     // tile rows filled by one wave-wide load instruction (1 KiB)
-  constexpr int KS = GBK / 16;      // MFMA k-steps per slice
+  constexpr int KS = GBK / 32;      // MFMA k-steps (32 deep) per slice
   constexpr int A_LD = BM / RPI / NW, B_LD = BN / RPI / NW;  // load instructions per wave per slice
   constexpr int LD = A_LD + B_LD;
   static_assert(BM % (RPI * NW) == 0 && BN % (RPI * NW) == 0, "tile rows must split evenly over the waves");
@@ -181,13 +186,13 @@ __global__ void __launch_bounds__(WM* WN * 64)
     __syncthreads();                                                                                              \
   }
 
-  f32x16 acc[MI][NI];
+  f32x4 acc[MI][NI];
 #pragma unroll
   for (int i = 0; i < MI; ++i)
 #pragma unroll
     for (int j = 0; j < NI; ++j)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+      for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f;
 
   // NST LDS stages: slices kt+1 .. kt+NST-1 are in flight (or landed) while slice kt is multiplied
   const int kt_begin = (int)((long)piece * (K / GBK) / pieces);
@@ -218,25 +223,28 @@ __global__ void __launch_bounds__(WM* WN * 64)
     return;
   }
 
-  const int a_row0 = wm * TM + (lane & 31);
-  const int b_row0 = wn * TN + (lane & 31);
-  const int kg = lane >> 5;
-  // LDS element offsets of this lane's operand chunks per k-step (rows differ by multiples of 32,
+  const int a_row0 = wm * TM + (lane & 15);
+  const int b_row0 = wn * TN + (lane & 15);
+  const int kg = lane >> 4;
+  // LDS element offsets of this lane's operand chunks per k-step (rows differ by multiples of 16,
   // which leaves the swizzle term unchanged, so one offset per k-step serves every row tile)
   int a_off[KS], b_off[KS];
 #pragma unroll
   for (int ks = 0; ks < KS; ++ks) {
-    a_off[ks] = lds_off<GBK>(a_row0, ks * 2 + kg);
-    b_off[ks] = BM * GBK + lds_off<GBK>(b_row0, ks * 2 + kg);
+    a_off[ks] = lds_off<GBK>(a_row0, ks * 4 + kg);
+    b_off[ks] = BM * GBK + lds_off<GBK>(b_row0, ks * 4 + kg);
   }
 
-  // operand fragments, double-buffered over k-steps: the loads of step ks+1 are in flight while the
-  // MFMAs of step ks run
-  bf16x8 af[2][MI], bfr[2][NI];
+  // A slice is walked in steps (k-step, group of four 16-column tiles): MI x 4 MFMAs each.  The A fragments
+  // of a k-step serve all its groups; the B fragments of the next step (and, at the end of a k-step, the next
+  // k-step's A fragments) are read while a step multiplies.
+  constexpr int NG = NI / 4;        // column groups per k-step
+  constexpr int STEPS = KS * NG;    // steps per slice
+  bf16x8 af[2][MI], bfr[2][4];
 #pragma unroll
-  for (int i = 0; i < MI; ++i) af[0][i] = *reinterpret_cast<const bf16x8*>(smem + a_off[0] + i * 32 * GBK);
+  for (int i = 0; i < MI; ++i) af[0][i] = *reinterpret_cast<const bf16x8*>(smem + a_off[0] + i * 16 * GBK);
 #pragma unroll
-  for (int j = 0; j < NI; ++j) bfr[0][j] = *reinterpret_cast<const bf16x8*>(smem + b_off[0] + j * 32 * GBK);
+  for (int j = 0; j < 4; ++j) bfr[0][j] = *reinterpret_cast<const bf16x8*>(smem + b_off[0] + j * 16 * GBK);
 
   int stage = 0;
   for (int kt = kt_begin; kt < KT; ++kt) {
@@ -246,65 +254,79 @@ __global__ void __launch_bounds__(WM* WN * 64)
     const uint16_t* cbuf = smem + stage * BUF;
     const uint16_t* nbuf = smem + next_stage * BUF;
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      const int fc = ks & 1, fn = fc ^ 1;
-      if (ks + 1 < KS) {
+    for (int st = 0; st < STEPS; ++st) {
+      const int ks = st / NG, g = st % NG;
+      const int bc = st & 1, bn = bc ^ 1, ac = ks & 1, an = ac ^ 1;
+      // (STEPS is even or 1, and a slice ends on an A switch, so the buffer parities carry over the slices)
+      bool new_a;
+      if (st + 1 < STEPS) {
+        const int ks1 = (st + 1) / NG, g1 = (st + 1) % NG;
 #pragma unroll
-        for (int i = 0; i < MI; ++i)
-          af[fn][i] = *reinterpret_cast<const bf16x8*>(cbuf + a_off[ks + 1] + i * 32 * GBK);
+        for (int j = 0; j < 4; ++j)
+          bfr[bn][j] = *reinterpret_cast<const bf16x8*>(cbuf + b_off[ks1] + (g1 * 4 + j) * 16 * GBK);
+        new_a = g1 == 0;
+        if (new_a) {
 #pragma unroll
-        for (int j = 0; j < NI; ++j)
-          bfr[fn][j] = *reinterpret_cast<const bf16x8*>(cbuf + b_off[ks + 1] + j * 32 * GBK);
+          for (int i = 0; i < MI; ++i) af[an][i] = *reinterpret_cast<const bf16x8*>(cbuf + a_off[ks1] + i * 16 * GBK);
+        }
       } else {
-        // Last k-step of the slice: its operands are already in registers, so the workgroup waits for
+        // Last step of the slice: its operands are already in registers, so the workgroup waits for
         // slice kt+1 and synchronises BEFORE these MFMAs; the first operand reads of the next slice
         // are then in flight while they run.
         __builtin_amdgcn_s_waitcnt(vmcnt_imm((NST - 2) * LD));
         __syncthreads();
         GEMM_STAGE(min(kt + NST, KT - 1), stage)
 #pragma unroll
-        for (int i = 0; i < MI; ++i) af[fn][i] = *reinterpret_cast<const bf16x8*>(nbuf + a_off[0] + i * 32 * GBK);
+        for (int j = 0; j < 4; ++j) bfr[bn][j] = *reinterpret_cast<const bf16x8*>(nbuf + b_off[0] + j * 16 * GBK);
 #pragma unroll
-        for (int j = 0; j < NI; ++j) bfr[fn][j] = *reinterpret_cast<const bf16x8*>(nbuf + b_off[0] + j * 32 * GBK);
+        for (int i = 0; i < MI; ++i) af[an][i] = *reinterpret_cast<const bf16x8*>(nbuf + a_off[0] + i * 16 * GBK);
+        new_a = true;
       }
 #pragma unroll
       for (int i = 0; i < MI; ++i)
 #pragma unroll
-        for (int j = 0; j < NI; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[fc][i], bfr[fc][j], acc[i][j], 0, 0, 0);
-      // interleave the MFMAs of this k-step with the operand reads issued above
-      constexpr int MF = MI * NI;  // MFMAs per k-step
-      constexpr int RD = MI + NI;  // operand reads per k-step
+        for (int j = 0; j < 4; ++j)
+          acc[i][g * 4 + j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[ac][i], bfr[bc][j], acc[i][g * 4 + j], 0, 0, 0);
+      // interleave the operand reads issued above with the first half of the step's MFMAs (the second half
+      // covers the latency of the last read)
+      if (new_a) {
 #pragma unroll
-      for (int r = 0; r < RD; ++r) {
-        __builtin_amdgcn_sched_group_barrier(0x008, MF / RD > 0 ? MF / RD : 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        for (int r = 0; r < 4 + MI; ++r) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+      } else {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
       }
     }
     stage = next_stage;
   }
   __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));  // no LDS write of this workgroup may outlive it
 
-  // ---- epilogue.  acc[i][j][e]: row = i*32 + 8*(e/4) + 4*(lane/32) + e%4, col = j*32 + lane%32
-  const int col_l = lane & 31;
-  const int row_l = 4 * (lane >> 5);
+  // ---- epilogue.  acc[i][j][e]: row = i*16 + 4*(lane/16) + e, col = j*16 + lane%16
+  const int col_l = lane & 15;
+  const int row_l = 4 * (lane >> 4);
   if (pieces > 1) {  // partial tile [BM][BN] in tile coordinates
     const int rem_per_xcd = per_xcd - full_per_xcd;
     float* pt = part + ((size_t)(xcd * rem_per_xcd + (tl - full_per_xcd)) * split_s + piece) * (BM * BN);
 #pragma unroll
     for (int i = 0; i < MI; ++i)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int r = wm * TM + i * 32 + 8 * (e >> 2) + row_l + (e & 3);
+      for (int e = 0; e < 4; ++e) {
+        const int r = wm * TM + i * 16 + row_l + e;
 #pragma unroll
-        for (int j = 0; j < NI; ++j) pt[(size_t)r * BN + wn * TN + j * 32 + col_l] = acc[i][j][e];
+        for (int j = 0; j < NI; ++j) pt[(size_t)r * BN + wn * TN + j * 16 + col_l] = acc[i][j][e];
       }
     return;
   }
   if constexpr (EPI == EPI_QKV_ROPE) {
     // The wave's TN = 128 columns are one head: query head, key head or value head by where they start.
-    // RoPE pairs column c with c + 64: accumulator tiles j and j + 2, same lane, same register.
-    static_assert(EPI != EPI_QKV_ROPE || (TN == 128 && NI == 4 && BM / NW == 32),
+    // RoPE pairs column c with c + 64: accumulator tiles j and j + 4, same lane, same register.
+    static_assert(EPI != EPI_QKV_ROPE || (TN == 128 && NI == 8 && BM / NW == 32),
                   "the fused QKV epilogue needs one head per wave and 32 staged rows per wave");
     QKV_STAGE_TABLES
     const float* tab = reinterpret_cast<const float*>(smem);
@@ -313,28 +335,28 @@ __global__ void __launch_bounds__(WM* WN * 64)
     const int kind = col0 < qe.q_dim ? 0 : (col0 < qe.q_dim + qe.kv_dim ? 1 : 2);
     const int hcol = kind == 0 ? col0 : (kind == 1 ? col0 - qe.q_dim : col0 - qe.q_dim - qe.kv_dim);  // column inside q / k / v
     const bf16_t* bias = reinterpret_cast<const bf16_t*>(qe.bias[kind]);
-    float bl[2] = {0.f, 0.f}, bh[2] = {0.f, 0.f};
+    float bl[4] = {0.f, 0.f, 0.f, 0.f}, bh[4] = {0.f, 0.f, 0.f, 0.f};
     if (bias) {
 #pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        bl[j] = bf16_bits_to_f32(bias[hcol + j * 32 + col_l].bits);
-        bh[j] = bf16_bits_to_f32(bias[hcol + 64 + j * 32 + col_l].bits);
+      for (int j = 0; j < 4; ++j) {
+        bl[j] = bf16_bits_to_f32(bias[hcol + j * 16 + col_l].bits);
+        bh[j] = bf16_bits_to_f32(bias[hcol + 64 + j * 16 + col_l].bits);
       }
     }
 #pragma unroll
     for (int i = 0; i < MI; ++i) {
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int rt = wm * TM + i * 32 + 8 * (e >> 2) + row_l + (e & 3);  // row inside the tile
+      for (int e = 0; e < 4; ++e) {
+        const int rt = wm * TM + i * 16 + row_l + e;  // row inside the tile
         const int gm = m0 + rt;
         if (gm >= M) continue;
         const int pos = spos[rt];
         if (kind == 2) {
           bf16_t* dst = reinterpret_cast<bf16_t*>(qe.v_cache) + (size_t)pos * qe.kv_dim + hcol;
 #pragma unroll
-          for (int j = 0; j < 2; ++j) {
-            dst[j * 32 + col_l].bits = f32_to_bf16_bits(acc[i][j][e] + bl[j]);
-            dst[64 + j * 32 + col_l].bits = f32_to_bf16_bits(acc[i][j + 2][e] + bh[j]);
+          for (int j = 0; j < 4; ++j) {
+            dst[j * 16 + col_l].bits = f32_to_bf16_bits(acc[i][j][e] + bl[j]);
+            dst[64 + j * 16 + col_l].bits = f32_to_bf16_bits(acc[i][j + 4][e] + bh[j]);
           }
         } else {
           const float* cs = tab + rt * 128;
@@ -343,9 +365,9 @@ __global__ void __launch_bounds__(WM* WN * 64)
                                  : reinterpret_cast<bf16_t*>(qe.k_compact) + (size_t)gm * qe.kv_dim + hcol;
           bf16_t* d2 = reinterpret_cast<bf16_t*>(qe.k_cache) + (size_t)pos * qe.kv_dim + hcol;
 #pragma unroll
-          for (int j = 0; j < 2; ++j) {
-            const int c = j * 32 + col_l;
-            const float lo = acc[i][j][e] + bl[j], hi = acc[i][j + 2][e] + bh[j];
+          for (int j = 0; j < 4; ++j) {
+            const int c = j * 16 + col_l;
+            const float lo = acc[i][j][e] + bl[j], hi = acc[i][j + 4][e] + bh[j];
             const float cc = cs[c], ss = sn[c];
             const uint16_t olo = f32_to_bf16_bits(lo * cc - hi * ss), ohi = f32_to_bf16_bits(hi * cc + lo * ss);
             d1[c].bits = olo;
@@ -363,14 +385,14 @@ __global__ void __launch_bounds__(WM* WN * 64)
 #pragma unroll
   for (int i = 0; i < MI; ++i) {
 #pragma unroll
-    for (int e = 0; e < 16; ++e) {
-      const int gm = m0 + wm * TM + i * 32 + 8 * (e >> 2) + row_l + (e & 3);
+    for (int e = 0; e < 4; ++e) {
+      const int gm = m0 + wm * TM + i * 16 + row_l + e;
       if (gm >= M) continue;
       if (EPI == EPI_SWIGLU_STORE) {
         const int n_out = N;  // N = ffn_dim (output width)
 #pragma unroll
         for (int j = 0; j < NI / 2; ++j) {
-          const int gn = (n0 / 2) + wn * (TN / 2) + j * 32 + col_l;
+          const int gn = (n0 / 2) + wn * (TN / 2) + j * 16 + col_l;
           const float g = acc[i][j][e], u = acc[i][j + NI / 2][e];
           const float v = g / (1.0f + __expf(-g)) * u;
           reinterpret_cast<bf16_t*>(Cv)[(size_t)gm * n_out + gn].bits = f32_to_bf16_bits(v);
@@ -378,7 +400,7 @@ __global__ void __launch_bounds__(WM* WN * 64)
       } else {
 #pragma unroll
         for (int j = 0; j < NI; ++j) {
-          const int gn = n0 + wn * TN + j * 32 + col_l;
+          const int gn = n0 + wn * TN + j * 16 + col_l;
           const size_t idx = (size_t)gm * N + gn;
           if (EPI == EPI_STORE_F32) {
             reinterpret_cast<float*>(Cv)[idx] = acc[i][j][e];
