@@ -399,6 +399,60 @@ __global__ void __launch_bounds__(512)
   if (d4 == 0) lse[(size_t)r * n_q_heads + head] = 0.6931471805599453f * (m_all + log2f(l_all));
 }
 
+// The same merge for tiles with many chunks and very few query rows (decoding: one row, a handful of heads):
+// 16 lanes share one (query row, 4 output dimensions) item and take the chunks 16 apart,
+// so the partials of 16 chunks are in flight at once instead of one after the other; the lanes' maxima and
+// weighted sums are joined by a fixed butterfly (reproducible).  blockIdx.y * 16 + threadIdx.x / 16 = item
+// = query row * 32 + dimension group.
+__global__ void __launch_bounds__(256)
+    k_attn_combine_spread(const int4* __restrict__ splits, const float* __restrict__ part_o,
+                        const float* __restrict__ part_ml, const int32_t* __restrict__ row_list, int n_rows,
+                        int n_q_heads, int n_kv_heads, bf16_t* __restrict__ o, float* __restrict__ lse) {
+  const int hk = blockIdx.x % n_kv_heads;
+  const int4 sp = splits[blockIdx.x / n_kv_heads];  // {tile, first slot, chunks, -}
+  const int rep = n_q_heads / n_kv_heads;
+  const int item = blockIdx.y * 16 + (threadIdx.x >> 4);
+  const int cl = threadIdx.x & 15;
+  const int ql = item >> 5, d4 = item & 31;
+  const int x = sp.x * 128 + ql;
+  if (ql >= 128 || x >= n_rows * rep) return;  // (whole 16-lane groups leave together)
+  const int r = row_list ? row_list[x / rep] : x / rep, head = hk * rep + x % rep;
+  const float* ml = part_ml + ((size_t)sp.y * n_kv_heads + hk) * 256 + ql;
+  const size_t ml_step = (size_t)n_kv_heads * 256;
+  float m_all = M_FLOOR;
+  for (int c = cl; c < sp.z; c += 16) m_all = fmaxf(m_all, ml[c * ml_step]);
+#pragma unroll
+  for (int off = 1; off < 16; off <<= 1) m_all = fmaxf(m_all, __shfl_xor(m_all, off, 64));
+  float l_all = 0.f;
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  const float* po = part_o + ((size_t)sp.y * n_kv_heads + hk) * PART_FLOATS + ((size_t)d4 * 128 + ql) * 4;
+  const size_t po_step = (size_t)n_kv_heads * PART_FLOATS;
+  for (int c = cl; c < sp.z; c += 16) {
+    const float w = __builtin_amdgcn_exp2f(ml[c * ml_step] - m_all);
+    l_all += ml[c * ml_step + 128] * w;
+    const float4 v = *reinterpret_cast<const float4*>(po + c * po_step);
+    acc.x += w * v.x;
+    acc.y += w * v.y;
+    acc.z += w * v.z;
+    acc.w += w * v.w;
+  }
+#pragma unroll
+  for (int off = 1; off < 16; off <<= 1) {
+    l_all += __shfl_xor(l_all, off, 64);
+    acc.x += __shfl_xor(acc.x, off, 64);
+    acc.y += __shfl_xor(acc.y, off, 64);
+    acc.z += __shfl_xor(acc.z, off, 64);
+    acc.w += __shfl_xor(acc.w, off, 64);
+  }
+  if (cl != 0) return;
+  const float inv = 1.0f / l_all;
+  uint2 u;
+  u.x = pack_bf16x2(acc.x * inv, acc.y * inv);
+  u.y = pack_bf16x2(acc.z * inv, acc.w * inv);
+  *reinterpret_cast<uint2*>(o + ((size_t)r * n_q_heads + head) * DH + d4 * 4) = u;
+  if (d4 == 0) lse[(size_t)r * n_q_heads + head] = 0.6931471805599453f * (m_all + log2f(l_all));
+}
+
 // ---- host-side work list ---------------------------------------------------
 constexpr int ATT_MAX_SLOTS = 4096;      // partial buffers (cut items x KV heads) the scratch can hold
 constexpr int ATT_SLOTS = 512;           // resident workgroups: 2 per CU x 256 CUs
@@ -437,8 +491,13 @@ static void launch_attn_planned(const bf16_t* q, const bf16_t* k_cache, const bf
   hipLaunchKernelGGL(k_attn_mfma, dim3(n_items * n_kv_heads), dim3(256), sh, s, q, k_cache, v_cache, d_row_pos, d_row_lo,
                      d_row_list, n_rows, n_total, n_q_heads, n_kv_heads, d_items, scale_log2e, o, lse, part_o, part_ml);
   if (n_splits && wide_combine) {
-    hipLaunchKernelGGL(k_attn_combine_wide, dim3(n_splits * n_kv_heads, 32), dim3(512), 0, s, d_splits, part_o, part_ml,
-                       d_row_list, n_rows, n_q_heads, n_kv_heads, o, lse);
+    const int pairs = std::min(128, n_rows * rep);  // query rows of the fullest tile
+    if (pairs < 32)  // too few rows to fill the row-major kernel's lanes: spread the chunks over lanes instead
+      hipLaunchKernelGGL(k_attn_combine_spread, dim3(n_splits * n_kv_heads, (pairs * 32 + 15) / 16), dim3(256), 0, s,
+                         d_splits, part_o, part_ml, d_row_list, n_rows, n_q_heads, n_kv_heads, o, lse);
+    else
+      hipLaunchKernelGGL(k_attn_combine_wide, dim3(n_splits * n_kv_heads, 32), dim3(512), 0, s, d_splits, part_o,
+                         part_ml, d_row_list, n_rows, n_q_heads, n_kv_heads, o, lse);
   } else if (n_splits) {
     hipLaunchKernelGGL(k_attn_combine, dim3(n_splits * n_kv_heads, 16), dim3(256), 0, s, d_splits, part_o, part_ml,
                        d_row_list, n_rows, n_q_heads, n_kv_heads, o, lse);
