@@ -19,6 +19,14 @@ def max_rel(a: np.ndarray, b: np.ndarray) -> float:
     return float(np.abs(a - b).max() / (den if den > 0 else 1.0))
 
 
+def mean_rel(a: np.ndarray, b: np.ndarray) -> float:
+    """mean |a - b| / mean |b| (reported beside the maximum; not a tolerance)."""
+    a = np.asarray(a, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    den = np.abs(b).mean()
+    return float(np.abs(a - b).mean() / (den if den > 0 else 1.0))
+
+
 def update_err(x_out: np.ndarray, x_in: np.ndarray, ref_out: np.ndarray, storage: str):
     """Error of the layer's UPDATE (x_out - x_in: output projection of the attention plus FFN), relative to the
     largest reference update, and the share of that error the output format itself accounts for.

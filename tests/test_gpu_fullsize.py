@@ -9,7 +9,7 @@ import torch
 
 import keep_synth as ks
 from oracle import keep_oracle as ko
-from gpu_util import max_rel, to_np, update_err, layer_state_err
+from gpu_util import max_rel, mean_rel, to_np, update_err, layer_state_err
 
 pytestmark = pytest.mark.gpu
 TOL = 2e-2
@@ -284,6 +284,10 @@ def test_fullsize_first_two_layers_against_the_oracle():
     print("two layers at full size: set sizes %s  layer 0 K %.2e V %.2e | layer 1 K %.2e V %.2e, refreshed rows K %.2e "
           "V %.2e | x_final %.2e, its layer-1 update %.2e (format %.1e)"
           % ([len(x) for x in sets], ek0, ev0, ek1, ev1, ek1r, ev1r, ex, ed, allow))
+    print("  mean relative errors: layer 0 K %.2e V %.2e | layer 1 refreshed rows K %.2e V %.2e | x_final %.2e"
+          % (mean_rel(to_np(r["kc"][0]), kh0), mean_rel(to_np(r["vc"][0]), vh0),
+             mean_rel(to_np(r["kc"][1])[keep_rows], kh1[keep_rows]), mean_rel(to_np(r["vc"][1])[keep_rows], vh1[keep_rows]),
+             mean_rel(to_np(r["xf"]), xf_ref)))
     assert not torch.isnan(r["kc"]).any() and not torch.isnan(r["vc"]).any()
     assert max(ek0, ev0, ek1, ev1, ek1r, ev1r, ex) < TOL and ed < TOL + allow
 
