@@ -240,6 +240,7 @@ __global__ void __launch_bounds__(WM* WN * 64)
   // k-step's A fragments) are read while a step multiplies.
   constexpr int NG = NI / 4;        // column groups per k-step
   constexpr int STEPS = KS * NG;    // steps per slice
+  static_assert(KS % 2 == 0, "the A fragments' two buffers alternate by k-step and must come out even over a slice");
   bf16x8 af[2][MI], bfr[2][4];
 #pragma unroll
   for (int i = 0; i < MI; ++i) af[0][i] = *reinterpret_cast<const bf16x8*>(smem + a_off[0] + i * 16 * GBK);
@@ -257,7 +258,7 @@ __global__ void __launch_bounds__(WM* WN * 64)
     for (int st = 0; st < STEPS; ++st) {
       const int ks = st / NG, g = st % NG;
       const int bc = st & 1, bn = bc ^ 1, ac = ks & 1, an = ac ^ 1;
-      // (STEPS is even or 1, and a slice ends on an A switch, so the buffer parities carry over the slices)
+      // (KS is even, so both buffer parities come out even over a slice and carry over to the next one)
       bool new_a;
       if (st + 1 < STEPS) {
         const int ks1 = (st + 1) / NG, g1 = (st + 1) % NG;
